@@ -1,0 +1,150 @@
+/*
+ * halp_ref.h -- CPU oracle for the HALP epoch (De Sa et al., "High-Accuracy
+ * Low-Precision Training", arXiv 1803.03383).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, single-threaded reference
+ * written from the paper.  Only the test-suite, the smoke check and the
+ * benchmark's "cpu_baseline" leg may load it.  It shares no code, header,
+ * table or helper with the HIP library, and the HIP library never calls it.
+ *
+ * What it follows:
+ *   - Sec. 3 "Representation" / "Quantization": dom(delta,b) and the unbiased
+ *     quantizer Q_(delta,b); up/down probabilities as in the proof of Lemma 1.
+ *   - Sec. 4 "Bit centering" and Algorithm 3 (HALP): delta = ||g~||/(mu(2^(b-1)-1)).
+ *   - Sec. 4 "Efficient implementation" and Algorithm 4 (LM-HALP): the cached
+ *     margins phi, the three compatible scales delta_m, delta_i, delta_s, the
+ *     quantized scalar gamma and the integer update of the offset z.
+ *
+ * Floating point is fp64 throughout; integers are exact (int64 inside).
+ * Build with contraction off (-ffp-contract=off) so every fp64 operation
+ * below is rounded on its own.
+ *
+ * Readings of points the paper leaves open (each one is also listed in the
+ * repository's design notes):
+ *   - h~ is held in (delta_i, 2b) as the text after Algorithm 4 says (the
+ *     listing's "b" for it is read as a slip).
+ *   - the norm is the Euclidean / Frobenius norm.
+ *   - real -> integer rounding is floor(x * (1/delta) + rho), rho = r32 * 2^-32
+ *     with one 32-bit random word: P(up) equals the fractional part to 2^-32.
+ *   - integer (delta_i,2b) -> (delta_m,b) rounding is floor((u + r) / 2^b) with
+ *     exactly b random bits r: exactly unbiased.
+ *   - random numbers: counter-based Philox4x32-10 (Salmon et al., SC'11);
+ *     every draw is a pure function of (seed, purpose, epoch, step, position).
+ *   - indices are drawn with replacement, i = floor(r32 * N / 2^32).
+ *   - minibatch B > 1: all rows of a step see the same z, each row has its own
+ *     gamma, beta carries alpha/B, z is quantized once per step.
+ *   - L2 term lambda: outer gradient gets + lambda w~; inner update gets
+ *     - c_lambda * z with c_lambda = Q_(2^-b, b)(alpha lambda), one draw per step.
+ *   - multiclass: softmax cross-entropy, W stored [K][d], one gamma per class.
+ *   - squared loss l(a) = (a-y)^2/2, so beta = (alpha/B) * (x^T z) exactly.
+ *   - logistic labels are -1/+1, l(a) = log(1 + exp(-y a)).
+ *
+ * Parity pins: see tests/test_oracle_*.py.  Unpinned by the paper itself
+ * ("parity unpinned" beyond unbiasedness against Algorithm 3 and reduction to
+ * the written algorithm at K=1, B=1, lambda=0): the softmax, minibatch and L2
+ * readings above.
+ */
+#ifndef HALP_REF_H
+#define HALP_REF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { HALP_REF_SQUARED = 0, HALP_REF_LOGISTIC = 1, HALP_REF_SOFTMAX = 2 };
+
+/* purposes of the random streams (counter word 3) */
+enum {
+  HALP_REF_PURPOSE_IDX = 0,    /* sampled example indices            */
+  HALP_REF_PURPOSE_GAMMA = 1,  /* rounding of the scalar beta         */
+  HALP_REF_PURPOSE_ZROUND = 2, /* rounding of the offset vector z     */
+  HALP_REF_PURPOSE_REG = 3,    /* rounding of alpha*lambda            */
+  HALP_REF_PURPOSE_HROUND = 4  /* rounding of alpha*g~ into h~        */
+};
+
+typedef struct {
+  int64_t N;      /* examples                                         */
+  int32_t d;      /* features                                         */
+  int32_t K;      /* classes (1 unless softmax)                       */
+  int32_t loss;   /* HALP_REF_*                                       */
+  int32_t b;      /* bits of the low-precision model: 8, 16 (or up to 24 on the CPU only) */
+  int32_t B;      /* inner minibatch                                  */
+  int32_t pad_;
+  double alpha;   /* step size                                        */
+  double mu;      /* strong-convexity parameter used by bit centering */
+  double lambda;  /* L2                                               */
+  double delta_d; /* scale of the low-precision data (delta_d, b)     */
+  uint64_t seed;  /* seed of this chain                               */
+} halp_ref_problem;
+
+/* optional per-step record of the first M steps; any pointer may be NULL */
+typedef struct {
+  int64_t M;
+  int64_t* idx;    /* [M][B]        sampled indices                   */
+  int64_t* D;      /* [M][B][K]     integer dot products x^T z         */
+  double* beta;    /* [M][B][K]                                        */
+  int32_t* gamma;  /* [M][B][K]                                        */
+  int32_t* ztraj;  /* [M][K][d]     z after the step                   */
+} halp_ref_trace;
+
+/* scales[8]: 0 delta_m, 1 delta_i, 2 delta_s, 3 ||g~||, 4 1/delta_i,
+ * 5 1/delta_s, 6 f(w~) (filled by the epoch driver), 7 status
+ * (0 ok, 1 gradient is exactly zero: converged, -1 non-finite).           */
+
+/* Philox4x32-10, Salmon et al. SC'11 */
+void halp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* word n of a purpose's stream: Philox block n/4, word n%4,
+ * counter = (lo32(n/4), hi32(n/4), epoch, purpose), key = (lo32 seed, hi32 seed) */
+uint32_t halp_ref_stream_word(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n);
+
+/* the b rounding bits of coordinate (c,j) at 0-based step t */
+uint32_t halp_ref_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
+                              int32_t c, int32_t j);
+
+/* index of minibatch slot m at 0-based step t */
+int64_t halp_ref_sample_index(uint64_t seed, uint32_t epoch, uint64_t t, int32_t B, int32_t m,
+                              int64_t N);
+
+/* Q for a real: clamp(floor(x * inv_delta + r32 * 2^-32), lo, hi); clamped!=NULL gets 1 if it hit a bound */
+int64_t halp_ref_quantize_real(double x, double inv_delta, uint32_t r32, int64_t lo, int64_t hi,
+                               int* clamped);
+
+/* Q_(delta_m,b) of u = (z << b) + v held in (delta_i, 2b): clamp(z + floor((v + r) / 2^b)) */
+int64_t halp_ref_round_shift(int64_t z, int64_t v, uint32_t r, int b, int* clamped);
+
+/* X -> (delta_d, b): clamp(round-half-even(X / delta_d), -(2^(b-1)-1), 2^(b-1)-1);
+ * Xq is int8 when b == 8, int16 when b == 16, int32 for 16 < b <= 24 (CPU only) */
+void halp_ref_quantize_data(const float* X, int64_t n, double delta_d, int b, void* Xq);
+
+/* Algorithm 4, the two outer lines: margins phi_i = x_i^T w~ and
+ * g~ = (1/N) sum l'_i(phi_i) x_i (+ lambda w~); loss = f(w~).
+ * y: float* for squared / logistic (+-1), int32* for softmax.           */
+int halp_ref_full_gradient(const halp_ref_problem* p, const float* X, int64_t ldx, const void* y,
+                           const float* w, double* phi, double* g, double* loss);
+
+/* Algorithm 4, the re-scale lines, h~ = Q(alpha g~) and z = Q(0) */
+int halp_ref_recenter(const halp_ref_problem* p, const float* g, uint32_t epoch, double scales[8],
+                      int64_t* h, int32_t* z);
+
+/* Algorithm 4, the inner loop: T steps on z (in/out) */
+int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq, const float* phi,
+                        const void* y, const int64_t* h, const double scales[8], uint32_t epoch,
+                        int64_t T, int32_t* z, const halp_ref_trace* trace, uint64_t counters[4]);
+
+/* Algorithm 4, last outer line (option I): w~ <- w~ + delta_m z */
+void halp_ref_apply_offset(const halp_ref_problem* p, const double scales[8], const int32_t* z,
+                           float* w);
+
+/* one whole epoch: the four calls above in order; phi32 / g32 receive the
+ * fp32-rounded margins and gradient that the inner loop consumed           */
+int halp_ref_epoch(const halp_ref_problem* p, const float* X, int64_t ldx, const void* Xq,
+                   int64_t ldxq, const void* y, float* w, uint32_t epoch, int64_t T, float* phi32,
+                   float* g32, double scales[8], int64_t* h, int32_t* z, uint64_t counters[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

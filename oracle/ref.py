@@ -1,0 +1,220 @@
+"""ctypes front end of the CPU oracle (oracle/halp_ref.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  It never imports the HIP package.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+SQUARED, LOGISTIC, SOFTMAX = 0, 1, 2
+PURPOSE_IDX, PURPOSE_GAMMA, PURPOSE_ZROUND, PURPOSE_REG, PURPOSE_HROUND = 0, 1, 2, 3, 4
+
+
+class Problem(C.Structure):
+    _fields_ = [
+        ("N", C.c_int64), ("d", C.c_int32), ("K", C.c_int32), ("loss", C.c_int32),
+        ("b", C.c_int32), ("B", C.c_int32), ("pad_", C.c_int32),
+        ("alpha", C.c_double), ("mu", C.c_double), ("lam", C.c_double),
+        ("delta_d", C.c_double), ("seed", C.c_uint64),
+    ]
+
+
+class Trace(C.Structure):
+    _fields_ = [
+        ("M", C.c_int64), ("idx", C.c_void_p), ("D", C.c_void_p), ("beta", C.c_void_p),
+        ("gamma", C.c_void_p), ("ztraj", C.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.halp_ref_stream_word.restype = C.c_uint32
+        L.halp_ref_stream_word.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64]
+        L.halp_ref_zround_bits.restype = C.c_uint32
+        L.halp_ref_zround_bits.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32,
+                                           C.c_int32, C.c_int32, C.c_int32]
+        L.halp_ref_sample_index.restype = C.c_int64
+        L.halp_ref_sample_index.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32,
+                                            C.c_int32, C.c_int64]
+        L.halp_ref_quantize_real.restype = C.c_int64
+        L.halp_ref_quantize_real.argtypes = [C.c_double, C.c_double, C.c_uint32, C.c_int64,
+                                             C.c_int64, C.c_void_p]
+        L.halp_ref_round_shift.restype = C.c_int64
+        L.halp_ref_round_shift.argtypes = [C.c_int64, C.c_int64, C.c_uint32, C.c_int, C.c_void_p]
+        L.halp_ref_philox4x32_10.restype = None
+        L.halp_ref_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.halp_ref_quantize_data.restype = None
+        L.halp_ref_quantize_data.argtypes = [C.c_void_p, C.c_int64, C.c_double, C.c_int, C.c_void_p]
+        L.halp_ref_full_gradient.restype = C.c_int
+        L.halp_ref_full_gradient.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.halp_ref_recenter.restype = C.c_int
+        L.halp_ref_recenter.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
+                                        C.c_void_p, C.c_void_p]
+        L.halp_ref_inner_loop.restype = C.c_int
+        L.halp_ref_inner_loop.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_uint32, C.c_int64, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
+        L.halp_ref_apply_offset.restype = None
+        L.halp_ref_apply_offset.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.halp_ref_epoch.restype = C.c_int
+        L.halp_ref_epoch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                     C.c_void_p, C.c_void_p, C.c_uint32, C.c_int64, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def xq_dtype(b):
+    return np.int8 if b == 8 else (np.int16 if b == 16 else np.int32)
+
+
+def make_problem(N, d, K=1, loss=SQUARED, b=8, B=1, alpha=0.01, mu=1.0, lam=0.0, delta_d=1.0,
+                 seed=0):
+    return Problem(N=N, d=d, K=K, loss=loss, b=b, B=B, pad_=0, alpha=alpha, mu=mu, lam=lam,
+                   delta_d=delta_d, seed=seed)
+
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().halp_ref_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def stream_word(seed, purpose, epoch, n):
+    return int(lib().halp_ref_stream_word(seed, purpose, epoch, n))
+
+
+def zround_bits(seed, epoch, t, d, b, c, j):
+    return int(lib().halp_ref_zround_bits(seed, epoch, t, d, b, c, j))
+
+
+def sample_index(seed, epoch, t, B, m, N):
+    return int(lib().halp_ref_sample_index(seed, epoch, t, B, m, N))
+
+
+def quantize_real(x, inv_delta, r32, lo, hi):
+    hit = C.c_int(0)
+    q = lib().halp_ref_quantize_real(x, inv_delta, r32, lo, hi, C.addressof(hit))
+    return int(q), bool(hit.value)
+
+
+def round_shift(z, v, r, b):
+    hit = C.c_int(0)
+    q = lib().halp_ref_round_shift(z, v, r, b, C.addressof(hit))
+    return int(q), bool(hit.value)
+
+
+def quantize_data(X, delta_d, b):
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    Xq = np.zeros(X.shape, dtype=xq_dtype(b))
+    lib().halp_ref_quantize_data(_p(X), X.size, float(delta_d), b, _p(Xq))
+    return Xq
+
+
+def _ylike(prob, y):
+    if prob.loss == SOFTMAX:
+        return np.ascontiguousarray(y, dtype=np.int32)
+    return np.ascontiguousarray(y, dtype=np.float32)
+
+
+def full_gradient(prob, X, y, w):
+    """returns (phi[N,K] f64, g[K,d] f64, loss f64)"""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    w = np.ascontiguousarray(w, dtype=np.float32).reshape(prob.K, prob.d)
+    yy = _ylike(prob, y)
+    phi = np.zeros((prob.N, prob.K), dtype=np.float64)
+    g = np.zeros((prob.K, prob.d), dtype=np.float64)
+    loss = np.zeros(1, dtype=np.float64)
+    rc = lib().halp_ref_full_gradient(C.addressof(prob), _p(X), X.shape[1], _p(yy), _p(w), _p(phi),
+                                      _p(g), _p(loss))
+    if rc != 0:
+        raise ValueError(f"halp_ref_full_gradient rc={rc}")
+    return phi, g, float(loss[0])
+
+
+def recenter(prob, g32, epoch):
+    """returns (scales[8] f64, h[K,d] i64, z[K,d] i32)"""
+    g32 = np.ascontiguousarray(g32, dtype=np.float32)
+    scales = np.zeros(8, dtype=np.float64)
+    h = np.zeros((prob.K, prob.d), dtype=np.int64)
+    z = np.zeros((prob.K, prob.d), dtype=np.int32)
+    rc = lib().halp_ref_recenter(C.addressof(prob), _p(g32), epoch, _p(scales), _p(h), _p(z))
+    if rc != 0:
+        raise ValueError(f"halp_ref_recenter rc={rc}")
+    return scales, h, z
+
+
+def inner_loop(prob, Xq, phi32, y, h, scales, epoch, T, z0=None, trace_steps=0):
+    """returns dict(z=..., counters=..., and trace arrays when trace_steps > 0)"""
+    Xq = np.ascontiguousarray(Xq, dtype=xq_dtype(prob.b))
+    phi32 = np.ascontiguousarray(phi32, dtype=np.float32)
+    yy = _ylike(prob, y)
+    h = np.ascontiguousarray(h, dtype=np.int64)
+    scales = np.ascontiguousarray(scales, dtype=np.float64)
+    z = np.zeros((prob.K, prob.d), dtype=np.int32) if z0 is None else np.array(z0, dtype=np.int32)
+    counters = np.zeros(4, dtype=np.uint64)
+    out = {}
+    tr = None
+    if trace_steps > 0:
+        M, B, K, d = trace_steps, prob.B, prob.K, prob.d
+        out["idx"] = np.zeros((M, B), dtype=np.int64)
+        out["D"] = np.zeros((M, B, K), dtype=np.int64)
+        out["beta"] = np.zeros((M, B, K), dtype=np.float64)
+        out["gamma"] = np.zeros((M, B, K), dtype=np.int32)
+        out["ztraj"] = np.zeros((M, K, d), dtype=np.int32)
+        tr = Trace(M=M, idx=out["idx"].ctypes.data, D=out["D"].ctypes.data,
+                   beta=out["beta"].ctypes.data, gamma=out["gamma"].ctypes.data,
+                   ztraj=out["ztraj"].ctypes.data)
+    rc = lib().halp_ref_inner_loop(C.addressof(prob), _p(Xq), Xq.shape[1], _p(phi32), _p(yy), _p(h),
+                                   _p(scales), epoch, T, _p(z),
+                                   C.addressof(tr) if tr is not None else None, _p(counters))
+    if rc != 0:
+        raise ValueError(f"halp_ref_inner_loop rc={rc}")
+    out["z"] = z
+    out["counters"] = counters
+    return out
+
+
+def apply_offset(prob, scales, z, w):
+    w = np.array(w, dtype=np.float32).reshape(prob.K, prob.d)
+    z = np.ascontiguousarray(z, dtype=np.int32)
+    scales = np.ascontiguousarray(scales, dtype=np.float64)
+    lib().halp_ref_apply_offset(C.addressof(prob), _p(scales), _p(z), _p(w))
+    return w
+
+
+def epoch(prob, X, Xq, y, w, epoch_no, T):
+    """one HALP epoch; returns dict(w, phi, g, scales, h, z, counters)"""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    Xq = np.ascontiguousarray(Xq, dtype=xq_dtype(prob.b))
+    yy = _ylike(prob, y)
+    w = np.array(w, dtype=np.float32).reshape(prob.K, prob.d)
+    phi = np.zeros((prob.N, prob.K), dtype=np.float32)
+    g = np.zeros((prob.K, prob.d), dtype=np.float32)
+    scales = np.zeros(8, dtype=np.float64)
+    h = np.zeros((prob.K, prob.d), dtype=np.int64)
+    z = np.zeros((prob.K, prob.d), dtype=np.int32)
+    counters = np.zeros(4, dtype=np.uint64)
+    rc = lib().halp_ref_epoch(C.addressof(prob), _p(X), X.shape[1], _p(Xq), Xq.shape[1], _p(yy),
+                              _p(w), epoch_no, T, _p(phi), _p(g), _p(scales), _p(h), _p(z),
+                              _p(counters))
+    if rc != 0:
+        raise ValueError(f"halp_ref_epoch rc={rc}")
+    return dict(w=w, phi=phi, g=g, scales=scales, h=h, z=z, counters=counters)
