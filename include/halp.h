@@ -1,0 +1,178 @@
+/*
+ * halp.h -- C ABI of the MI355X (gfx950) HALP epoch library.
+ *
+ * The library runs the epoch of HALP for linear models (De Sa et al.,
+ * "High-Accuracy Low-Precision Training", arXiv 1803.03383, Algorithm 4,
+ * "LM-HALP") on one GPU for R independent chains at once:
+ *
+ *   1. full-precision pass   phi_i = x_i^T w~,  g~ = (1/N) sum_i l_i'(phi_i) x_i
+ *   2. bit centering         delta_m = ||g~|| / (mu (2^(b-1) - 1)), the two
+ *                            derived scales, h~ = Q(alpha g~), z = 0
+ *   3. T low-precision inner steps on the integer offset z
+ *   4. w~ <- w~ + delta_m z  (option I)
+ *
+ * The problem is the finite sum of the paper's eq. (1) with linear-model terms
+ * f_i(w) = l_i(x_i^T w) (+ lambda/2 ||w||^2) (Sec. 4, "Efficient implementation").
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     never frees or reallocates caller memory.  Strides are in elements.
+ *   - Every call that takes a stream is asynchronous on that hipStream_t
+ *     (passed as void*; NULL is the default stream).  halp_create,
+ *     halp_destroy, halp_bind, halp_set_option and halp_get_stats are host
+ *     calls; halp_get_stats synchronizes the stream it is given.
+ *   - Return value: 0 on success, a negative HALP_ERR_* otherwise.  Nothing is
+ *     launched when an error is returned.  Conditions only the device can see
+ *     (a zero or non-finite gradient) are reported through scales[7] and
+ *     halp_get_stats, and turn the rest of that epoch into a no-op.
+ *   - A handle is not thread-safe; distinct handles are independent.  There is
+ *     no global state.
+ *   - All randomness is counter-based (Philox4x32-10): each draw is a pure
+ *     function of (seed + chain, epoch, step, purpose, position), so a run can
+ *     be resumed from (w~, epoch, seed) alone and replayed on a CPU.
+ */
+#ifndef HALP_H
+#define HALP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HALP_OK 0
+#define HALP_ERR_NULL (-1)        /* a required pointer is NULL                         */
+#define HALP_ERR_INVALID (-2)     /* a parameter is out of range                        */
+#define HALP_ERR_UNSUPPORTED (-3) /* valid, but no kernel covers this shape             */
+#define HALP_ERR_NOT_BOUND (-4)   /* halp_bind has not been called / lacks a buffer     */
+#define HALP_ERR_HIP (-5)         /* a HIP runtime call failed                          */
+#define HALP_ERR_ALIGN (-6)       /* pointer or stride alignment requirement not met    */
+
+/* scalar loss l_i of the linear model (Sec. 4); labels y as noted */
+#define HALP_LOSS_SQUARED 0  /* l(a) = (a - y)^2 / 2,        y: float               */
+#define HALP_LOSS_LOGISTIC 1 /* l(a) = log(1 + exp(-y a)),   y: float in {-1,+1}    */
+#define HALP_LOSS_SOFTMAX 2  /* l(a) = -log softmax(a)_y,    y: int32 in [0,K)      */
+
+typedef struct halp_handle halp_handle; /* opaque, library-owned */
+
+/* The "given" lists of Algorithm 4 plus the problem sizes of eq. (1). */
+typedef struct {
+  int64_t N;          /* examples per chain, 1 <= N < 2^31                             */
+  int32_t d;          /* features, >= 1                                                */
+  int32_t K;          /* classes: 1 for squared / logistic, 2..16 for softmax          */
+  int32_t R;          /* independent chains (seeds / problem instances), >= 1          */
+  int32_t loss;       /* HALP_LOSS_*                                                   */
+  int32_t b;          /* bits of z, gamma and the data: 8 or 16                        */
+  int32_t B;          /* inner minibatch (rows per step), >= 1                         */
+  int32_t share_data; /* 0: each chain has its own X, Xq, y; 1: all chains share one   */
+  int32_t reserved;   /* must be 0                                                     */
+  int64_t T;          /* inner steps per epoch, 0 <= T < 2^32                          */
+  double alpha;       /* step size, > 0                                                */
+  double mu;          /* strong-convexity parameter of bit centering, > 0              */
+  double lambda;      /* L2 coefficient, >= 0                                          */
+  double delta_d;     /* scale of the low-precision data representation (delta_d, b)   */
+  uint64_t seed;      /* chain r draws with seed + r                                   */
+} halp_params;
+
+/* Device buffers.  Rd = 1 if share_data else R.  "in" = read by the library,
+ * "out" = written, both relative to a whole halp_epoch.                              */
+typedef struct {
+  const float* X;     /* in   [Rd][N][ldx] fp32 examples, ldx >= d, ldx % 4 == 0, 16-byte aligned */
+  int64_t ldx;
+  void* Xq;           /* in (out of halp_quantize_data) [Rd][N][ldxq] int8 (b=8) / int16 (b=16);
+                         row stride a multiple of 8 bytes, base 8-byte aligned          */
+  int64_t ldxq;
+  const void* y;      /* in   [Rd][N] float or int32, see HALP_LOSS_*; may be NULL for squared loss
+                         if halp_full_gradient is never called                          */
+  float* w;           /* in/out [R][K][d] the full-precision model w~                   */
+  float* phi;         /* out  [R][N][K] margins x_i^T w~ of the last full-gradient pass */
+  float* g;           /* out  [R][K][d] full gradient g~                                */
+  void* z;            /* out  [R][K][d] int8 / int16 offset in (delta_m, b)             */
+  void* h;            /* out  [R][K][d] int16 / int32 h~ in (delta_i, 2b)               */
+  double* scales;     /* out  [R][8]: delta_m, delta_i, delta_s, ||g~||, 1/delta_i, 1/delta_s,
+                         f(w~), status (0 ok, 1 gradient exactly zero, -1 not finite)   */
+  uint64_t* counters; /* out  [R][4]: coordinates of z clamped by the last inner loop, gammas
+                         clamped, steps with a non-zero L2 draw, reserved               */
+} halp_buffers;
+
+typedef struct {
+  double delta_m, delta_i, delta_s, grad_norm, loss;
+  int32_t status;         /* 0 ok, 1 converged (gradient exactly zero), -1 gradient not finite */
+  int32_t inner_variant;  /* kernel that ran the last inner loop: 1 generic, 2 register-resident */
+  uint64_t n_clamped_z, n_clamped_gamma, n_reg_draws;
+  float ms_full_gradient, ms_recenter, ms_inner_loop; /* mean per halp_epoch over timed_epochs */
+  int32_t timed_epochs;   /* halp_epoch calls averaged (the last 32 at most since timing was set) */
+} halp_stats;
+
+#define HALP_OPT_INNER_VARIANT 1 /* 0 auto (default), 1 generic, 2 register-resident     */
+#define HALP_OPT_TIMING 2        /* 1: halp_epoch brackets its phases with events on its stream;
+                                    setting it restarts the averages of halp_get_stats     */
+#define HALP_OPT_COUNT_CLAMPS 3  /* 1 (default): counters[0] is exact; 0: not counted, the
+                                    register-resident kernel writes UINT64_MAX instead     */
+#define HALP_OPT_FULLGRAD_BLOCKS 4 /* workgroups per chain of the gradient pass, 0 = auto  */
+
+/* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
+ * library's own device workspace on the current device.                               */
+int halp_create(halp_handle** out, const halp_params* p);
+int halp_destroy(halp_handle* h);
+
+/* Records the caller's buffers (the struct is copied).  Checks alignment and
+ * strides.  Any pointer may be NULL if no later call needs it; calls that do
+ * return HALP_ERR_NOT_BOUND.                                                          */
+int halp_bind(halp_handle* h, const halp_buffers* buf);
+
+int halp_set_option(halp_handle* h, int32_t option, int64_t value);
+
+/* Data in the low-precision representation (delta_d, b) that Algorithm 4 is
+ * given: Xq = clamp(round-half-even(X / delta_d), -(2^(b-1)-1), 2^(b-1)-1).
+ * Needs X, Xq.                                                                        */
+int halp_quantize_data(halp_handle* h, void* stream);
+
+/* Algorithm 4, outer lines: phi_i = x_i^T w~ for every example and
+ * g~ = (1/N) sum_i l_i'(phi_i) x_i + lambda w~, in fp32 with X read once;
+ * also f(w~) into scales[6].  Needs X, y, w, phi, g, scales.                          */
+int halp_full_gradient(halp_handle* h, void* stream);
+
+/* Algorithm 4, the re-scale lines (bit centering, Sec. 4): from g~ computes
+ * delta_m = ||g~||_2 / (mu (2^(b-1)-1)), delta_i = 2^-b delta_m,
+ * delta_s = delta_i / delta_d, h~ = Q_(delta_i,2b)(alpha g~) and z = 0.
+ * epoch < 2^32 selects the random stream.  Needs g, h, z, scales.                     */
+int halp_recenter(halp_handle* h, int64_t epoch, void* stream);
+
+/* Algorithm 4, inner loop: T steps of  sample i; beta = alpha (l_i'(phi_i +
+ * x_i^T z) - l_i'(phi_i)); gamma = Q_(delta_s,b)(beta); u = z - gamma x_i - h~;
+ * z = Q_(delta_m,b)(u)  in integer arithmetic, then w~ <- w~ + delta_m z.
+ * Needs Xq, phi (not for squared loss), y (logistic only), h, z, scales, w, counters. */
+int halp_inner_loop(halp_handle* h, int64_t epoch, void* stream);
+
+/* The three calls above in order: one outer iteration of Algorithm 4.                 */
+int halp_epoch(halp_handle* h, int64_t epoch, void* stream);
+
+/* Debug form of halp_inner_loop (generic kernel): additionally records the
+ * first M steps of every chain.  Any trace pointer may be NULL.
+ *   idx   int64  [R][M][B]      sampled example indices
+ *   D     int64  [R][M][B][K]   integer dot products x_i^T z
+ *   beta  double [R][M][B][K]
+ *   gamma int32  [R][M][B][K]
+ *   ztraj int32  [R][M][K][d]   z after each step                                      */
+int halp_inner_loop_trace(halp_handle* h, int64_t epoch, int64_t M, int64_t* idx, int64_t* D,
+                          double* beta, int32_t* gamma, int32_t* ztraj, void* stream);
+
+/* Synchronizes stream, then reads chain r's scales and counters.                      */
+int halp_get_stats(halp_handle* h, int32_t chain, void* stream, halp_stats* out);
+
+/* Debug: words n0 .. n0+count-1 of a purpose's random stream (purposes: 0 index,
+ * 1 gamma, 3 L2, 4 h~), and the b rounding bits of every coordinate [K][d] of z at
+ * step t (purpose 2), written as uint32 to device memory.                             */
+int halp_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
+                            int64_t count, uint32_t* out, void* stream);
+int halp_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
+                           int32_t K, uint32_t* out, void* stream);
+
+const char* halp_strerror(int code);
+const char* halp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,455 @@
+// Full-precision pass of a HALP epoch (Algorithm 4, outer lines):
+//   phi_i = x_i^T w~   and   g~ = (1/N) sum_i l_i'(phi_i) x_i + lambda w~,
+// fused so that every example row crosses HBM once.
+//
+// One wave owns a row at a time.  A lane holds NV F4 column chunks of the
+// row (columns 4*(lane + 64 k)), the same chunks of w~ and of its partial
+// gradient, all in registers.  The margin is a lane-local dot product folded
+// across the wave with DPP; the residual l'(phi) is then a wave-uniform scalar
+// and the gradient update is a broadcast multiply-add.  Rows are fetched one
+// batch ahead of the batch being reduced so that loads stay in flight while the
+// wave computes.  Waves of a workgroup fold their partial gradients through
+// LDS; a second small kernel adds the per-workgroup partials in a fixed order
+// (fp64), so the result does not depend on scheduling.
+#include "halp_device.hpp"
+#include "halp_internal.hpp"
+
+namespace halp {
+namespace {
+
+typedef float F4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ F4 make_f4(float a, float b, float c, float d) { return F4{a, b, c, d}; }
+
+struct FgArgs {
+  const float* X;
+  const void* y;
+  const float* w;
+  float* phi;
+  float* partial_g;
+  double* partial_loss;
+  int64_t N, ldx;
+  int64_t x_chain_stride, y_chain_stride;  // 0 when chains share the data
+  int d, K, parts;
+};
+
+__device__ __forceinline__ float dot4(const F4& a, const F4& b, float acc) {
+  acc = __builtin_fmaf(a.x, b.x, acc);
+  acc = __builtin_fmaf(a.y, b.y, acc);
+  acc = __builtin_fmaf(a.z, b.z, acc);
+  acc = __builtin_fmaf(a.w, b.w, acc);
+  return acc;
+}
+__device__ __forceinline__ void axpy4(float s, const F4& x, F4& g) {
+  g.x = __builtin_fmaf(s, x.x, g.x);
+  g.y = __builtin_fmaf(s, x.y, g.y);
+  g.z = __builtin_fmaf(s, x.z, g.z);
+  g.w = __builtin_fmaf(s, x.w, g.w);
+}
+
+// Loads the chunk at column `col` of a row; columns >= d read as 0.  The row
+// stride is a multiple of 4 floats, so a whole F4 is always inside the row.
+template <bool EXACT>
+__device__ __forceinline__ F4 load_chunk(const float* row, int col, int d) {
+  if (EXACT) return __builtin_nontemporal_load(reinterpret_cast<const F4*>(row + col));
+  F4 v = make_f4(0.f, 0.f, 0.f, 0.f);
+  if (col < d) {
+    v = __builtin_nontemporal_load(reinterpret_cast<const F4*>(row + col));
+    if (col + 1 >= d) v.y = 0.f;
+    if (col + 2 >= d) v.z = 0.f;
+    if (col + 3 >= d) v.w = 0.f;
+  }
+  return v;
+}
+
+// ---- K = 1: squared and logistic ---------------------------------------------
+// NV chunks per lane, RB rows per batch, two batches in registers.
+template <int NV, int RB, int LOSS, bool EXACT>
+__global__ __launch_bounds__(256) void fullgrad_k1(FgArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int chain = blockIdx.y;
+  const float* __restrict__ X = a.X + (int64_t)chain * a.x_chain_stride;
+  const float* __restrict__ y =
+      reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
+  const float* __restrict__ w = a.w + (int64_t)chain * a.d;
+  float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
+  const int d = a.d;
+  const int64_t N = a.N, ldx = a.ldx;
+
+  F4 wv[NV], gv[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int col = 4 * (lane + 64 * k);
+    wv[k] = make_f4(0.f, 0.f, 0.f, 0.f);
+    if (col < d) wv[k].x = w[col];
+    if (col + 1 < d) wv[k].y = w[col + 1];
+    if (col + 2 < d) wv[k].z = w[col + 2];
+    if (col + 3 < d) wv[k].w = w[col + 3];
+    gv[k] = make_f4(0.f, 0.f, 0.f, 0.f);
+  }
+  double loss_acc = 0.0;
+
+  const int64_t nblk = (N + RB - 1) / RB;
+  const int64_t stride = (int64_t)a.parts * 4;
+  int64_t bi = (int64_t)blockIdx.x * 4 + wave;
+
+  F4 xa[RB][NV], xb[RB][NV];
+
+  auto load_batch = [&](F4(&xv)[RB][NV], int64_t blk) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const int64_t row = blk * RB + r;
+      const float* rp = X + row * ldx;
+      if (row < N) {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) xv[r][k] = load_chunk<EXACT>(rp, 4 * (lane + 64 * k), d);
+      } else {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) xv[r][k] = make_f4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+  };
+
+  auto reduce_batch = [&](F4(&xv)[RB][NV], int64_t blk) {
+    float res[RB];
+    float mine = 0.f;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      float p = 0.f;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) p = dot4(xv[r][k], wv[k], p);
+      const float m = wave_sum_f32(p);  // phi_i
+      const int64_t row = blk * RB + r;
+      const bool ok = row < N;
+      const float yi = ok ? y[row] : 0.f;
+      float rr, li;
+      if (LOSS == HALP_LOSS_SQUARED) {
+        rr = m - yi;
+        li = 0.5f * rr * rr;
+      } else {
+        rr = -yi / (1.0f + expf(yi * m));
+        const float s = -yi * m;
+        li = fmaxf(s, 0.f) + log1pf(expf(-fabsf(s)));
+      }
+      res[r] = ok ? rr : 0.f;
+      if (ok) loss_acc += (double)li;
+      if (lane == r) mine = m;
+    }
+    if (lane < RB && blk * RB + lane < N) phi[blk * RB + lane] = mine;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+#pragma unroll
+      for (int k = 0; k < NV; ++k) axpy4(res[r], xv[r][k], gv[k]);
+    }
+  };
+
+  if (bi < nblk) load_batch(xa, bi);
+  while (bi < nblk) {
+    const int64_t b1 = bi + stride;
+    if (b1 < nblk) load_batch(xb, b1);
+    reduce_batch(xa, bi);
+    if (b1 >= nblk) break;
+    const int64_t b2 = b1 + stride;
+    if (b2 < nblk) load_batch(xa, b2);
+    reduce_batch(xb, b1);
+    bi = b2;
+  }
+
+  // fold the four waves' partial gradients in wave order through LDS
+  __shared__ F4 fold[64 * NV];
+  __shared__ double fold_loss[4];
+  if (lane == 0) fold_loss[wave] = loss_acc;
+  for (int s = 1; s < 4; ++s) {
+    if (wave == s) {
+#pragma unroll
+      for (int k = 0; k < NV; ++k) fold[lane + 64 * k] = gv[k];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const F4 o = fold[lane + 64 * k];
+        gv[k].x += o.x; gv[k].y += o.y; gv[k].z += o.z; gv[k].w += o.w;
+      }
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+    float* pg = a.partial_g + ((int64_t)chain * a.parts + blockIdx.x) * (int64_t)d;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int col = 4 * (lane + 64 * k);
+      if (col < d) pg[col] = gv[k].x;
+      if (col + 1 < d) pg[col + 1] = gv[k].y;
+      if (col + 2 < d) pg[col + 2] = gv[k].z;
+      if (col + 3 < d) pg[col + 3] = gv[k].w;
+    }
+    if (lane == 0)
+      a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] =
+          ((fold_loss[0] + fold_loss[1]) + fold_loss[2]) + fold_loss[3];
+  }
+}
+
+// ---- softmax: KC classes held in registers -----------------------------------
+template <int NV, int KC>
+__global__ __launch_bounds__(256) void fullgrad_softmax(FgArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int chain = blockIdx.y;
+  const int d = a.d, K = a.K;
+  const float* __restrict__ X = a.X + (int64_t)chain * a.x_chain_stride;
+  const int32_t* __restrict__ y =
+      reinterpret_cast<const int32_t*>(a.y) + (int64_t)chain * a.y_chain_stride;
+  const float* __restrict__ w = a.w + (int64_t)chain * K * d;
+  float* __restrict__ phi = a.phi + (int64_t)chain * a.N * K;
+  const int64_t N = a.N, ldx = a.ldx;
+
+  F4 wv[KC][NV], gv[KC][NV];
+#pragma unroll
+  for (int c = 0; c < KC; ++c) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int col = 4 * (lane + 64 * k);
+      wv[c][k] = make_f4(0.f, 0.f, 0.f, 0.f);
+      gv[c][k] = make_f4(0.f, 0.f, 0.f, 0.f);
+      if (c < K) {
+        const float* wc = w + (int64_t)c * d;
+        if (col < d) wv[c][k].x = wc[col];
+        if (col + 1 < d) wv[c][k].y = wc[col + 1];
+        if (col + 2 < d) wv[c][k].z = wc[col + 2];
+        if (col + 3 < d) wv[c][k].w = wc[col + 3];
+      }
+    }
+  }
+  double loss_acc = 0.0;
+  const int64_t stride = (int64_t)a.parts * 4;
+  int64_t row = (int64_t)blockIdx.x * 4 + wave;
+
+  F4 xa[NV], xb[NV];
+  auto load_row = [&](F4(&xv)[NV], int64_t r) {
+    const float* rp = X + r * ldx;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) xv[k] = load_chunk<false>(rp, 4 * (lane + 64 * k), d);
+  };
+  auto reduce_row = [&](F4(&xv)[NV], int64_t r) {
+    float logit[KC];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      float p = 0.f;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) p = dot4(xv[k], wv[c][k], p);
+      logit[c] = wave_sum_f32(p);
+      if (c < K) mx = fmaxf(mx, logit[c]);
+    }
+    float e[KC], se = 0.f;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      e[c] = c < K ? expf(logit[c] - mx) : 0.f;
+      se += e[c];
+    }
+    const int yi = y[r];
+    const float inv = 1.0f / se;
+    float mine = 0.f, ly = 0.f;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      const float rc = e[c] * inv - (c == yi ? 1.0f : 0.f);
+      if (c == yi) ly = logit[c];
+      if (lane == c) mine = logit[c];
+#pragma unroll
+      for (int k = 0; k < NV; ++k) axpy4(rc, xv[k], gv[c][k]);
+    }
+    loss_acc += (double)(logf(se) + mx - ly);
+    if (lane < K) phi[r * K + lane] = mine;
+  };
+
+  if (row < N) load_row(xa, row);
+  while (row < N) {
+    const int64_t r1 = row + stride;
+    if (r1 < N) load_row(xb, r1);
+    reduce_row(xa, row);
+    if (r1 >= N) break;
+    const int64_t r2 = r1 + stride;
+    if (r2 < N) load_row(xa, r2);
+    reduce_row(xb, r1);
+    row = r2;
+  }
+
+  __shared__ F4 fold[KC * 64 * NV];
+  __shared__ double fold_loss[4];
+  if (lane == 0) fold_loss[wave] = loss_acc;
+  for (int s = 1; s < 4; ++s) {
+    if (wave == s) {
+#pragma unroll
+      for (int c = 0; c < KC; ++c)
+#pragma unroll
+        for (int k = 0; k < NV; ++k) fold[(c * NV + k) * 64 + lane] = gv[c][k];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int c = 0; c < KC; ++c)
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          const F4 o = fold[(c * NV + k) * 64 + lane];
+          gv[c][k].x += o.x; gv[c][k].y += o.y; gv[c][k].z += o.z; gv[c][k].w += o.w;
+        }
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+    float* pg = a.partial_g + ((int64_t)chain * a.parts + blockIdx.x) * (int64_t)K * d;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      if (c < K) {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          const int col = 4 * (lane + 64 * k);
+          float* pc = pg + (int64_t)c * d;
+          if (col < d) pc[col] = gv[c][k].x;
+          if (col + 1 < d) pc[col + 1] = gv[c][k].y;
+          if (col + 2 < d) pc[col + 2] = gv[c][k].z;
+          if (col + 3 < d) pc[col + 3] = gv[c][k].w;
+        }
+      }
+    }
+    if (lane == 0)
+      a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] =
+          ((fold_loss[0] + fold_loss[1]) + fold_loss[2]) + fold_loss[3];
+  }
+}
+
+// ---- second stage: fixed-order sum of the per-workgroup partials --------------
+struct RedArgs {
+  const float* partial_g;
+  const double* partial_loss;
+  const float* w;
+  float* g;
+  double* scales;
+  int64_t N;
+  int n;  // K*d
+  int parts;
+  double lambda;
+};
+
+__global__ __launch_bounds__(256) void fullgrad_reduce(RedArgs a) {
+  const int chain = blockIdx.y;
+  const int k = blockIdx.x * 256 + threadIdx.x;
+  const float* pg = a.partial_g + (int64_t)chain * a.parts * a.n;
+  const float* w = a.w + (int64_t)chain * a.n;
+  if (k < a.n) {
+    double s = 0.0;
+    for (int p = 0; p < a.parts; ++p) s += (double)pg[(int64_t)p * a.n + k];
+    a.g[(int64_t)chain * a.n + k] = (float)(s / (double)a.N + a.lambda * (double)w[k]);
+  }
+  if (blockIdx.x == 0) {  // f(w~): data term plus lambda/2 ||w~||^2
+    __shared__ double red[256];
+    double w2 = 0.0;
+    for (int j = threadIdx.x; j < a.n; j += 256) w2 += (double)w[j] * (double)w[j];
+    red[threadIdx.x] = w2;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+      if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+      double l = 0.0;
+      for (int p = 0; p < a.parts; ++p) l += a.partial_loss[(int64_t)chain * a.parts + p];
+      a.scales[(int64_t)chain * 8 + 6] = l / (double)a.N + 0.5 * a.lambda * red[0];
+    }
+  }
+}
+
+// ---- dispatch ------------------------------------------------------------------
+int nv_for(int d) {
+  const int chunks = (d + 255) / 256;  // F4 chunks per lane
+  int nv = 1;
+  while (nv < chunks) nv *= 2;
+  return nv;
+}
+
+template <int NV, int RB>
+int launch_k1(const FgArgs& a, int loss, bool exact, dim3 grid, hipStream_t s) {
+  if (loss == HALP_LOSS_SQUARED) {
+    if (exact) hipLaunchKernelGGL((fullgrad_k1<NV, RB, HALP_LOSS_SQUARED, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((fullgrad_k1<NV, RB, HALP_LOSS_SQUARED, false>), grid, dim3(256), 0, s, a);
+  } else {
+    if (exact) hipLaunchKernelGGL((fullgrad_k1<NV, RB, HALP_LOSS_LOGISTIC, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((fullgrad_k1<NV, RB, HALP_LOSS_LOGISTIC, false>), grid, dim3(256), 0, s, a);
+  }
+  return hip_ok(hipGetLastError());
+}
+
+template <int NV>
+int launch_sm(const FgArgs& a, dim3 grid, hipStream_t s) {
+  if (a.K <= 2) hipLaunchKernelGGL((fullgrad_softmax<NV, 2>), grid, dim3(256), 0, s, a);
+  else if (a.K <= 4) hipLaunchKernelGGL((fullgrad_softmax<NV, 4>), grid, dim3(256), 0, s, a);
+  else if (a.K <= 8) hipLaunchKernelGGL((fullgrad_softmax<NV, 8>), grid, dim3(256), 0, s, a);
+  else if (a.K <= 10) hipLaunchKernelGGL((fullgrad_softmax<NV, 10>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((fullgrad_softmax<NV, 16>), grid, dim3(256), 0, s, a);
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace
+
+int fullgrad_supported(const halp_params& p) {
+  const int nv = nv_for(p.d);
+  if (p.loss == HALP_LOSS_SOFTMAX) {
+    if (p.K < 2 || p.K > 16) return HALP_ERR_UNSUPPORTED;
+    const int kc = p.K <= 2 ? 2 : (p.K <= 4 ? 4 : (p.K <= 8 ? 8 : (p.K <= 10 ? 10 : 16)));
+    if (nv > 4 || kc * nv > 40) return HALP_ERR_UNSUPPORTED;  // register budget
+    return HALP_OK;
+  }
+  return nv <= 16 ? HALP_OK : HALP_ERR_UNSUPPORTED;  // d <= 4096
+}
+
+static int rows_per_batch(int nv) { return nv >= 16 ? 1 : 16 / nv; }
+
+int fullgrad_parts(const halp_handle& h) {
+  const halp_params& p = h.p;
+  if (h.fullgrad_blocks > 0) return h.fullgrad_blocks;
+  const int rb = p.loss == HALP_LOSS_SOFTMAX ? 1 : rows_per_batch(nv_for(p.d));
+  const int64_t nblk = (p.N + rb - 1) / rb;
+  int64_t parts = (2 * (int64_t)h.num_cus + p.R - 1) / p.R;  // two workgroups per CU
+  const int64_t most = (nblk + 3) / 4;                        // one batch per wave at least
+  if (parts > most) parts = most;
+  if (parts < 1) parts = 1;
+  return (int)parts;
+}
+
+int launch_full_gradient(const halp_handle& h, hipStream_t s) {
+  const halp_params& p = h.p;
+  int rc = fullgrad_supported(p);
+  if (rc != HALP_OK) return rc;
+  FgArgs a;
+  a.X = h.buf.X; a.y = h.buf.y; a.w = h.buf.w; a.phi = h.buf.phi;
+  a.partial_g = h.partial_g; a.partial_loss = h.partial_loss;
+  a.N = p.N; a.ldx = h.buf.ldx;
+  a.x_chain_stride = p.share_data ? 0 : p.N * h.buf.ldx;
+  a.y_chain_stride = p.share_data ? 0 : p.N;
+  a.d = p.d; a.K = p.K; a.parts = h.parts;
+  const dim3 grid(h.parts, p.R);
+  const int nv = nv_for(p.d);
+  if (p.loss == HALP_LOSS_SOFTMAX) {
+    if (nv == 1) rc = launch_sm<1>(a, grid, s);
+    else if (nv == 2) rc = launch_sm<2>(a, grid, s);
+    else rc = launch_sm<4>(a, grid, s);
+  } else {
+    const bool exact = p.d == 256 * nv;
+    switch (nv) {
+      case 1: rc = launch_k1<1, 16>(a, p.loss, exact, grid, s); break;
+      case 2: rc = launch_k1<2, 8>(a, p.loss, exact, grid, s); break;
+      case 4: rc = launch_k1<4, 4>(a, p.loss, exact, grid, s); break;
+      case 8: rc = launch_k1<8, 2>(a, p.loss, exact, grid, s); break;
+      default: rc = launch_k1<16, 1>(a, p.loss, exact, grid, s); break;
+    }
+  }
+  if (rc != HALP_OK) return rc;
+  RedArgs r;
+  r.partial_g = h.partial_g; r.partial_loss = h.partial_loss; r.w = h.buf.w; r.g = h.buf.g;
+  r.scales = h.buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = h.parts; r.lambda = p.lambda;
+  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 255) / 256, p.R), dim3(256), 0, s, r);
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace halp

@@ -1,0 +1,139 @@
+// Device-side building blocks shared by the HALP kernels (gfx950, wave64):
+// Philox4x32-10, the random-stream layout, wave reductions on DPP, and the two
+// quantizers of Sec. 3 "Quantization" in the forms the library's contract fixes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace halp {
+
+constexpr int kWave = 64;
+
+enum Purpose : uint32_t { kIdx = 0, kGamma = 1, kZround = 2, kReg = 3, kHround = 4 };
+
+struct U4 {
+  uint32_t x, y, z, w;
+};
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies
+// whose high halves are mixed with the neighbouring counter words and a Weyl
+// sequence of round keys.
+__device__ __forceinline__ U4 philox4x32_10(U4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c.x;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c.z;
+    U4 n;
+    n.x = (uint32_t)(p1 >> 32) ^ c.y ^ k0;
+    n.y = (uint32_t)p1;
+    n.z = (uint32_t)(p0 >> 32) ^ c.w ^ k1;
+    n.w = (uint32_t)p0;
+    c = n;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c;
+}
+
+// Block `blk` of the word stream of a purpose: counter (lo(blk), hi(blk), epoch, purpose).
+__device__ __forceinline__ U4 stream_block(uint64_t seed, uint32_t purpose, uint32_t epoch,
+                                           uint64_t blk) {
+  return philox4x32_10(U4{(uint32_t)blk, (uint32_t)(blk >> 32), epoch, purpose}, (uint32_t)seed,
+                       (uint32_t)(seed >> 32));
+}
+
+__device__ __forceinline__ uint32_t pick(const U4& v, uint32_t k) {
+  return k == 0 ? v.x : (k == 1 ? v.y : (k == 2 ? v.z : v.w));
+}
+
+// Block holding the rounding bits of coordinate group `gid` for the step pair (2s, 2s+1).
+__device__ __forceinline__ U4 zround_block(uint64_t seed, uint32_t epoch, uint32_t gid,
+                                           uint32_t s) {
+  return philox4x32_10(U4{gid, s, epoch, (uint32_t)kZround}, (uint32_t)seed,
+                       (uint32_t)(seed >> 32));
+}
+
+// ---- wave-wide sums --------------------------------------------------------
+// Four DPP steps fold each row of 16 lanes (quad swaps, half-row mirror, row
+// mirror); the four row totals are then read with v_readlane and added.
+
+template <typename T>
+__device__ __forceinline__ T dpp_quad_swap1(T v) {  // lanes 1,0,3,2
+  return __builtin_bit_cast(
+      T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+}
+template <typename T>
+__device__ __forceinline__ T dpp_quad_swap2(T v) {  // lanes 2,3,0,1
+  return __builtin_bit_cast(
+      T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
+}
+template <typename T>
+__device__ __forceinline__ T dpp_half_mirror(T v) {  // reverse within 8 lanes
+  return __builtin_bit_cast(
+      T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
+}
+template <typename T>
+__device__ __forceinline__ T dpp_row_mirror(T v) {  // reverse within 16 lanes
+  return __builtin_bit_cast(
+      T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ int wave_sum_i32(int v) {
+  v += dpp_quad_swap1(v);
+  v += dpp_quad_swap2(v);
+  v += dpp_half_mirror(v);
+  v += dpp_row_mirror(v);
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+
+__device__ __forceinline__ float wave_sum_f32(float v) {
+  v += dpp_quad_swap1(v);
+  v += dpp_quad_swap2(v);
+  v += dpp_half_mirror(v);
+  v += dpp_row_mirror(v);
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+  return (a + b) + (c + d);
+}
+
+__device__ __forceinline__ long long wave_sum_i64(long long v) {
+  // exact 64-bit sum: move both halves with the same DPP pattern, add as a pair
+  auto step = [](long long x, auto mv) {
+    const int lo = mv((int)(uint32_t)x), hi = mv((int)(x >> 32));
+    return x + (long long)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+  };
+  v = step(v, [](int t) { return dpp_quad_swap1(t); });
+  v = step(v, [](int t) { return dpp_quad_swap2(t); });
+  v = step(v, [](int t) { return dpp_half_mirror(t); });
+  v = step(v, [](int t) { return dpp_row_mirror(t); });
+  long long tot = 0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 16 * r);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(v >> 32), 16 * r);
+    tot += (long long)(((uint64_t)hi << 32) | lo);
+  }
+  return tot;
+}
+
+// ---- quantizers -------------------------------------------------------------
+
+// Real -> integer lattice: clamp(floor(x * inv_delta + rho)), rho = r32 / 2^32.
+// Multiplication and addition are rounded separately (no fused multiply-add).
+__device__ __forceinline__ long long quantize_real(double x, double inv_delta, uint32_t r32,
+                                                   double lo, double hi, bool* clamped) {
+  const double rho = __dmul_rn((double)r32, 0x1p-32);
+  const double q = __dmul_rn(x, inv_delta);
+  double f = floor(__dadd_rn(q, rho));
+  bool hit = false;
+  if (f < lo) { f = lo; hit = true; }
+  if (f > hi) { f = hi; hit = true; }
+  if (clamped) *clamped = hit;
+  return (long long)f;
+}
+
+}  // namespace halp

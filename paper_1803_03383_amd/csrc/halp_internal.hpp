@@ -1,0 +1,59 @@
+// Host-side context of a handle and the launchers each kernel file exports.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/halp.h"
+
+struct halp_handle {
+  halp_params p;
+  halp_buffers buf;
+  bool bound = false;
+  int device = 0;
+  int num_cus = 256;
+  // options
+  int inner_variant = 0;
+  bool timing = false;
+  bool count_clamps = true;
+  int fullgrad_blocks = 0;
+  // library-owned workspace of the gradient pass: per-workgroup partial sums
+  float* partial_g = nullptr;    // [R][parts][K*d]
+  double* partial_loss = nullptr;  // [R][parts]
+  int parts = 0;                 // workgroups per chain the workspace was sized for
+  size_t partial_g_bytes = 0;
+  int last_inner_variant = 0;
+  // timing: a ring of event quadruples, one per halp_epoch call since timing was switched on
+  static constexpr int kTimedEpochs = 32;
+  hipEvent_t ev[kTimedEpochs][4] = {};
+  int64_t timed = 0;
+};
+
+namespace halp {
+
+struct TraceBufs {
+  int64_t M = 0;
+  int64_t* idx = nullptr;
+  int64_t* D = nullptr;
+  double* beta = nullptr;
+  int32_t* gamma = nullptr;
+  int32_t* ztraj = nullptr;
+};
+
+// each returns HALP_OK or a HALP_ERR_* and launches nothing on error
+int launch_quantize_data(const halp_handle& h, hipStream_t s);
+int fullgrad_supported(const halp_params& p);
+int fullgrad_parts(const halp_handle& h);  // workgroups per chain for this shape
+int launch_full_gradient(const halp_handle& h, hipStream_t s);
+int launch_recenter(const halp_handle& h, uint32_t epoch, hipStream_t s);
+int inner_reg_supported(const halp_params& p);
+int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s);
+int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s);
+int launch_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
+                              int64_t count, uint32_t* out, hipStream_t s);
+int launch_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
+                             int32_t K, uint32_t* out, hipStream_t s);
+
+inline int hip_ok(hipError_t e) { return e == hipSuccess ? HALP_OK : HALP_ERR_HIP; }
+
+}  // namespace halp

@@ -1,0 +1,43 @@
+// Kernel arguments shared by the inner-loop kernels (Algorithm 4, inner `for t`).
+#pragma once
+
+#include <stdint.h>
+
+#include "halp_internal.hpp"
+
+namespace halp {
+
+struct InArgs {
+  const void* Xq;       // [Rd][N][ldxq] int8 / int16
+  const float* phi;     // [R][N][K]
+  const void* y;        // [Rd][N] float (+-1) for logistic; unused otherwise
+  const void* h;        // [R][K][d] int16 / int32
+  void* z;              // [R][K][d] int8 / int16
+  float* w;             // [R][K][d]
+  const double* scales; // [R][8]
+  uint64_t* counters;   // [R][4]
+  int64_t N, ldxq, T;
+  int64_t xq_chain_stride, y_chain_stride;  // elements; 0 when chains share the data
+  int d, K, B, loss;
+  double alpha, lambda, delta_d;
+  uint64_t seed;
+  uint32_t epoch;
+  int count_clamps;
+  TraceBufs tr;
+};
+
+inline InArgs make_inner_args(const halp_handle& h, uint32_t epoch) {
+  const halp_params& p = h.p;
+  InArgs a;
+  a.Xq = h.buf.Xq; a.phi = h.buf.phi; a.y = h.buf.y; a.h = h.buf.h; a.z = h.buf.z; a.w = h.buf.w;
+  a.scales = h.buf.scales; a.counters = h.buf.counters;
+  a.N = p.N; a.ldxq = h.buf.ldxq; a.T = p.T;
+  a.xq_chain_stride = p.share_data ? 0 : p.N * h.buf.ldxq;
+  a.y_chain_stride = p.share_data ? 0 : p.N;
+  a.d = p.d; a.K = p.K; a.B = p.B; a.loss = p.loss;
+  a.alpha = p.alpha; a.lambda = p.lambda; a.delta_d = p.delta_d;
+  a.seed = p.seed; a.epoch = epoch; a.count_clamps = h.count_clamps ? 1 : 0;
+  return a;
+}
+
+}  // namespace halp

@@ -1,0 +1,217 @@
+// Inner loop of Algorithm 4 (LM-HALP), general form: any loss, K classes,
+// minibatch B, 8 or 16 bits, optional per-step trace.  One workgroup per chain;
+// z and h~ live in LDS as 32-bit integers, all integer arithmetic is exact in
+// 64 bits, the scalar path (beta, gamma) is fp64.  This kernel is the fallback
+// for shapes the register-resident kernel does not take and the one the debug
+// trace runs on; it favours simplicity over speed.
+#include "halp_device.hpp"
+#include "inner_args.hpp"
+
+namespace halp {
+namespace {
+
+__device__ __forceinline__ double logistic_dl(double a, double y) {
+  // l'(a) for l(a) = log(1 + exp(-y a))
+  return __ddiv_rn(-y, __dadd_rn(1.0, exp(__dmul_rn(y, a))));
+}
+
+template <int BITS>
+__global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
+  using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
+  using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
+  constexpr int CPG = 64 / BITS;  // coordinates sharing 64 rounding bits
+  const int chain = blockIdx.x;
+  const int tid = threadIdx.x, NT = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6, NW = NT >> 6;
+  const int d = a.d, K = a.K, B = a.B;
+  const int n = K * d;
+  const int G = (d + CPG - 1) / CPG;
+  const int64_t N = a.N, ldxq = a.ldxq;
+  const XT* __restrict__ Xq = reinterpret_cast<const XT*>(a.Xq) + (int64_t)chain * a.xq_chain_stride;
+  const float* __restrict__ phi = a.phi + (int64_t)chain * N * K;
+  const float* __restrict__ y =
+      reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
+  const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + (int64_t)chain * n;
+  XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + (int64_t)chain * n;
+  float* __restrict__ wg = a.w + (int64_t)chain * n;
+  const double* sc = a.scales + (int64_t)chain * 8;
+  uint64_t* cnt_out = a.counters + (int64_t)chain * 4;
+  const uint64_t seed = a.seed + (uint64_t)chain;
+
+  if (sc[7] != 0.0) {  // converged or unusable gradient: the epoch is a no-op
+    if (tid < 4) cnt_out[tid] = 0;
+    return;
+  }
+
+  extern __shared__ unsigned char smem_raw[];
+  int32_t* zs = reinterpret_cast<int32_t*>(smem_raw);
+  int32_t* hs = zs + n;
+  long long* idxs = reinterpret_cast<long long*>(hs + n + (n & 1));
+  long long* Ds = idxs + B;
+  int32_t* gams = reinterpret_cast<int32_t*>(Ds + (int64_t)B * K);
+  __shared__ unsigned long long s_cnt[3];
+  __shared__ int s_clambda;
+
+  for (int k = tid; k < n; k += NT) {
+    zs[k] = (int32_t)zg[k];
+    hs[k] = (int32_t)hg[k];
+  }
+  if (tid < 3) s_cnt[tid] = 0;
+  if (tid == 0) s_clambda = 0;
+  __syncthreads();
+
+  const double delta_m = sc[0], inv_s = sc[5];
+  const double dscale = __dmul_rn(a.delta_d, delta_m);
+  const double aB = __ddiv_rn(a.alpha, (double)B);
+  const double qmaxd = (double)((1 << (BITS - 1)) - 1), qmind = -(double)(1 << (BITS - 1));
+  const long long qmax = (1 << (BITS - 1)) - 1, qmin = -(1 << (BITS - 1));
+  unsigned long long my_zclamp = 0, my_gclamp = 0;
+
+  for (int64_t t = 0; t < a.T; ++t) {
+    const bool rec = t < a.tr.M;
+    // sample i uniformly (with replacement)
+    if (tid < B) {
+      const uint64_t nn = (uint64_t)t * (uint64_t)B + (uint64_t)tid;
+      const uint32_t r = pick(stream_block(seed, kIdx, a.epoch, nn >> 2), (uint32_t)(nn & 3));
+      const long long i = (long long)(((uint64_t)r * (uint64_t)N) >> 32);
+      idxs[tid] = i;
+      if (rec && a.tr.idx) a.tr.idx[((int64_t)chain * a.tr.M + t) * B + tid] = i;
+    }
+    if (tid == 0 && a.lambda > 0) {  // c_lambda = Q_(2^-b, b)(alpha lambda)
+      const uint32_t r = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
+      const int cl = (int)quantize_real(__dmul_rn(a.alpha, a.lambda), (double)(1 << BITS), r, 0.0,
+                                        qmaxd, nullptr);
+      s_clambda = cl;
+      if (cl != 0) s_cnt[2] += 1;
+    }
+    __syncthreads();
+    // integer dot products x_i^T z, one (row, class) pair per wave at a time
+    for (int pr = wave; pr < B * K; pr += NW) {
+      const int m = pr / K, c = pr % K;
+      const XT* xr = Xq + idxs[m] * ldxq;
+      long long acc = 0;
+      for (int j = lane; j < d; j += 64) acc += (long long)xr[j] * (long long)zs[c * d + j];
+      acc = wave_sum_i64(acc);
+      if (lane == 0) {
+        Ds[pr] = acc;
+        if (rec && a.tr.D) a.tr.D[((int64_t)chain * a.tr.M + t) * B * K + pr] = acc;
+      }
+    }
+    __syncthreads();
+    // beta = (alpha/B)(l'(phi_i + x_i^T z) - l'(phi_i)); gamma = Q_(delta_s, b)(beta)
+    if (tid < B) {
+      const int m = tid;
+      const long long i = idxs[m];
+      double mx0 = 0, mx1 = 0, s0 = 0, s1 = 0;
+      if (a.loss == HALP_LOSS_SOFTMAX) {
+        mx0 = (double)phi[i * K];
+        mx1 = __dadd_rn(mx0, __dmul_rn(dscale, (double)Ds[m * K]));
+        for (int c = 1; c < K; ++c) {
+          const double a0 = (double)phi[i * K + c];
+          const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[m * K + c]));
+          if (a0 > mx0) mx0 = a0;
+          if (a1 > mx1) mx1 = a1;
+        }
+        for (int c = 0; c < K; ++c) {
+          const double a0 = (double)phi[i * K + c];
+          const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[m * K + c]));
+          s0 = __dadd_rn(s0, exp(__dadd_rn(a0, -mx0)));
+          s1 = __dadd_rn(s1, exp(__dadd_rn(a1, -mx1)));
+        }
+      }
+      for (int c = 0; c < K; ++c) {
+        const double delta = __dmul_rn(dscale, (double)Ds[m * K + c]);
+        double diff;
+        if (a.loss == HALP_LOSS_SQUARED) {
+          diff = delta;
+        } else if (a.loss == HALP_LOSS_LOGISTIC) {
+          const double a0 = (double)phi[i];
+          const double yi = (double)y[i];
+          diff = __dadd_rn(logistic_dl(__dadd_rn(a0, delta), yi), -logistic_dl(a0, yi));
+        } else {
+          const double a0 = (double)phi[i * K + c];
+          const double a1 = __dadd_rn(a0, delta);
+          const double p0 = __ddiv_rn(exp(__dadd_rn(a0, -mx0)), s0);
+          const double p1 = __ddiv_rn(exp(__dadd_rn(a1, -mx1)), s1);
+          diff = __dadd_rn(p1, -p0);
+        }
+        const double beta = __dmul_rn(aB, diff);
+        const uint64_t nn = ((uint64_t)t * (uint64_t)B + (uint64_t)m) * (uint64_t)K + (uint64_t)c;
+        const uint32_t r = pick(stream_block(seed, kGamma, a.epoch, nn >> 2), (uint32_t)(nn & 3));
+        bool hit = false;
+        const int gq = (int)quantize_real(beta, inv_s, r, qmind, qmaxd, &hit);
+        gams[m * K + c] = gq;
+        if (hit) my_gclamp += 1;
+        if (rec) {
+          const int64_t o = ((int64_t)chain * a.tr.M + t) * B * K + m * K + c;
+          if (a.tr.beta) a.tr.beta[o] = beta;
+          if (a.tr.gamma) a.tr.gamma[o] = gq;
+        }
+      }
+    }
+    __syncthreads();
+    // u = z - gamma x_i - h~ (- c_lambda z) in (delta_i, 2b); z = Q_(delta_m, b)(u)
+    const long long cl = s_clambda;
+    for (int u = tid; u < K * G; u += NT) {
+      const int c = u / G, grp = u % G;
+      const U4 r = zround_block(seed, a.epoch, (uint32_t)u, (uint32_t)(t >> 1));
+      const uint64_t bits = (t & 1) ? (((uint64_t)r.w << 32) | r.z) : (((uint64_t)r.y << 32) | r.x);
+      for (int e = 0; e < CPG; ++e) {
+        const int j = grp * CPG + e;
+        if (j >= d) break;
+        const int k = c * d + j;
+        const long long zk = zs[k];
+        long long v = -(long long)hs[k] - cl * zk;
+        for (int m = 0; m < B; ++m) v -= (long long)gams[m * K + c] * (long long)Xq[idxs[m] * ldxq + j];
+        const long long rb = (long long)((bits >> (e * BITS)) & ((1ull << BITS) - 1ull));
+        long long zn = zk + ((v + rb) >> BITS);  // arithmetic shift: floor
+        if (zn > qmax) { zn = qmax; my_zclamp += 1; }
+        if (zn < qmin) { zn = qmin; my_zclamp += 1; }
+        zs[k] = (int32_t)zn;
+      }
+    }
+    __syncthreads();
+    if (rec && a.tr.ztraj) {
+      int32_t* zt = a.tr.ztraj + ((int64_t)chain * a.tr.M + t) * n;
+      for (int k = tid; k < n; k += NT) zt[k] = zs[k];
+    }
+  }
+
+  // w~ <- w~ + delta_m z (option I), and hand z out
+  for (int k = tid; k < n; k += NT) {
+    const int32_t zk = zs[k];
+    zg[k] = (XT)zk;
+    wg[k] = (float)__dadd_rn((double)wg[k], __dmul_rn(delta_m, (double)zk));
+  }
+  if (my_zclamp) atomicAdd(&s_cnt[0], my_zclamp);
+  if (my_gclamp) atomicAdd(&s_cnt[1], my_gclamp);
+  __syncthreads();
+  if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
+}
+
+}  // namespace
+
+int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s) {
+  const halp_params& p = h.p;
+  InArgs a = make_inner_args(h, epoch);
+  a.tr = tr;
+  const int64_t n = (int64_t)p.K * p.d;
+  const size_t smem = (size_t)(2 * n + (n & 1)) * 4 + (size_t)p.B * 8 + (size_t)p.B * p.K * 12;
+  if (smem > 150 * 1024 || p.B > 512) return HALP_ERR_UNSUPPORTED;
+  const int threads = 512;
+  hipError_t e;
+  if (p.b == 8) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(inner_generic_kernel<8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return HALP_ERR_HIP;
+    hipLaunchKernelGGL(inner_generic_kernel<8>, dim3(p.R), dim3(threads), smem, s, a);
+  } else {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(inner_generic_kernel<16>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return HALP_ERR_HIP;
+    hipLaunchKernelGGL(inner_generic_kernel<16>, dim3(p.R), dim3(threads), smem, s, a);
+  }
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace halp

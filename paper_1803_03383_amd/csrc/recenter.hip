@@ -1,0 +1,196 @@
+// Bit centering (Sec. 4; the re-scale lines of Algorithm 4), the one-off data
+// quantization into (delta_d, b), and two debug kernels that expose the random
+// streams.
+#include "halp_device.hpp"
+#include "halp_internal.hpp"
+
+namespace halp {
+namespace {
+
+struct RcArgs {
+  const float* g;
+  void* h;
+  void* z;
+  double* scales;
+  int n;  // K*d
+  int b;
+  double alpha, mu, delta_d;
+  uint64_t seed;
+  uint32_t epoch;
+};
+
+// One workgroup per chain.  ||g~||^2 is accumulated by a single lane in index
+// order in fp64 (every square of an fp32 value is exact in fp64), so the scales
+// are the same bits whatever the launch shape; K*d is at most a few thousand
+// and this runs once per epoch.
+template <int BITS>
+__global__ __launch_bounds__(256) void recenter_kernel(RcArgs a) {
+  using ZT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
+  using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
+  const int chain = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float* __restrict__ g = a.g + (int64_t)chain * a.n;
+  HT* __restrict__ h = reinterpret_cast<HT*>(a.h) + (int64_t)chain * a.n;
+  ZT* __restrict__ z = reinterpret_cast<ZT*>(a.z) + (int64_t)chain * a.n;
+  double* sc = a.scales + (int64_t)chain * 8;
+
+  constexpr int kChunk = 4096;
+  __shared__ float stage[kChunk];
+  __shared__ double s_inv_i;
+  __shared__ int s_status;
+  double ss = 0.0;
+  for (int base = 0; base < a.n; base += kChunk) {
+    const int m = min(kChunk, a.n - base);
+    for (int k = tid; k < m; k += 256) stage[k] = g[base + k];
+    __syncthreads();
+    if (tid == 0) {
+      for (int k = 0; k < m; ++k) {
+        const double v = (double)stage[k];
+        ss = __dadd_rn(ss, __dmul_rn(v, v));
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const double nrm = __dsqrt_rn(ss);
+    const double qmax = (double)((1 << (BITS - 1)) - 1);
+    int status = 0;
+    double delta_m = 0, delta_i = 0, delta_s = 0, inv_i = 0, inv_s = 0;
+    if (!isfinite(nrm)) {
+      status = -1;
+    } else if (nrm == 0.0) {
+      status = 1;
+    } else {
+      delta_m = __ddiv_rn(nrm, __dmul_rn(a.mu, qmax));
+      delta_i = __dmul_rn(delta_m, BITS == 8 ? 0x1p-8 : 0x1p-16);
+      delta_s = __ddiv_rn(delta_i, a.delta_d);
+      inv_i = __ddiv_rn(1.0, delta_i);
+      inv_s = __ddiv_rn(1.0, delta_s);
+      if (!(delta_i > 0) || !isfinite(inv_i) || !isfinite(inv_s)) {
+        status = -1;
+        delta_m = delta_i = delta_s = inv_i = inv_s = 0;
+      }
+    }
+    sc[0] = delta_m; sc[1] = delta_i; sc[2] = delta_s; sc[3] = nrm;
+    sc[4] = inv_i; sc[5] = inv_s; sc[7] = (double)status;
+    s_inv_i = inv_i;
+    s_status = status;
+  }
+  __syncthreads();
+  const double inv_i = s_inv_i;
+  const bool live = s_status == 0;
+  const double hmax = BITS == 8 ? 32767.0 : 2147483647.0;
+  const double hmin = BITS == 8 ? -32768.0 : -2147483648.0;
+  const int nblk = (a.n + 3) / 4;
+  for (int blk = tid; blk < nblk; blk += 256) {
+    U4 r = U4{0, 0, 0, 0};
+    if (live) r = stream_block(a.seed + (uint64_t)chain, kHround, a.epoch, (uint64_t)blk);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int k = 4 * blk + e;
+      if (k < a.n) {
+        long long q = 0;
+        if (live)  // h~ = Q_(delta_i, 2b)(alpha g~)
+          q = quantize_real(__dmul_rn(a.alpha, (double)g[k]), inv_i, pick(r, e), hmin, hmax, nullptr);
+        h[k] = (HT)q;
+        z[k] = (ZT)0;  // z_{k,0} = Q(0) = 0
+      }
+    }
+  }
+}
+
+struct QdArgs {
+  const float* X;
+  void* Xq;
+  int64_t rows, ldx, ldxq;
+  int d;
+  double delta_d;
+};
+
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_data_kernel(QdArgs a) {
+  using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
+  const double qmax = (double)((1 << (BITS - 1)) - 1);
+  XT* __restrict__ Xq = reinterpret_cast<XT*>(a.Xq);
+  for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+    const float* xr = a.X + row * a.ldx;
+    XT* qr = Xq + row * a.ldxq;
+    for (int64_t j = threadIdx.x; j < a.ldxq; j += 256) {
+      double q = 0.0;
+      if (j < a.d) {
+        q = rint(__ddiv_rn((double)xr[j], a.delta_d));  // ties to even
+        q = fmin(fmax(q, -qmax), qmax);
+      }
+      qr[j] = (XT)(int)q;
+    }
+  }
+}
+
+__global__ void debug_words_kernel(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
+                                   int64_t count, uint32_t* out) {
+  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= count) return;
+  const uint64_t n = n0 + (uint64_t)k;
+  const U4 r = stream_block(seed, purpose, epoch, n >> 2);
+  out[k] = pick(r, (uint32_t)(n & 3));
+}
+
+__global__ void debug_zround_kernel(uint64_t seed, uint32_t epoch, uint64_t t, int d, int b, int K,
+                                    uint32_t* out) {
+  const int cpg = 64 / b;
+  const int G = (d + cpg - 1) / cpg;
+  const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= (int64_t)K * G) return;
+  const int c = (int)(u / G), grp = (int)(u % G);
+  const U4 r = zround_block(seed, epoch, (uint32_t)u, (uint32_t)(t >> 1));
+  const uint32_t w0 = (t & 1) ? r.z : r.x, w1 = (t & 1) ? r.w : r.y;
+  const uint64_t bits = ((uint64_t)w1 << 32) | w0;
+  for (int e = 0; e < cpg; ++e) {
+    const int j = grp * cpg + e;
+    if (j < d) out[(int64_t)c * d + j] = (uint32_t)((bits >> (e * b)) & ((1ull << b) - 1ull));
+  }
+}
+
+}  // namespace
+
+int launch_recenter(const halp_handle& h, uint32_t epoch, hipStream_t s) {
+  const halp_params& p = h.p;
+  RcArgs a;
+  a.g = h.buf.g; a.h = h.buf.h; a.z = h.buf.z; a.scales = h.buf.scales;
+  a.n = p.K * p.d; a.b = p.b; a.alpha = p.alpha; a.mu = p.mu; a.delta_d = p.delta_d;
+  a.seed = p.seed; a.epoch = epoch;
+  if (p.b == 8) hipLaunchKernelGGL(recenter_kernel<8>, dim3(p.R), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(recenter_kernel<16>, dim3(p.R), dim3(256), 0, s, a);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_quantize_data(const halp_handle& h, hipStream_t s) {
+  const halp_params& p = h.p;
+  QdArgs a;
+  a.X = h.buf.X; a.Xq = h.buf.Xq;
+  a.rows = (p.share_data ? 1 : (int64_t)p.R) * p.N;
+  a.ldx = h.buf.ldx; a.ldxq = h.buf.ldxq; a.d = p.d; a.delta_d = p.delta_d;
+  const int grid = (int)(a.rows < 65536 ? a.rows : 65536);
+  if (p.b == 8) hipLaunchKernelGGL(quantize_data_kernel<8>, dim3(grid), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(quantize_data_kernel<16>, dim3(grid), dim3(256), 0, s, a);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
+                              int64_t count, uint32_t* out, hipStream_t s) {
+  if (count == 0) return HALP_OK;
+  hipLaunchKernelGGL(debug_words_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+                     seed, purpose, epoch, n0, count, out);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
+                             int32_t K, uint32_t* out, hipStream_t s) {
+  const int cpg = 64 / b;
+  const int64_t units = (int64_t)K * ((d + cpg - 1) / cpg);
+  hipLaunchKernelGGL(debug_zround_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
+                     seed, epoch, t, d, b, K, out);
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace halp

@@ -1,0 +1,340 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, on the
+same seeded inputs.  Integer work (random streams, quantized data, h~, dot
+products, gamma, the z trajectory, counters) must match bit for bit; fp32
+margins / gradients / losses within rel-L2 1e-5.  Inputs of every GPU call come
+from the seeded generators or from the oracle -- never the other way round."""
+import numpy as np
+import pytest
+import torch
+
+import halp_inputs as inp
+import paper_1803_03383_amd as hp
+from oracle import ref
+from gpu_util import GpuProblem, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5  # rel-L2 for fp32 outputs of the full-gradient pass
+
+
+# ------------------------------------------------------------ random streams
+
+def test_stream_words_match_oracle():
+    seed = 0x9E3779B97F4A7C15
+    for purpose, epoch, n0, cnt in [(0, 0, 0, 1000), (1, 7, 4093, 777), (3, 2 ** 32 - 1, 2 ** 34 + 1, 64),
+                                    (4, 3, 5, 129)]:
+        got = hp.debug_stream_words(seed, purpose, epoch, n0, cnt).cpu().numpy().view(np.uint32)
+        want = np.array([ref.stream_word(seed, purpose, epoch, n0 + k) for k in range(cnt)], np.uint32)
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("b,d,K", [(8, 64, 1), (8, 100, 3), (16, 50, 2), (16, 4096, 1)])
+def test_zround_bits_match_oracle(b, d, K):
+    seed, epoch = 12345, 9
+    for t in (0, 1, 2, 2 ** 20 + 1):
+        got = hp.debug_zround_bits(seed, epoch, t, d, b, K).cpu().numpy()
+        cols = range(d) if d <= 128 else list(range(0, d, 97)) + [d - 1]
+        for c in range(K):
+            for j in cols:
+                assert got[c, j] == ref.zround_bits(seed, epoch, t, d, b, c, j)
+
+
+# ------------------------------------------------------------ data quantization
+
+@pytest.mark.parametrize("b", [8, 16])
+def test_quantize_data_bit_exact(b):
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((2, 301, 100)).astype(np.float32)
+    X[0, 0, :5] = [0.5, 1.5, 2.5, -0.5, 1e9]  # ties and clamping
+    dd = 1.0 if b == 8 else float(np.abs(X[:, 1:]).max()) / (2 ** 15 - 1)
+    y = np.zeros((2, 301), np.float32)
+    P = GpuProblem(X, None, y, R=2, b=b, delta_d=dd)
+    P.h.quantize_data()
+    torch.cuda.synchronize()
+    got = P.Xq.cpu().numpy()
+    want = ref.quantize_data(X, dd, b)
+    assert np.array_equal(got[..., :100], want)
+    assert not got[..., 100:].any()  # padding columns are zero
+
+
+# ------------------------------------------------------------ full gradient
+
+FG_CASES = [
+    # loss, N, d, K, R, lam
+    (hp.LOSS_SQUARED, 1000, 64, 1, 1, 0.0),
+    (hp.LOSS_SQUARED, 3001, 512, 1, 2, 0.0),
+    (hp.LOSS_SQUARED, 777, 1000, 1, 1, 1e-3),
+    (hp.LOSS_SQUARED, 301, 4096, 1, 1, 0.0),
+    (hp.LOSS_SQUARED, 129, 2048, 1, 3, 0.0),
+    (hp.LOSS_LOGISTIC, 2500, 1024, 1, 1, 1e-5),
+    (hp.LOSS_LOGISTIC, 403, 4096, 1, 2, 1e-5),
+    (hp.LOSS_LOGISTIC, 5, 7 * 4, 1, 1, 0.0),
+    (hp.LOSS_SOFTMAX, 1500, 784, 10, 1, 1e-4),
+    (hp.LOSS_SOFTMAX, 333, 100, 3, 2, 1e-4),
+    (hp.LOSS_SOFTMAX, 64, 257, 16, 1, 0.0),
+]
+
+
+def _make_data(loss, N, d, K, seed):
+    if loss == hp.LOSS_SQUARED:
+        X, y, _ = inp.linreg(N, d, seed=seed, x_var="inv_d", noise=0.1)
+    elif loss == hp.LOSS_LOGISTIC:
+        X, y, _ = inp.logistic(N, d, seed=seed)
+    else:
+        X, y, _ = inp.softmax_sparse(N, d, K, seed=seed)
+    return X, y
+
+
+@pytest.mark.parametrize("loss,N,d,K,R,lam", FG_CASES)
+def test_full_gradient_matches_oracle(loss, N, d, K, R, lam):
+    rng = np.random.default_rng(7)
+    Xs, ys = zip(*[_make_data(loss, N, d, K, seed=10 + r) for r in range(R)])
+    X, y = np.stack(Xs), np.stack(ys)
+    w0 = (rng.standard_normal((R, K, d)) * (1.0 if loss != hp.LOSS_SOFTMAX else 0.3)).astype(np.float32)
+    P = GpuProblem(X, None, y, K=K, R=R, loss=loss, lam=lam, w0=w0)
+    P.h.full_gradient()
+    phi, g, sc = P.get("phi"), P.get("g"), P.get("scales")
+    for r in range(R):
+        prob = ref.make_problem(N, d, K=K, loss=loss, lam=lam)
+        phi_r, g_r, loss_r = ref.full_gradient(prob, X[r], y[r], w0[r])
+        assert rel_l2(phi[r], phi_r) <= TOL
+        assert rel_l2(g[r], g_r) <= TOL
+        assert abs(sc[r, 6] - loss_r) <= TOL * abs(loss_r)
+    # a second run gives the same bits (fixed-order reduction, no atomics)
+    P.h.full_gradient()
+    assert np.array_equal(P.get("g"), g) and np.array_equal(P.get("phi"), phi)
+
+
+def test_full_gradient_shared_data_and_block_counts():
+    X, y = _make_data(hp.LOSS_SQUARED, 2000, 512, 1, seed=3)
+    rng = np.random.default_rng(1)
+    w0 = rng.standard_normal((3, 1, 512)).astype(np.float32)
+    P = GpuProblem(X, None, y, R=3, share_data=True, w0=w0)
+    outs = []
+    for blocks in (0, 1, 7, 64):
+        P.h.set_option(hp.OPT_FULLGRAD_BLOCKS, blocks)
+        P.h.full_gradient()
+        outs.append(P.get("g"))
+    prob = ref.make_problem(2000, 512)
+    for r in range(3):
+        _, g_r, _ = ref.full_gradient(prob, X, y, w0[r])
+        for g in outs:
+            assert rel_l2(g[r], g_r) <= TOL
+
+
+# ------------------------------------------------------------ bit centering
+
+@pytest.mark.parametrize("b,K,d,R", [(8, 1, 64, 1), (8, 10, 784, 1), (16, 1, 4096, 2), (16, 3, 50, 2),
+                                     (8, 1, 5000, 1)])
+def test_recenter_bit_exact(b, K, d, R):
+    rng = np.random.default_rng(b + d)
+    g = (rng.standard_normal((R, K, d)) * 10.0 ** rng.uniform(-6, 1)).astype(np.float32)
+    X = np.zeros((R, 4, d), np.float32)
+    loss = hp.LOSS_SOFTMAX if K > 1 else hp.LOSS_SQUARED
+    yz = np.zeros((R, 4), np.int32 if K > 1 else np.float32)
+    P = GpuProblem(X, None, yz, K=K, R=R, loss=loss, b=b, alpha=0.037, mu=2.5, delta_d=0.0123, seed=77)
+    P.put("g", g)
+    P.st["z"].fill_(5)
+    P.h.recenter(11)
+    sc, h, z = P.get("scales"), P.get("h"), P.get("z")
+    for r in range(R):
+        prob = ref.make_problem(4, d, K=K, loss=loss, b=b, alpha=0.037, mu=2.5, delta_d=0.0123,
+                                seed=77 + r)
+        s_r, h_r, _ = ref.recenter(prob, g[r], 11)
+        for k in (0, 1, 2, 3, 4, 5, 7):
+            assert sc[r, k] == s_r[k], (k, sc[r, k], s_r[k])
+        assert np.array_equal(h[r].astype(np.int64), h_r)
+        assert not z[r].any()
+
+
+def test_recenter_flags_zero_and_nonfinite_gradients():
+    X = np.zeros((3, 4, 16), np.float32)
+    P = GpuProblem(X, None, np.zeros((3, 4), np.float32), R=3, T=5)
+    g = np.zeros((3, 1, 16), np.float32)
+    g[1, 0, 3] = np.inf
+    g[2, 0, 0] = 1.0
+    P.put("g", g)
+    P.h.recenter(0)
+    sc = P.get("scales")
+    assert sc[0, 7] == 1.0 and sc[1, 7] == -1.0 and sc[2, 7] == 0.0
+    assert not P.get("h")[:2].any()
+    # flagged chains are left alone by the inner loop
+    w_before = P.get("w").copy()
+    P.h.inner_loop(0)
+    assert np.array_equal(P.get("w")[:2], w_before[:2])
+    st = P.h.get_stats(0)
+    assert st.status == 1
+    assert P.h.get_stats(1).status == -1
+
+
+# ------------------------------------------------------------ inner loop
+
+def _inner_case(loss, N, d, K, B, b, lam, R, T, seed, alpha=0.02, mu=0.5):
+    """Oracle-made inputs of the inner loop for R chains."""
+    Xqs, phis, hs, scs, ws = [], [], [], [], []
+    rng = np.random.default_rng(seed)
+    data = [_make_data(loss, N, d, K, seed=seed + r) for r in range(R)]
+    Xs, ys = [x for x, _ in data], [y for _, y in data]
+    dd = inp.default_delta_d(np.stack(Xs), b)  # one data scale for all chains
+    for r in range(R):
+        X, y = Xs[r], ys[r]
+        Xq = ref.quantize_data(X, dd, b)
+        w = (0.1 * rng.standard_normal((K, d))).astype(np.float32)
+        prob = ref.make_problem(N, d, K=K, loss=loss, b=b, B=B, alpha=alpha, mu=mu, lam=lam,
+                                delta_d=dd, seed=1000 + seed + r)
+        phi, g, _ = ref.full_gradient(prob, X, y, w)
+        s, h, _ = ref.recenter(prob, g.astype(np.float32), 3)
+        Xqs.append(Xq); phis.append(phi.astype(np.float32))
+        hs.append(h); scs.append(s); ws.append(w)
+    return dict(X=np.stack(Xs), Xq=np.stack(Xqs), y=np.stack(ys), phi=np.stack(phis),
+                h=np.stack(hs), scales=np.stack(scs), w=np.stack(ws), dd=dd,
+                mk=lambda r: ref.make_problem(N, d, K=K, loss=loss, b=b, B=B, alpha=alpha, mu=mu,
+                                              lam=lam, delta_d=dd, seed=1000 + seed + r))
+
+
+def _run_inner(case, loss, K, B, b, lam, R, T, seed, variant, alpha=0.02, mu=0.5, trace=0):
+    N, d = case["X"].shape[1:]
+    P = GpuProblem(case["X"], case["Xq"], case["y"], K=K, R=R, loss=loss, b=b, B=B, T=T, alpha=alpha,
+                   mu=mu, lam=lam, delta_d=case["dd"], seed=1000 + seed, w0=case["w"])
+    P.put("phi", case["phi"]); P.put("h", case["h"]); P.put("scales", case["scales"])
+    P.st["z"].zero_()
+    P.h.set_option(hp.OPT_INNER_VARIANT, variant)
+    return P
+
+
+INNER_REG_CASES = [
+    # loss, N, d, b, lam, R, T, mu
+    (hp.LOSS_SQUARED, 1000, 64, 8, 0.0, 1, 2000, 0.5),      # one partly filled wave
+    (hp.LOSS_SQUARED, 700, 512, 8, 0.0, 3, 1003, 0.05),     # one full wave, T not a multiple of 8
+    (hp.LOSS_SQUARED, 600, 1024, 8, 0.0, 2, 700, 0.02),     # two waves
+    (hp.LOSS_SQUARED, 300, 100, 8, 1e-2, 1, 900, 0.5),      # ragged last group, L2 draws
+    (hp.LOSS_SQUARED, 200, 4096, 8, 0.0, 1, 300, 0.01),     # four waves, two groups per lane
+    (hp.LOSS_LOGISTIC, 900, 512, 8, 1e-3, 2, 1500, 0.05),
+    (hp.LOSS_LOGISTIC, 500, 256, 16, 1e-4, 2, 800, 0.05),
+    (hp.LOSS_SQUARED, 400, 50, 16, 0.0, 1, 1000, 0.5),      # ragged, 16 bits
+    (hp.LOSS_SQUARED, 300, 2048, 16, 0.0, 1, 300, 0.02),
+    (hp.LOSS_SQUARED, 50, 64, 8, 0.0, 1, 1, 0.5),           # a single step
+    (hp.LOSS_SQUARED, 50, 64, 8, 0.0, 1, 0, 0.5),           # no step at all
+    (hp.LOSS_SQUARED, 64, 64, 8, 0.0, 1, 600, 500.0),       # box far too small: z saturates
+]
+
+
+@pytest.mark.parametrize("variant", [2, 1])
+@pytest.mark.parametrize("loss,N,d,b,lam,R,T,mu", INNER_REG_CASES)
+def test_inner_loop_bit_exact(loss, N, d, b, lam, R, T, mu, variant):
+    seed = 40 + d + T
+    case = _inner_case(loss, N, d, 1, 1, b, lam, R, T, seed, mu=mu)
+    P = _run_inner(case, loss, 1, 1, b, lam, R, T, seed, variant, mu=mu)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    assert P.h.get_stats(0).inner_variant == variant
+    for r in range(R):
+        out = ref.inner_loop(case["mk"](r), case["Xq"][r], case["phi"][r], case["y"][r],
+                             case["h"][r], case["scales"][r], 3, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        w_r = ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r])
+        assert np.array_equal(w[r], w_r)
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    if mu > 100:
+        assert cnt[0, 0] > 0  # the saturating case really saturates
+
+
+GENERIC_CASES = [
+    # loss, N, d, K, B, b, lam, R, T
+    (hp.LOSS_SOFTMAX, 400, 784, 10, 1, 8, 1e-4, 1, 300),
+    (hp.LOSS_SOFTMAX, 300, 100, 3, 2, 16, 1e-3, 2, 400),
+    (hp.LOSS_LOGISTIC, 500, 256, 1, 8, 16, 1e-5, 1, 300),
+    (hp.LOSS_SQUARED, 400, 64, 1, 64, 8, 0.0, 2, 200),
+    (hp.LOSS_LOGISTIC, 300, 4096, 1, 64, 16, 1e-5, 1, 40),
+]
+
+
+@pytest.mark.parametrize("loss,N,d,K,B,b,lam,R,T", GENERIC_CASES)
+def test_inner_loop_generic_trace_bit_exact(loss, N, d, K, B, b, lam, R, T):
+    seed = 90 + d + B
+    case = _inner_case(loss, N, d, K, B, b, lam, R, T, seed, mu=0.05)
+    P = _run_inner(case, loss, K, B, b, lam, R, T, seed, 0, mu=0.05)
+    M = min(T, 50)
+    tr = dict(idx=torch.zeros((R, M, B), dtype=torch.int64, device="cuda"),
+              D=torch.zeros((R, M, B, K), dtype=torch.int64, device="cuda"),
+              beta=torch.zeros((R, M, B, K), dtype=torch.float64, device="cuda"),
+              gamma=torch.zeros((R, M, B, K), dtype=torch.int32, device="cuda"),
+              ztraj=torch.zeros((R, M, K, d), dtype=torch.int32, device="cuda"))
+    P.h.inner_loop_trace(3, M, **tr)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    for r in range(R):
+        out = ref.inner_loop(case["mk"](r), case["Xq"][r], case["phi"][r], case["y"][r],
+                             case["h"][r], case["scales"][r], 3, T, trace_steps=M)
+        assert np.array_equal(tr["idx"][r].cpu().numpy(), out["idx"])
+        assert np.array_equal(tr["D"][r].cpu().numpy(), out["D"])
+        bg, bo = tr["beta"][r].cpu().numpy(), out["beta"]
+        assert np.all(np.abs(bg - bo) <= 1e-12 * np.abs(bo).max() + 1e-9 * np.abs(bo))
+        assert np.array_equal(tr["gamma"][r].cpu().numpy(), out["gamma"])
+        assert np.array_equal(tr["ztraj"][r].cpu().numpy(), out["ztraj"])
+        assert np.array_equal(z[r].astype(np.int32), out["z"])
+        assert np.array_equal(w[r], ref.apply_offset(case["mk"](r), case["scales"][r], out["z"],
+                                                     case["w"][r]))
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+
+
+# ------------------------------------------------------------ whole epochs
+
+def test_epoch_bit_exact_when_fp32_sums_are_exact():
+    """Small-integer data and w~ = 0 make every fp32 sum of the gradient pass exact,
+    so one whole epoch (gradient, centering, inner loop, update) must match to the bit."""
+    rng = np.random.default_rng(5)
+    N, d, R = 256, 64, 2
+    Xq = rng.integers(-100, 101, size=(R, N, d)).astype(np.int8)
+    dd = 2.0 ** -6
+    X = (Xq * dd).astype(np.float32)
+    y = (rng.integers(-64, 65, size=(R, N)) / 16.0).astype(np.float32)
+    P = GpuProblem(X, Xq, y, R=R, T=2 * N, alpha=0.01, mu=0.3, delta_d=dd, seed=21)
+    P.h.epoch(0)
+    for r in range(R):
+        prob = ref.make_problem(N, d, alpha=0.01, mu=0.3, delta_d=dd, seed=21 + r)
+        out = ref.epoch(prob, X[r], Xq[r], y[r], np.zeros((1, d), np.float32), 0, 2 * N)
+        assert np.array_equal(P.get("phi")[r], out["phi"])
+        assert np.array_equal(P.get("g")[r], out["g"])
+        assert np.array_equal(P.get("scales")[r][[0, 1, 2, 3, 4, 5, 7]], out["scales"][[0, 1, 2, 3, 4, 5, 7]])
+        assert np.array_equal(P.get("h")[r].astype(np.int64), out["h"])
+        assert np.array_equal(P.get("z")[r].astype(np.int32), out["z"])
+        assert np.array_equal(P.get("w")[r], out["w"])
+
+
+def test_epochs_converge_like_the_oracle():
+    """Config-1-shaped run (N=1000, d=64, b=8, mu=1, alpha=0.01, T=2N, 10 epochs): the GPU and
+    the oracle contract the distance to the least-squares solution at the same rate."""
+    N, d = 1000, 64
+    X, y, _ = inp.linreg(N, d, seed=0, x_var="unit", noise=0.01)
+    dd = inp.default_delta_d(X, 8)
+    Xq = ref.quantize_data(X, dd, 8)
+    w_star = np.linalg.lstsq(X.astype(np.float64), y.astype(np.float64), rcond=None)[0]
+    P = GpuProblem(X, None, y, T=2 * N, alpha=0.01, mu=1.0, delta_d=dd, seed=0)
+    P.h.quantize_data()
+    prob = ref.make_problem(N, d, alpha=0.01, mu=1.0, delta_d=dd, seed=0)
+    w_ref = np.zeros((1, d), np.float32)
+    d_gpu, d_ref = [], []
+    for k in range(10):
+        P.h.epoch(k)
+        w_ref = ref.epoch(prob, X, Xq, y, w_ref, k, 2 * N)["w"]
+        d_gpu.append(np.linalg.norm(P.get("w")[0, 0] - w_star))
+        d_ref.append(np.linalg.norm(w_ref[0] - w_star))
+    d0 = np.linalg.norm(w_star)
+    assert d_gpu[-1] < 0.05 * d0 and d_ref[-1] < 0.05 * d0
+    ratio = np.array(d_gpu) / np.array(d_ref)
+    assert np.all(ratio < 3) and np.all(ratio > 1 / 3)
+
+
+def test_missing_buffers_and_bad_calls_are_errors():
+    X = np.zeros((1, 8, 16), np.float32)
+    P = GpuProblem(X, None, np.zeros((1, 8), np.float32))
+    h2 = hp.Halp(8, 16)
+    with pytest.raises(hp.HalpError) as e:
+        h2.epoch(0)
+    assert e.value.code == hp.ERR_NOT_BOUND
+    with pytest.raises(hp.HalpError) as e:
+        P.h.epoch(-1)
+    assert e.value.code == hp.ERR_INVALID
+    with pytest.raises(hp.HalpError) as e:
+        P.h.bind(X=P.X[:, :, 1:], ldx=16, **P.st)  # misaligned base pointer
+    assert e.value.code == hp.ERR_ALIGN
