@@ -170,6 +170,9 @@ int halp_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d,
                            int32_t K, uint32_t* out, void* stream);
 
 const char* halp_strerror(int code);
+/* Text of the last HIP runtime failure seen by this thread inside the library
+ * (which call, and HIP's message); empty if there was none.                            */
+const char* halp_last_error_detail(void);
 const char* halp_version(void);
 
 #ifdef __cplusplus

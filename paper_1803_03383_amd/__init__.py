@@ -19,14 +19,15 @@ EXPORTS = [
     "halp_create", "halp_destroy", "halp_bind", "halp_set_option", "halp_quantize_data",
     "halp_full_gradient", "halp_recenter", "halp_inner_loop", "halp_epoch",
     "halp_inner_loop_trace", "halp_get_stats", "halp_debug_stream_words",
-    "halp_debug_zround_bits", "halp_strerror", "halp_version",
+    "halp_debug_zround_bits", "halp_strerror", "halp_last_error_detail", "halp_version",
 ]
 
 
 class HalpError(RuntimeError):
     def __init__(self, code, what):
         self.code = code
-        super().__init__(f"{what}: {strerror(code)} ({code})")
+        detail = lib().halp_last_error_detail().decode() if code == ERR_HIP else ""
+        super().__init__(f"{what}: {strerror(code)} ({code})" + (f" [{detail}]" if detail else ""))
 
 
 class Params(C.Structure):
@@ -66,6 +67,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_1803_03383_amd.build`")
+        # torch first: the process must end up with ONE HIP runtime, the one torch's
+        # allocations and streams live in; libhalp.so then binds to that copy
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i64, i32, u64, u32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_uint32
         L.halp_create.argtypes = [C.POINTER(vp), C.POINTER(Params)]
@@ -85,6 +89,8 @@ def lib():
             getattr(L, name).restype = C.c_int
         L.halp_strerror.restype = C.c_char_p
         L.halp_strerror.argtypes = [C.c_int]
+        L.halp_last_error_detail.restype = C.c_char_p
+        L.halp_last_error_detail.argtypes = []
         L.halp_version.restype = C.c_char_p
         L.halp_version.argtypes = []
         _lib = L

@@ -2,6 +2,7 @@
 // order of the three phases of an epoch (Algorithm 4).  No arithmetic of the
 // method happens on the host.
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
 
@@ -10,6 +11,16 @@
 using namespace halp;
 
 namespace {
+
+// text of the last failed HIP runtime call on this thread, for halp_last_error_detail
+thread_local char g_detail[256] = "";
+
+bool hip_fail(hipError_t e, const char* what) {
+  if (e == hipSuccess) return false;
+  std::snprintf(g_detail, sizeof g_detail, "%s: %s", what, hipGetErrorString(e));
+  (void)hipGetLastError();
+  return true;
+}
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
@@ -85,24 +96,26 @@ int halp_create(halp_handle** out, const halp_params* p) {
   if (!h) return HALP_ERR_HIP;
   h->p = *p;
   std::memset(&h->buf, 0, sizeof h->buf);
-  if (hipGetDevice(&h->device) != hipSuccess) { delete h; return HALP_ERR_HIP; }
-  hipDeviceProp_t prop;
-  if (hipGetDeviceProperties(&prop, h->device) != hipSuccess) { delete h; return HALP_ERR_HIP; }
-  h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (hip_fail(hipGetDevice(&h->device), "hipGetDevice")) { delete h; return HALP_ERR_HIP; }
+  int cus = 0;
+  if (hip_fail(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device),
+               "hipDeviceGetAttribute")) { delete h; return HALP_ERR_HIP; }
+  h->num_cus = cus > 0 ? cus : 256;
   // workspace of the gradient pass, if a kernel covers this shape
   if (fullgrad_supported(h->p) == HALP_OK) {
     h->parts = fullgrad_parts(*h);
     h->partial_g_bytes = sizeof(float) * (size_t)p->R * h->parts * (size_t)p->K * p->d;
-    if (hipMalloc(reinterpret_cast<void**>(&h->partial_g), h->partial_g_bytes) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void**>(&h->partial_loss),
-                  sizeof(double) * (size_t)p->R * h->parts) != hipSuccess) {
+    if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->partial_g), h->partial_g_bytes),
+                 "hipMalloc(partial_g)") ||
+        hip_fail(hipMalloc(reinterpret_cast<void**>(&h->partial_loss),
+                           sizeof(double) * (size_t)p->R * h->parts), "hipMalloc(partial_loss)")) {
       halp_destroy(h);
       return HALP_ERR_HIP;
     }
   }
   for (auto& quad : h->ev)
     for (auto& e : quad)
-      if (hipEventCreate(&e) != hipSuccess) { halp_destroy(h); return HALP_ERR_HIP; }
+      if (hip_fail(hipEventCreate(&e), "hipEventCreate")) { halp_destroy(h); return HALP_ERR_HIP; }
   *out = h;
   return HALP_OK;
 }
@@ -334,6 +347,8 @@ const char* halp_strerror(int code) {
     default: return "unknown error code";
   }
 }
+
+const char* halp_last_error_detail(void) { return g_detail; }
 
 const char* halp_version(void) { return "halp-gfx950 0.1"; }
 
