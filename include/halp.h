@@ -110,6 +110,9 @@ typedef struct {
 #define HALP_OPT_COUNT_CLAMPS 3  /* 1 (default): counters[0] is exact; 0: not counted, the
                                     register-resident kernel writes UINT64_MAX instead     */
 #define HALP_OPT_FULLGRAD_BLOCKS 4 /* workgroups per chain of the gradient pass, 0 = auto  */
+#define HALP_OPT_INNER_WAVES 5   /* waves per chain of the register-resident inner loop: 1, 2, 4,
+                                    8, 16, or 0 = auto (several when chains are few, one when
+                                    they are many); results do not depend on it             */
 
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */

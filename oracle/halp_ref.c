@@ -46,22 +46,28 @@ uint32_t halp_ref_stream_word(uint64_t seed, uint32_t purpose, uint32_t epoch, u
   return out[n & 3];
 }
 
-/* Rounding bits of z.  Coordinates of one class are cut into groups holding
- * 64 bits of rounding (64/b coordinates); one Philox block serves a group for
- * the two steps 2s and 2s+1: counter = (group, s, epoch, ZROUND). */
+/* Rounding bits of z.  A row of z is cut into strips 16 bits of rounding wide
+ * (16/b coordinates: two at b = 8, one at b = 16).  One Philox block serves a
+ * strip for the eight steps 8s .. 8s+7: counter = (strip, s, epoch, ZROUND);
+ * step t uses the 16-bit field t mod 8 of the block (field f = half f%2 of
+ * word f/2), and coordinate k of the strip the bits [k b, (k+1) b) of it. */
 uint32_t halp_ref_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
                               int32_t c, int32_t j) {
-  const int32_t cpg = 64 / b;               /* coordinates per group */
-  const int32_t G = (d + cpg - 1) / cpg;    /* groups per class      */
-  const uint32_t gid = (uint32_t)c * (uint32_t)G + (uint32_t)(j / cpg);
-  const uint32_t ctr[4] = {gid, (uint32_t)(t >> 1), epoch, HALP_REF_PURPOSE_ZROUND};
+  if (b > 16) { /* wide models exist on the CPU only (the many-bits check against SVRG): one
+                   word of the stream per step and coordinate, low b bits */
+    const uint64_t n = t * (uint64_t)d * 64u + (uint64_t)c * (uint64_t)d + (uint64_t)j;
+    return halp_ref_stream_word(seed, HALP_REF_PURPOSE_ZROUND, epoch, n) & ((1u << b) - 1u);
+  }
+  const int32_t cps = 16 / b;               /* coordinates per strip */
+  const int32_t U = (d + cps - 1) / cps;    /* strips per class      */
+  const uint32_t strip = (uint32_t)c * (uint32_t)U + (uint32_t)(j / cps);
+  const uint32_t ctr[4] = {strip, (uint32_t)(t >> 3), epoch, HALP_REF_PURPOSE_ZROUND};
   const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
   uint32_t out[4];
   halp_ref_philox4x32_10(ctr, key, out);
-  const int bitpos = (int)(t & 1) * 64 + (j % cpg) * b;
-  const uint64_t two = (uint64_t)out[bitpos / 32] |
-                       ((uint64_t)(bitpos / 32 + 1 < 4 ? out[bitpos / 32 + 1] : 0u) << 32);
-  return (uint32_t)((two >> (bitpos % 32)) & ((1ull << b) - 1ull));
+  const int f = (int)(t & 7);
+  const uint32_t field = (out[f >> 1] >> (16 * (f & 1))) & 0xFFFFu;
+  return (field >> ((j % cps) * b)) & ((1u << b) - 1u);
 }
 
 int64_t halp_ref_sample_index(uint64_t seed, uint32_t epoch, uint64_t t, int32_t B, int32_t m,

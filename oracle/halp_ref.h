@@ -69,7 +69,7 @@ typedef struct {
   int32_t d;      /* features                                         */
   int32_t K;      /* classes (1 unless softmax)                       */
   int32_t loss;   /* HALP_REF_*                                       */
-  int32_t b;      /* bits of the low-precision model: 8, 16 (or up to 24 on the CPU only) */
+  int32_t b;      /* bits of the low-precision model: 8 or 16 (up to 24 on the CPU only) */
   int32_t B;      /* inner minibatch                                  */
   int32_t pad_;
   double alpha;   /* step size                                        */

@@ -47,11 +47,19 @@ __device__ __forceinline__ uint32_t pick(const U4& v, uint32_t k) {
   return k == 0 ? v.x : (k == 1 ? v.y : (k == 2 ? v.z : v.w));
 }
 
-// Block holding the rounding bits of coordinate group `gid` for the step pair (2s, 2s+1).
-__device__ __forceinline__ U4 zround_block(uint64_t seed, uint32_t epoch, uint32_t gid,
+// Rounding bits of z: a row of z is cut into strips 16 rounding bits wide (16/b
+// coordinates: two at b = 8, one at b = 16).  One block serves strip `strip` for the
+// eight steps 8s .. 8s+7; step t reads the 16-bit field t % 8 (half f % 2 of word f / 2).
+__device__ __forceinline__ U4 zround_block(uint64_t seed, uint32_t epoch, uint32_t strip,
                                            uint32_t s) {
-  return philox4x32_10(U4{gid, s, epoch, (uint32_t)kZround}, (uint32_t)seed,
+  return philox4x32_10(U4{strip, s, epoch, (uint32_t)kZround}, (uint32_t)seed,
                        (uint32_t)(seed >> 32));
+}
+
+// the 16-bit field of step t (any t; only t % 8 matters) in a strip's block
+__device__ __forceinline__ uint32_t zround_field(const U4& r, uint32_t t) {
+  const uint32_t f = t & 7u;
+  return (pick(r, f >> 1) >> (16u * (f & 1u))) & 0xFFFFu;
 }
 
 // ---- wave-wide sums --------------------------------------------------------

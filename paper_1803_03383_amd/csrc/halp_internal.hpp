@@ -17,6 +17,7 @@ struct halp_handle {
   bool timing = false;
   bool count_clamps = true;
   int fullgrad_blocks = 0;
+  int inner_waves = 0;  // waves per chain of the register-resident inner loop, 0 = auto
   // library-owned workspace of the gradient pass: per-workgroup partial sums
   float* partial_g = nullptr;    // [R][parts][K*d]
   double* partial_loss = nullptr;  // [R][parts]

@@ -19,13 +19,13 @@ template <int BITS>
 __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
-  constexpr int CPG = 64 / BITS;  // coordinates sharing 64 rounding bits
+  constexpr int CPS = 16 / BITS;  // coordinates per strip of 16 rounding bits
   const int chain = blockIdx.x;
   const int tid = threadIdx.x, NT = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, NW = NT >> 6;
   const int d = a.d, K = a.K, B = a.B;
   const int n = K * d;
-  const int G = (d + CPG - 1) / CPG;
+  const int U = (d + CPS - 1) / CPS;
   const int64_t N = a.N, ldxq = a.ldxq;
   const XT* __restrict__ Xq = reinterpret_cast<const XT*>(a.Xq) + (int64_t)chain * a.xq_chain_stride;
   const float* __restrict__ phi = a.phi + (int64_t)chain * N * K;
@@ -66,6 +66,9 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
   const double qmaxd = (double)((1 << (BITS - 1)) - 1), qmind = -(double)(1 << (BITS - 1));
   const long long qmax = (1 << (BITS - 1)) - 1, qmin = -(1 << (BITS - 1));
   unsigned long long my_zclamp = 0, my_gclamp = 0;
+  constexpr int kCached = 8;
+  U4 zcache[kCached];
+  const bool cache_blocks = K * U <= kCached * NT;
 
   for (int64_t t = 0; t < a.T; ++t) {
     const bool rec = t < a.tr.M;
@@ -152,23 +155,35 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
     __syncthreads();
     // u = z - gamma x_i - h~ (- c_lambda z) in (delta_i, 2b); z = Q_(delta_m, b)(u)
     const long long cl = s_clambda;
-    for (int u = tid; u < K * G; u += NT) {
-      const int c = u / G, grp = u % G;
-      const U4 r = zround_block(seed, a.epoch, (uint32_t)u, (uint32_t)(t >> 1));
-      const uint64_t bits = (t & 1) ? (((uint64_t)r.w << 32) | r.z) : (((uint64_t)r.y << 32) | r.x);
-      for (int e = 0; e < CPG; ++e) {
-        const int j = grp * CPG + e;
+    auto update_strip = [&](int u, const U4& r) {
+      const int c = u / U, strip = u % U;
+      const uint32_t field = zround_field(r, (uint32_t)t);
+      for (int e = 0; e < CPS; ++e) {
+        const int j = strip * CPS + e;
         if (j >= d) break;
         const int k = c * d + j;
         const long long zk = zs[k];
         long long v = -(long long)hs[k] - cl * zk;
         for (int m = 0; m < B; ++m) v -= (long long)gams[m * K + c] * (long long)Xq[idxs[m] * ldxq + j];
-        const long long rb = (long long)((bits >> (e * BITS)) & ((1ull << BITS) - 1ull));
+        const long long rb = (long long)((field >> (e * BITS)) & ((1u << BITS) - 1u));
         long long zn = zk + ((v + rb) >> BITS);  // arithmetic shift: floor
         if (zn > qmax) { zn = qmax; my_zclamp += 1; }
         if (zn < qmin) { zn = qmin; my_zclamp += 1; }
         zs[k] = (int32_t)zn;
       }
+    };
+    if (cache_blocks) {  // a thread's strips are the same every step: keep their blocks for 8 steps
+#pragma unroll
+      for (int s = 0; s < kCached; ++s) {
+        const int u = tid + s * NT;
+        if (u < K * U) {
+          if ((t & 7) == 0) zcache[s] = zround_block(seed, a.epoch, (uint32_t)u, (uint32_t)(t >> 3));
+          update_strip(u, zcache[s]);
+        }
+      }
+    } else {
+      for (int u = tid; u < K * U; u += NT)
+        update_strip(u, zround_block(seed, a.epoch, (uint32_t)u, (uint32_t)(t >> 3)));
     }
     __syncthreads();
     if (rec && a.tr.ztraj) {

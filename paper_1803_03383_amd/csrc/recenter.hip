@@ -137,17 +137,16 @@ __global__ void debug_words_kernel(uint64_t seed, uint32_t purpose, uint32_t epo
 
 __global__ void debug_zround_kernel(uint64_t seed, uint32_t epoch, uint64_t t, int d, int b, int K,
                                     uint32_t* out) {
-  const int cpg = 64 / b;
-  const int G = (d + cpg - 1) / cpg;
+  const int cps = 16 / b;
+  const int U = (d + cps - 1) / cps;
   const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= (int64_t)K * G) return;
-  const int c = (int)(u / G), grp = (int)(u % G);
-  const U4 r = zround_block(seed, epoch, (uint32_t)u, (uint32_t)(t >> 1));
-  const uint32_t w0 = (t & 1) ? r.z : r.x, w1 = (t & 1) ? r.w : r.y;
-  const uint64_t bits = ((uint64_t)w1 << 32) | w0;
-  for (int e = 0; e < cpg; ++e) {
-    const int j = grp * cpg + e;
-    if (j < d) out[(int64_t)c * d + j] = (uint32_t)((bits >> (e * b)) & ((1ull << b) - 1ull));
+  if (u >= (int64_t)K * U) return;
+  const int c = (int)(u / U), strip = (int)(u % U);
+  const U4 r = zround_block(seed, epoch, (uint32_t)u, (uint32_t)(t >> 3));
+  const uint32_t field = zround_field(r, (uint32_t)t);
+  for (int e = 0; e < cps; ++e) {
+    const int j = strip * cps + e;
+    if (j < d) out[(int64_t)c * d + j] = (field >> (e * b)) & ((1u << b) - 1u);
   }
 }
 
@@ -186,8 +185,8 @@ int launch_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, u
 
 int launch_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
                              int32_t K, uint32_t* out, hipStream_t s) {
-  const int cpg = 64 / b;
-  const int64_t units = (int64_t)K * ((d + cpg - 1) / cpg);
+  const int cps = 16 / b;
+  const int64_t units = (int64_t)K * ((d + cps - 1) / cps);
   hipLaunchKernelGGL(debug_zround_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
                      seed, epoch, t, d, b, K, out);
   return hip_ok(hipGetLastError());

@@ -219,24 +219,55 @@ INNER_REG_CASES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [2, 1])
+# (kernel variant, waves per chain): the register-resident kernel in every launch shape, then
+# the generic kernel; the result must not depend on the choice
+KERNELS = [(2, 0), (2, 1), (2, 2), (2, 4), (2, 16), (1, 0)]
+
+
+@pytest.mark.parametrize("variant,waves", KERNELS)
 @pytest.mark.parametrize("loss,N,d,b,lam,R,T,mu", INNER_REG_CASES)
-def test_inner_loop_bit_exact(loss, N, d, b, lam, R, T, mu, variant):
+def test_inner_loop_bit_exact(loss, N, d, b, lam, R, T, mu, variant, waves):
     seed = 40 + d + T
     case = _inner_case(loss, N, d, 1, 1, b, lam, R, T, seed, mu=mu)
     P = _run_inner(case, loss, 1, 1, b, lam, R, T, seed, variant, mu=mu)
+    P.h.set_option(hp.OPT_INNER_WAVES, waves)
     P.h.inner_loop(3)
     z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
     assert P.h.get_stats(0).inner_variant == variant
     for r in range(R):
-        out = ref.inner_loop(case["mk"](r), case["Xq"][r], case["phi"][r], case["y"][r],
-                             case["h"][r], case["scales"][r], 3, T)
+        out = _oracle_inner(case, r, T)
         assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
         w_r = ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r])
         assert np.array_equal(w[r], w_r)
         assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
     if mu > 100:
         assert cnt[0, 0] > 0  # the saturating case really saturates
+
+
+_ORACLE_CACHE = {}
+
+
+def _oracle_inner(case, r, T):
+    """the oracle's inner loop for chain r of a case (cached: the same case runs on several kernels)"""
+    key = (id(case["Xq"]), r, T)
+    prob = case["mk"](r)
+    key = (prob.N, prob.d, prob.b, prob.loss, prob.seed, prob.mu, prob.lam, T)
+    if key not in _ORACLE_CACHE:
+        _ORACLE_CACHE[key] = ref.inner_loop(prob, case["Xq"][r], case["phi"][r], case["y"][r],
+                                            case["h"][r], case["scales"][r], 3, T)
+    return _ORACLE_CACHE[key]
+
+
+def test_clamp_counting_can_be_switched_off():
+    case = _inner_case(hp.LOSS_SQUARED, 64, 64, 1, 1, 8, 0.0, 1, 600, 7, mu=500.0)
+    P = _run_inner(case, hp.LOSS_SQUARED, 1, 1, 8, 0.0, 1, 600, 7, 2, mu=500.0)
+    P.h.set_option(hp.OPT_COUNT_CLAMPS, 0)
+    P.h.inner_loop(3)
+    out = ref.inner_loop(case["mk"](0), case["Xq"][0], case["phi"][0], case["y"][0], case["h"][0],
+                         case["scales"][0], 3, 600)
+    assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
+    assert P.get("counters")[0, 0] == -1  # UINT64_MAX: not counted
+    assert P.get("counters")[0, 1] == out["counters"][1]
 
 
 GENERIC_CASES = [

@@ -54,19 +54,19 @@ def test_stream_word_layout():
 
 @pytest.mark.parametrize("b", [8, 16])
 def test_zround_bits_layout(b):
-    """64/b coordinates share a block with the step pair (2s, 2s+1)."""
-    seed, epoch, d = 99, 3, 50
-    cpg = 64 // b
-    G = (d + cpg - 1) // cpg
+    """16/b coordinates form a strip; a strip shares one block with the eight steps 8s..8s+7."""
+    seed, epoch, d = 99, 3, 51
+    cps = 16 // b
+    U = (d + cps - 1) // cps
     for c in range(2):
-        for j in [0, 1, cpg - 1, cpg, d - 1]:
-            for t in [0, 1, 2, 7]:
-                out = ref.philox4x32_10([c * G + j // cpg, t >> 1, epoch, ref.PURPOSE_ZROUND],
-                                        [seed, 0])
+        for j in [0, 1, cps - 1, cps, d - 2, d - 1]:
+            for t in [0, 1, 2, 7, 8, 13, 2 ** 33 + 5]:
+                out = ref.philox4x32_10([c * U + j // cps, (t >> 3) & 0xFFFFFFFF, epoch,
+                                         ref.PURPOSE_ZROUND], [seed, 0])
                 bits = 0
                 for k, w in enumerate(out):
                     bits |= int(w) << (32 * k)
-                pos = (t & 1) * 64 + (j % cpg) * b
+                pos = (t & 7) * 16 + (j % cps) * b
                 want = (bits >> pos) & ((1 << b) - 1)
                 assert ref.zround_bits(seed, epoch, t, d, b, c, j) == want
 
