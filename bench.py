@@ -124,6 +124,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
     ap.add_argument("--cpu-chains", type=int, default=64)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of X (known size) to calibrate HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every chain and the whole gradient "
@@ -186,6 +188,12 @@ def main():
         "paper_context": "paper reports HALP up to 4x faster per epoch than its AVX2 fp64 SVRG on 56 "
                          "Xeon E7-4850 v3 cores (Table 3); no GPU or bandwidth figure is published",
     }
+    if args.copy_probe:  # read R*N*d*4 bytes, write as many: the yardstick for FETCH_SIZE / WRITE_SIZE
+        Y = torch.empty_like(X)
+        Y.copy_(X)
+        torch.cuda.synchronize()
+        out["copy_probe_bytes_each_way"] = X.numel() * 4
+        del Y
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, X, Xq, y, delta_d, 0, min(args.cpu_chains, R))
     h.close()

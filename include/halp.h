@@ -107,8 +107,6 @@ typedef struct {
 #define HALP_OPT_INNER_VARIANT 1 /* 0 auto (default), 1 generic, 2 register-resident     */
 #define HALP_OPT_TIMING 2        /* 1: halp_epoch brackets its phases with events on its stream;
                                     setting it restarts the averages of halp_get_stats     */
-#define HALP_OPT_COUNT_CLAMPS 3  /* 1 (default): counters[0] is exact; 0: not counted, the
-                                    register-resident kernel writes UINT64_MAX instead     */
 #define HALP_OPT_FULLGRAD_BLOCKS 4 /* workgroups per chain of the gradient pass, 0 = auto  */
 #define HALP_OPT_INNER_WAVES 5   /* waves per chain of the register-resident inner loop: 1, 2, 4,
                                     8, 16, or 0 = auto (several when chains are few, one when

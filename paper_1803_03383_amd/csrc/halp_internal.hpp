@@ -15,7 +15,6 @@ struct halp_handle {
   // options
   int inner_variant = 0;
   bool timing = false;
-  bool count_clamps = true;
   int fullgrad_blocks = 0;
   int inner_waves = 0;  // waves per chain of the register-resident inner loop, 0 = auto
   // library-owned workspace of the gradient pass: per-workgroup partial sums

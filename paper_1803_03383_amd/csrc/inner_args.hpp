@@ -22,7 +22,6 @@ struct InArgs {
   double alpha, lambda, delta_d;
   uint64_t seed;
   uint32_t epoch;
-  int count_clamps;
   TraceBufs tr;
 };
 
@@ -36,7 +35,7 @@ inline InArgs make_inner_args(const halp_handle& h, uint32_t epoch) {
   a.y_chain_stride = p.share_data ? 0 : p.N;
   a.d = p.d; a.K = p.K; a.B = p.B; a.loss = p.loss;
   a.alpha = p.alpha; a.lambda = p.lambda; a.delta_d = p.delta_d;
-  a.seed = p.seed; a.epoch = epoch; a.count_clamps = h.count_clamps ? 1 : 0;
+  a.seed = p.seed; a.epoch = epoch;
   return a;
 }
 

@@ -5,8 +5,8 @@
 
 namespace halp {
 
-int launch_inner_reg_b8(const InArgs& a, int nw, int upl, bool count, int R, hipStream_t s);
-int launch_inner_reg_b16(const InArgs& a, int nw, int upl, bool count, int R, hipStream_t s);
+int launch_inner_reg_b8(const InArgs& a, int nw, int upl, int R, hipStream_t s);
+int launch_inner_reg_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
 
 namespace {
 
@@ -81,8 +81,8 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
     sh.upl /= 2;
   }
   if (!launchable(sh)) return HALP_ERR_UNSUPPORTED;
-  return p.b == 8 ? launch_inner_reg_b8(a, sh.nw, sh.upl, h.count_clamps, p.R, s)
-                  : launch_inner_reg_b16(a, sh.nw, sh.upl, h.count_clamps, p.R, s);
+  return p.b == 8 ? launch_inner_reg_b8(a, sh.nw, sh.upl, p.R, s)
+                  : launch_inner_reg_b16(a, sh.nw, sh.upl, p.R, s);
 }
 
 }  // namespace halp

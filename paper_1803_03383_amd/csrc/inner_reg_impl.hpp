@@ -38,8 +38,18 @@ __device__ __forceinline__ double logistic_dl(double a, double y) {
   return __ddiv_rn(-y, __dadd_rn(1.0, exp(__dmul_rn(y, a))));
 }
 
-template <int BITS, int UPL, int NWT, bool COUNT>
+// a * b + c on the 24-bit multiplier; a and b must fit 24 bits (they are codes of at most
+// 16 bits here).  Written as the instruction because the compiler cannot see the range of
+// a value that comes out of a float conversion and would re-extend it first.
+__device__ __forceinline__ int mad24(int a, int b, int c) {
+  int r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+template <int BITS, int LOSS, int UPL, int NWT>
 __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
+  constexpr bool COUNT = true;  // clamped coordinates are always counted
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
   using AccT = typename std::conditional<BITS == 8, int, long long>::type;
@@ -85,7 +95,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   const double dscale = __dmul_rn(a.delta_d, delta_m);
   const double aB = a.alpha;  // B = 1: alpha / 1
   const bool use_reg = a.lambda > 0;
-  const bool logistic = a.loss == HALP_LOSS_LOGISTIC;
+  constexpr bool logistic = LOSS == HALP_LOSS_LOGISTIC;
   const double al = __dmul_rn(a.alpha, a.lambda);
 
   // ---- per-lane state
@@ -254,7 +264,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
           const uint32_t xv = xw[s][(k * BITS) / 32];
           const int sh = (k * BITS) % 32;
           xe[k] = BITS == 8 ? (int)(int8_t)(xv >> sh) : (int)(int16_t)(xv >> sh);
-          if (BITS == 8) part += __mul24(xe[k], z[k]);
+          if (BITS == 8) part = (AccT)mad24(xe[k], z[k], (int)part);
           else part += (AccT)((long long)xe[k] * (long long)z[k]);
         }
         AccT D;
@@ -279,8 +289,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
         const double f = floor(__dadd_rn(__dmul_rn(beta, inv_s), rho[s]));
         const double fc = fmin(fmax(f, (double)QMIN), (double)QMAX);
         n_gclamp += (f != fc) ? 1u : 0u;
-        const int ng = -(int)fc;
-        __builtin_assume(ng >= -QMAX && ng <= -QMIN);
+        const int ng = (int)(-fc);
         int cl = 0;
         if (REGW) {
           cl = __builtin_amdgcn_readfirstlane(creg[s]);
@@ -294,8 +303,8 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
           const int re = (int)((word >> sh) & (BITS == 8 ? 0xFFu : 0xFFFFu));
           int zu;
           if (BITS == 8) {
-            int v = __mul24(ng, xe[k]) + (hv[k] + re);
-            if (REGW) v -= __mul24(cl, z[k]);
+            int v = mad24(ng, xe[k], hv[k] + re);
+            if (REGW) v = mad24(-cl, z[k], v);
             zu = z[k] + (v >> 8);
           } else {
             long long v = (long long)ng * (long long)xe[k] - (long long)hv[k] + (long long)re;
@@ -365,26 +374,24 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     s_cnt[2] = n_reg;
   }
   __syncthreads();
-  if (tid < 4) {
-    unsigned long long v = tid < 3 ? s_cnt[tid] : 0ull;
-    if (tid == 0 && !COUNT) v = ~0ull;
-    cnt_out[tid] = v;
-  }
+  if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
 }
 
 template <int BITS, int UPL, int NWT>
-int launch_one(const InArgs& a, bool count, int R, hipStream_t s) {
+int launch_one(const InArgs& a, int R, hipStream_t s) {
   const dim3 grid(R), block(64 * NWT);
-  if (count) hipLaunchKernelGGL((inner_reg_kernel<BITS, UPL, NWT, true>), grid, block, 0, s, a);
-  else hipLaunchKernelGGL((inner_reg_kernel<BITS, UPL, NWT, false>), grid, block, 0, s, a);
+  if (a.loss == HALP_LOSS_SQUARED)
+    hipLaunchKernelGGL((inner_reg_kernel<BITS, HALP_LOSS_SQUARED, UPL, NWT>), grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL((inner_reg_kernel<BITS, HALP_LOSS_LOGISTIC, UPL, NWT>), grid, block, 0, s, a);
   return hip_ok(hipGetLastError());
 }
 
 // every (strips per lane, waves per chain) pair the library launches
 template <int BITS>
-int launch_bits(const InArgs& a, int nw, int upl, bool count, int R, hipStream_t s) {
+int launch_bits(const InArgs& a, int nw, int upl, int R, hipStream_t s) {
 #define HALP_CASE(U_, W_) \
-  if (upl == U_ && nw == W_) return launch_one<BITS, U_, W_>(a, count, R, s);
+  if (upl == U_ && nw == W_) return launch_one<BITS, U_, W_>(a, R, s);
   HALP_CASE(1, 1) HALP_CASE(2, 1) HALP_CASE(4, 1) HALP_CASE(8, 1)
   HALP_CASE(1, 2) HALP_CASE(2, 2) HALP_CASE(4, 2) HALP_CASE(8, 2)
   HALP_CASE(1, 4) HALP_CASE(2, 4) HALP_CASE(4, 4) HALP_CASE(8, 4)

@@ -258,18 +258,6 @@ def _oracle_inner(case, r, T):
     return _ORACLE_CACHE[key]
 
 
-def test_clamp_counting_can_be_switched_off():
-    case = _inner_case(hp.LOSS_SQUARED, 64, 64, 1, 1, 8, 0.0, 1, 600, 7, mu=500.0)
-    P = _run_inner(case, hp.LOSS_SQUARED, 1, 1, 8, 0.0, 1, 600, 7, 2, mu=500.0)
-    P.h.set_option(hp.OPT_COUNT_CLAMPS, 0)
-    P.h.inner_loop(3)
-    out = ref.inner_loop(case["mk"](0), case["Xq"][0], case["phi"][0], case["y"][0], case["h"][0],
-                         case["scales"][0], 3, 600)
-    assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
-    assert P.get("counters")[0, 0] == -1  # UINT64_MAX: not counted
-    assert P.get("counters")[0, 1] == out["counters"][1]
-
-
 GENERIC_CASES = [
     # loss, N, d, K, B, b, lam, R, T
     (hp.LOSS_SOFTMAX, 400, 784, 10, 1, 8, 1e-4, 1, 300),
