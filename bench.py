@@ -46,14 +46,29 @@ WORKLOADS = {
 }
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            t = line.split()
+            if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == kernel and t[2] == workload:
+                return int(t[3])
+    except OSError:
+        pass
+    return None
+
+
 def make_problem(hp, inp, torch, cfg, seed=0):
     R, N, d = cfg["R"], cfg["N"], cfg["d"]
-    X, y, _ = inp.linreg_chains_device(R, N, d, seed=seed, noise=cfg["noise"])
+    share = bool(cfg.get("share_data"))
+    Rd = 1 if share else R
+    X, y, _ = inp.linreg_chains_device(Rd, N, d, seed=seed, noise=cfg["noise"])
     delta_d = float(X.abs().max().item()) / 127.0
     st = hp.alloc_state(N, d, R=R, b=8)
-    Xq = torch.zeros((R, N, d), dtype=torch.int8, device="cuda")
+    Xq = torch.zeros((Rd, N, d), dtype=torch.int8, device="cuda")
     h = hp.Halp(N, d, R=R, b=8, T=cfg["T"], alpha=cfg["alpha"], mu=cfg["mu"], delta_d=delta_d,
-                seed=seed)
+                seed=seed, share_data=share)
     h.bind(X=X, Xq=Xq, y=y, **st)
     h.quantize_data()
     torch.cuda.synchronize()
@@ -68,7 +83,8 @@ def cpu_baseline(cfg, X, Xq, y, delta_d, seed, budget_chains):
     R, N, d, T = cfg["R"], cfg["N"], cfg["d"], cfg["T"]
     cores = min(16, os.cpu_count() or 1)
     chains = list(range(0, R, max(1, R // budget_chains)))[:budget_chains]
-    host = [(X[r].cpu().numpy(), Xq[r].cpu().numpy(), y[r].cpu().numpy()) for r in chains]
+    src = [0 if cfg.get("share_data") else r for r in chains]
+    host = [(X[r].cpu().numpy(), Xq[r].cpu().numpy(), y[r].cpu().numpy()) for r in src]
     ref.lib()
 
     def one(k):
@@ -124,6 +140,10 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
     ap.add_argument("--cpu-chains", type=int, default=64)
+    ap.add_argument("--inner-waves", type=int, default=0, help="waves per chain (0 = library's choice)")
+    ap.add_argument("--chains", type=int, default=0,
+                    help="override the number of chains; above the workload's R the chains share "
+                         "chain 0's data and differ in their seeds only")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of X (known size) to calibrate HBM counters")
     args = ap.parse_args()
@@ -139,9 +159,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
-    cfg = WORKLOADS[args.workload]
+    cfg = dict(WORKLOADS[args.workload])
+    if args.chains > 0 and args.chains != cfg["R"]:
+        cfg["share_data"] = args.chains > cfg["R"]
+        cfg["R"] = args.chains
     R, N, d, T = cfg["R"], cfg["N"], cfg["d"], cfg["T"]
     h, X, Xq, y, st, delta_d = make_problem(hp, inp, torch, cfg)
+    if args.inner_waves:
+        h.set_option(hp.OPT_INNER_WAVES, args.inner_waves)
 
     for k in range(args.warmup):
         h.epoch(k)
@@ -158,12 +183,15 @@ def main():
     loss1 = float(st["scales"][:, 6].mean().item())
     clamped = int(st["counters"][:, 0].sum().item())
 
+    # counter summaries are only valid for the unmodified workload
+    wl_key = args.workload if (args.chains in (0, WORKLOADS[args.workload]["R"])) else "none"
     ms_step = dt / args.steps * 1e3
     updates = R * T * d
     value = updates / (ms_step * 1e-3)
     inner_ms, fg_ms = stats.ms_inner_loop, stats.ms_full_gradient
     alu_achieved = updates * LANEOPS_PER_UPDATE_B8 / (inner_ms * 1e-3)
-    fg_bytes = R * N * (4 * d + 4 + 4)
+    fg_bytes = (1 if cfg.get("share_data") else R) * N * (4 * d + 4 + 4) + \
+        (R * N * 4 if cfg.get("share_data") else 0)
     fg_gbs = fg_bytes / (fg_ms * 1e-3) / 1e9
 
     out = {
@@ -173,16 +201,18 @@ def main():
         "vs_baseline": None, "dtype": "int8 (inner loop) / f32 (gradient pass)", "data": "synthetic",
         "config": {"workload": f"{args.workload}: R={R} independent linear-regression chains, N={N}, "
                                f"d={d}, b=8, T={T} inner steps per epoch, one step = one halp_epoch",
-                   "alpha": cfg["alpha"], "mu": cfg["mu"], "inner_variant": stats.inner_variant,
+                   "alpha": cfg["alpha"], "mu": cfg["mu"], "inner_variant": stats.inner_variant, "inner_waves": args.inner_waves,
+                   "share_data": bool(cfg.get("share_data")),
                    "timed_epochs": stats.timed_epochs},
         "roofline": {"kernel": "inner_reg_kernel", "bound": "alu", "achieved": alu_achieved / 1e12,
                      "peak": ALU_PEAK_LANEOPS / 1e12, "unit": "Tlane-op/s",
-                     "frac": alu_achieved / ALU_PEAK_LANEOPS, "traffic": None,
+                     "frac": alu_achieved / ALU_PEAK_LANEOPS,
+                     "traffic": measured_traffic("inner_reg_kernel", wl_key),
                      "ms": inner_ms, "feature_updates_per_s": updates / (inner_ms * 1e-3),
                      "steps_per_s_per_chain": T / (inner_ms * 1e-3)},
         "roofline_full_gradient": {"kernel": "fullgrad_k1", "bound": "hbm", "achieved": fg_gbs,
                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fg_gbs / HBM_PEAK_GBS,
-                                   "traffic": None, "ms": fg_ms, "bytes": fg_bytes},
+                                   "traffic": measured_traffic("fullgrad_k1", wl_key), "ms": fg_ms, "bytes": fg_bytes},
         "ms_recenter": stats.ms_recenter,
         "loss_first_timed": loss0, "loss_last": loss1, "clamped_coordinates_last_epoch": clamped,
         "paper_context": "paper reports HALP up to 4x faster per epoch than its AVX2 fp64 SVRG on 56 "
