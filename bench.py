@@ -131,12 +131,55 @@ def c5_full_gradient(hp, inp, torch, reps=5):
     return out
 
 
+def side_inner_loop(hp, inp, torch, which, T):
+    """Inner-loop step rate of the configurations that run on the general kernel (softmax
+    K=10 at b=8/16; logistic with a minibatch of 64 at b=16), at a reduced step count."""
+    out = {}
+    if which == "c3":
+        N, d, K = 60000, 784, 10
+        X, y, _ = inp.softmax_sparse(N, d, K, seed=0)
+        Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+        cases = [dict(b=8, B=1, loss=hp.LOSS_SOFTMAX, lam=1e-4, alpha=1e-2, mu=2.5),
+                 dict(b=16, B=1, loss=hp.LOSS_SOFTMAX, lam=1e-4, alpha=1e-2, mu=2.5)]
+    else:
+        N, d, K = 1_000_000, 4096, 1
+        Xd, yd, _ = inp.logistic_device(N, d, seed=0)
+        cases = [dict(b=16, B=64, loss=hp.LOSS_LOGISTIC, lam=1e-5, alpha=0.05, mu=0.01)]
+    for c in cases:
+        b = c["b"]
+        delta_d = float(Xd.abs().max().item()) / float(2 ** (b - 1) - 1)
+        st = hp.alloc_state(N, d, K=K, b=b)
+        st["w"].normal_(0.0, 0.01)
+        Xq = torch.zeros((1, N, d), dtype=torch.int8 if b == 8 else torch.int16, device="cuda")
+        h = hp.Halp(N, d, K=K, loss=c["loss"], b=b, B=c["B"], T=T, alpha=c["alpha"], mu=c["mu"],
+                    lam=c["lam"], delta_d=delta_d, seed=0)
+        h.bind(X=Xd, Xq=Xq, y=yd, **st)
+        h.quantize_data()
+        h.set_option(hp.OPT_TIMING, 1)
+        for k in range(3):
+            h.epoch(k)
+        s = h.get_stats(0)
+        out[f"{which}_b{b}_B{c['B']}"] = dict(
+            N=N, d=d, K=K, b=b, B=c["B"], T=T, inner_variant=s.inner_variant,
+            ms_inner_loop=s.ms_inner_loop, ms_full_gradient=s.ms_full_gradient,
+            steps_per_s=T / (s.ms_inner_loop * 1e-3),
+            feature_updates_per_s=T * d * K / (s.ms_inner_loop * 1e-3),
+            full_gradient_GBs=N * (4 * d + 4 * K + 4) / (s.ms_full_gradient * 1e-3) / 1e9,
+            loss=s.loss)
+        h.close()
+        del Xq, st
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c5"],
+                    help="c4 (default), c2, c1: the headline line; c3, c5: step rate of the "
+                         "configurations that run on the general inner-loop kernel")
+    ap.add_argument("--inner-steps", type=int, default=2000, help="T for --workload c3 / c5")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
     ap.add_argument("--cpu-chains", type=int, default=64)
@@ -159,6 +202,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    if args.workload in ("c3", "c5"):
+        print(json.dumps({"workload": args.workload, "inner_loop_general_kernel":
+                          side_inner_loop(hp, inp, torch, args.workload, args.inner_steps)}))
+        return
     cfg = dict(WORKLOADS[args.workload])
     if args.chains > 0 and args.chains != cfg["R"]:
         cfg["share_data"] = args.chains > cfg["R"]

@@ -64,7 +64,9 @@ __device__ __forceinline__ uint32_t zround_field(const U4& r, uint32_t t) {
 
 // ---- wave-wide sums --------------------------------------------------------
 // Four DPP steps fold each row of 16 lanes (quad swaps, half-row mirror, row
-// mirror); the four row totals are then read with v_readlane and added.
+// mirror); two row broadcasts (lane 15 of rows 0 and 2 into rows 1 and 3, then
+// lane 31 into rows 2 and 3) bring the total to lane 63, which is read out.
+// All 64 lanes must be active.
 
 template <typename T>
 __device__ __forceinline__ T dpp_quad_swap1(T v) {  // lanes 1,0,3,2
@@ -86,14 +88,25 @@ __device__ __forceinline__ T dpp_row_mirror(T v) {  // reverse within 16 lanes
   return __builtin_bit_cast(
       T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
 }
+template <typename T>
+__device__ __forceinline__ T dpp_bcast15(T v) {  // rows 1, 3 get lane 15 of rows 0, 2; others 0
+  return __builtin_bit_cast(
+      T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false));
+}
+template <typename T>
+__device__ __forceinline__ T dpp_bcast31(T v) {  // rows 2, 3 get lane 31; rows 0, 1 get 0
+  return __builtin_bit_cast(
+      T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false));
+}
 
 __device__ __forceinline__ int wave_sum_i32(int v) {
   v += dpp_quad_swap1(v);
   v += dpp_quad_swap2(v);
   v += dpp_half_mirror(v);
   v += dpp_row_mirror(v);
-  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
-         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+  v += dpp_bcast15(v);
+  v += dpp_bcast31(v);
+  return __builtin_amdgcn_readlane(v, 63);
 }
 
 __device__ __forceinline__ float wave_sum_f32(float v) {
@@ -101,11 +114,9 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
   v += dpp_quad_swap2(v);
   v += dpp_half_mirror(v);
   v += dpp_row_mirror(v);
-  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-  return (a + b) + (c + d);
+  v += dpp_bcast15(v);
+  v += dpp_bcast31(v);
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 __device__ __forceinline__ long long wave_sum_i64(long long v) {
@@ -118,14 +129,11 @@ __device__ __forceinline__ long long wave_sum_i64(long long v) {
   v = step(v, [](int t) { return dpp_quad_swap2(t); });
   v = step(v, [](int t) { return dpp_half_mirror(t); });
   v = step(v, [](int t) { return dpp_row_mirror(t); });
-  long long tot = 0;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 16 * r);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(v >> 32), 16 * r);
-    tot += (long long)(((uint64_t)hi << 32) | lo);
-  }
-  return tot;
+  v = step(v, [](int t) { return dpp_bcast15(t); });
+  v = step(v, [](int t) { return dpp_bcast31(t); });
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 63);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(v >> 32), 63);
+  return (long long)(((uint64_t)hi << 32) | lo);
 }
 
 // ---- quantizers -------------------------------------------------------------

@@ -48,7 +48,9 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
   int32_t* hs = zs + n;
   long long* idxs = reinterpret_cast<long long*>(hs + n + (n & 1));
   long long* Ds = idxs + B;
-  int32_t* gams = reinterpret_cast<int32_t*>(Ds + (int64_t)B * K);
+  double* es = reinterpret_cast<double*>(Ds + (int64_t)B * K);  // softmax: exp terms [B*K][2]
+  double* rowst = es + 2 * (int64_t)B * K;                       // per row: max0, max1, sum0, sum1
+  int32_t* gams = reinterpret_cast<int32_t*>(rowst + 4 * (int64_t)B);
   __shared__ unsigned long long s_cnt[3];
   __shared__ int s_clambda;
 
@@ -101,55 +103,71 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
       }
     }
     __syncthreads();
-    // beta = (alpha/B)(l'(phi_i + x_i^T z) - l'(phi_i)); gamma = Q_(delta_s, b)(beta)
-    if (tid < B) {
-      const int m = tid;
-      const long long i = idxs[m];
-      double mx0 = 0, mx1 = 0, s0 = 0, s1 = 0;
-      if (a.loss == HALP_LOSS_SOFTMAX) {
-        mx0 = (double)phi[i * K];
-        mx1 = __dadd_rn(mx0, __dmul_rn(dscale, (double)Ds[m * K]));
+    // beta = (alpha/B)(l'(phi_i + x_i^T z) - l'(phi_i)); gamma = Q_(delta_s, b)(beta).
+    // One thread per (row, class) pair; the softmax normalisers are formed per row, the
+    // exponentials summed in class order.
+    const bool softmax = a.loss == HALP_LOSS_SOFTMAX;
+    if (softmax) {
+      if (tid < B) {
+        const long long i = idxs[tid];
+        double mx0 = (double)phi[i * K];
+        double mx1 = __dadd_rn(mx0, __dmul_rn(dscale, (double)Ds[tid * K]));
         for (int c = 1; c < K; ++c) {
           const double a0 = (double)phi[i * K + c];
-          const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[m * K + c]));
+          const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[tid * K + c]));
           if (a0 > mx0) mx0 = a0;
           if (a1 > mx1) mx1 = a1;
         }
-        for (int c = 0; c < K; ++c) {
-          const double a0 = (double)phi[i * K + c];
-          const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[m * K + c]));
-          s0 = __dadd_rn(s0, exp(__dadd_rn(a0, -mx0)));
-          s1 = __dadd_rn(s1, exp(__dadd_rn(a1, -mx1)));
-        }
+        rowst[4 * tid + 0] = mx0;
+        rowst[4 * tid + 1] = mx1;
       }
-      for (int c = 0; c < K; ++c) {
-        const double delta = __dmul_rn(dscale, (double)Ds[m * K + c]);
-        double diff;
-        if (a.loss == HALP_LOSS_SQUARED) {
-          diff = delta;
-        } else if (a.loss == HALP_LOSS_LOGISTIC) {
-          const double a0 = (double)phi[i];
-          const double yi = (double)y[i];
-          diff = __dadd_rn(logistic_dl(__dadd_rn(a0, delta), yi), -logistic_dl(a0, yi));
-        } else {
-          const double a0 = (double)phi[i * K + c];
-          const double a1 = __dadd_rn(a0, delta);
-          const double p0 = __ddiv_rn(exp(__dadd_rn(a0, -mx0)), s0);
-          const double p1 = __ddiv_rn(exp(__dadd_rn(a1, -mx1)), s1);
-          diff = __dadd_rn(p1, -p0);
+      __syncthreads();
+      for (int pr = tid; pr < B * K; pr += NT) {
+        const int m = pr / K, c = pr % K;
+        const double a0 = (double)phi[idxs[m] * K + c];
+        const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[pr]));
+        es[2 * pr + 0] = exp(__dadd_rn(a0, -rowst[4 * m + 0]));
+        es[2 * pr + 1] = exp(__dadd_rn(a1, -rowst[4 * m + 1]));
+      }
+      __syncthreads();
+      if (tid < B) {
+        double s0 = 0, s1 = 0;
+        for (int c = 0; c < K; ++c) {
+          s0 = __dadd_rn(s0, es[2 * (tid * K + c) + 0]);
+          s1 = __dadd_rn(s1, es[2 * (tid * K + c) + 1]);
         }
-        const double beta = __dmul_rn(aB, diff);
-        const uint64_t nn = ((uint64_t)t * (uint64_t)B + (uint64_t)m) * (uint64_t)K + (uint64_t)c;
-        const uint32_t r = pick(stream_block(seed, kGamma, a.epoch, nn >> 2), (uint32_t)(nn & 3));
-        bool hit = false;
-        const int gq = (int)quantize_real(beta, inv_s, r, qmind, qmaxd, &hit);
-        gams[m * K + c] = gq;
-        if (hit) my_gclamp += 1;
-        if (rec) {
-          const int64_t o = ((int64_t)chain * a.tr.M + t) * B * K + m * K + c;
-          if (a.tr.beta) a.tr.beta[o] = beta;
-          if (a.tr.gamma) a.tr.gamma[o] = gq;
-        }
+        rowst[4 * tid + 2] = s0;
+        rowst[4 * tid + 3] = s1;
+      }
+      __syncthreads();
+    }
+    for (int pr = tid; pr < B * K; pr += NT) {
+      const int m = pr / K, c = pr % K;
+      const long long i = idxs[m];
+      const double delta = __dmul_rn(dscale, (double)Ds[pr]);
+      double diff;
+      if (a.loss == HALP_LOSS_SQUARED) {
+        diff = delta;
+      } else if (a.loss == HALP_LOSS_LOGISTIC) {
+        const double a0 = (double)phi[i];
+        const double yi = (double)y[i];
+        diff = __dadd_rn(logistic_dl(__dadd_rn(a0, delta), yi), -logistic_dl(a0, yi));
+      } else {
+        const double p0 = __ddiv_rn(es[2 * pr + 0], rowst[4 * m + 2]);
+        const double p1 = __ddiv_rn(es[2 * pr + 1], rowst[4 * m + 3]);
+        diff = __dadd_rn(p1, -p0);
+      }
+      const double beta = __dmul_rn(aB, diff);
+      const uint64_t nn = ((uint64_t)t * (uint64_t)B + (uint64_t)m) * (uint64_t)K + (uint64_t)c;
+      const uint32_t r = pick(stream_block(seed, kGamma, a.epoch, nn >> 2), (uint32_t)(nn & 3));
+      bool hit = false;
+      const int gq = (int)quantize_real(beta, inv_s, r, qmind, qmaxd, &hit);
+      gams[pr] = gq;
+      if (hit) my_gclamp += 1;
+      if (rec) {
+        const int64_t o = ((int64_t)chain * a.tr.M + t) * B * K + pr;
+        if (a.tr.beta) a.tr.beta[o] = beta;
+        if (a.tr.gamma) a.tr.gamma[o] = gq;
       }
     }
     __syncthreads();
@@ -211,7 +229,8 @@ int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& 
   InArgs a = make_inner_args(h, epoch);
   a.tr = tr;
   const int64_t n = (int64_t)p.K * p.d;
-  const size_t smem = (size_t)(2 * n + (n & 1)) * 4 + (size_t)p.B * 8 + (size_t)p.B * p.K * 12;
+  const size_t smem = (size_t)(2 * n + (n & 1)) * 4 + (size_t)p.B * 8 + (size_t)p.B * p.K * 8 +
+                      (size_t)p.B * p.K * 16 + (size_t)p.B * 32 + (size_t)p.B * p.K * 4;
   if (smem > 150 * 1024 || p.B > 512) return HALP_ERR_UNSUPPORTED;
   const int threads = 512;
   hipError_t e;
