@@ -145,13 +145,70 @@ static double logistic_l(double a, double y) {
   return (s > 0 ? s : 0.0) + log1p(exp(-fabs(s)));
 }
 
-/* softmax probabilities of K logits, summed in class order */
+/* softmax probabilities of K logits (full-precision pass: the plain definition) */
 static void softmax_p(const double* a, int K, double* prob) {
   double mx = a[0];
   for (int c = 1; c < K; ++c) if (a[c] > mx) mx = a[c];
   double s = 0.0;
   for (int c = 0; c < K; ++c) { prob[c] = exp(a[c] - mx); s += prob[c]; }
   for (int c = 0; c < K; ++c) prob[c] = prob[c] / s;
+}
+
+/* ---------------------------------------------- scalar path of the inner loop */
+
+/* The inner loop turns l'(phi + x^T z) - l'(phi) into the integer gamma, so the last bit of
+ * exp can decide an integer.  The paper does not say how exp is rounded; to make that decision
+ * reproducible, the inner loop's exp is this fixed sequence of IEEE double operations (every
+ * one of them correctly rounded, so any conforming machine gives the same bits):
+ *   k = rint(x log2 e);  r = x - k ln2 (ln2 in two parts, two fused multiply-adds);
+ *   e^r = 1 + (r + r^2 Q(r)), Q the Taylor polynomial sum_{n=2..13} r^(n-2)/n! evaluated
+ *   pairwise (coefficients joined in pairs by r, pairs by r^2, then by r^4);
+ *   result = e^r 2^k.
+ * |r| <= ln2/2, where the omitted terms are below 1e-17; the result is within 1 ulp of exp. */
+double halp_ref_exp(double x) {
+  if (x != x) return x;
+  if (x > 0x1.62e42fefa39efp+9) return INFINITY;  /* above log(DBL_MAX) */
+  if (x < -0x1.74910d52d3052p+9) return 0.0;      /* below log of half the least subnormal */
+  const double k = nearbyint(x * 0x1.71547652b82fep+0);
+  double r = fma(-k, 0x1.62e42fefa39efp-1, x);
+  r = fma(-k, 0x1.abc9e3b39803fp-56, r);
+  const double r2 = r * r, r4 = r2 * r2;
+  const double a0 = fma(0x1.5555555555555p-3, r, 0x1.0000000000000p-1);   /* 1/2!  + r/3!  */
+  const double a1 = fma(0x1.1111111111111p-7, r, 0x1.5555555555555p-5);   /* 1/4!  + r/5!  */
+  const double a2 = fma(0x1.a01a01a01a01ap-13, r, 0x1.6c16c16c16c17p-10); /* 1/6!  + r/7!  */
+  const double a3 = fma(0x1.71de3a556c734p-19, r, 0x1.a01a01a01a01ap-16); /* 1/8!  + r/9!  */
+  const double a4 = fma(0x1.ae64567f544e4p-26, r, 0x1.27e4fb7789f5cp-22); /* 1/10! + r/11! */
+  const double a5 = fma(0x1.6124613a86d09p-33, r, 0x1.1eed8eff8d898p-29); /* 1/12! + r/13! */
+  const double b0 = fma(a1, r2, a0), b1 = fma(a3, r2, a2), b2 = fma(a5, r2, a4);
+  const double q = fma(fma(b2, r4, b1), r4, b0);
+  const double e = fma(r2, q, r) + 1.0;
+  return ldexp(e, (int)k);
+}
+
+void halp_ref_exp_array(const double* x, int64_t n, double* out) {
+  for (int64_t k = 0; k < n; ++k) out[k] = halp_ref_exp(x[k]);
+}
+
+static double logistic_dl_inner(double a, double y) { /* l'(a), exp as above */
+  return -y / (1.0 + halp_ref_exp(y * a));
+}
+
+/* Softmax probabilities of K logits for the inner loop.  The normaliser is summed pairwise
+ * (classes 0+1, 2+3, ..., then those sums in adjacent pairs, and so on; missing classes count
+ * as +0, which changes nothing): again a fixed order, chosen because it is a reduction tree. */
+static void softmax_p_inner(const double* a, int K, double* prob) {
+  double mx = a[0];
+  for (int c = 1; c < K; ++c) if (a[c] > mx) mx = a[c];
+  double v[64];
+  int P = 1;
+  while (P < K) P *= 2;
+  for (int c = 0; c < P; ++c) {
+    v[c] = 0.0;
+    if (c < K) { prob[c] = halp_ref_exp(a[c] - mx); v[c] = prob[c]; }
+  }
+  for (; P > 1; P /= 2)
+    for (int c = 0; c < P / 2; ++c) v[c] = v[2 * c] + v[2 * c + 1];
+  for (int c = 0; c < K; ++c) prob[c] = prob[c] / v[0];
 }
 
 /* --------------------------------------------------- Algorithm 4, outer part */
@@ -270,11 +327,11 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
       }
       if (p->loss == HALP_REF_LOGISTIC) {
         const double yi = ((const float*)y)[i];
-        p1[0] = logistic_dl(a1[0], yi) - logistic_dl(a0[0], yi);
+        p1[0] = logistic_dl_inner(a1[0], yi) - logistic_dl_inner(a0[0], yi);
       } else if (p->loss == HALP_REF_SOFTMAX) {
         double q0[64], q1[64];
-        softmax_p(a0, K, q0);
-        softmax_p(a1, K, q1);
+        softmax_p_inner(a0, K, q0);
+        softmax_p_inner(a1, K, q1);
         for (int c = 0; c < K; ++c) p1[c] = q1[c] - q0[c];
       } else {
         p1[0] = p0[0]; /* (phi + D - y) - (phi - y) = D without cancellation */

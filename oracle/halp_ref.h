@@ -38,6 +38,11 @@
  *   - multiclass: softmax cross-entropy, W stored [K][d], one gamma per class.
  *   - squared loss l(a) = (a-y)^2/2, so beta = (alpha/B) * (x^T z) exactly.
  *   - logistic labels are -1/+1, l(a) = log(1 + exp(-y a)).
+ *   - in the inner loop, where the last bit of l' can decide the integer gamma,
+ *     exp is a fixed sequence of correctly rounded double operations
+ *     (halp_ref_exp, within 1 ulp of exp) and the softmax normaliser is summed
+ *     pairwise over adjacent classes; the full-precision pass uses libm and
+ *     plain loops.
  *
  * Parity pins: see tests/test_oracle_*.py.  Unpinned by the paper itself
  * ("parity unpinned" beyond unbiasedness against Algorithm 3 and reduction to
@@ -114,6 +119,10 @@ int64_t halp_ref_quantize_real(double x, double inv_delta, uint32_t r32, int64_t
 
 /* Q_(delta_m,b) of u = (z << b) + v held in (delta_i, 2b): clamp(z + floor((v + r) / 2^b)) */
 int64_t halp_ref_round_shift(int64_t z, int64_t v, uint32_t r, int b, int* clamped);
+
+/* exp as the inner loop evaluates it (see the readings above); n values at once */
+double halp_ref_exp(double x);
+void halp_ref_exp_array(const double* x, int64_t n, double* out);
 
 /* X -> (delta_d, b): clamp(round-half-even(X / delta_d), -(2^(b-1)-1), 2^(b-1)-1);
  * Xq is int8 when b == 8, int16 when b == 16, int32 for 16 < b <= 24 (CPU only) */

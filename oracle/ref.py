@@ -49,6 +49,8 @@ def lib():
         L.halp_ref_quantize_real.restype = C.c_int64
         L.halp_ref_quantize_real.argtypes = [C.c_double, C.c_double, C.c_uint32, C.c_int64,
                                              C.c_int64, C.c_void_p]
+        L.halp_ref_exp_array.restype = None
+        L.halp_ref_exp_array.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         L.halp_ref_round_shift.restype = C.c_int64
         L.halp_ref_round_shift.argtypes = [C.c_int64, C.c_int64, C.c_uint32, C.c_int, C.c_void_p]
         L.halp_ref_philox4x32_10.restype = None
@@ -113,6 +115,14 @@ def quantize_real(x, inv_delta, r32, lo, hi):
     hit = C.c_int(0)
     q = lib().halp_ref_quantize_real(x, inv_delta, r32, lo, hi, C.addressof(hit))
     return int(q), bool(hit.value)
+
+
+def exp_inner(x):
+    """exp as the inner loop's scalar path evaluates it, elementwise"""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty_like(x)
+    lib().halp_ref_exp_array(x.ctypes.data, x.size, out.ctypes.data)
+    return out
 
 
 def round_shift(z, v, r, b):

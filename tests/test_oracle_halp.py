@@ -344,3 +344,45 @@ def test_trace_records_the_steps():
             assert i == ref.sample_index(9, 0, t, 2, m, 20)
             assert out["D"][t, m, 0] == int(Xq[i].astype(np.int64) @ z_prev[0])
         z_prev = out["ztraj"][t].astype(np.int64)
+
+
+# ---------------------------------------- scalar path of the inner loop (fp64)
+
+@pytest.mark.parametrize("loss,K,B", [(ref.SOFTMAX, 5, 1), (ref.SOFTMAX, 10, 2), (ref.SOFTMAX, 16, 1),
+                                      (ref.LOGISTIC, 1, 3)])
+def test_beta_matches_the_plain_definition(loss, K, B):
+    """beta = (alpha/B)(l'(phi_i + x_i^T z) - l'(phi_i)) recomputed with numpy's exp and plain
+    sums from the traced indices and dot products: the inner loop's own exp and its pairwise
+    normaliser agree with the definition to rounding error, class by class."""
+    N, d, b = 40, 12, 8
+    X, Xq, dd = exact_lowprec_data(N, d, b, seed=21)
+    rng = np.random.default_rng(22)
+    if loss == ref.SOFTMAX:
+        y = rng.integers(0, K, size=N).astype(np.int32)
+    else:
+        y = rng.choice([-1.0, 1.0], size=N).astype(np.float32)
+    w = (2.0 * rng.standard_normal((K, d))).astype(np.float32)  # margins of a few units
+    alpha = 0.05
+    prob = ref.make_problem(N, d, K=K, loss=loss, b=b, B=B, alpha=alpha, mu=0.05, delta_d=dd, seed=3)
+    phi, g, _ = ref.full_gradient(prob, X, y, w)
+    phi32 = phi.astype(np.float32)
+    s, h, _ = ref.recenter(prob, g.astype(np.float32), 0)
+    M = 60
+    out = ref.inner_loop(prob, Xq, phi32, y, h, s, 0, M, trace_steps=M)
+    assert np.abs(out["D"]).max() > 0
+    dscale = dd * s[0]
+    worst = 0.0
+    for t in range(M):
+        for m in range(B):
+            i = out["idx"][t, m]
+            a0 = phi32[i].astype(np.float64)
+            a1 = a0 + dscale * out["D"][t, m].astype(np.float64)
+            if loss == ref.SOFTMAX:
+                sm = lambda a: np.exp(a - a.max()) / np.exp(a - a.max()).sum()
+                want = (alpha / B) * (sm(a1) - sm(a0))
+            else:
+                dl = lambda a: -float(y[i]) / (1.0 + np.exp(float(y[i]) * a))
+                want = (alpha / B) * (dl(a1) - dl(a0))
+            worst = max(worst, np.abs(out["beta"][t, m] - want).max())
+    assert worst < 1e-15 * alpha * 20, worst
+    assert np.abs(out["beta"]).max() > 1e-6 * alpha  # the comparison is not between zeros

@@ -208,3 +208,34 @@ def test_sample_index_range_and_uniformity():
     # slot (t, m) reads word t*B+m of the IDX stream
     r = ref.stream_word(11, ref.PURPOSE_IDX, 2, 5 * B + 1)
     assert ref.sample_index(11, 2, 5, B, 1, N) == (r * N) >> 32
+
+
+# -------------------------------------------------- exp of the inner loop
+
+def test_inner_exp_is_within_one_ulp_of_exp():
+    """Against exp computed to 50 digits on sampled points (all magnitudes, subnormal results
+    included), and against libm on a dense sample."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 50
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.uniform(-745.0, 709.7, 1500), rng.uniform(-30, 30, 1500),
+                        rng.normal(0, 1, 1000), rng.uniform(-1e-6, 1e-6, 200),
+                        np.array([0.5, -0.5, np.log(2.0), -np.log(2.0) / 2, 1.0, -1.0, 100.0, -100.0])])
+    e = ref.exp_inner(x)
+    for xv, ev in zip(x, e):
+        exact = Decimal(float(xv)).exp()
+        assert abs(Decimal(float(ev)) - exact) <= Decimal(float(np.spacing(ev))), xv
+    xs = np.concatenate([rng.uniform(-700, 700, 500_000), rng.uniform(-20, 20, 500_000)])
+    es, ts = ref.exp_inner(xs), np.exp(xs)
+    assert np.all(np.abs(es - ts) <= 2 * np.spacing(ts))
+
+
+def test_inner_exp_special_values():
+    x = np.array([0.0, -0.0, -np.inf, np.inf, -745.2, -800.0, 709.79, 1e6])
+    assert np.array_equal(ref.exp_inner(x), np.array([1.0, 1.0, 0.0, np.inf, 0.0, 0.0, np.inf, np.inf]))
+    assert np.isnan(ref.exp_inner(np.array([np.nan]))[0])
+    assert np.isfinite(ref.exp_inner(np.array([709.78]))[0])
+    tiny = ref.exp_inner(np.array([-745.0, -744.0, -710.0]))  # subnormal results
+    assert np.all(tiny > 0) and np.all(tiny < 2.3e-308)
+    grid = np.linspace(-5, 5, 200_001)  # monotone
+    assert np.all(np.diff(ref.exp_inner(grid)) >= 0)
