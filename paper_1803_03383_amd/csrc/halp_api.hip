@@ -50,10 +50,20 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 int need(const void* p) { return p ? HALP_OK : HALP_ERR_NOT_BOUND; }
 
+// the register-resident family: one kernel for scalar margins, one for softmax
+int reg_supported(const halp_handle& h) {
+  return h.p.loss == HALP_LOSS_SOFTMAX ? inner_softmax_supported(h) : inner_reg_supported(h.p);
+}
+
+int launch_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
+  return h.p.loss == HALP_LOSS_SOFTMAX ? launch_inner_softmax(h, epoch, s)
+                                       : launch_inner_reg(h, epoch, s);
+}
+
 int pick_inner_variant(const halp_handle& h) {
   if (h.inner_variant == 1) return 1;
   if (h.inner_variant == 2) return 2;
-  return inner_reg_supported(h.p) == HALP_OK ? 2 : 1;
+  return reg_supported(h) == HALP_OK ? 2 : 1;
 }
 
 int check_epoch(int64_t epoch) {
@@ -79,7 +89,7 @@ int need_inner(const halp_handle& h, int variant) {
     return HALP_ERR_NOT_BOUND;
   if (h.p.loss != HALP_LOSS_SQUARED && !h.buf.phi) return HALP_ERR_NOT_BOUND;
   if (h.p.loss == HALP_LOSS_LOGISTIC && !h.buf.y) return HALP_ERR_NOT_BOUND;
-  if (variant == 2) return inner_reg_supported(h.p);
+  if (variant == 2) return reg_supported(h);
   return HALP_OK;
 }
 
@@ -231,7 +241,7 @@ int halp_inner_loop(halp_handle* h, int64_t epoch, void* stream) {
   const int variant = pick_inner_variant(*h);
   rc = need_inner(*h, variant);
   if (rc != HALP_OK) return rc;
-  rc = variant == 2 ? launch_inner_reg(*h, (uint32_t)epoch, as_stream(stream))
+  rc = variant == 2 ? launch_reg(*h, (uint32_t)epoch, as_stream(stream))
                     : launch_inner_generic(*h, (uint32_t)epoch, TraceBufs{}, as_stream(stream));
   if (rc == HALP_OK) h->last_inner_variant = variant;
   return rc;
@@ -268,7 +278,7 @@ int halp_epoch(halp_handle* h, int64_t epoch, void* stream) {
   if (h->timing && hipEventRecord(ev[1], s) != hipSuccess) return HALP_ERR_HIP;
   if ((rc = launch_recenter(*h, (uint32_t)epoch, s)) != HALP_OK) return rc;
   if (h->timing && hipEventRecord(ev[2], s) != hipSuccess) return HALP_ERR_HIP;
-  rc = variant == 2 ? launch_inner_reg(*h, (uint32_t)epoch, s)
+  rc = variant == 2 ? launch_reg(*h, (uint32_t)epoch, s)
                     : launch_inner_generic(*h, (uint32_t)epoch, TraceBufs{}, s);
   if (rc != HALP_OK) return rc;
   h->last_inner_variant = variant;

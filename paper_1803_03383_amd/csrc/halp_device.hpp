@@ -136,6 +136,33 @@ __device__ __forceinline__ long long wave_sum_i64(long long v) {
   return (long long)(((uint64_t)hi << 32) | lo);
 }
 
+// ---- exp of the inner loop's scalar path -----------------------------------------
+// l'(phi + x^T z) - l'(phi) is rounded to the integer gamma (Algorithm 4), so the last bit of
+// exp can decide an integer.  The library fixes exp as this sequence of correctly rounded
+// double operations, which every conforming implementation reproduces bit for bit:
+//   k = rint(x log2 e);  r = x - k ln2 (ln2 in two parts, fused multiply-adds);
+//   e^r = 1 + (r + r^2 Q(r)),  Q = sum_{n=2..13} r^(n-2)/n!  joined pairwise by r, r^2, r^4;
+//   exp(x) = e^r 2^k.   Within 1 ulp of exp; a short dependency chain, no table.
+__device__ __forceinline__ double halp_exp(double x) {
+  const double k = __builtin_rint(__dmul_rn(x, 0x1.71547652b82fep+0));
+  double r = __fma_rn(-k, 0x1.62e42fefa39efp-1, x);
+  r = __fma_rn(-k, 0x1.abc9e3b39803fp-56, r);
+  const double r2 = __dmul_rn(r, r), r4 = __dmul_rn(r2, r2);
+  const double a0 = __fma_rn(0x1.5555555555555p-3, r, 0x1.0000000000000p-1);
+  const double a1 = __fma_rn(0x1.1111111111111p-7, r, 0x1.5555555555555p-5);
+  const double a2 = __fma_rn(0x1.a01a01a01a01ap-13, r, 0x1.6c16c16c16c17p-10);
+  const double a3 = __fma_rn(0x1.71de3a556c734p-19, r, 0x1.a01a01a01a01ap-16);
+  const double a4 = __fma_rn(0x1.ae64567f544e4p-26, r, 0x1.27e4fb7789f5cp-22);
+  const double a5 = __fma_rn(0x1.6124613a86d09p-33, r, 0x1.1eed8eff8d898p-29);
+  const double b0 = __fma_rn(a1, r2, a0), b1 = __fma_rn(a3, r2, a2), b2 = __fma_rn(a5, r2, a4);
+  const double q = __fma_rn(__fma_rn(b2, r4, b1), r4, b0);
+  const double e = __dadd_rn(__fma_rn(r2, q, r), 1.0);
+  double res = ldexp(e, (int)k);
+  res = x > 0x1.62e42fefa39efp+9 ? __builtin_inf() : res;  // above log(DBL_MAX)
+  res = x < -0x1.74910d52d3052p+9 ? 0.0 : res;             // below half the least subnormal
+  return x != x ? x : res;
+}
+
 // ---- quantizers -------------------------------------------------------------
 
 // Real -> integer lattice: clamp(floor(x * inv_delta + rho)), rho = r32 / 2^32.

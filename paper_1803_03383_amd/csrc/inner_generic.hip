@@ -12,7 +12,7 @@ namespace {
 
 __device__ __forceinline__ double logistic_dl(double a, double y) {
   // l'(a) for l(a) = log(1 + exp(-y a))
-  return __ddiv_rn(-y, __dadd_rn(1.0, exp(__dmul_rn(y, a))));
+  return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
 }
 
 template <int BITS>
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
     __syncthreads();
     // beta = (alpha/B)(l'(phi_i + x_i^T z) - l'(phi_i)); gamma = Q_(delta_s, b)(beta).
     // One thread per (row, class) pair; the softmax normalisers are formed per row, the
-    // exponentials summed in class order.
+    // exponentials summed pairwise over adjacent classes.
     const bool softmax = a.loss == HALP_LOSS_SOFTMAX;
     if (softmax) {
       if (tid < B) {
@@ -126,16 +126,27 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
         const int m = pr / K, c = pr % K;
         const double a0 = (double)phi[idxs[m] * K + c];
         const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[pr]));
-        es[2 * pr + 0] = exp(__dadd_rn(a0, -rowst[4 * m + 0]));
-        es[2 * pr + 1] = exp(__dadd_rn(a1, -rowst[4 * m + 1]));
+        es[2 * pr + 0] = halp_exp(__dadd_rn(a0, -rowst[4 * m + 0]));
+        es[2 * pr + 1] = halp_exp(__dadd_rn(a1, -rowst[4 * m + 1]));
       }
       __syncthreads();
       if (tid < B) {
-        double s0 = 0, s1 = 0;
-        for (int c = 0; c < K; ++c) {
-          s0 = __dadd_rn(s0, es[2 * (tid * K + c) + 0]);
-          s1 = __dadd_rn(s1, es[2 * (tid * K + c) + 1]);
+        // pairwise over adjacent classes (absent classes count as +0), K <= 16
+        double v0[16], v1[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+          v0[c] = c < K ? es[2 * (tid * K + c) + 0] : 0.0;
+          v1[c] = c < K ? es[2 * (tid * K + c) + 1] : 0.0;
         }
+#pragma unroll
+        for (int P = 16; P > 1; P /= 2) {
+#pragma unroll
+          for (int c = 0; c < P / 2; ++c) {
+            v0[c] = __dadd_rn(v0[2 * c], v0[2 * c + 1]);
+            v1[c] = __dadd_rn(v1[2 * c], v1[2 * c + 1]);
+          }
+        }
+        const double s0 = v0[0], s1 = v1[0];
         rowst[4 * tid + 2] = s0;
         rowst[4 * tid + 3] = s1;
       }

@@ -35,7 +35,7 @@ constexpr int kBatch = 256;  // steps per batch of precomputed draws
 constexpr int kWin = 8;      // steps per window
 
 __device__ __forceinline__ double logistic_dl(double a, double y) {
-  return __ddiv_rn(-y, __dadd_rn(1.0, exp(__dmul_rn(y, a))));
+  return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
 }
 
 // a * b + c on the 24-bit multiplier; a and b must fit 24 bits (they are codes of at most

@@ -1,0 +1,467 @@
+// Inner loop of Algorithm 4 (LM-HALP) for softmax regression (K classes, one
+// sampled row per step), register-resident form with specialised waves.
+//
+// One workgroup per chain: K class waves and one service wave.
+//
+// Class wave c owns row c of z ([K][d]): lane l holds the UPL consecutive strips
+// (16 rounding bits each) starting at l * UPL, with -h~ and the strips' Philox
+// blocks of the current window of 8 steps, in registers for the whole epoch.
+//
+// The service wave owns everything that does not scale with d: it draws the
+// sample indices, fetches the sampled rows of the quantized data and their margins
+// two windows ahead and stages them in LDS, draws the rounding words of gamma and
+// of the L2 term, and evaluates the softmax.  It holds no part of z, so its
+// double-precision work has the register file to itself.
+//
+// One step:
+//   class waves   x_i^T z_c (24-bit multiply-adds, DPP fold), one LDS word each      | barrier
+//   service wave  softmax before and after the offset, one class per lane (lanes c    |
+//                 and 16 + c), gamma_c = Q_(delta_s,b)(beta_c) into LDS;              |
+//   class waves   meanwhile: operands of the update that do not need gamma, and one   |
+//                 Philox block of the next window (parked in LDS until it starts)     | barrier
+//   class waves   integer update of row c of z;
+//   service wave  meanwhile, once per window: stage the next window, request the one after.
+#include "halp_device.hpp"
+#include "inner_args.hpp"
+
+namespace halp {
+namespace {
+
+constexpr int kWin = 8;   // steps per window
+constexpr int kKC = 16;   // classes are padded to one DPP row
+constexpr int kRowQ = 4;  // dwords of a row per service lane: rows up to 1 KB
+
+__device__ __forceinline__ int mad24(int a, int b, int c) {
+  int r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// the value of lane ^ 16 (the two rows of each half-wave trade places)
+__device__ __forceinline__ double swap16_f64(double v) {
+  const uint64_t u = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)u, 0x401F);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(u >> 32), 0x401F);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+template <typename F>
+__device__ __forceinline__ double row_fold_f64(double v, F op) {
+  auto step = [&](double x, auto mv) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, x);
+    const uint32_t lo = (uint32_t)mv((int)(uint32_t)u), hi = (uint32_t)mv((int)(u >> 32));
+    return op(x, __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo));
+  };
+  v = step(v, [](int t) { return dpp_quad_swap1(t); });
+  v = step(v, [](int t) { return dpp_quad_swap2(t); });
+  v = step(v, [](int t) { return dpp_half_mirror(t); });
+  v = step(v, [](int t) { return dpp_row_mirror(t); });
+  return v;
+}
+
+// Sum over each row of 16 lanes, left in every lane of the row: lanes are joined in
+// adjacent pairs, the pairs' sums in adjacent pairs, and so on (a + b and b + a round
+// alike, so every lane of a group holds the same bits).
+__device__ __forceinline__ double row_sum_f64(double v) {
+  return row_fold_f64(v, [](double x, double y) { return __dadd_rn(x, y); });
+}
+
+// maximum over each row of 16 lanes, left in every lane of the row
+__device__ __forceinline__ double row_max_f64(double v) {
+  return row_fold_f64(v, [](double x, double y) { return fmax(x, y); });
+}
+
+template <int BITS, int UPL, int KT>
+__global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
+  using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
+  using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
+  using AccT = typename std::conditional<BITS == 8, int, long long>::type;
+  constexpr int CT = 16 / BITS;
+  constexpr int CPL = UPL * CT;
+  constexpr int NDW = (UPL + 1) / 2;
+  constexpr int PQ = UPL >= 4 ? UPL / 4 : 1;  // 16-byte slots per word of a lane's parked blocks
+  constexpr int QMAX = (1 << (BITS - 1)) - 1, QMIN = -(1 << (BITS - 1));
+  const int chain = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int d = a.d, K = a.K;
+  const int NTc = 64 * K;  // class-wave threads
+  const int U = (d + CT - 1) / CT;
+  const int64_t T = a.T;
+  const int64_t row_bytes = a.ldxq * (BITS / 8);
+  const int row_dw = (int)(row_bytes / 4);
+  const double* sc = a.scales + (int64_t)chain * 8;
+  uint64_t* cnt_out = a.counters + (int64_t)chain * 4;
+  const uint64_t seed = a.seed + (uint64_t)chain;
+
+  if (sc[7] != 0.0) {
+    if (tid < 4) cnt_out[tid] = 0;
+    return;
+  }
+
+  __shared__ __attribute__((aligned(16))) uint32_t s_rho[2][kWin][kKC];  // words of the gamma stream
+  __shared__ __attribute__((aligned(16))) float s_phi[2][kWin][kKC];     // margins of the sampled rows
+  __shared__ int s_creg[2][kWin];                                        // c_lambda
+  __shared__ __attribute__((aligned(16))) AccT s_D[2][kKC];              // x_i^T z_c
+  __shared__ int s_ng[2][kKC];                                           // -gamma_c
+  __shared__ unsigned long long s_cnt[3];
+  // [2][kWin][row_dw] staged rows, then the parked Philox blocks: [word][slot][class thread]
+  // of 16 bytes, so that a wave reads consecutive addresses; a thread reads only its own
+  extern __shared__ __attribute__((aligned(16))) uint32_t s_ring[];
+  uint32_t* s_park = s_ring + 2 * kWin * row_dw;
+
+  if (tid < 3) s_cnt[tid] = 0;
+  const bool use_reg = a.lambda > 0;
+
+  if (wave == K) {
+    // ===================================================================== service wave
+    const uint32_t N = (uint32_t)a.N;
+    const unsigned char* __restrict__ Xq = reinterpret_cast<const unsigned char*>(a.Xq) +
+                                           (int64_t)chain * a.xq_chain_stride * (BITS / 8);
+    const float* __restrict__ phi = a.phi + (int64_t)chain * a.N * K;
+    const double delta_m = sc[0], inv_s = sc[5];
+    const double dscale = __dmul_rn(a.delta_d, delta_m);
+    const double aB = a.alpha;  // B = 1
+    const double al = __dmul_rn(a.alpha, a.lambda);
+    unsigned int n_gclamp = 0, n_reg = 0;
+
+    // sample index of step tw + (lane & 7): any step number names a valid row, so windows
+    // past T are fetched like the others and never used
+    auto draw_idx = [&](int64_t tw) {
+      const uint64_t t = (uint64_t)tw + (uint64_t)(lane & 7);
+      const U4 r = stream_block(seed, kIdx, a.epoch, t >> 2);
+      return (int)__umulhi(pick(r, (uint32_t)(t & 3)), N);
+    };
+    uint32_t xn[kWin][kRowQ];
+    float phin[2];
+    // dwords lane, lane + 64, ... of the window's rows; 8K margins, two per lane
+    auto request = [&](int idxv) {
+#pragma unroll
+      for (int s = 0; s < kWin; ++s) {
+        const int i = __builtin_amdgcn_readlane(idxv, s);
+        const uint32_t* row = reinterpret_cast<const uint32_t*>(Xq + (int64_t)i * row_bytes);
+#pragma unroll
+        for (int q = 0; q < kRowQ; ++q) xn[s][q] = row[min(lane + 64 * q, row_dw - 1)];
+      }
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int e = min(lane + 64 * q, kWin * K - 1);
+        const int s = e / K, c = e - s * K;
+        phin[q] = phi[(int64_t)__shfl(idxv, s) * K + c];
+      }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+      for (int s = 0; s < kWin; ++s)
+#pragma unroll
+        for (int q = 0; q < kRowQ; ++q)
+          if (lane + 64 * q < row_dw) s_ring[(buf * kWin + s) * row_dw + lane + 64 * q] = xn[s][q];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int e = lane + 64 * q;
+        if (e < kWin * K) {
+          const int s = e / K, c = e - s * K;
+          s_phi[buf][s][c] = phin[q];
+        }
+      }
+    };
+    // rounding words of gamma (word t*K + c of that stream; a window starts at a multiple
+    // of 4 words) and c_lambda = Q_(2^-b, b)(alpha lambda) for the window starting at tw
+    auto draw_scalars = [&](int64_t tw, int buf) {
+      const uint64_t n0 = (uint64_t)tw * (uint64_t)K;
+      if (lane < 2 * K) {
+        const U4 rg = stream_block(seed, kGamma, a.epoch, (n0 >> 2) + (uint64_t)lane);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int rel = 4 * lane + e;  // = step * K + class
+          const int s = rel / K;
+          s_rho[buf][s][rel - s * K] = pick(rg, e);
+        }
+      }
+      if (use_reg && lane < kWin) {
+        const uint64_t t = (uint64_t)tw + (uint64_t)lane;
+        const U4 rr = stream_block(seed, kReg, a.epoch, t >> 2);
+        const int cl = (int)quantize_real(al, (double)(1 << BITS), pick(rr, (uint32_t)(t & 3)), 0.0,
+                                          (double)QMAX, nullptr);
+        s_creg[buf][lane] = cl;
+        n_reg += (cl != 0 && (int64_t)t < T) ? 1u : 0u;
+      }
+    };
+
+    // window 0 staged, window 1 requested
+    request(draw_idx(0));
+    stage(0);
+    draw_scalars(0, 0);
+    request(draw_idx(kWin));
+    __syncthreads();
+
+    const int lc = lane & 15;
+    const bool after = (lane & 16) != 0;
+    const bool live = lc < K;
+    for (int64_t t0 = 0; t0 < T; t0 += kWin) {
+      const int buf = (int)((t0 >> 3) & 1);
+      for (int s = 0; s < kWin && t0 + s < T; ++s) {
+        __syncthreads();  // the dot products of this step are in LDS
+        double val = -INFINITY;
+        uint32_t rw = 0;
+        if (live) {
+          const double a0 = (double)s_phi[buf][s][lc];
+          val = after ? __dadd_rn(a0, __dmul_rn(dscale, (double)s_D[s & 1][lc])) : a0;
+          rw = s_rho[buf][s][lc];
+        }
+        const double mx = row_max_f64(val);
+        const double e = live ? halp_exp(__dadd_rn(val, -mx)) : 0.0;
+        // normaliser: pairwise over adjacent classes, the order the DPP fold gives
+        const double p = __ddiv_rn(e, row_sum_f64(e));
+        const double diff = __dadd_rn(swap16_f64(p), -p);  // lanes 0..15: p_after - p_before
+        // beta_c = alpha (p_c(phi + x^T z) - p_c(phi)), gamma_c = Q_(delta_s, b)(beta_c)
+        const double beta = __dmul_rn(aB, diff);
+        const double rho = __dmul_rn((double)rw, 0x1p-32);
+        const double f = floor(__dadd_rn(__dmul_rn(beta, inv_s), rho));
+        const double fc = fmin(fmax(f, (double)QMIN), (double)QMAX);
+        if (lane < K) {
+          n_gclamp += (f != fc) ? 1u : 0u;
+          s_ng[s & 1][lane] = (int)(-fc);
+        }
+        __syncthreads();  // gamma is out; the class waves update z
+        if (s == 0) {
+          // The other buffers were last read in the previous window: stage the next window
+          // there, and request the one after it, which has eight steps to arrive.
+          stage(buf ^ 1);
+          draw_scalars(t0 + kWin, buf ^ 1);
+          request(draw_idx(t0 + 2 * kWin));
+        }
+      }
+    }
+    if (n_gclamp) atomicAdd(&s_cnt[1], (unsigned long long)n_gclamp);
+    if (n_reg) atomicAdd(&s_cnt[2], (unsigned long long)n_reg);
+  } else {
+    // ======================================================================= class wave
+    const int cls = wave;
+    const int64_t row0 = ((int64_t)chain * K + cls) * d;
+    const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + row0;
+    XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + row0;
+    float* __restrict__ wg = a.w + row0;
+    const int s0 = lane * UPL;
+    const int j0 = s0 * CT;
+    const bool lane_ok = s0 < U;
+    int z[CPL];
+    int hv[CPL];  // -h~ at b = 8, h~ at b = 16
+    uint32_t xmask[NDW];
+#pragma unroll
+    for (int k = 0; k < NDW; ++k) xmask[k] = 0;
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+      const int j = j0 + k;
+      const bool ok = j < d;
+      z[k] = ok ? (int)zg[j] : 0;
+      hv[k] = ok ? (BITS == 8 ? -(int)hg[j] : (int)hg[j]) : 0;
+      if (ok) xmask[(k * BITS) / 32] |= (BITS == 8 ? 0xFFu : 0xFFFFu) << ((k * BITS) % 32);
+    }
+    const int frag_dw = lane_ok ? (s0 * 2) >> 2 : 0;  // dword index of the fragment in a row
+    const int half_sh = (UPL == 1 && lane_ok) ? ((s0 * 2) & 2) * 8 : 0;
+    const uint32_t strip0 = (uint32_t)(cls * U + s0);
+    const uint4* park = reinterpret_cast<const uint4*>(s_park);
+
+    uint32_t zrw[4][UPL];  // the window's rounding words: [word of the block][strip]
+#pragma unroll
+    for (int u = 0; u < UPL; ++u) {
+      const U4 r = zround_block(seed, a.epoch, strip0 + (uint32_t)u, 0u);
+      zrw[0][u] = r.x; zrw[1][u] = r.y; zrw[2][u] = r.z; zrw[3][u] = r.w;
+    }
+    unsigned long long n_zclamp = 0;
+    __syncthreads();
+
+    for (int64_t t0 = 0; t0 < T; t0 += kWin) {
+      const int buf = (int)((t0 >> 3) & 1);
+      const bool more = t0 + kWin < T;
+      if (t0 > 0) {  // the blocks parked during the previous window
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd)
+#pragma unroll
+          for (int q = 0; q < PQ; ++q) {
+            const uint4 v = park[(wd * PQ + q) * NTc + tid];
+            if (4 * q + 0 < UPL) zrw[wd][(4 * q + 0) % UPL] = v.x;
+            if (4 * q + 1 < UPL) zrw[wd][(4 * q + 1) % UPL] = v.y;
+            if (4 * q + 2 < UPL) zrw[wd][(4 * q + 2) % UPL] = v.z;
+            if (4 * q + 3 < UPL) zrw[wd][(4 * q + 3) % UPL] = v.w;
+          }
+      }
+#pragma unroll
+      for (int s = 0; s < kWin; ++s) {
+        if (t0 + s < T) {
+          // this lane's fragment of the row, from the ring
+          uint32_t xw[NDW];
+          {
+            const uint32_t* rp = s_ring + (buf * kWin + s) * row_dw + frag_dw;
+            if (NDW == 1) {
+              xw[0] = rp[0];
+            } else if (NDW == 2) {
+              const uint2 v = *reinterpret_cast<const uint2*>(rp);
+              xw[0] = v.x; xw[NDW > 1 ? 1 : 0] = v.y;
+            } else {
+              const uint4 v = *reinterpret_cast<const uint4*>(rp);
+              xw[0] = v.x; xw[NDW > 1 ? 1 : 0] = v.y; xw[NDW > 2 ? 2 : 0] = v.z; xw[NDW > 3 ? 3 : 0] = v.w;
+            }
+#pragma unroll
+            for (int k = 0; k < NDW; ++k) xw[k] = (UPL == 1 ? xw[k] >> half_sh : xw[k]) & xmask[k];
+          }
+          int xe[CPL];
+          AccT part = 0;
+#pragma unroll
+          for (int k = 0; k < CPL; ++k) {
+            const uint32_t xv = xw[(k * BITS) / 32];
+            const int xs = (k * BITS) % 32;
+            xe[k] = BITS == 8 ? (int)(int8_t)(xv >> xs) : (int)(int16_t)(xv >> xs);
+            if (BITS == 8) part = (AccT)mad24(xe[k], z[k], (int)part);
+            else part += (AccT)((long long)xe[k] * (long long)z[k]);
+          }
+          AccT D;
+          if (BITS == 8) D = (AccT)wave_sum_i32((int)part);
+          else D = (AccT)wave_sum_i64((long long)part);
+          if (lane == 0) s_D[s & 1][cls] = D;
+          __syncthreads();
+          // While the service wave evaluates the softmax: the part of the update that does
+          // not need gamma, and one Philox block of the next window.
+          int hr[CPL];  // b = 8: -h~ + rounding bits; b = 16: the rounding bits
+#pragma unroll
+          for (int k = 0; k < CPL; ++k) {
+            const uint32_t word = zrw[s >> 1][k / CT];
+            const int sh = 16 * (s & 1) + (k % CT) * BITS;
+            const int re = (int)((word >> sh) & (BITS == 8 ? 0xFFu : 0xFFFFu));
+            hr[k] = BITS == 8 ? hv[k] + re : re;
+          }
+          if (s < UPL && more) {
+            const U4 r = zround_block(seed, a.epoch, strip0 + (uint32_t)s, (uint32_t)(t0 >> 3) + 1u);
+            uint32_t* slot = s_park + ((size_t)((s / 4) * NTc + tid)) * 4 + (s % 4);
+            const size_t word_stride = (size_t)PQ * NTc * 4;
+            slot[0] = r.x; slot[word_stride] = r.y; slot[2 * word_stride] = r.z; slot[3 * word_stride] = r.w;
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          __syncthreads();
+          const int ng = __builtin_amdgcn_readfirstlane(s_ng[s & 1][cls]);
+          const int cl = use_reg ? __builtin_amdgcn_readfirstlane(s_creg[buf][s]) : 0;
+          // u = z - gamma x - h~ (- c_lambda z), z = Q_(delta_m, b)(u)
+          auto update = [&](auto with_l2) {
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+              int zu;
+              if (BITS == 8) {
+                int hk = hr[k];
+                if (decltype(with_l2)::value) hk = mad24(-cl, z[k], hk);
+                zu = z[k] + (mad24(ng, xe[k], hk) >> 8);
+              } else {
+                long long hk = (long long)hr[k] - (long long)hv[k];
+                if (decltype(with_l2)::value) hk -= (long long)(cl * z[k]);
+                const long long v = (long long)ng * (long long)xe[k] + hk;
+                zu = z[k] + (int)(v >> 16);
+              }
+              const int zc = min(max(zu, QMIN), QMAX);
+              // clamps are counted on the scalar unit: one compare here, the rest is wave-wide
+              n_zclamp += (unsigned long long)__builtin_popcountll(__ballot(zu != zc));
+              z[k] = zc;
+            }
+          };
+          if (cl != 0) update(std::true_type{});  // the L2 term is rare: c_lambda is mostly 0
+          else update(std::false_type{});
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep one step's temporaries from overlapping the next's
+      }
+    }
+
+    // ---- w~ <- w~ + delta_m z (option I); hand z out
+    const double delta_m = sc[0];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+      const int j = j0 + k;
+      if (j < d) {
+        zg[j] = (XT)z[k];
+        wg[j] = (float)__dadd_rn((double)wg[j], __dmul_rn(delta_m, (double)z[k]));
+      }
+    }
+    if (lane == 0 && n_zclamp) atomicAdd(&s_cnt[0], n_zclamp);  // wave-wide count
+  }
+  __syncthreads();
+  if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
+}
+
+template <int BITS, int UPL>
+int launch_kt(const InArgs& a, int R, size_t smem, hipStream_t s) {
+  const dim3 grid(R), block(64 * (a.K + 1));
+#define HALP_SM(KT_)                                                                              \
+  do {                                                                                            \
+    auto kern = inner_softmax_kernel<BITS, UPL, KT_>;                                             \
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) \
+      return HALP_ERR_HIP;                                                                        \
+    hipLaunchKernelGGL(kern, grid, block, smem, s, a);                                            \
+  } while (0)
+  if (a.K + 1 <= 4) HALP_SM(4);
+  else if (a.K + 1 <= 8) HALP_SM(8);
+  else if (a.K + 1 <= 12) HALP_SM(12);
+  else HALP_SM(16);
+#undef HALP_SM
+  return hip_ok(hipGetLastError());
+}
+
+template <int BITS>
+int launch_upl(const InArgs& a, int upl, int R, size_t smem, hipStream_t s) {
+  switch (upl) {
+    case 1: return launch_kt<BITS, 1>(a, R, smem, s);
+    case 2: return launch_kt<BITS, 2>(a, R, smem, s);
+    case 4: return launch_kt<BITS, 4>(a, R, smem, s);
+    case 8: return launch_kt<BITS, 8>(a, R, smem, s);
+    default: return HALP_ERR_UNSUPPORTED;
+  }
+}
+
+int strips_per_lane(const halp_params& p) {
+  const int ct = 16 / p.b;
+  const int U = (p.d + ct - 1) / ct;
+  const int upl = (U + 63) / 64;
+  int u2 = 1;
+  while (u2 < upl) u2 *= 2;
+  return u2;
+}
+
+// the ring of staged rows, and the parked Philox blocks (16 bytes per strip, 64 at least,
+// per class thread)
+size_t dynamic_lds(const halp_params& p, int64_t row_bytes) {
+  const int upl = strips_per_lane(p);
+  return (size_t)2 * kWin * (size_t)row_bytes + (size_t)64 * p.K * 16 * (size_t)(upl >= 4 ? upl : 4);
+}
+
+}  // namespace
+
+// softmax, one row per step, at most 15 classes (one wave each, plus the service wave), a
+// class's row of z within one wave (8 strips per lane at most), data rows up to 1 KB
+int inner_softmax_supported(const halp_handle& h) {
+  const halp_params& p = h.p;
+  if (p.loss != HALP_LOSS_SOFTMAX || p.B != 1 || p.K < 2 || p.K > 15) return HALP_ERR_UNSUPPORTED;
+  if (p.b == 8 && p.d > 131071) return HALP_ERR_UNSUPPORTED;  // int32 dot product stays exact
+  const int upl = strips_per_lane(p);
+  if (upl > 8) return HALP_ERR_UNSUPPORTED;
+  if (!h.bound || !h.buf.Xq) return HALP_ERR_NOT_BOUND;
+  const int64_t row_bytes = h.buf.ldxq * (p.b / 8);
+  const int ct = 16 / p.b;
+  const int U = (p.d + ct - 1) / ct;
+  // fragments are read whole (2 * UPL bytes, up to 16) from the staged row
+  const int frag = upl == 8 ? 16 : (upl == 4 ? 8 : 4);
+  if (row_bytes % frag != 0 || row_bytes / 4 > 64 * kRowQ) return HALP_ERR_UNSUPPORTED;
+  if ((int64_t)((U + upl - 1) / upl) * upl * 2 > row_bytes) return HALP_ERR_UNSUPPORTED;
+  if (dynamic_lds(p, row_bytes) > 150 * 1024) return HALP_ERR_UNSUPPORTED;
+  return HALP_OK;
+}
+
+int launch_inner_softmax(const halp_handle& h, uint32_t epoch, hipStream_t s) {
+  const halp_params& p = h.p;
+  const int rc = inner_softmax_supported(h);
+  if (rc != HALP_OK) return rc;
+  const InArgs a = make_inner_args(h, epoch);
+  const int upl = strips_per_lane(p);
+  const size_t smem = dynamic_lds(p, h.buf.ldxq * (p.b / 8));
+  return p.b == 8 ? launch_upl<8>(a, upl, p.R, smem, s) : launch_upl<16>(a, upl, p.R, smem, s);
+}
+
+}  // namespace halp

@@ -258,6 +258,56 @@ def _oracle_inner(case, r, T):
     return _ORACLE_CACHE[key]
 
 
+SOFTMAX_REG_CASES = [
+    # N, d, K, b, lam, R, T, mu
+    (400, 784, 10, 8, 1e-4, 2, 303, 0.05),    # the 10-class shape: 8 strips per lane, ragged wave
+    (300, 100, 3, 8, 1e-2, 2, 1000, 0.05),    # one strip per lane, few classes, L2 draws
+    (300, 256, 15, 16, 1e-3, 1, 203, 0.05),   # 15 classes at 16 bits
+    (200, 1024, 12, 8, 0.0, 1, 150, 0.05),    # every lane full
+    (250, 200, 5, 16, 0.0, 1, 520, 0.05),     # crosses two batches of draws
+    (100, 64, 2, 8, 0.0, 1, 1, 0.05),         # a single step
+    (100, 64, 2, 8, 0.0, 1, 0, 0.05),         # no step at all
+    (64, 64, 4, 8, 0.0, 1, 600, 500.0),       # box far too small: z saturates
+]
+
+
+@pytest.mark.parametrize("variant", [2, 1])
+@pytest.mark.parametrize("N,d,K,b,lam,R,T,mu", SOFTMAX_REG_CASES)
+def test_inner_loop_softmax_bit_exact(N, d, K, b, lam, R, T, mu, variant):
+    loss = hp.LOSS_SOFTMAX
+    seed = 70 + d + T
+    case = _inner_case(loss, N, d, K, 1, b, lam, R, T, seed, mu=mu)
+    P = _run_inner(case, loss, K, 1, b, lam, R, T, seed, variant, mu=mu)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    assert P.h.get_stats(0).inner_variant == variant
+    for r in range(R):
+        prob = case["mk"](r)
+        out = ref.inner_loop(prob, case["Xq"][r], case["phi"][r], case["y"][r], case["h"][r],
+                             case["scales"][r], 3, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        assert np.array_equal(w[r], ref.apply_offset(prob, case["scales"][r], out["z"], case["w"][r]))
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    if mu > 100:
+        assert cnt[0, 0] > 0
+
+
+def test_softmax_shapes_outside_the_register_kernel_fall_back():
+    # 784 coordinates at 16 bits need more than 8 strips per lane: the automatic choice is the
+    # general kernel, and forcing the register kernel is an error, not a wrong answer
+    loss, N, d, K, b, T = hp.LOSS_SOFTMAX, 120, 784, 10, 16, 40
+    case = _inner_case(loss, N, d, K, 1, b, 0.0, 1, T, 77, mu=0.05)
+    P = _run_inner(case, loss, K, 1, b, 0.0, 1, T, 77, 0, mu=0.05)
+    P.h.inner_loop(3)
+    assert P.h.get_stats(0).inner_variant == 1
+    out = ref.inner_loop(case["mk"](0), case["Xq"][0], case["phi"][0], case["y"][0], case["h"][0],
+                         case["scales"][0], 3, T)
+    assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
+    P.h.set_option(hp.OPT_INNER_VARIANT, 2)
+    with pytest.raises(hp.HalpError):
+        P.h.inner_loop(3)
+
+
 GENERIC_CASES = [
     # loss, N, d, K, B, b, lam, R, T
     (hp.LOSS_SOFTMAX, 400, 784, 10, 1, 8, 1e-4, 1, 300),
