@@ -132,8 +132,9 @@ def c5_full_gradient(hp, inp, torch, reps=5):
 
 
 def side_inner_loop(hp, inp, torch, which, T):
-    """Inner-loop step rate of the configurations that run on the general kernel (softmax
-    K=10 at b=8/16; logistic with a minibatch of 64 at b=16), at a reduced step count."""
+    """Inner-loop step rate of the configurations beside the headline one (softmax K=10 at
+    b=8/16; logistic with a minibatch of 64 at b=16), at a reduced step count; `inner_variant`
+    says which kernel ran (1 general, 2 register-resident)."""
     out = {}
     if which == "c3":
         N, d, K = 60000, 784, 10
@@ -177,8 +178,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c5"],
-                    help="c4 (default), c2, c1: the headline line; c3, c5: step rate of the "
-                         "configurations that run on the general inner-loop kernel")
+                    help="c4 (default), c2, c1: the headline line; c3, c5: inner-loop step rate "
+                         "of the softmax and minibatch configurations")
     ap.add_argument("--inner-steps", type=int, default=2000, help="T for --workload c3 / c5")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
@@ -203,7 +204,7 @@ def main():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
     if args.workload in ("c3", "c5"):
-        print(json.dumps({"workload": args.workload, "inner_loop_general_kernel":
+        print(json.dumps({"workload": args.workload, "side_inner_loop":
                           side_inner_loop(hp, inp, torch, args.workload, args.inner_steps)}))
         return
     cfg = dict(WORKLOADS[args.workload])

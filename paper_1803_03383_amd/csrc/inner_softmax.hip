@@ -372,12 +372,15 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
 
     // ---- w~ <- w~ + delta_m z (option I); hand z out
     const double delta_m = sc[0];
+    float wv[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) wv[k] = wg[min(j0 + k, d - 1)];  // all loads in flight at once
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
       const int j = j0 + k;
       if (j < d) {
         zg[j] = (XT)z[k];
-        wg[j] = (float)__dadd_rn((double)wg[j], __dmul_rn(delta_m, (double)z[k]));
+        wg[j] = (float)__dadd_rn((double)wv[k], __dmul_rn(delta_m, (double)z[k]));
       }
     }
     if (lane == 0 && n_zclamp) atomicAdd(&s_cnt[0], n_zclamp);  // wave-wide count
