@@ -12,6 +12,7 @@
 // LDS; a second small kernel adds the per-workgroup partials in a fixed order
 // (fp64), so the result does not depend on scheduling.
 #include "halp_device.hpp"
+#include "fullgrad_args.hpp"
 #include "halp_internal.hpp"
 
 namespace halp {
@@ -20,17 +21,6 @@ namespace {
 typedef float F4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ F4 make_f4(float a, float b, float c, float d) { return F4{a, b, c, d}; }
 
-struct FgArgs {
-  const float* X;
-  const void* y;
-  const float* w;
-  float* phi;
-  float* partial_g;
-  double* partial_loss;
-  int64_t N, ldx;
-  int64_t x_chain_stride, y_chain_stride;  // 0 when chains share the data
-  int d, K, parts;
-};
 
 __device__ __forceinline__ float dot4(const F4& a, const F4& b, float acc) {
   acc = __builtin_fmaf(a.x, b.x, acc);
@@ -190,135 +180,6 @@ __global__ __launch_bounds__(256) void fullgrad_k1(FgArgs a) {
   }
 }
 
-// ---- softmax: KC classes held in registers -----------------------------------
-template <int NV, int KC>
-__global__ __launch_bounds__(256) void fullgrad_softmax(FgArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int chain = blockIdx.y;
-  const int d = a.d, K = a.K;
-  const float* __restrict__ X = a.X + (int64_t)chain * a.x_chain_stride;
-  const int32_t* __restrict__ y =
-      reinterpret_cast<const int32_t*>(a.y) + (int64_t)chain * a.y_chain_stride;
-  const float* __restrict__ w = a.w + (int64_t)chain * K * d;
-  float* __restrict__ phi = a.phi + (int64_t)chain * a.N * K;
-  const int64_t N = a.N, ldx = a.ldx;
-
-  F4 wv[KC][NV], gv[KC][NV];
-#pragma unroll
-  for (int c = 0; c < KC; ++c) {
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      const int col = 4 * (lane + 64 * k);
-      wv[c][k] = make_f4(0.f, 0.f, 0.f, 0.f);
-      gv[c][k] = make_f4(0.f, 0.f, 0.f, 0.f);
-      if (c < K) {
-        const float* wc = w + (int64_t)c * d;
-        if (col < d) wv[c][k].x = wc[col];
-        if (col + 1 < d) wv[c][k].y = wc[col + 1];
-        if (col + 2 < d) wv[c][k].z = wc[col + 2];
-        if (col + 3 < d) wv[c][k].w = wc[col + 3];
-      }
-    }
-  }
-  double loss_acc = 0.0;
-  const int64_t stride = (int64_t)a.parts * 4;
-  int64_t row = (int64_t)blockIdx.x * 4 + wave;
-
-  F4 xa[NV], xb[NV];
-  auto load_row = [&](F4(&xv)[NV], int64_t r) {
-    const float* rp = X + r * ldx;
-#pragma unroll
-    for (int k = 0; k < NV; ++k) xv[k] = load_chunk<false>(rp, 4 * (lane + 64 * k), d);
-  };
-  auto reduce_row = [&](F4(&xv)[NV], int64_t r) {
-    float logit[KC];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int c = 0; c < KC; ++c) {
-      float p = 0.f;
-#pragma unroll
-      for (int k = 0; k < NV; ++k) p = dot4(xv[k], wv[c][k], p);
-      logit[c] = wave_sum_f32(p);
-      if (c < K) mx = fmaxf(mx, logit[c]);
-    }
-    float e[KC], se = 0.f;
-#pragma unroll
-    for (int c = 0; c < KC; ++c) {
-      e[c] = c < K ? expf(logit[c] - mx) : 0.f;
-      se += e[c];
-    }
-    const int yi = y[r];
-    const float inv = 1.0f / se;
-    float mine = 0.f, ly = 0.f;
-#pragma unroll
-    for (int c = 0; c < KC; ++c) {
-      const float rc = e[c] * inv - (c == yi ? 1.0f : 0.f);
-      if (c == yi) ly = logit[c];
-      if (lane == c) mine = logit[c];
-#pragma unroll
-      for (int k = 0; k < NV; ++k) axpy4(rc, xv[k], gv[c][k]);
-    }
-    loss_acc += (double)(logf(se) + mx - ly);
-    if (lane < K) phi[r * K + lane] = mine;
-  };
-
-  if (row < N) load_row(xa, row);
-  while (row < N) {
-    const int64_t r1 = row + stride;
-    if (r1 < N) load_row(xb, r1);
-    reduce_row(xa, row);
-    if (r1 >= N) break;
-    const int64_t r2 = r1 + stride;
-    if (r2 < N) load_row(xa, r2);
-    reduce_row(xb, r1);
-    row = r2;
-  }
-
-  __shared__ F4 fold[KC * 64 * NV];
-  __shared__ double fold_loss[4];
-  if (lane == 0) fold_loss[wave] = loss_acc;
-  for (int s = 1; s < 4; ++s) {
-    if (wave == s) {
-#pragma unroll
-      for (int c = 0; c < KC; ++c)
-#pragma unroll
-        for (int k = 0; k < NV; ++k) fold[(c * NV + k) * 64 + lane] = gv[c][k];
-    }
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int c = 0; c < KC; ++c)
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-          const F4 o = fold[(c * NV + k) * 64 + lane];
-          gv[c][k].x += o.x; gv[c][k].y += o.y; gv[c][k].z += o.z; gv[c][k].w += o.w;
-        }
-    }
-    __syncthreads();
-  }
-  if (wave == 0) {
-    float* pg = a.partial_g + ((int64_t)chain * a.parts + blockIdx.x) * (int64_t)K * d;
-#pragma unroll
-    for (int c = 0; c < KC; ++c) {
-      if (c < K) {
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-          const int col = 4 * (lane + 64 * k);
-          float* pc = pg + (int64_t)c * d;
-          if (col < d) pc[col] = gv[c][k].x;
-          if (col + 1 < d) pc[col + 1] = gv[c][k].y;
-          if (col + 2 < d) pc[col + 2] = gv[c][k].z;
-          if (col + 3 < d) pc[col + 3] = gv[c][k].w;
-        }
-      }
-    }
-    if (lane == 0)
-      a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] =
-          ((fold_loss[0] + fold_loss[1]) + fold_loss[2]) + fold_loss[3];
-  }
-}
-
 // ---- second stage: fixed-order sum of the per-workgroup partials --------------
 struct RedArgs {
   const float* partial_g;
@@ -332,15 +193,26 @@ struct RedArgs {
   double lambda;
 };
 
+// A workgroup sums 64 entries: thread (entry tid % 64, group tid / 64) adds every fourth
+// partial in index order, the four group sums are then added in group order: a fixed order
+// with four times as many loads in flight as one thread per entry would have.
 __global__ __launch_bounds__(256) void fullgrad_reduce(RedArgs a) {
   const int chain = blockIdx.y;
-  const int k = blockIdx.x * 256 + threadIdx.x;
+  const int e = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int k = blockIdx.x * 64 + e;
   const float* pg = a.partial_g + (int64_t)chain * a.parts * a.n;
   const float* w = a.w + (int64_t)chain * a.n;
+  __shared__ double gsum[4][64];
+  double s = 0.0;
   if (k < a.n) {
-    double s = 0.0;
-    for (int p = 0; p < a.parts; ++p) s += (double)pg[(int64_t)p * a.n + k];
-    a.g[(int64_t)chain * a.n + k] = (float)(s / (double)a.N + a.lambda * (double)w[k]);
+#pragma unroll 8
+    for (int p = grp; p < a.parts; p += 4) s += (double)pg[(int64_t)p * a.n + k];
+  }
+  gsum[grp][e] = s;
+  __syncthreads();
+  if (grp == 0 && k < a.n) {
+    const double t = ((gsum[0][e] + gsum[1][e]) + gsum[2][e]) + gsum[3][e];
+    a.g[(int64_t)chain * a.n + k] = (float)(t / (double)a.N + a.lambda * (double)w[k]);
   }
   if (blockIdx.x == 0) {  // f(w~): data term plus lambda/2 ||w~||^2
     __shared__ double red[256];
@@ -380,26 +252,11 @@ int launch_k1(const FgArgs& a, int loss, bool exact, dim3 grid, hipStream_t s) {
   return hip_ok(hipGetLastError());
 }
 
-template <int NV>
-int launch_sm(const FgArgs& a, dim3 grid, hipStream_t s) {
-  if (a.K <= 2) hipLaunchKernelGGL((fullgrad_softmax<NV, 2>), grid, dim3(256), 0, s, a);
-  else if (a.K <= 4) hipLaunchKernelGGL((fullgrad_softmax<NV, 4>), grid, dim3(256), 0, s, a);
-  else if (a.K <= 8) hipLaunchKernelGGL((fullgrad_softmax<NV, 8>), grid, dim3(256), 0, s, a);
-  else if (a.K <= 10) hipLaunchKernelGGL((fullgrad_softmax<NV, 10>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((fullgrad_softmax<NV, 16>), grid, dim3(256), 0, s, a);
-  return hip_ok(hipGetLastError());
-}
-
 }  // namespace
 
 int fullgrad_supported(const halp_params& p) {
   const int nv = nv_for(p.d);
-  if (p.loss == HALP_LOSS_SOFTMAX) {
-    if (p.K < 2 || p.K > 16) return HALP_ERR_UNSUPPORTED;
-    const int kc = p.K <= 2 ? 2 : (p.K <= 4 ? 4 : (p.K <= 8 ? 8 : (p.K <= 10 ? 10 : 16)));
-    if (nv > 4 || kc * nv > 40) return HALP_ERR_UNSUPPORTED;  // register budget
-    return HALP_OK;
-  }
+  if (p.loss == HALP_LOSS_SOFTMAX) return fullgrad_softmax_supported(p);
   return nv <= 16 ? HALP_OK : HALP_ERR_UNSUPPORTED;  // d <= 4096
 }
 
@@ -408,7 +265,13 @@ static int rows_per_batch(int nv) { return nv >= 16 ? 1 : 16 / nv; }
 int fullgrad_parts(const halp_handle& h) {
   const halp_params& p = h.p;
   if (h.fullgrad_blocks > 0) return h.fullgrad_blocks;
-  const int rb = p.loss == HALP_LOSS_SOFTMAX ? 1 : rows_per_batch(nv_for(p.d));
+  if (p.loss == HALP_LOSS_SOFTMAX) {  // two workgroups per CU, tiles of 16 rows
+    int64_t parts = (2 * (int64_t)h.num_cus + p.R - 1) / p.R;
+    const int64_t tiles = (p.N + 15) / 16;
+    if (parts > tiles) parts = tiles;
+    return (int)(parts < 1 ? 1 : parts);
+  }
+  const int rb = rows_per_batch(nv_for(p.d));
   const int64_t nblk = (p.N + rb - 1) / rb;
   int64_t parts = (2 * (int64_t)h.num_cus + p.R - 1) / p.R;  // two workgroups per CU
   const int64_t most = (nblk + 3) / 4;                        // one batch per wave at least
@@ -431,9 +294,7 @@ int launch_full_gradient(const halp_handle& h, hipStream_t s) {
   const dim3 grid(h.parts, p.R);
   const int nv = nv_for(p.d);
   if (p.loss == HALP_LOSS_SOFTMAX) {
-    if (nv == 1) rc = launch_sm<1>(a, grid, s);
-    else if (nv == 2) rc = launch_sm<2>(a, grid, s);
-    else rc = launch_sm<4>(a, grid, s);
+    rc = launch_fullgrad_softmax(a, p.R, s);
   } else {
     const bool exact = p.d == 256 * nv;
     switch (nv) {
@@ -448,7 +309,7 @@ int launch_full_gradient(const halp_handle& h, hipStream_t s) {
   RedArgs r;
   r.partial_g = h.partial_g; r.partial_loss = h.partial_loss; r.w = h.buf.w; r.g = h.buf.g;
   r.scales = h.buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = h.parts; r.lambda = p.lambda;
-  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 255) / 256, p.R), dim3(256), 0, s, r);
+  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 63) / 64, p.R), dim3(256), 0, s, r);
   return hip_ok(hipGetLastError());
 }
 
