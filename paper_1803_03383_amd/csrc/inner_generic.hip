@@ -20,12 +20,14 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
   constexpr int CPS = 16 / BITS;  // coordinates per strip of 16 rounding bits
+  constexpr int EPG = 64 / BITS;  // elements per 8-byte group of a data row
   const int chain = blockIdx.x;
   const int tid = threadIdx.x, NT = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, NW = NT >> 6;
   const int d = a.d, K = a.K, B = a.B;
   const int n = K * d;
   const int U = (d + CPS - 1) / CPS;
+  const int ngroups = (d + EPG - 1) / EPG;
   const int64_t N = a.N, ldxq = a.ldxq;
   const XT* __restrict__ Xq = reinterpret_cast<const XT*>(a.Xq) + (int64_t)chain * a.xq_chain_stride;
   const float* __restrict__ phi = a.phi + (int64_t)chain * N * K;
@@ -93,9 +95,28 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
     // integer dot products x_i^T z, one (row, class) pair per wave at a time
     for (int pr = wave; pr < B * K; pr += NW) {
       const int m = pr / K, c = pr % K;
-      const XT* xr = Xq + idxs[m] * ldxq;
+      // rows are 8-byte aligned and padded to whole 8-byte groups: one load per group
+      const uint2* xr = reinterpret_cast<const uint2*>(Xq + idxs[m] * ldxq);
       long long acc = 0;
-      for (int j = lane; j < d; j += 64) acc += (long long)xr[j] * (long long)zs[c * d + j];
+      for (int q0 = lane; q0 < ngroups; q0 += 64 * 8) {  // eight loads in flight per lane
+        uint2 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = xr[min(q0 + 64 * i, ngroups - 1)];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int q = q0 + 64 * i;
+          if (q < ngroups) {
+#pragma unroll
+            for (int e = 0; e < EPG; ++e) {
+              const uint32_t wv = e < EPG / 2 ? v[i].x : v[i].y;
+              const int sh = (e % (EPG / 2)) * BITS;
+              const int xv = BITS == 8 ? (int)(int8_t)(wv >> sh) : (int)(int16_t)(wv >> sh);
+              const int j = q * EPG + e;
+              if (j < d) acc += (long long)(xv * zs[c * d + j]);  // |x z| < 2^30
+            }
+          }
+        }
+      }
       acc = wave_sum_i64(acc);
       if (lane == 0) {
         Ds[pr] = acc;
@@ -184,7 +205,8 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
     __syncthreads();
     // u = z - gamma x_i - h~ (- c_lambda z) in (delta_i, 2b); z = Q_(delta_m, b)(u)
     const long long cl = s_clambda;
-    auto update_strip = [&](int u, const U4& r) {
+    // gsum = sum over the minibatch of gamma_m x_m for one strip
+    auto finish_strip = [&](int u, const U4& r, const long long (&gsum)[CPS]) {
       const int c = u / U, strip = u % U;
       const uint32_t field = zround_field(r, (uint32_t)t);
       for (int e = 0; e < CPS; ++e) {
@@ -192,8 +214,7 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
         if (j >= d) break;
         const int k = c * d + j;
         const long long zk = zs[k];
-        long long v = -(long long)hs[k] - cl * zk;
-        for (int m = 0; m < B; ++m) v -= (long long)gams[m * K + c] * (long long)Xq[idxs[m] * ldxq + j];
+        const long long v = -(long long)hs[k] - cl * zk - gsum[e];
         const long long rb = (long long)((field >> (e * BITS)) & ((1u << BITS) - 1u));
         long long zn = zk + ((v + rb) >> BITS);  // arithmetic shift: floor
         if (zn > qmax) { zn = qmax; my_zclamp += 1; }
@@ -201,18 +222,53 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
         zs[k] = (int32_t)zn;
       }
     };
-    if (cache_blocks) {  // a thread's strips are the same every step: keep their blocks for 8 steps
+    if (cache_blocks) {
+      // A thread's strips are the same every step: their Philox blocks are kept for 8 steps,
+      // and the minibatch is summed row by row over all of them, so that the loads of a
+      // row are independent of each other and in flight together.
+      long long gsum[kCached][CPS];
+      int sc[kCached], sj[kCached];  // class and first coordinate of each strip (-1: none)
+#pragma unroll
+      for (int s = 0; s < kCached; ++s) {
+        const int u = tid + s * NT;
+        sc[s] = u < K * U ? u / U : -1;
+        sj[s] = u < K * U ? (u % U) * CPS : 0;
+#pragma unroll
+        for (int e = 0; e < CPS; ++e) gsum[s][e] = 0;
+      }
+#pragma unroll 4
+      for (int m = 0; m < B; ++m) {
+        const XT* xr = Xq + idxs[m] * ldxq;
+#pragma unroll
+        for (int s = 0; s < kCached; ++s) {
+          if (sc[s] >= 0) {
+            const long long g = gams[m * K + sc[s]];
+#pragma unroll
+            for (int e = 0; e < CPS; ++e)
+              if (sj[s] + e < d) gsum[s][e] += g * (long long)xr[sj[s] + e];
+          }
+        }
+      }
 #pragma unroll
       for (int s = 0; s < kCached; ++s) {
         const int u = tid + s * NT;
         if (u < K * U) {
           if ((t & 7) == 0) zcache[s] = zround_block(seed, a.epoch, (uint32_t)u, (uint32_t)(t >> 3));
-          update_strip(u, zcache[s]);
+          finish_strip(u, zcache[s], gsum[s]);
         }
       }
     } else {
-      for (int u = tid; u < K * U; u += NT)
-        update_strip(u, zround_block(seed, a.epoch, (uint32_t)u, (uint32_t)(t >> 3)));
+      for (int u = tid; u < K * U; u += NT) {
+        const int c = u / U, j0 = (u % U) * CPS;
+        long long gsum[CPS];
+#pragma unroll
+        for (int e = 0; e < CPS; ++e) gsum[e] = 0;
+        for (int m = 0; m < B; ++m)
+#pragma unroll
+          for (int e = 0; e < CPS; ++e)
+            if (j0 + e < d) gsum[e] += (long long)gams[m * K + c] * (long long)Xq[idxs[m] * ldxq + j0 + e];
+        finish_strip(u, zround_block(seed, a.epoch, (uint32_t)u, (uint32_t)(t >> 3)), gsum);
+      }
     }
     __syncthreads();
     if (rec && a.tr.ztraj) {
