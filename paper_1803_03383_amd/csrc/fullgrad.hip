@@ -193,25 +193,27 @@ struct RedArgs {
   double lambda;
 };
 
-// A workgroup sums 64 entries: thread (entry tid % 64, group tid / 64) adds every fourth
-// partial in index order, the four group sums are then added in group order: a fixed order
-// with four times as many loads in flight as one thread per entry would have.
+// A workgroup sums 32 entries: thread (entry tid % 32, group tid / 32) adds every eighth
+// partial in index order, the eight group sums are then added in group order: a fixed order
+// with eight times as many loads in flight as one thread per entry would have.
 __global__ __launch_bounds__(256) void fullgrad_reduce(RedArgs a) {
   const int chain = blockIdx.y;
-  const int e = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int k = blockIdx.x * 64 + e;
+  const int e = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int k = blockIdx.x * 32 + e;
   const float* pg = a.partial_g + (int64_t)chain * a.parts * a.n;
   const float* w = a.w + (int64_t)chain * a.n;
-  __shared__ double gsum[4][64];
+  __shared__ double gsum[8][32];
   double s = 0.0;
   if (k < a.n) {
 #pragma unroll 8
-    for (int p = grp; p < a.parts; p += 4) s += (double)pg[(int64_t)p * a.n + k];
+    for (int p = grp; p < a.parts; p += 8) s += (double)pg[(int64_t)p * a.n + k];
   }
   gsum[grp][e] = s;
   __syncthreads();
   if (grp == 0 && k < a.n) {
-    const double t = ((gsum[0][e] + gsum[1][e]) + gsum[2][e]) + gsum[3][e];
+    double t = gsum[0][e];
+#pragma unroll
+    for (int q = 1; q < 8; ++q) t += gsum[q][e];
     a.g[(int64_t)chain * a.n + k] = (float)(t / (double)a.N + a.lambda * (double)w[k]);
   }
   if (blockIdx.x == 0) {  // f(w~): data term plus lambda/2 ||w~||^2
@@ -309,7 +311,7 @@ int launch_full_gradient(const halp_handle& h, hipStream_t s) {
   RedArgs r;
   r.partial_g = h.partial_g; r.partial_loss = h.partial_loss; r.w = h.buf.w; r.g = h.buf.g;
   r.scales = h.buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = h.parts; r.lambda = p.lambda;
-  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 63) / 64, p.R), dim3(256), 0, s, r);
+  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 31) / 32, p.R), dim3(256), 0, s, r);
   return hip_ok(hipGetLastError());
 }
 
