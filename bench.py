@@ -172,15 +172,48 @@ def side_inner_loop(hp, inp, torch, which, T):
     return out
 
 
+def softmax_gradient_pass(hp, torch, rows, reps):
+    """The softmax gradient pass alone on a seeded uniform matrix [rows x 784], K=10: the C3
+    shape at a row count that can be raised past the last-level cache."""
+    d, K = 784, 10
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    X = torch.rand((1, rows, d), device="cuda", generator=g)
+    y = torch.randint(0, K, (1, rows), dtype=torch.int32, device="cuda", generator=g)
+    st = hp.alloc_state(rows, d, K=K, b=8)
+    st["w"].normal_(0.0, 0.01, generator=g)
+    Xq = torch.zeros((1, rows, d), dtype=torch.int8, device="cuda")
+    h = hp.Halp(rows, d, K=K, loss=hp.LOSS_SOFTMAX, b=8, T=8, alpha=1e-2, mu=2.5, lam=1e-4,
+                delta_d=1.0 / 127.0, seed=0)
+    h.bind(X=X, Xq=Xq, y=y, **st)
+    for _ in range(3):
+        h.full_gradient()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        h.full_gradient()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes = rows * (4 * d + 4 * K + 4)
+    out = dict(workload=f"softmax gradient pass, N={rows}, d={d}, K={K}, fp32", ms=ms, bytes=nbytes,
+               achieved=nbytes / (ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+               frac=nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, loss=h.get_stats(0).loss)
+    h.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c5"],
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c5", "c3grad"],
                     help="c4 (default), c2, c1: the headline line; c3, c5: inner-loop step rate "
                          "of the softmax and minibatch configurations")
     ap.add_argument("--inner-steps", type=int, default=2000, help="T for --workload c3 / c5")
+    ap.add_argument("--rows", type=int, default=960000, help="N for --workload c3grad")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
     ap.add_argument("--cpu-chains", type=int, default=64)
@@ -203,6 +236,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    if args.workload == "c3grad":
+        print(json.dumps({"workload": "c3grad",
+                          "softmax_gradient_pass": softmax_gradient_pass(hp, torch, args.rows, args.steps)}))
+        return
     if args.workload in ("c3", "c5"):
         print(json.dumps({"workload": args.workload, "side_inner_loop":
                           side_inner_loop(hp, inp, torch, args.workload, args.inner_steps)}))
