@@ -104,7 +104,13 @@ typedef struct {
   int32_t timed_epochs;   /* halp_epoch calls averaged (the last 32 at most since timing was set) */
 } halp_stats;
 
-#define HALP_OPT_INNER_VARIANT 1 /* 0 auto (default), 1 generic, 2 register-resident     */
+#define HALP_OPT_INNER_VARIANT 1 /* 0 auto (default), 1 general, 2 register-resident.
+                                    Register-resident kernels exist for B = 1 with K = 1 (squared,
+                                    logistic; d up to 8 strips of 16 rounding bits per lane and
+                                    16 waves) and for softmax with K <= 15 (a class's row of z
+                                    within 8 strips per lane of one wave, data rows up to 1 KB);
+                                    auto takes them when the shape fits, 2 fails with
+                                    HALP_ERR_UNSUPPORTED when it does not                   */
 #define HALP_OPT_TIMING 2        /* 1: halp_epoch brackets its phases with events on its stream;
                                     setting it restarts the averages of halp_get_stats     */
 #define HALP_OPT_FULLGRAD_BLOCKS 4 /* workgroups per chain of the gradient pass, 0 = auto  */
