@@ -290,6 +290,44 @@ int halp_ref_recenter(const halp_ref_problem* p, const float* g, uint32_t epoch,
   return 0;
 }
 
+/* ------------------------------------------- Algorithm 2 in integers, epoch start */
+
+int halp_ref_lp_begin(const halp_ref_problem* p, const float* g, const float* w, uint32_t epoch,
+                      double scales[8], int64_t* h, int32_t* z) {
+  const int b = p->b;
+  const int64_t n = (int64_t)p->K * p->d;
+  if (b < 2 || b > 24 || !(p->delta > 0) || !(p->alpha > 0) || !(p->delta_d > 0)) return -1;
+  if (p->lambda != 0) return -1;
+  const double qmax = (double)(((int64_t)1 << (b - 1)) - 1), qmin = -(double)((int64_t)1 << (b - 1));
+  double ss = 0.0;
+  for (int64_t k = 0; k < n; ++k) ss += (double)g[k] * (double)g[k];
+  const double nrm = sqrt(ss);
+  for (int64_t k = 0; k < n; ++k) { /* w_{k,0} = w~_k in (delta, b) */
+    double q = nearbyint((double)w[k] / p->delta);
+    if (!(q >= qmin)) q = qmin; /* also catches NaN */
+    if (q > qmax) q = qmax;
+    z[k] = (int32_t)q;
+    h[k] = 0;
+  }
+  for (int k = 0; k < 8; ++k) scales[k] = 0.0;
+  scales[3] = nrm;
+  if (!isfinite(nrm)) { scales[7] = -1.0; return 0; }
+  if (nrm == 0.0) { scales[7] = 1.0; return 0; }
+  const double delta_m = p->delta;
+  const double delta_i = delta_m * ldexp(1.0, -b);
+  const double delta_s = delta_i / p->delta_d;
+  const double inv_i = 1.0 / delta_i, inv_s = 1.0 / delta_s;
+  if (!(delta_i > 0) || !isfinite(inv_i) || !isfinite(inv_s)) { scales[7] = -1.0; return 0; }
+  scales[0] = delta_m; scales[1] = delta_i; scales[2] = delta_s;
+  scales[4] = inv_i; scales[5] = inv_s;
+  const int64_t hmax = ((int64_t)1 << (2 * b - 1)) - 1, hmin = -((int64_t)1 << (2 * b - 1));
+  for (int64_t k = 0; k < n; ++k) {
+    const uint32_t r = halp_ref_stream_word(p->seed, HALP_REF_PURPOSE_HROUND, epoch, (uint64_t)k);
+    h[k] = halp_ref_quantize_real(p->alpha * (double)g[k], inv_i, r, hmin, hmax, 0);
+  }
+  return 0;
+}
+
 /* --------------------------------------------------- Algorithm 4, inner loop */
 
 int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq, const float* phi,
@@ -303,6 +341,8 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
   const double delta_m = scales[0], inv_s = scales[5];
   const double dscale = p->delta_d * delta_m;  /* scale of the integer product x^T z */
   const double aB = p->alpha / (double)B;
+  const int lp = p->algorithm == HALP_REF_ALG_LPSVRG;
+  if (lp && p->lambda != 0) return -1;
   int64_t* idx = (int64_t*)malloc(sizeof(int64_t) * (size_t)B);
   int64_t* gam = (int64_t*)malloc(sizeof(int64_t) * (size_t)B * (size_t)K);
   int64_t* znew = (int64_t*)malloc(sizeof(int64_t) * (size_t)K * (size_t)d);
@@ -321,7 +361,8 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
         int64_t D = 0; /* low-precision dot product, scale delta_d * delta_m */
         for (int j = 0; j < d; ++j) D += xq_at(Xq, b, i * ldxq + j) * (int64_t)z[(int64_t)c * d + j];
         a0[c] = (double)phi[i * K + c];
-        a1[c] = a0[c] + dscale * (double)D;
+        /* Algorithm 4: the margin moves by x^T z; Algorithm 2: x^T w is the whole margin */
+        a1[c] = lp ? dscale * (double)D : a0[c] + dscale * (double)D;
         if (rec && trace->D) trace->D[(t * B + m) * K + c] = D;
         p0[c] = dscale * (double)D; /* kept for the squared loss */
       }
@@ -334,7 +375,9 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
         softmax_p_inner(a1, K, q1);
         for (int c = 0; c < K; ++c) p1[c] = q1[c] - q0[c];
       } else {
-        p1[0] = p0[0]; /* (phi + D - y) - (phi - y) = D without cancellation */
+        /* Algorithm 4: (phi + D - y) - (phi - y) = D without cancellation;
+         * Algorithm 2: (x^T w - y) - (phi - y) */
+        p1[0] = lp ? p0[0] - a0[0] : p0[0];
       }
       for (int c = 0; c < K; ++c) {
         const double beta = aB * p1[c];
@@ -382,7 +425,8 @@ void halp_ref_apply_offset(const halp_ref_problem* p, const double scales[8], co
   const double delta_m = scales[0];
   for (int64_t k = 0; k < (int64_t)p->K * p->d; ++k) {
     const double step = delta_m * (double)z[k];
-    w[k] = (float)((double)w[k] + step);
+    if (p->algorithm == HALP_REF_ALG_LPSVRG) w[k] = (float)step; /* w~ = delta w (option I) */
+    else w[k] = (float)((double)w[k] + step);
   }
 }
 
@@ -398,7 +442,8 @@ int halp_ref_epoch(const halp_ref_problem* p, const float* X, int64_t ldx, const
     /* the full-precision pass hands fp32 margins and an fp32 gradient on */
     for (int64_t k = 0; k < nphi; ++k) phi32[k] = (float)phi[k];
     for (int64_t k = 0; k < nw; ++k) g32[k] = (float)g[k];
-    rc = halp_ref_recenter(p, g32, epoch, scales, h, z);
+    rc = p->algorithm == HALP_REF_ALG_LPSVRG ? halp_ref_lp_begin(p, g32, w, epoch, scales, h, z)
+                                             : halp_ref_recenter(p, g32, epoch, scales, h, z);
     scales[6] = loss;
   }
   free(phi); free(g);

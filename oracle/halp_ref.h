@@ -44,6 +44,15 @@
  *     pairwise over adjacent classes; the full-precision pass uses libm and
  *     plain loops.
  *
+ *   - LP-SVRG (Algorithm 2) for linear models, which the paper says can be put in
+ *     integers "using a similar technique" without printing it: the model w itself
+ *     is the integer vector (scale delta given, b bits, box around 0); an epoch
+ *     starts from w = round-to-nearest(w~ / delta), keeps the (delta_i, 2b) and
+ *     (delta_s, b) bookkeeping of Algorithm 4 with delta_m = delta,
+ *     beta = alpha (l'(x_i^T w) - l'(phi_i)) with x_i^T w the integer product and
+ *     phi_i the margin of w~ from the full-precision pass, and ends with
+ *     w~ = delta w (option I).  No L2 term in this mode.
+ *
  * Parity pins: see tests/test_oracle_*.py.  Unpinned by the paper itself
  * ("parity unpinned" beyond unbiasedness against Algorithm 3 and reduction to
  * the written algorithm at K=1, B=1, lambda=0): the softmax, minibatch and L2
@@ -59,6 +68,7 @@ extern "C" {
 #endif
 
 enum { HALP_REF_SQUARED = 0, HALP_REF_LOGISTIC = 1, HALP_REF_SOFTMAX = 2 };
+enum { HALP_REF_ALG_HALP = 0, HALP_REF_ALG_LPSVRG = 1 };
 
 /* purposes of the random streams (counter word 3) */
 enum {
@@ -76,12 +86,13 @@ typedef struct {
   int32_t loss;   /* HALP_REF_*                                       */
   int32_t b;      /* bits of the low-precision model: 8 or 16 (up to 24 on the CPU only) */
   int32_t B;      /* inner minibatch                                  */
-  int32_t pad_;
+  int32_t algorithm; /* HALP_REF_ALG_HALP (Algorithm 4) or HALP_REF_ALG_LPSVRG (Algorithm 2) */
   double alpha;   /* step size                                        */
   double mu;      /* strong-convexity parameter used by bit centering */
   double lambda;  /* L2                                               */
   double delta_d; /* scale of the low-precision data (delta_d, b)     */
   uint64_t seed;  /* seed of this chain                               */
+  double delta;   /* LP-SVRG only: the fixed scale of the model (delta, b) */
 } halp_ref_problem;
 
 /* optional per-step record of the first M steps; any pointer may be NULL */
@@ -127,6 +138,12 @@ void halp_ref_exp_array(const double* x, int64_t n, double* out);
 /* X -> (delta_d, b): clamp(round-half-even(X / delta_d), -(2^(b-1)-1), 2^(b-1)-1);
  * Xq is int8 when b == 8, int16 when b == 16, int32 for 16 < b <= 24 (CPU only) */
 void halp_ref_quantize_data(const float* X, int64_t n, double delta_d, int b, void* Xq);
+
+/* Algorithm 2 in integers, start of an epoch: scales from the fixed p->delta
+ * (delta_m = delta), h~ = Q_(delta_i,2b)(alpha g~), z = clamp(rne(w~ / delta)).
+ * Same scales[] layout and status codes as halp_ref_recenter.               */
+int halp_ref_lp_begin(const halp_ref_problem* p, const float* g, const float* w, uint32_t epoch,
+                      double scales[8], int64_t* h, int32_t* z);
 
 /* Algorithm 4, the two outer lines: margins phi_i = x_i^T w~ and
  * g~ = (1/N) sum l'_i(phi_i) x_i (+ lambda w~); loss = f(w~).

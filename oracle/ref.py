@@ -17,9 +17,9 @@ PURPOSE_IDX, PURPOSE_GAMMA, PURPOSE_ZROUND, PURPOSE_REG, PURPOSE_HROUND = 0, 1, 
 class Problem(C.Structure):
     _fields_ = [
         ("N", C.c_int64), ("d", C.c_int32), ("K", C.c_int32), ("loss", C.c_int32),
-        ("b", C.c_int32), ("B", C.c_int32), ("pad_", C.c_int32),
+        ("b", C.c_int32), ("B", C.c_int32), ("algorithm", C.c_int32),
         ("alpha", C.c_double), ("mu", C.c_double), ("lam", C.c_double),
-        ("delta_d", C.c_double), ("seed", C.c_uint64),
+        ("delta_d", C.c_double), ("seed", C.c_uint64), ("delta", C.c_double),
     ]
 
 
@@ -63,6 +63,9 @@ def lib():
         L.halp_ref_recenter.restype = C.c_int
         L.halp_ref_recenter.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                         C.c_void_p, C.c_void_p]
+        L.halp_ref_lp_begin.restype = C.c_int
+        L.halp_ref_lp_begin.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
+                                        C.c_void_p, C.c_void_p]
         L.halp_ref_inner_loop.restype = C.c_int
         L.halp_ref_inner_loop.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_uint32, C.c_int64, C.c_void_p,
@@ -85,10 +88,13 @@ def xq_dtype(b):
     return np.int8 if b == 8 else (np.int16 if b == 16 else np.int32)
 
 
+ALG_HALP, ALG_LPSVRG = 0, 1
+
+
 def make_problem(N, d, K=1, loss=SQUARED, b=8, B=1, alpha=0.01, mu=1.0, lam=0.0, delta_d=1.0,
-                 seed=0):
-    return Problem(N=N, d=d, K=K, loss=loss, b=b, B=B, pad_=0, alpha=alpha, mu=mu, lam=lam,
-                   delta_d=delta_d, seed=seed)
+                 seed=0, algorithm=ALG_HALP, delta=0.0):
+    return Problem(N=N, d=d, K=K, loss=loss, b=b, B=B, algorithm=algorithm, alpha=alpha, mu=mu,
+                   lam=lam, delta_d=delta_d, seed=seed, delta=delta)
 
 
 def philox4x32_10(ctr, key):
@@ -168,6 +174,19 @@ def recenter(prob, g32, epoch):
     rc = lib().halp_ref_recenter(C.addressof(prob), _p(g32), epoch, _p(scales), _p(h), _p(z))
     if rc != 0:
         raise ValueError(f"halp_ref_recenter rc={rc}")
+    return scales, h, z
+
+
+def lp_begin(prob, g32, w, epoch):
+    """start of an LP-SVRG epoch; returns (scales[8] f64, h[K,d] i64, z[K,d] i32)"""
+    g32 = np.ascontiguousarray(g32, dtype=np.float32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    scales = np.zeros(8, dtype=np.float64)
+    h = np.zeros((prob.K, prob.d), dtype=np.int64)
+    z = np.zeros((prob.K, prob.d), dtype=np.int32)
+    rc = lib().halp_ref_lp_begin(C.addressof(prob), _p(g32), _p(w), epoch, _p(scales), _p(h), _p(z))
+    if rc != 0:
+        raise ValueError(f"halp_ref_lp_begin rc={rc}")
     return scales, h, z
 
 
