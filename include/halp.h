@@ -53,6 +53,15 @@ extern "C" {
 #define HALP_LOSS_LOGISTIC 1 /* l(a) = log(1 + exp(-y a)),   y: float in {-1,+1}    */
 #define HALP_LOSS_SOFTMAX 2  /* l(a) = -log softmax(a)_y,    y: int32 in [0,K)      */
 
+/* Which of the paper's algorithms an epoch runs.  HALP_ALG_LPSVRG is Algorithm 2 for linear
+ * models in the integer form the paper mentions after Algorithm 4: the model itself is the
+ * integer vector z (scale delta, b bits, box around 0); halp_recenter then takes the scales
+ * from delta instead of ||g~|| and sets z = round(w~ / delta); the inner loop uses
+ * beta = alpha (l'(x_i^T z delta_d delta) - l'(phi_i)); an epoch ends with w~ = delta z.
+ * lambda must be 0 in that mode; mu is ignored.                                          */
+#define HALP_ALG_HALP 0
+#define HALP_ALG_LPSVRG 1
+
 typedef struct halp_handle halp_handle; /* opaque, library-owned */
 
 /* The "given" lists of Algorithm 4 plus the problem sizes of eq. (1). */
@@ -65,13 +74,14 @@ typedef struct {
   int32_t b;          /* bits of z, gamma and the data: 8 or 16                        */
   int32_t B;          /* inner minibatch (rows per step), >= 1                         */
   int32_t share_data; /* 0: each chain has its own X, Xq, y; 1: all chains share one   */
-  int32_t reserved;   /* must be 0                                                     */
+  int32_t algorithm;  /* HALP_ALG_HALP (Algorithm 4) or HALP_ALG_LPSVRG (Algorithm 2)  */
   int64_t T;          /* inner steps per epoch, 0 <= T < 2^32                          */
   double alpha;       /* step size, > 0                                                */
   double mu;          /* strong-convexity parameter of bit centering, > 0              */
   double lambda;      /* L2 coefficient, >= 0                                          */
   double delta_d;     /* scale of the low-precision data representation (delta_d, b)   */
   uint64_t seed;      /* chain r draws with seed + r                                   */
+  double delta;       /* HALP_ALG_LPSVRG: the fixed scale of the model (delta, b), > 0 */
 } halp_params;
 
 /* Device buffers.  Rd = 1 if share_data else R.  "in" = read by the library,

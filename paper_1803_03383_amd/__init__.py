@@ -12,6 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhalp.so")
 
 LOSS_SQUARED, LOSS_LOGISTIC, LOSS_SOFTMAX = 0, 1, 2
+ALG_HALP, ALG_LPSVRG = 0, 1
 OPT_INNER_VARIANT, OPT_TIMING, OPT_FULLGRAD_BLOCKS, OPT_INNER_WAVES = 1, 2, 4, 5
 ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_NOT_BOUND, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6
 
@@ -33,9 +34,9 @@ class HalpError(RuntimeError):
 class Params(C.Structure):
     _fields_ = [
         ("N", C.c_int64), ("d", C.c_int32), ("K", C.c_int32), ("R", C.c_int32), ("loss", C.c_int32),
-        ("b", C.c_int32), ("B", C.c_int32), ("share_data", C.c_int32), ("reserved", C.c_int32),
+        ("b", C.c_int32), ("B", C.c_int32), ("share_data", C.c_int32), ("algorithm", C.c_int32),
         ("T", C.c_int64), ("alpha", C.c_double), ("mu", C.c_double), ("lam", C.c_double),
-        ("delta_d", C.c_double), ("seed", C.c_uint64),
+        ("delta_d", C.c_double), ("seed", C.c_uint64), ("delta", C.c_double),
     ]
 
 
@@ -126,10 +127,10 @@ class Halp:
     owned by the caller; the handle keeps references so they outlive it."""
 
     def __init__(self, N, d, K=1, R=1, loss=LOSS_SQUARED, b=8, B=1, T=0, alpha=0.01, mu=1.0,
-                 lam=0.0, delta_d=1.0, seed=0, share_data=False):
+                 lam=0.0, delta_d=1.0, seed=0, share_data=False, algorithm=ALG_HALP, delta=0.0):
         self.params = Params(N=N, d=d, K=K, R=R, loss=loss, b=b, B=B, share_data=int(share_data),
-                             reserved=0, T=T, alpha=alpha, mu=mu, lam=lam, delta_d=delta_d,
-                             seed=seed)
+                             algorithm=algorithm, T=T, alpha=alpha, mu=mu, lam=lam,
+                             delta_d=delta_d, seed=seed, delta=delta)
         self._h = C.c_void_p()
         _check(lib().halp_create(C.byref(self._h), C.byref(self.params)), "halp_create")
         self._keep = {}

@@ -37,11 +37,15 @@ int check_params(const halp_params& p) {
     return HALP_ERR_INVALID;
   }
   if (!(p.alpha > 0) || !std::isfinite(p.alpha)) return HALP_ERR_INVALID;
-  if (!(p.mu > 0) || !std::isfinite(p.mu)) return HALP_ERR_INVALID;
+  if (p.algorithm != HALP_ALG_LPSVRG && (!(p.mu > 0) || !std::isfinite(p.mu))) return HALP_ERR_INVALID;
   if (!(p.lambda >= 0) || !std::isfinite(p.lambda)) return HALP_ERR_INVALID;
   if (!(p.delta_d > 0) || !std::isfinite(p.delta_d)) return HALP_ERR_INVALID;
   if (p.share_data != 0 && p.share_data != 1) return HALP_ERR_INVALID;
-  if (p.reserved != 0) return HALP_ERR_INVALID;
+  if (p.algorithm != HALP_ALG_HALP && p.algorithm != HALP_ALG_LPSVRG) return HALP_ERR_INVALID;
+  if (p.algorithm == HALP_ALG_LPSVRG) {
+    if (!(p.delta > 0) || !std::isfinite(p.delta)) return HALP_ERR_INVALID;
+    if (p.lambda != 0) return HALP_ERR_INVALID;  // no L2 term in the integer form of Algorithm 2
+  }
   if ((int64_t)p.K * p.d >= (int64_t(1) << 24)) return HALP_ERR_UNSUPPORTED;
   return HALP_OK;
 }
@@ -52,6 +56,7 @@ int need(const void* p) { return p ? HALP_OK : HALP_ERR_NOT_BOUND; }
 
 // the register-resident family: one kernel for scalar margins, one for softmax
 int reg_supported(const halp_handle& h) {
+  if (h.p.loss == HALP_LOSS_SOFTMAX && h.p.algorithm == HALP_ALG_LPSVRG) return HALP_ERR_UNSUPPORTED;
   return h.p.loss == HALP_LOSS_SOFTMAX ? inner_softmax_supported(h) : inner_reg_supported(h.p);
 }
 
@@ -80,6 +85,7 @@ int need_full_gradient(const halp_handle& h) {
 int need_recenter(const halp_handle& h) {
   if (!h.bound) return HALP_ERR_NOT_BOUND;
   if (!h.buf.g || !h.buf.h || !h.buf.z || !h.buf.scales) return HALP_ERR_NOT_BOUND;
+  if (h.p.algorithm == HALP_ALG_LPSVRG && !h.buf.w) return HALP_ERR_NOT_BOUND;
   return HALP_OK;
 }
 
@@ -87,7 +93,8 @@ int need_inner(const halp_handle& h, int variant) {
   if (!h.bound) return HALP_ERR_NOT_BOUND;
   if (!h.buf.Xq || !h.buf.h || !h.buf.z || !h.buf.scales || !h.buf.w || !h.buf.counters)
     return HALP_ERR_NOT_BOUND;
-  if (h.p.loss != HALP_LOSS_SQUARED && !h.buf.phi) return HALP_ERR_NOT_BOUND;
+  if ((h.p.loss != HALP_LOSS_SQUARED || h.p.algorithm == HALP_ALG_LPSVRG) && !h.buf.phi)
+    return HALP_ERR_NOT_BOUND;
   if (h.p.loss == HALP_LOSS_LOGISTIC && !h.buf.y) return HALP_ERR_NOT_BOUND;
   if (variant == 2) return reg_supported(h);
   return HALP_OK;

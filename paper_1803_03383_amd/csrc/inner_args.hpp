@@ -19,6 +19,7 @@ struct InArgs {
   int64_t N, ldxq, T;
   int64_t xq_chain_stride, y_chain_stride;  // elements; 0 when chains share the data
   int d, K, B, loss;
+  int lp;  // 1: LP-SVRG (Algorithm 2): z is the model itself, the margin is x^T z alone
   double alpha, lambda, delta_d;
   uint64_t seed;
   uint32_t epoch;
@@ -34,6 +35,7 @@ inline InArgs make_inner_args(const halp_handle& h, uint32_t epoch) {
   a.xq_chain_stride = p.share_data ? 0 : p.N * h.buf.ldxq;
   a.y_chain_stride = p.share_data ? 0 : p.N;
   a.d = p.d; a.K = p.K; a.B = p.B; a.loss = p.loss;
+  a.lp = p.algorithm == HALP_ALG_LPSVRG;
   a.alpha = p.alpha; a.lambda = p.lambda; a.delta_d = p.delta_d;
   a.seed = p.seed; a.epoch = epoch;
   return a;

@@ -67,6 +67,12 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
   const double aB = __ddiv_rn(a.alpha, (double)B);
+  const bool lp = a.lp != 0;
+  // the margin after the move: Algorithm 4 adds x^T z to phi, in Algorithm 2 x^T w is all of it
+  auto after_margin = [&](double a0, long long D) {
+    const double delta = __dmul_rn(dscale, (double)D);
+    return lp ? delta : __dadd_rn(a0, delta);
+  };
   const double qmaxd = (double)((1 << (BITS - 1)) - 1), qmind = -(double)(1 << (BITS - 1));
   const long long qmax = (1 << (BITS - 1)) - 1, qmin = -(1 << (BITS - 1));
   unsigned long long my_zclamp = 0, my_gclamp = 0;
@@ -132,10 +138,10 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
       if (tid < B) {
         const long long i = idxs[tid];
         double mx0 = (double)phi[i * K];
-        double mx1 = __dadd_rn(mx0, __dmul_rn(dscale, (double)Ds[tid * K]));
+        double mx1 = after_margin(mx0, Ds[tid * K]);
         for (int c = 1; c < K; ++c) {
           const double a0 = (double)phi[i * K + c];
-          const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[tid * K + c]));
+          const double a1 = after_margin(a0, Ds[tid * K + c]);
           if (a0 > mx0) mx0 = a0;
           if (a1 > mx1) mx1 = a1;
         }
@@ -146,7 +152,7 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
       for (int pr = tid; pr < B * K; pr += NT) {
         const int m = pr / K, c = pr % K;
         const double a0 = (double)phi[idxs[m] * K + c];
-        const double a1 = __dadd_rn(a0, __dmul_rn(dscale, (double)Ds[pr]));
+        const double a1 = after_margin(a0, Ds[pr]);
         es[2 * pr + 0] = halp_exp(__dadd_rn(a0, -rowst[4 * m + 0]));
         es[2 * pr + 1] = halp_exp(__dadd_rn(a1, -rowst[4 * m + 1]));
       }
@@ -179,11 +185,12 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
       const double delta = __dmul_rn(dscale, (double)Ds[pr]);
       double diff;
       if (a.loss == HALP_LOSS_SQUARED) {
-        diff = delta;
+        // Algorithm 4: (phi + Delta - y) - (phi - y) = Delta; Algorithm 2: (x^T w - y) - (phi - y)
+        diff = lp ? __dadd_rn(delta, -(double)phi[i]) : delta;
       } else if (a.loss == HALP_LOSS_LOGISTIC) {
         const double a0 = (double)phi[i];
         const double yi = (double)y[i];
-        diff = __dadd_rn(logistic_dl(__dadd_rn(a0, delta), yi), -logistic_dl(a0, yi));
+        diff = __dadd_rn(logistic_dl(after_margin(a0, Ds[pr]), yi), -logistic_dl(a0, yi));
       } else {
         const double p0 = __ddiv_rn(es[2 * pr + 0], rowst[4 * m + 2]);
         const double p1 = __ddiv_rn(es[2 * pr + 1], rowst[4 * m + 3]);
@@ -281,7 +288,8 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
   for (int k = tid; k < n; k += NT) {
     const int32_t zk = zs[k];
     zg[k] = (XT)zk;
-    wg[k] = (float)__dadd_rn((double)wg[k], __dmul_rn(delta_m, (double)zk));
+    const double step = __dmul_rn(delta_m, (double)zk);
+    wg[k] = lp ? (float)step : (float)__dadd_rn((double)wg[k], step);  // Alg. 2: w~ = delta w
   }
   if (my_zclamp) atomicAdd(&s_cnt[0], my_zclamp);
   if (my_gclamp) atomicAdd(&s_cnt[1], my_gclamp);

@@ -47,6 +47,9 @@ __device__ __forceinline__ int mad24(int a, int b, int c) {
   return r;
 }
 
+// squared loss whose step needs the margin phi_i of w~ (LP-SVRG); a value apart from HALP_LOSS_*
+constexpr int kLossSquaredWithMargins = 3;
+
 template <int BITS, int LOSS, int UPL, int NWT>
 __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   constexpr bool COUNT = true;  // clamped coordinates are always counted
@@ -96,6 +99,8 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   const double aB = a.alpha;  // B = 1: alpha / 1
   const bool use_reg = a.lambda > 0;
   constexpr bool logistic = LOSS == HALP_LOSS_LOGISTIC;
+  constexpr bool need_phi = LOSS != HALP_LOSS_SQUARED;  // logistic, or squared loss of LP-SVRG
+  const bool lp = a.lp != 0;
   const double al = __dmul_rn(a.alpha, a.lambda);
 
   // ---- per-lane state
@@ -127,11 +132,14 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
       iv.x = (int)__umulhi(ri.x, N); iv.y = (int)__umulhi(ri.y, N);
       iv.z = (int)__umulhi(ri.z, N); iv.w = (int)__umulhi(ri.w, N);
       *reinterpret_cast<int4*>(&s_idx[half + 4 * tid]) = iv;
-      if (logistic) {  // gather phi_i and y_i of the batch's rows here, off the step path
-        float4 pv, yv;
+      if (need_phi) {  // gather phi_i (and y_i) of the batch's rows here, off the step path
+        float4 pv;
         pv.x = phi[iv.x]; pv.y = phi[iv.y]; pv.z = phi[iv.z]; pv.w = phi[iv.w];
-        yv.x = y[iv.x]; yv.y = y[iv.y]; yv.z = y[iv.z]; yv.w = y[iv.w];
         *reinterpret_cast<float4*>(&s_phi[half + 4 * tid]) = pv;
+      }
+      if (logistic) {
+        float4 yv;
+        yv.x = y[iv.x]; yv.y = y[iv.y]; yv.z = y[iv.z]; yv.w = y[iv.w];
         *reinterpret_cast<float4*>(&s_y[half + 4 * tid]) = yv;
       }
       s_rho[half + 4 * tid + 0] = __dmul_rn((double)rg.x, 0x1p-32);
@@ -209,13 +217,15 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     float phi8[kWin], y8[kWin];
 #pragma unroll
     for (int s = 0; s < kWin; ++s) phi8[s] = y8[s] = 0.f;
-    if (logistic) {
+    if (need_phi) {
       const float4 p0 = *reinterpret_cast<const float4*>(&s_phi[base]);
       const float4 p1 = *reinterpret_cast<const float4*>(&s_phi[base + 4]);
-      const float4 y0 = *reinterpret_cast<const float4*>(&s_y[base]);
-      const float4 y1 = *reinterpret_cast<const float4*>(&s_y[base + 4]);
       phi8[0] = p0.x; phi8[1] = p0.y; phi8[2] = p0.z; phi8[3] = p0.w;
       phi8[4] = p1.x; phi8[5] = p1.y; phi8[6] = p1.z; phi8[7] = p1.w;
+    }
+    if (logistic) {
+      const float4 y0 = *reinterpret_cast<const float4*>(&s_y[base]);
+      const float4 y1 = *reinterpret_cast<const float4*>(&s_y[base + 4]);
       y8[0] = y0.x; y8[1] = y0.y; y8[2] = y0.z; y8[3] = y0.w;
       y8[4] = y1.x; y8[5] = y1.y; y8[6] = y1.z; y8[7] = y1.w;
     }
@@ -280,10 +290,14 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
         }
         // beta = alpha (l'(phi_i + x_i^T z) - l'(phi_i)), gamma = Q_(delta_s, b)(beta)
         const double delta = __dmul_rn(dscale, (double)D);
-        double diff = delta;
+        double diff = delta;  // squared loss of Algorithm 4: (phi + Delta - y) - (phi - y)
         if (logistic) {
+          // Algorithm 4 moves the margin by x^T z; in Algorithm 2 x^T w is the whole margin
           const double a0 = (double)phi8[s], yi = (double)y8[s];
-          diff = __dadd_rn(logistic_dl(__dadd_rn(a0, delta), yi), -logistic_dl(a0, yi));
+          const double a1 = lp ? delta : __dadd_rn(a0, delta);
+          diff = __dadd_rn(logistic_dl(a1, yi), -logistic_dl(a0, yi));
+        } else if (need_phi) {  // squared loss of Algorithm 2: (x^T w - y) - (phi - y)
+          diff = __dadd_rn(delta, -(double)phi8[s]);
         }
         const double beta = __dmul_rn(aB, diff);
         const double f = floor(__dadd_rn(__dmul_rn(beta, inv_s), rho[s]));
@@ -365,7 +379,8 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     const int j = j0 + k;
     if (j < d) {
       zg[j] = (XT)z[k];
-      wg[j] = (float)__dadd_rn((double)wg[j], __dmul_rn(delta_m, (double)z[k]));
+      const double step = __dmul_rn(delta_m, (double)z[k]);
+      wg[j] = lp ? (float)step : (float)__dadd_rn((double)wg[j], step);  // Alg. 2: w~ = delta w
     }
   }
   if (COUNT && n_zclamp) atomicAdd(&s_cnt[0], (unsigned long long)n_zclamp);
@@ -380,7 +395,9 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
 template <int BITS, int UPL, int NWT>
 int launch_one(const InArgs& a, int R, hipStream_t s) {
   const dim3 grid(R), block(64 * NWT);
-  if (a.loss == HALP_LOSS_SQUARED)
+  if (a.loss == HALP_LOSS_SQUARED && a.lp)
+    hipLaunchKernelGGL((inner_reg_kernel<BITS, kLossSquaredWithMargins, UPL, NWT>), grid, block, 0, s, a);
+  else if (a.loss == HALP_LOSS_SQUARED)
     hipLaunchKernelGGL((inner_reg_kernel<BITS, HALP_LOSS_SQUARED, UPL, NWT>), grid, block, 0, s, a);
   else
     hipLaunchKernelGGL((inner_reg_kernel<BITS, HALP_LOSS_LOGISTIC, UPL, NWT>), grid, block, 0, s, a);

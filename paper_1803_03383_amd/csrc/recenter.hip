@@ -9,6 +9,9 @@ namespace {
 
 struct RcArgs {
   const float* g;
+  const float* w;  // LP-SVRG only
+  int lp;          // 1: Algorithm 2 (fixed delta, z = round(w~ / delta)); 0: Algorithm 4
+  double delta;
   void* h;
   void* z;
   double* scales;
@@ -61,7 +64,8 @@ __global__ __launch_bounds__(256) void recenter_kernel(RcArgs a) {
     } else if (nrm == 0.0) {
       status = 1;
     } else {
-      delta_m = __ddiv_rn(nrm, __dmul_rn(a.mu, qmax));
+      // Algorithm 4: s~ = ||g~|| / (mu (2^(b-1) - 1)); Algorithm 2: the given delta
+      delta_m = a.lp ? a.delta : __ddiv_rn(nrm, __dmul_rn(a.mu, qmax));
       delta_i = __dmul_rn(delta_m, BITS == 8 ? 0x1p-8 : 0x1p-16);
       delta_s = __ddiv_rn(delta_i, a.delta_d);
       inv_i = __ddiv_rn(1.0, delta_i);
@@ -93,7 +97,12 @@ __global__ __launch_bounds__(256) void recenter_kernel(RcArgs a) {
         if (live)  // h~ = Q_(delta_i, 2b)(alpha g~)
           q = quantize_real(__dmul_rn(a.alpha, (double)g[k]), inv_i, pick(r, e), hmin, hmax, nullptr);
         h[k] = (HT)q;
-        z[k] = (ZT)0;  // z_{k,0} = Q(0) = 0
+        int z0 = 0;  // Algorithm 4: z_{k,0} = Q(0) = 0
+        if (a.lp) {  // Algorithm 2: w_{k,0} = w~_k in (delta, b), nearest (ties to even)
+          const double zq = rint(__ddiv_rn((double)a.w[(int64_t)chain * a.n + k], a.delta));
+          z0 = (int)fmin(fmax(zq, (double)(-(1 << (BITS - 1)))), (double)((1 << (BITS - 1)) - 1));
+        }
+        z[k] = (ZT)z0;
       }
     }
   }
@@ -158,6 +167,7 @@ int launch_recenter(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   a.g = h.buf.g; a.h = h.buf.h; a.z = h.buf.z; a.scales = h.buf.scales;
   a.n = p.K * p.d; a.b = p.b; a.alpha = p.alpha; a.mu = p.mu; a.delta_d = p.delta_d;
   a.seed = p.seed; a.epoch = epoch;
+  a.w = h.buf.w; a.lp = p.algorithm == HALP_ALG_LPSVRG; a.delta = p.delta;
   if (p.b == 8) hipLaunchKernelGGL(recenter_kernel<8>, dim3(p.R), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(recenter_kernel<16>, dim3(p.R), dim3(256), 0, s, a);
   return hip_ok(hipGetLastError());

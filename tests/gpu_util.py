@@ -33,7 +33,8 @@ class GpuProblem:
     """R chains; X [Rd,N,d] f32, Xq [Rd,N,d] int, y [Rd,N]; state buffers allocated here."""
 
     def __init__(self, X, Xq, y, *, K=1, R=1, loss=hp.LOSS_SQUARED, b=8, B=1, T=0, alpha=0.01,
-                 mu=1.0, lam=0.0, delta_d=1.0, seed=0, share_data=False, w0=None):
+                 mu=1.0, lam=0.0, delta_d=1.0, seed=0, share_data=False, w0=None,
+                 algorithm=hp.ALG_HALP, delta=0.0):
         X = np.asarray(X, dtype=np.float32)
         if X.ndim == 2:
             X = X[None]
@@ -58,7 +59,8 @@ class GpuProblem:
         if w0 is not None:
             self.st["w"].copy_(torch.from_numpy(np.asarray(w0, np.float32).reshape(R, K, d)))
         self.h = hp.Halp(N, d, K=K, R=R, loss=loss, b=b, B=B, T=T, alpha=alpha, mu=mu, lam=lam,
-                         delta_d=delta_d, seed=seed, share_data=share_data)
+                         delta_d=delta_d, seed=seed, share_data=share_data, algorithm=algorithm,
+                         delta=delta)
         self.h.bind(X=self.X, Xq=self.Xq, y=self.y, ldx=ldx, ldxq=ldxq, **self.st)
 
     # -- oracle-made inputs to the device
