@@ -67,8 +67,10 @@ def make_problem(hp, inp, torch, cfg, seed=0):
     delta_d = float(X.abs().max().item()) / 127.0
     st = hp.alloc_state(N, d, R=R, b=8)
     Xq = torch.zeros((Rd, N, d), dtype=torch.int8, device="cuda")
+    lp = cfg.get("algorithm") == "lpsvrg"
     h = hp.Halp(N, d, R=R, b=8, T=cfg["T"], alpha=cfg["alpha"], mu=cfg["mu"], delta_d=delta_d,
-                seed=seed, share_data=share)
+                seed=seed, share_data=share, algorithm=hp.ALG_LPSVRG if lp else hp.ALG_HALP,
+                delta=cfg.get("delta", 0.0))
     h.bind(X=X, Xq=Xq, y=y, **st)
     h.quantize_data()
     torch.cuda.synchronize()
@@ -214,6 +216,12 @@ def main():
                          "of the softmax and minibatch configurations")
     ap.add_argument("--inner-steps", type=int, default=2000, help="T for --workload c3 / c5")
     ap.add_argument("--rows", type=int, default=960000, help="N for --workload c3grad")
+    ap.add_argument("--algorithm", default="halp", choices=["halp", "lpsvrg"],
+                    help="halp (default, Algorithm 4) or lpsvrg (Algorithm 2 in integers, fixed "
+                         "delta = --delta) for the c4 / c2 / c1 workloads; lpsvrg is a side "
+                         "measurement and skips the oracle timing")
+    ap.add_argument("--delta", type=float, default=4.0 / 127.0,
+                    help="model scale of --algorithm lpsvrg (teacher weights are N(0,1))")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
     ap.add_argument("--cpu-chains", type=int, default=64)
@@ -249,6 +257,9 @@ def main():
         cfg["share_data"] = args.chains > cfg["R"]
         cfg["R"] = args.chains
     R, N, d, T = cfg["R"], cfg["N"], cfg["d"], cfg["T"]
+    if args.algorithm == "lpsvrg":
+        cfg["algorithm"], cfg["delta"] = "lpsvrg", args.delta
+        args.no_cpu = args.no_c5 = True
     h, X, Xq, y, st, delta_d = make_problem(hp, inp, torch, cfg)
     if args.inner_waves:
         h.set_option(hp.OPT_INNER_WAVES, args.inner_waves)
@@ -269,7 +280,8 @@ def main():
     clamped = int(st["counters"][:, 0].sum().item())
 
     # counter summaries are only valid for the unmodified workload
-    wl_key = args.workload if (args.chains in (0, WORKLOADS[args.workload]["R"])) else "none"
+    wl_key = args.workload if (args.chains in (0, WORKLOADS[args.workload]["R"])
+                               and args.algorithm == "halp") else "none"
     ms_step = dt / args.steps * 1e3
     updates = R * T * d
     value = updates / (ms_step * 1e-3)
@@ -286,6 +298,7 @@ def main():
         "vs_baseline": None, "dtype": "int8 (inner loop) / f32 (gradient pass)", "data": "synthetic",
         "config": {"workload": f"{args.workload}: R={R} independent linear-regression chains, N={N}, "
                                f"d={d}, b=8, T={T} inner steps per epoch, one step = one halp_epoch",
+                   "algorithm": args.algorithm, "delta": cfg.get("delta"),
                    "alpha": cfg["alpha"], "mu": cfg["mu"], "inner_variant": stats.inner_variant, "inner_waves": args.inner_waves,
                    "share_data": bool(cfg.get("share_data")),
                    "timed_epochs": stats.timed_epochs},
