@@ -419,6 +419,39 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
   return 0;
 }
 
+/* ------------------------------------------------------ Algorithm 1, inner loop */
+
+int halp_ref_svrg_inner(const halp_ref_problem* p, const float* X, int64_t ldx, const void* y,
+                        const float* phi, const float* g, uint32_t epoch, int64_t T, double* w) {
+  const int64_t N = p->N; const int d = p->d, B = p->B;
+  if (N <= 0 || d <= 0 || p->K != 1 || B <= 0 || T < 0) return -1;
+  if (p->loss != HALP_REF_SQUARED && p->loss != HALP_REF_LOGISTIC) return -1;
+  double* wt = (double*)malloc(sizeof(double) * (size_t)d);
+  double* step = (double*)malloc(sizeof(double) * (size_t)d);
+  for (int j = 0; j < d; ++j) wt[j] = w[j];
+  for (int64_t t = 0; t < T; ++t) {
+    for (int j = 0; j < d; ++j) step[j] = p->lambda * (w[j] - wt[j]) + (double)g[j];
+    for (int m = 0; m < B; ++m) {
+      const int64_t i = halp_ref_sample_index(p->seed, epoch, (uint64_t)t, B, m, N);
+      const float* x = X + i * ldx;
+      double a1 = 0.0;
+      for (int j = 0; j < d; ++j) a1 += (double)x[j] * w[j];
+      const double a0 = (double)phi[i];
+      double diff;
+      if (p->loss == HALP_REF_LOGISTIC) {
+        const double yi = ((const float*)y)[i];
+        diff = logistic_dl(a1, yi) - logistic_dl(a0, yi);
+      } else {
+        diff = a1 - a0; /* (a1 - y) - (a0 - y) */
+      }
+      for (int j = 0; j < d; ++j) step[j] += diff / (double)B * (double)x[j];
+    }
+    for (int j = 0; j < d; ++j) w[j] -= p->alpha * step[j];
+  }
+  free(wt); free(step);
+  return 0;
+}
+
 void halp_ref_apply_offset(const halp_ref_problem* p, const double scales[8], const int32_t* z,
                            float* w) {
   if (scales[7] != 0.0) return;

@@ -68,7 +68,7 @@ extern "C" {
 #endif
 
 enum { HALP_REF_SQUARED = 0, HALP_REF_LOGISTIC = 1, HALP_REF_SOFTMAX = 2 };
-enum { HALP_REF_ALG_HALP = 0, HALP_REF_ALG_LPSVRG = 1 };
+enum { HALP_REF_ALG_HALP = 0, HALP_REF_ALG_LPSVRG = 1, HALP_REF_ALG_SVRG = 2 };
 
 /* purposes of the random streams (counter word 3) */
 enum {
@@ -144,6 +144,13 @@ void halp_ref_quantize_data(const float* X, int64_t n, double delta_d, int b, vo
  * Same scales[] layout and status codes as halp_ref_recenter.               */
 int halp_ref_lp_begin(const halp_ref_problem* p, const float* g, const float* w, uint32_t epoch,
                       double scales[8], int64_t* h, int32_t* z);
+
+/* Algorithm 1 (SVRG), inner loop for a linear model in fp64, B rows per step averaged:
+ *   w <- w - alpha ( (1/B) sum_m (l'(x_m^T w) - l'(phi_m)) x_m + lambda (w - w~) + g~ )
+ * over T steps with the index stream of the other algorithms (squared or logistic loss, K = 1).
+ * w (double, [d]) enters as w~ and leaves as w_T; phi are the margins of w~, g is g~.     */
+int halp_ref_svrg_inner(const halp_ref_problem* p, const float* X, int64_t ldx, const void* y,
+                        const float* phi, const float* g, uint32_t epoch, int64_t T, double* w);
 
 /* Algorithm 4, the two outer lines: margins phi_i = x_i^T w~ and
  * g~ = (1/N) sum l'_i(phi_i) x_i (+ lambda w~); loss = f(w~).

@@ -66,6 +66,9 @@ def lib():
         L.halp_ref_lp_begin.restype = C.c_int
         L.halp_ref_lp_begin.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                         C.c_void_p, C.c_void_p]
+        L.halp_ref_svrg_inner.restype = C.c_int
+        L.halp_ref_svrg_inner.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_uint32, C.c_int64, C.c_void_p]
         L.halp_ref_inner_loop.restype = C.c_int
         L.halp_ref_inner_loop.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_uint32, C.c_int64, C.c_void_p,
@@ -88,7 +91,7 @@ def xq_dtype(b):
     return np.int8 if b == 8 else (np.int16 if b == 16 else np.int32)
 
 
-ALG_HALP, ALG_LPSVRG = 0, 1
+ALG_HALP, ALG_LPSVRG, ALG_SVRG = 0, 1, 2
 
 
 def make_problem(N, d, K=1, loss=SQUARED, b=8, B=1, alpha=0.01, mu=1.0, lam=0.0, delta_d=1.0,
@@ -219,6 +222,29 @@ def inner_loop(prob, Xq, phi32, y, h, scales, epoch, T, z0=None, trace_steps=0):
     out["z"] = z
     out["counters"] = counters
     return out
+
+
+def svrg_inner(prob, X, y, phi32, g32, w, epoch, T):
+    """T steps of Algorithm 1 from w~ = w (fp64 state); returns w_T as float64 [d]"""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    yy = _ylike(prob, y)
+    phi32 = np.ascontiguousarray(phi32, dtype=np.float32)
+    g32 = np.ascontiguousarray(g32, dtype=np.float32)
+    w = np.array(w, dtype=np.float64).reshape(prob.d)
+    rc = lib().halp_ref_svrg_inner(C.addressof(prob), _p(X), X.shape[1], _p(yy), _p(phi32), _p(g32),
+                                   epoch, T, _p(w))
+    if rc != 0:
+        raise ValueError(f"halp_ref_svrg_inner rc={rc}")
+    return w
+
+
+def svrg_epoch(prob, X, y, w, epoch, T):
+    """one SVRG epoch as the library runs it: fp64 gradient pass rounded to fp32, inner loop,
+    w~ <- fp32(w_T)"""
+    phi, g, loss = full_gradient(prob, X, y, np.asarray(w, np.float32).reshape(1, prob.d))
+    wT = svrg_inner(prob, X, y, phi.astype(np.float32), g.astype(np.float32),
+                    np.asarray(w, np.float32).reshape(prob.d), epoch, T)
+    return dict(w=wT.astype(np.float32).reshape(1, prob.d), w64=wT, phi=phi, g=g, loss=loss)
 
 
 def apply_offset(prob, scales, z, w):
