@@ -61,6 +61,12 @@ extern "C" {
  * lambda must be 0 in that mode; mu is ignored.                                          */
 #define HALP_ALG_HALP 0
 #define HALP_ALG_LPSVRG 1
+/* HALP_ALG_SVRG is Algorithm 1, full-precision SVRG, for squared and logistic loss with one
+ * row per step: the comparator of the paper's Table 3.  An epoch is halp_full_gradient and
+ * then T steps  w <- w - alpha ((l'(x_i^T w) - l'(phi_i)) x_i + lambda (w - w~) + g~)  on the
+ * fp32 data X with the same index stream as the other two; w~ <- w_T.  It needs X, y, w,
+ * phi, g only; halp_recenter is not part of it (HALP_ERR_INVALID); b, mu, delta_d are unused. */
+#define HALP_ALG_SVRG 2
 
 typedef struct halp_handle halp_handle; /* opaque, library-owned */
 

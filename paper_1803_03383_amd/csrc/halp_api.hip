@@ -37,11 +37,13 @@ int check_params(const halp_params& p) {
     return HALP_ERR_INVALID;
   }
   if (!(p.alpha > 0) || !std::isfinite(p.alpha)) return HALP_ERR_INVALID;
-  if (p.algorithm != HALP_ALG_LPSVRG && (!(p.mu > 0) || !std::isfinite(p.mu))) return HALP_ERR_INVALID;
+  if (p.algorithm == HALP_ALG_HALP && (!(p.mu > 0) || !std::isfinite(p.mu))) return HALP_ERR_INVALID;
   if (!(p.lambda >= 0) || !std::isfinite(p.lambda)) return HALP_ERR_INVALID;
   if (!(p.delta_d > 0) || !std::isfinite(p.delta_d)) return HALP_ERR_INVALID;
   if (p.share_data != 0 && p.share_data != 1) return HALP_ERR_INVALID;
-  if (p.algorithm != HALP_ALG_HALP && p.algorithm != HALP_ALG_LPSVRG) return HALP_ERR_INVALID;
+  if (p.algorithm < HALP_ALG_HALP || p.algorithm > HALP_ALG_SVRG) return HALP_ERR_INVALID;
+  if (p.algorithm == HALP_ALG_SVRG && (p.loss == HALP_LOSS_SOFTMAX || p.B != 1))
+    return HALP_ERR_UNSUPPORTED;
   if (p.algorithm == HALP_ALG_LPSVRG) {
     if (!(p.delta > 0) || !std::isfinite(p.delta)) return HALP_ERR_INVALID;
     if (p.lambda != 0) return HALP_ERR_INVALID;  // no L2 term in the integer form of Algorithm 2
@@ -54,6 +56,8 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 int need(const void* p) { return p ? HALP_OK : HALP_ERR_NOT_BOUND; }
 
+int launch_inner(const halp_handle& h, int variant, uint32_t epoch, hipStream_t s);
+
 // the register-resident family: one kernel for scalar margins, one for softmax
 int reg_supported(const halp_handle& h) {
   if (h.p.loss == HALP_LOSS_SOFTMAX && h.p.algorithm == HALP_ALG_LPSVRG) return HALP_ERR_UNSUPPORTED;
@@ -65,7 +69,13 @@ int launch_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
                                        : launch_inner_reg(h, epoch, s);
 }
 
+int launch_inner(const halp_handle& h, int variant, uint32_t epoch, hipStream_t s) {
+  if (variant == 3) return launch_inner_svrg(h, epoch, s);
+  return variant == 2 ? launch_reg(h, epoch, s) : launch_inner_generic(h, epoch, TraceBufs{}, s);
+}
+
 int pick_inner_variant(const halp_handle& h) {
+  if (h.p.algorithm == HALP_ALG_SVRG) return 3;  // the fp32 SVRG kernel
   if (h.inner_variant == 1) return 1;
   if (h.inner_variant == 2) return 2;
   return reg_supported(h) == HALP_OK ? 2 : 1;
@@ -91,6 +101,10 @@ int need_recenter(const halp_handle& h) {
 
 int need_inner(const halp_handle& h, int variant) {
   if (!h.bound) return HALP_ERR_NOT_BOUND;
+  if (h.p.algorithm == HALP_ALG_SVRG) {
+    if (!h.buf.X || !h.buf.y || !h.buf.w || !h.buf.phi || !h.buf.g) return HALP_ERR_NOT_BOUND;
+    return inner_svrg_supported(h);
+  }
   if (!h.buf.Xq || !h.buf.h || !h.buf.z || !h.buf.scales || !h.buf.w || !h.buf.counters)
     return HALP_ERR_NOT_BOUND;
   if ((h.p.loss != HALP_LOSS_SQUARED || h.p.algorithm == HALP_ALG_LPSVRG) && !h.buf.phi)
@@ -235,6 +249,7 @@ int halp_full_gradient(halp_handle* h, void* stream) {
 
 int halp_recenter(halp_handle* h, int64_t epoch, void* stream) {
   if (!h) return HALP_ERR_NULL;
+  if (h->p.algorithm == HALP_ALG_SVRG) return HALP_ERR_INVALID;
   int rc = check_epoch(epoch);
   if (rc == HALP_OK) rc = need_recenter(*h);
   if (rc != HALP_OK) return rc;
@@ -248,8 +263,7 @@ int halp_inner_loop(halp_handle* h, int64_t epoch, void* stream) {
   const int variant = pick_inner_variant(*h);
   rc = need_inner(*h, variant);
   if (rc != HALP_OK) return rc;
-  rc = variant == 2 ? launch_reg(*h, (uint32_t)epoch, as_stream(stream))
-                    : launch_inner_generic(*h, (uint32_t)epoch, TraceBufs{}, as_stream(stream));
+  rc = launch_inner(*h, variant, (uint32_t)epoch, as_stream(stream));
   if (rc == HALP_OK) h->last_inner_variant = variant;
   return rc;
 }
@@ -259,7 +273,7 @@ int halp_inner_loop_trace(halp_handle* h, int64_t epoch, int64_t M, int64_t* idx
   if (!h) return HALP_ERR_NULL;
   int rc = check_epoch(epoch);
   if (rc != HALP_OK) return rc;
-  if (M < 0) return HALP_ERR_INVALID;
+  if (M < 0 || h->p.algorithm == HALP_ALG_SVRG) return HALP_ERR_INVALID;
   rc = need_inner(*h, 1);
   if (rc != HALP_OK) return rc;
   TraceBufs tr;
@@ -276,18 +290,17 @@ int halp_epoch(halp_handle* h, int64_t epoch, void* stream) {
   // every requirement is checked before the first launch
   const int variant = pick_inner_variant(*h);
   if ((rc = need_full_gradient(*h)) != HALP_OK) return rc;
-  if ((rc = need_recenter(*h)) != HALP_OK) return rc;
+  const bool svrg = h->p.algorithm == HALP_ALG_SVRG;  // Algorithm 1 has no re-scaling step
+  if (!svrg && (rc = need_recenter(*h)) != HALP_OK) return rc;
   if ((rc = need_inner(*h, variant)) != HALP_OK) return rc;
   hipStream_t s = as_stream(stream);
   hipEvent_t* ev = h->ev[h->timed % halp_handle::kTimedEpochs];
   if (h->timing && hipEventRecord(ev[0], s) != hipSuccess) return HALP_ERR_HIP;
   if ((rc = launch_full_gradient(*h, s)) != HALP_OK) return rc;
   if (h->timing && hipEventRecord(ev[1], s) != hipSuccess) return HALP_ERR_HIP;
-  if ((rc = launch_recenter(*h, (uint32_t)epoch, s)) != HALP_OK) return rc;
+  if (!svrg && (rc = launch_recenter(*h, (uint32_t)epoch, s)) != HALP_OK) return rc;
   if (h->timing && hipEventRecord(ev[2], s) != hipSuccess) return HALP_ERR_HIP;
-  rc = variant == 2 ? launch_reg(*h, (uint32_t)epoch, s)
-                    : launch_inner_generic(*h, (uint32_t)epoch, TraceBufs{}, s);
-  if (rc != HALP_OK) return rc;
+  if ((rc = launch_inner(*h, variant, (uint32_t)epoch, s)) != HALP_OK) return rc;
   h->last_inner_variant = variant;
   if (h->timing) {
     if (hipEventRecord(ev[3], s) != hipSuccess) return HALP_ERR_HIP;

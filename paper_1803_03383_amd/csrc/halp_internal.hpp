@@ -51,6 +51,8 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_softmax_supported(const halp_handle& h);
 int launch_inner_softmax(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s);
+int inner_svrg_supported(const halp_handle& h);
+int launch_inner_svrg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int launch_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
                               int64_t count, uint32_t* out, hipStream_t s);
 int launch_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
