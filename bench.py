@@ -67,10 +67,9 @@ def make_problem(hp, inp, torch, cfg, seed=0):
     delta_d = float(X.abs().max().item()) / 127.0
     st = hp.alloc_state(N, d, R=R, b=8)
     Xq = torch.zeros((Rd, N, d), dtype=torch.int8, device="cuda")
-    lp = cfg.get("algorithm") == "lpsvrg"
+    alg = {"lpsvrg": hp.ALG_LPSVRG, "svrg": hp.ALG_SVRG}.get(cfg.get("algorithm"), hp.ALG_HALP)
     h = hp.Halp(N, d, R=R, b=8, T=cfg["T"], alpha=cfg["alpha"], mu=cfg["mu"], delta_d=delta_d,
-                seed=seed, share_data=share, algorithm=hp.ALG_LPSVRG if lp else hp.ALG_HALP,
-                delta=cfg.get("delta", 0.0))
+                seed=seed, share_data=share, algorithm=alg, delta=cfg.get("delta", 0.0))
     h.bind(X=X, Xq=Xq, y=y, **st)
     h.quantize_data()
     torch.cuda.synchronize()
@@ -216,10 +215,10 @@ def main():
                          "of the softmax and minibatch configurations")
     ap.add_argument("--inner-steps", type=int, default=2000, help="T for --workload c3 / c5")
     ap.add_argument("--rows", type=int, default=960000, help="N for --workload c3grad")
-    ap.add_argument("--algorithm", default="halp", choices=["halp", "lpsvrg"],
-                    help="halp (default, Algorithm 4) or lpsvrg (Algorithm 2 in integers, fixed "
-                         "delta = --delta) for the c4 / c2 / c1 workloads; lpsvrg is a side "
-                         "measurement and skips the oracle timing")
+    ap.add_argument("--algorithm", default="halp", choices=["halp", "lpsvrg", "svrg"],
+                    help="halp (default, Algorithm 4), lpsvrg (Algorithm 2 in integers, fixed "
+                         "delta = --delta) or svrg (Algorithm 1, fp32) for the c4 / c2 / c1 "
+                         "workloads; the last two are side measurements and skip the oracle timing")
     ap.add_argument("--delta", type=float, default=4.0 / 127.0,
                     help="model scale of --algorithm lpsvrg (teacher weights are N(0,1))")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
@@ -257,8 +256,10 @@ def main():
         cfg["share_data"] = args.chains > cfg["R"]
         cfg["R"] = args.chains
     R, N, d, T = cfg["R"], cfg["N"], cfg["d"], cfg["T"]
-    if args.algorithm == "lpsvrg":
-        cfg["algorithm"], cfg["delta"] = "lpsvrg", args.delta
+    if args.algorithm != "halp":
+        cfg["algorithm"] = args.algorithm
+        if args.algorithm == "lpsvrg":
+            cfg["delta"] = args.delta
         args.no_cpu = args.no_c5 = True
     h, X, Xq, y, st, delta_d = make_problem(hp, inp, torch, cfg)
     if args.inner_waves:
@@ -286,7 +287,10 @@ def main():
     updates = R * T * d
     value = updates / (ms_step * 1e-3)
     inner_ms, fg_ms = stats.ms_inner_loop, stats.ms_full_gradient
-    alu_achieved = updates * LANEOPS_PER_UPDATE_B8 / (inner_ms * 1e-3)
+    # fp32 SVRG: one FMA for the dot, one FMA and one subtraction for the update per coordinate
+    laneops = 3.0 if args.algorithm == "svrg" else LANEOPS_PER_UPDATE_B8
+    inner_kernel = "inner_svrg_kernel" if args.algorithm == "svrg" else "inner_reg_kernel"
+    alu_achieved = updates * laneops / (inner_ms * 1e-3)
     fg_bytes = (1 if cfg.get("share_data") else R) * N * (4 * d + 4 + 4) + \
         (R * N * 4 if cfg.get("share_data") else 0)
     fg_gbs = fg_bytes / (fg_ms * 1e-3) / 1e9
@@ -302,10 +306,10 @@ def main():
                    "alpha": cfg["alpha"], "mu": cfg["mu"], "inner_variant": stats.inner_variant, "inner_waves": args.inner_waves,
                    "share_data": bool(cfg.get("share_data")),
                    "timed_epochs": stats.timed_epochs},
-        "roofline": {"kernel": "inner_reg_kernel", "bound": "alu", "achieved": alu_achieved / 1e12,
+        "roofline": {"kernel": inner_kernel, "bound": "alu", "achieved": alu_achieved / 1e12,
                      "peak": ALU_PEAK_LANEOPS / 1e12, "unit": "Tlane-op/s",
                      "frac": alu_achieved / ALU_PEAK_LANEOPS,
-                     "traffic": measured_traffic("inner_reg_kernel", wl_key),
+                     "traffic": measured_traffic(inner_kernel, wl_key),
                      "ms": inner_ms, "feature_updates_per_s": updates / (inner_ms * 1e-3),
                      "steps_per_s_per_chain": T / (inner_ms * 1e-3)},
         "roofline_full_gradient": {"kernel": "fullgrad_k1", "bound": "hbm", "achieved": fg_gbs,

@@ -51,6 +51,8 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_softmax_supported(const halp_handle& h);
 int launch_inner_softmax(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s);
+int inner_batch_supported(const halp_handle& h);
+int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_svrg_supported(const halp_handle& h);
 int launch_inner_svrg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int launch_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,

@@ -1,0 +1,363 @@
+// Inner loop of Algorithm 4 (LM-HALP) with a minibatch of B rows per step (K = 1):
+// all rows of a step see the same z, each has its own gamma, z is quantized once per step.
+//
+// One workgroup per chain: worker waves and one service wave.
+//
+// A worker thread owns the coordinates of one 4/8/16-byte fragment of a row (CPT of them)
+// with z, h~ and the window's Philox words in registers.  The B rows of a step (B d b/8
+// bytes: 512 KB at B = 64, d = 4096, b = 16 — the size of a CU's register file) cannot stay
+// on chip between the dot products and the update, so they are read twice: once from HBM
+// for the dots, once more (from L2) for the update.
+//   pass 1   per row: packed integer dot of the fragment with z (v_dot4 at 8 bits; at 16
+//            bits v_dot2 against a low and a high part of z separately, so that
+//            32-bit sums stay exact), DPP fold, one LDS slot per wave and row      | barrier
+//   service  one row per lane: D_m, beta_m, gamma_m = Q_(delta_s,b)(beta_m) into LDS     | barrier
+//   pass 2   per row: sum_m gamma_m x_m accumulated per coordinate (gamma split into its
+//            low and high byte at 16 bits), then the rounding of z
+// The service wave also draws the indices two steps ahead and gathers the margins and
+// labels of the next step's rows; its loads stay in flight across the barriers, which
+// wait for LDS only.
+#include "halp_device.hpp"
+#include "inner_args.hpp"
+
+namespace halp {
+namespace {
+
+constexpr int kMaxB = 64;   // rows per step: one per service lane
+constexpr int kChunk = 8;   // rows in flight per worker thread
+
+typedef short short2v __attribute__((ext_vector_type(2)));
+
+// workgroup barrier that waits for this wave's LDS traffic only: global loads may stay in
+// flight across it (their registers are waited for where they are used)
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ int mad24(int a, int b, int c) {
+  int r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+__device__ __forceinline__ double logistic_dl(double a, double y) {
+  return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
+}
+
+// NDW: dwords of a row per worker thread; KT: most waves of the workgroup (workers + 1)
+template <int BITS, int NDW, int KT>
+__global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk) {
+  using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
+  using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
+  constexpr int EPD = 32 / BITS;       // elements per dword
+  constexpr int CPT = NDW * EPD;       // coordinates per thread
+  constexpr int CT = 16 / BITS;        // coordinates per strip of 16 rounding bits
+  constexpr int UPL = CPT / CT;        // strips per thread (= 2 NDW)
+  constexpr int QMAX = (1 << (BITS - 1)) - 1, QMIN = -(1 << (BITS - 1));
+  const int chain = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int d = a.d, B = a.B;
+  const int64_t T = a.T;
+  const int64_t row_bytes = a.ldxq * (BITS / 8);
+  const unsigned char* __restrict__ Xq = reinterpret_cast<const unsigned char*>(a.Xq) +
+                                         (int64_t)chain * a.xq_chain_stride * (BITS / 8);
+  const double* sc = a.scales + (int64_t)chain * 8;
+  uint64_t* cnt_out = a.counters + (int64_t)chain * 4;
+  const uint64_t seed = a.seed + (uint64_t)chain;
+
+  if (sc[7] != 0.0) {
+    if (tid < 4) cnt_out[tid] = 0;
+    return;
+  }
+
+  __shared__ int s_idx[4][kMaxB];            // sampled rows of steps t .. t+2, slot = step % 4
+  __shared__ int s_part[2][16][kMaxB];       // per wave and row: low / high partial dot
+  __shared__ int s_gam[kMaxB];               // gamma_m
+  __shared__ int s_cl;                       // c_lambda of the step
+  __shared__ unsigned long long s_cnt[3];
+  if (tid < 3) s_cnt[tid] = 0;
+  const bool use_reg = a.lambda > 0;
+  const bool lp = a.lp != 0;
+
+  if (wave == nwk) {
+    // ===================================================================== service wave
+    const uint32_t N = (uint32_t)a.N;
+    const float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
+    const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
+    const double delta_m = sc[0], inv_s = sc[5];
+    const double dscale = __dmul_rn(a.delta_d, delta_m);
+    const double aB = __ddiv_rn(a.alpha, (double)B);
+    const double al = __dmul_rn(a.alpha, a.lambda);
+    const bool row = lane < B;
+    const bool need_phi = a.loss != HALP_LOSS_SQUARED || lp;
+    unsigned int n_gclamp = 0, n_reg = 0;
+    auto draw_idx = [&](int64_t t) {  // row `lane` of step t (any t names a valid row)
+      const uint64_t n = (uint64_t)t * (uint64_t)B + (uint64_t)min(lane, B - 1);
+      const U4 r = stream_block(seed, kIdx, a.epoch, n >> 2);
+      return (int)__umulhi(pick(r, (uint32_t)(n & 3)), N);
+    };
+    int i0 = draw_idx(0), i1 = draw_idx(1);
+    if (row) { s_idx[0][lane] = i0; s_idx[1][lane] = i1; }
+    float phi_c = need_phi ? phi[i0] : 0.f;
+    float y_c = a.loss == HALP_LOSS_LOGISTIC ? y[i0] : 0.f;
+    __syncthreads();
+    int i_next = i1;
+    for (int64_t t = 0; t < T; ++t) {
+      // margins and labels of the next step's rows: requested now, used after the next barrier pair
+      const float phi_n = need_phi ? phi[i_next] : 0.f;
+      const float y_n = a.loss == HALP_LOSS_LOGISTIC ? y[i_next] : 0.f;
+      // the rounding word of gamma_m and the L2 draw do not depend on the dots either
+      const uint64_t n = (uint64_t)t * (uint64_t)B + (uint64_t)min(lane, B - 1);
+      const uint32_t rw = pick(stream_block(seed, kGamma, a.epoch, n >> 2), (uint32_t)(n & 3));
+      int cl = 0;
+      if (use_reg) {
+        const uint32_t rr = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
+        cl = (int)quantize_real(al, (double)(1 << BITS), rr, 0.0, (double)QMAX, nullptr);
+        n_reg += (lane == 0 && cl != 0) ? 1u : 0u;
+      }
+      lds_barrier();  // the partial dots of this step are in LDS
+      long long D = 0;
+      for (int w2 = 0; w2 < nwk; ++w2) {
+        const long long lo = s_part[0][w2][min(lane, B - 1)];
+        const long long hi = BITS == 8 ? 0 : s_part[1][w2][min(lane, B - 1)];
+        D += lo + hi * 256;
+      }
+      // beta_m = (alpha / B) (l'(phi_m + x_m^T z) - l'(phi_m)), gamma_m = Q_(delta_s, b)(beta_m)
+      const double delta = __dmul_rn(dscale, (double)D);
+      const double a0 = (double)phi_c, yi = (double)y_c;
+      double diff;
+      if (a.loss == HALP_LOSS_LOGISTIC) {
+        const double a1 = lp ? delta : __dadd_rn(a0, delta);
+        diff = __dadd_rn(logistic_dl(a1, yi), -logistic_dl(a0, yi));
+      } else {
+        diff = lp ? __dadd_rn(delta, -a0) : delta;
+      }
+      const double beta = __dmul_rn(aB, diff);
+      bool hit = false;
+      const int gq = (int)quantize_real(beta, inv_s, rw, (double)QMIN, (double)QMAX, &hit);
+      if (row) {
+        s_gam[lane] = gq;
+        n_gclamp += hit ? 1u : 0u;
+      }
+      if (lane == 0) s_cl = cl;
+      lds_barrier();  // gamma is out; the workers update z
+      // indices two steps ahead (slot (t + 2) % 4 was last read in step t - 2)
+      const int i2 = draw_idx(t + 2);
+      if (row) s_idx[(t + 2) & 3][lane] = i2;
+      phi_c = phi_n; y_c = y_n;
+      i_next = i2;
+    }
+    if (n_gclamp) atomicAdd(&s_cnt[1], (unsigned long long)n_gclamp);
+    if (n_reg) atomicAdd(&s_cnt[2], (unsigned long long)n_reg);
+  } else {
+    // ========================================================================= worker
+    const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + (int64_t)chain * d;
+    XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + (int64_t)chain * d;
+    float* __restrict__ wg = a.w + (int64_t)chain * d;
+    const int j0 = tid * CPT;
+    const bool active = j0 < d;
+    // Rows are padded to whole 8-byte groups; a 16-byte fragment is only used when rows are
+    // 16-byte multiples (checked on the host), so a fragment that starts below d lies inside
+    // the row.  Threads past the row re-read its first fragment; their z stays 0.
+    const int frag_off = active ? j0 * (BITS / 8) : 0;
+    int z[CPT], hv[CPT];
+    bool ok[CPT];
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      ok[k] = j0 + k < d;
+      const int j = min(j0 + k, d - 1);
+      z[k] = ok[k] ? (int)zg[j] : 0;
+      hv[k] = ok[k] ? (int)hg[j] : 0;
+    }
+    const uint32_t strip0 = (uint32_t)(j0 / CT);
+    U4 zr[UPL];
+    unsigned long long n_zclamp = 0;
+    auto load_frag = [&](uint32_t (&dst)[NDW], int i) {
+      const unsigned char* rp = Xq + (int64_t)i * row_bytes + frag_off;
+      if (NDW == 1) {
+        dst[0] = *reinterpret_cast<const uint32_t*>(rp);
+      } else if (NDW == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(rp);
+        dst[0] = v.x; dst[NDW > 1 ? 1 : 0] = v.y;
+      } else {
+        const uint4 v = *reinterpret_cast<const uint4*>(rp);
+        dst[0] = v.x; dst[NDW > 1 ? 1 : 0] = v.y; dst[NDW > 2 ? 2 : 0] = v.z; dst[NDW > 3 ? 3 : 0] = v.w;
+      }
+    };
+    __syncthreads();
+
+    for (int64_t t = 0; t < T; ++t) {
+      const int* idx = s_idx[t & 3];
+      if ((t & 7) == 0) {
+#pragma unroll
+        for (int u = 0; u < UPL; ++u) zr[u] = zround_block(seed, a.epoch, strip0 + (uint32_t)u, (uint32_t)(t >> 3));
+      }
+      // z packed for the dots: bytes at 8 bits; low parts and high parts apart at 16 bits
+      uint32_t zp[NDW], zq[NDW];
+#pragma unroll
+      for (int q = 0; q < NDW; ++q) {
+        if (BITS == 8) {
+          zp[q] = (uint32_t)(z[4 * q] & 0xFF) | ((uint32_t)(z[4 * q + 1] & 0xFF) << 8) |
+                  ((uint32_t)(z[4 * q + 2] & 0xFF) << 16) | ((uint32_t)(z[4 * q + 3] & 0xFF) << 24);
+          zq[q] = 0;
+        } else {
+          // z = 256 zh + zl with zl in [-128, 127]: both parts at most 128 in magnitude, so a
+          // wave's sum of 512 products with |x| <= 32767 stays below 2^31
+          const int za = z[(2 * q) % CPT], zb = z[(2 * q + 1) % CPT];
+          const int ha = (za + 128) >> 8, hb = (zb + 128) >> 8;
+          const int la = za - 256 * ha, lb = zb - 256 * hb;
+          zp[q] = (uint32_t)(la & 0xFFFF) | ((uint32_t)lb << 16);
+          zq[q] = (uint32_t)(ha & 0xFFFF) | ((uint32_t)hb << 16);
+        }
+      }
+      // ---- pass 1: dots
+      for (int m0 = 0; m0 < B; m0 += kChunk) {
+        uint32_t xf[kChunk][NDW];
+#pragma unroll
+        for (int r = 0; r < kChunk; ++r) load_frag(xf[r], idx[min(m0 + r, B - 1)]);
+#pragma unroll
+        for (int r = 0; r < kChunk; ++r) {
+          int lo = 0, hi = 0;
+#pragma unroll
+          for (int q = 0; q < NDW; ++q) {
+            if (BITS == 8) {
+              lo = __builtin_amdgcn_sdot4((int)xf[r][q], (int)zp[q], lo, false);
+            } else {
+              const short2v xv = __builtin_bit_cast(short2v, xf[r][q]);
+              lo = __builtin_amdgcn_sdot2(xv, __builtin_bit_cast(short2v, zp[q]), lo, false);
+              hi = __builtin_amdgcn_sdot2(xv, __builtin_bit_cast(short2v, zq[q]), hi, false);
+            }
+          }
+          lo = wave_sum_i32(lo);
+          if (BITS == 16) hi = wave_sum_i32(hi);
+          if (lane == 0 && m0 + r < B) {
+            s_part[0][wave][m0 + r] = lo;
+            if (BITS == 16) s_part[1][wave][m0 + r] = hi;
+          }
+        }
+      }
+      lds_barrier();
+      lds_barrier();
+      // ---- pass 2: sum_m gamma_m x_m per coordinate (low / high byte of gamma apart at 16 bits)
+      int acc[CPT], acch[CPT];
+#pragma unroll
+      for (int k = 0; k < CPT; ++k) acc[k] = acch[k] = 0;
+      for (int m0 = 0; m0 < B; m0 += kChunk) {
+        uint32_t xf[kChunk][NDW];
+        int gm[kChunk];
+#pragma unroll
+        for (int r = 0; r < kChunk; ++r) {
+          load_frag(xf[r], idx[min(m0 + r, B - 1)]);
+          gm[r] = m0 + r < B ? s_gam[m0 + r] : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < kChunk; ++r) {
+          const int gl = BITS == 8 ? gm[r] : (gm[r] & 0xFF), gh = gm[r] >> 8;
+#pragma unroll
+          for (int k = 0; k < CPT; ++k) {
+            const uint32_t xv = xf[r][k / EPD];
+            const int sh = (k % EPD) * BITS;
+            const int x = BITS == 8 ? (int)(int8_t)(xv >> sh) : (int)(int16_t)(xv >> sh);
+            acc[k] = mad24(gl, x, acc[k]);
+            if (BITS == 16) acch[k] = mad24(gh, x, acch[k]);
+          }
+        }
+      }
+      // ---- u = z - sum gamma x - h~ - c_lambda z in (delta_i, 2b); z = Q_(delta_m, b)(u)
+      const int cl = use_reg ? s_cl : 0;
+#pragma unroll
+      for (int k = 0; k < CPT; ++k) {
+        const U4& blk = zr[k / CT];
+        const uint32_t field = zround_field(blk, (uint32_t)t);
+        const long long re = (long long)((field >> ((k % CT) * BITS)) & ((1u << BITS) - 1u));
+        const long long gsum = (long long)acc[k] + (BITS == 16 ? (long long)acch[k] * 256 : 0);
+        const long long v = -(long long)hv[k] - (long long)cl * (long long)z[k] - gsum;
+        const long long zu = (long long)z[k] + ((v + re) >> BITS);
+        const long long zc = zu > QMAX ? QMAX : (zu < QMIN ? QMIN : zu);
+        n_zclamp += (ok[k] && zu != zc) ? 1u : 0u;
+        z[k] = ok[k] ? (int)zc : 0;
+      }
+    }
+
+    // ---- w~ <- w~ + delta_m z (option I; Algorithm 2: w~ = delta z); hand z out
+    const double delta_m = sc[0];
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      if (ok[k]) {
+        const int j = j0 + k;
+        zg[j] = (XT)z[k];
+        const double step = __dmul_rn(delta_m, (double)z[k]);
+        wg[j] = lp ? (float)step : (float)__dadd_rn((double)wg[j], step);
+      }
+    }
+    if (n_zclamp) atomicAdd(&s_cnt[0], n_zclamp);
+  }
+  __syncthreads();
+  if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
+}
+
+struct BtShape {
+  int ndw, nwk;
+};
+
+// dwords per thread and worker waves: the widest fragment the row alignment allows that
+// still gives every SIMD a wave, at most 15 worker waves
+BtShape pick_shape(const halp_params& p, int64_t row_bytes) {
+  const int epd = 32 / p.b;
+  int ndw = row_bytes % 16 == 0 ? 4 : 2;
+  while (ndw > 1 && (p.d + 64 * ndw * epd - 1) / (64 * ndw * epd) < 4) ndw /= 2;
+  int nwk = (p.d + 64 * ndw * epd - 1) / (64 * ndw * epd);
+  while (nwk > 15 && ndw < (row_bytes % 16 == 0 ? 4 : 2)) {
+    ndw *= 2;
+    nwk = (p.d + 64 * ndw * epd - 1) / (64 * ndw * epd);
+  }
+  return BtShape{ndw, nwk};
+}
+
+}  // namespace
+
+// K = 1, 2 <= B <= 64, squared or logistic loss, up to 15 worker waves of 16-byte fragments
+int inner_batch_supported(const halp_handle& h) {
+  const halp_params& p = h.p;
+  if (p.K != 1 || p.B < 2 || p.B > kMaxB) return HALP_ERR_UNSUPPORTED;
+  if (p.loss != HALP_LOSS_SQUARED && p.loss != HALP_LOSS_LOGISTIC) return HALP_ERR_UNSUPPORTED;
+  if (p.b == 8 && p.d > 131071) return HALP_ERR_UNSUPPORTED;  // int32 dots stay exact
+  if (!h.bound || !h.buf.Xq) return HALP_ERR_NOT_BOUND;
+  const int64_t row_bytes = h.buf.ldxq * (p.b / 8);
+  const BtShape sh = pick_shape(p, row_bytes);
+  if (sh.nwk > 15) return HALP_ERR_UNSUPPORTED;
+  // every fragment that starts below d must lie inside the row
+  const int cpt = sh.ndw * 32 / p.b;
+  if ((int64_t)((p.d + cpt - 1) / cpt) * sh.ndw * 4 > row_bytes) return HALP_ERR_UNSUPPORTED;
+  if (sh.ndw == 4 && reinterpret_cast<uintptr_t>(h.buf.Xq) % 16 != 0) return HALP_ERR_UNSUPPORTED;
+  return HALP_OK;
+}
+
+int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
+  const halp_params& p = h.p;
+  const int rc = inner_batch_supported(h);
+  if (rc != HALP_OK) return rc;
+  const InArgs a = make_inner_args(h, epoch);
+  const BtShape sh = pick_shape(p, h.buf.ldxq * (p.b / 8));
+  const dim3 grid(p.R), block(64 * (sh.nwk + 1));
+#define HALP_BT(BITS_, NDW_)                                                                   \
+  if (p.b == BITS_ && sh.ndw == NDW_) {                                                        \
+    if (sh.nwk + 1 <= 4)                                                                       \
+      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 4>), grid, block, 0, s, a, sh.nwk);  \
+    else if (sh.nwk + 1 <= 8)                                                                  \
+      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 8>), grid, block, 0, s, a, sh.nwk);  \
+    else if (sh.nwk + 1 <= 12)                                                                 \
+      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 12>), grid, block, 0, s, a, sh.nwk); \
+    else                                                                                       \
+      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 16>), grid, block, 0, s, a, sh.nwk); \
+    return hip_ok(hipGetLastError());                                                          \
+  }
+  HALP_BT(8, 1) HALP_BT(8, 2) HALP_BT(8, 4)
+  HALP_BT(16, 1) HALP_BT(16, 2) HALP_BT(16, 4)
+#undef HALP_BT
+  return HALP_ERR_UNSUPPORTED;
+}
+
+}  // namespace halp

@@ -251,7 +251,7 @@ def _oracle_inner(case, r, T):
     """the oracle's inner loop for chain r of a case (cached: the same case runs on several kernels)"""
     key = (id(case["Xq"]), r, T)
     prob = case["mk"](r)
-    key = (prob.N, prob.d, prob.b, prob.loss, prob.seed, prob.mu, prob.lam, T)
+    key = (prob.N, prob.d, prob.b, prob.B, prob.loss, prob.seed, prob.mu, prob.lam, T)
     if key not in _ORACLE_CACHE:
         _ORACLE_CACHE[key] = ref.inner_loop(prob, case["Xq"][r], case["phi"][r], case["y"][r],
                                             case["h"][r], case["scales"][r], 3, T)
@@ -306,6 +306,38 @@ def test_softmax_shapes_outside_the_register_kernel_fall_back():
     P.h.set_option(hp.OPT_INNER_VARIANT, 2)
     with pytest.raises(hp.HalpError):
         P.h.inner_loop(3)
+
+
+BATCH_CASES = [
+    # loss, N, d, B, b, lam, R, T
+    (hp.LOSS_SQUARED, 400, 64, 64, 8, 0.0, 2, 200),        # one worker wave, 4-byte fragments
+    (hp.LOSS_SQUARED, 300, 1000, 7, 8, 1e-2, 1, 303),      # ragged row, odd batch, L2 draws
+    (hp.LOSS_LOGISTIC, 500, 256, 8, 16, 1e-5, 1, 300),
+    (hp.LOSS_LOGISTIC, 300, 4096, 64, 16, 1e-5, 1, 40),    # the C5 shape: 8 worker waves, 16-byte fragments
+    (hp.LOSS_SQUARED, 200, 2048, 33, 16, 0.0, 2, 100),
+    (hp.LOSS_SQUARED, 200, 512, 2, 8, 0.0, 1, 1),
+    (hp.LOSS_SQUARED, 64, 64, 16, 8, 0.0, 1, 300),         # box far too small (mu below): z saturates
+]
+
+
+@pytest.mark.parametrize("variant", [2, 1])
+@pytest.mark.parametrize("loss,N,d,B,b,lam,R,T", BATCH_CASES)
+def test_inner_loop_minibatch_bit_exact(loss, N, d, B, b, lam, R, T, variant):
+    seed = 60 + d + B
+    mu = 500.0 if (N, d, B) == (64, 64, 16) else 0.05
+    case = _inner_case(loss, N, d, 1, B, b, lam, R, T, seed, mu=mu)
+    P = _run_inner(case, loss, 1, B, b, lam, R, T, seed, variant, mu=mu)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    assert P.h.get_stats(0).inner_variant == variant
+    for r in range(R):
+        out = _oracle_inner(case, r, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        w_r = ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r])
+        assert np.array_equal(w[r], w_r)
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    if mu > 100:
+        assert cnt[0, 0] > 0
 
 
 GENERIC_CASES = [
