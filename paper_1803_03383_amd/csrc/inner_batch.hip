@@ -40,6 +40,25 @@ __device__ __forceinline__ int mad24(int a, int b, int c) {
   return r;
 }
 
+// Sums of 8 values over the 64 lanes of a wave at once: v[m] is this lane's share of sum m.
+// Three exchange steps inside each group of 8 lanes (partner lane ^ 7, ^ 2, ^ 1) halve the
+// number of values a lane carries while doubling the lanes each covers, leaving lane l with
+// sum l % 8 over its group; three more (lane ^ 8, ^ 16, ^ 32) add the groups.  Every lane
+// returns the complete sum number l % 8.  Integer sums: the order does not matter.
+__device__ __forceinline__ int wave_sums8_i32(const int (&v)[8], int lane) {
+  const bool f2 = (lane & 4) != 0, f1 = (lane & 2) != 0, f0 = (lane & 1) != 0;
+  int w[4], u[2];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) w[m] = (f2 ? v[m + 4] : v[m]) + dpp_half_mirror(f2 ? v[m] : v[m + 4]);
+#pragma unroll
+  for (int m = 0; m < 2; ++m) u[m] = (f1 ? w[m + 2] : w[m]) + dpp_quad_swap2(f1 ? w[m] : w[m + 2]);
+  int r = (f0 ? u[1] : u[0]) + dpp_quad_swap1(f0 ? u[0] : u[1]);
+  r += __builtin_amdgcn_update_dpp(0, r, 0x128, 0xF, 0xF, false);  // row_ror:8 = lane ^ 8
+  r += __builtin_amdgcn_ds_swizzle(r, 0x401F);                      // lane ^ 16
+  r += __shfl_xor(r, 32);
+  return r;
+}
+
 __device__ __forceinline__ double logistic_dl(double a, double y) {
   return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
 }
@@ -172,7 +191,14 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
       hv[k] = ok[k] ? (int)hg[j] : 0;
     }
     const uint32_t strip0 = (uint32_t)(j0 / CT);
-    U4 zr[UPL];
+    // At 8 strips per thread the window's 8 Philox blocks (32 registers) are parked in LDS
+    // as [word][strips 0..3 | 4..7][thread] of 16 bytes (a wave reads consecutive addresses;
+    // a thread reads only what it wrote) and the words of two steps are fetched at a time.
+    constexpr bool kPark = UPL == 8;
+    extern __shared__ __attribute__((aligned(16))) uint4 s_zr[];
+    const int nworkers = 64 * nwk;
+    U4 zr[kPark ? 1 : UPL];
+    uint32_t zw[kPark ? UPL : 1];
     unsigned long long n_zclamp = 0;
     auto load_frag = [&](uint32_t (&dst)[NDW], int i) {
       const unsigned char* rp = Xq + (int64_t)i * row_bytes + frag_off;
@@ -186,13 +212,42 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
         dst[0] = v.x; dst[NDW > 1 ? 1 : 0] = v.y; dst[NDW > 2 ? 2 : 0] = v.z; dst[NDW > 3 ? 3 : 0] = v.w;
       }
     };
+    uint32_t xa[kChunk][NDW], xb[kChunk][NDW];
+    auto load_chunk = [&](uint32_t (&dst)[kChunk][NDW], const int* idx, int m0) {
+#pragma unroll
+      for (int r = 0; r < kChunk; ++r) load_frag(dst[r], idx[min(m0 + r, B - 1)]);
+    };
     __syncthreads();
+    load_chunk(xa, s_idx[0], 0);
 
     for (int64_t t = 0; t < T; ++t) {
       const int* idx = s_idx[t & 3];
       if ((t & 7) == 0) {
+        if (kPark) {
 #pragma unroll
-        for (int u = 0; u < UPL; ++u) zr[u] = zround_block(seed, a.epoch, strip0 + (uint32_t)u, (uint32_t)(t >> 3));
+          for (int q = 0; q < UPL / 4; ++q) {
+            U4 blk[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              blk[u] = zround_block(seed, a.epoch, strip0 + (uint32_t)(4 * q + u), (uint32_t)(t >> 3));
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd)
+              s_zr[(wd * (UPL / 4) + q) * nworkers + tid] =
+                  make_uint4(pick(blk[0], wd), pick(blk[1], wd), pick(blk[2], wd), pick(blk[3], wd));
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < (kPark ? 1 : UPL); ++u)
+            zr[u] = zround_block(seed, a.epoch, strip0 + (uint32_t)u, (uint32_t)(t >> 3));
+        }
+      }
+      if (kPark && (t & 1) == 0) {  // the block word that serves steps t and t + 1
+#pragma unroll
+        for (int q = 0; q < UPL / 4; ++q) {
+          const uint4 v = s_zr[(((int)(t & 7) >> 1) * (UPL / 4) + q) * nworkers + tid];
+          zw[(4 * q) % UPL] = v.x; zw[(4 * q + 1) % UPL] = v.y;
+          zw[(4 * q + 2) % UPL] = v.z; zw[(4 * q + 3) % UPL] = v.w;
+        }
       }
       // z packed for the dots: bytes at 8 bits; low parts and high parts apart at 16 bits
       uint32_t zp[NDW], zq[NDW];
@@ -212,31 +267,38 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
           zq[q] = (uint32_t)(ha & 0xFFFF) | ((uint32_t)hb << 16);
         }
       }
+      // Rows come in chunks of 8 through two register buffers: while one chunk is worked on
+      // the next is in flight, across the passes and across the steps (the chunk after the
+      // last of pass 1 is the first of pass 2; after pass 2, the first of the next step).
       // ---- pass 1: dots
-      for (int m0 = 0; m0 < B; m0 += kChunk) {
-        uint32_t xf[kChunk][NDW];
-#pragma unroll
-        for (int r = 0; r < kChunk; ++r) load_frag(xf[r], idx[min(m0 + r, B - 1)]);
+      auto dots = [&](uint32_t (&xf)[kChunk][NDW], int m0) {
+        int lo[kChunk], hi[kChunk];
 #pragma unroll
         for (int r = 0; r < kChunk; ++r) {
-          int lo = 0, hi = 0;
+          lo[r] = hi[r] = 0;
 #pragma unroll
           for (int q = 0; q < NDW; ++q) {
             if (BITS == 8) {
-              lo = __builtin_amdgcn_sdot4((int)xf[r][q], (int)zp[q], lo, false);
+              lo[r] = __builtin_amdgcn_sdot4((int)xf[r][q], (int)zp[q], lo[r], false);
             } else {
               const short2v xv = __builtin_bit_cast(short2v, xf[r][q]);
-              lo = __builtin_amdgcn_sdot2(xv, __builtin_bit_cast(short2v, zp[q]), lo, false);
-              hi = __builtin_amdgcn_sdot2(xv, __builtin_bit_cast(short2v, zq[q]), hi, false);
+              lo[r] = __builtin_amdgcn_sdot2(xv, __builtin_bit_cast(short2v, zp[q]), lo[r], false);
+              hi[r] = __builtin_amdgcn_sdot2(xv, __builtin_bit_cast(short2v, zq[q]), hi[r], false);
             }
           }
-          lo = wave_sum_i32(lo);
-          if (BITS == 16) hi = wave_sum_i32(hi);
-          if (lane == 0 && m0 + r < B) {
-            s_part[0][wave][m0 + r] = lo;
-            if (BITS == 16) s_part[1][wave][m0 + r] = hi;
-          }
         }
+        const int slo = wave_sums8_i32(lo, lane);  // row m0 + lane % 8
+        const int shi = BITS == 16 ? wave_sums8_i32(hi, lane) : 0;
+        if (lane < kChunk && m0 + lane < B) {
+          s_part[0][wave][m0 + lane] = slo;
+          if (BITS == 16) s_part[1][wave][m0 + lane] = shi;
+        }
+      };
+      for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
+        load_chunk(xb, idx, m0 + kChunk);
+        dots(xa, m0);
+        load_chunk(xa, idx, m0 + 2 * kChunk < B ? m0 + 2 * kChunk : 0);
+        if (m0 + kChunk < B) dots(xb, m0 + kChunk);
       }
       lds_barrier();
       lds_barrier();
@@ -244,33 +306,58 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
       int acc[CPT], acch[CPT];
 #pragma unroll
       for (int k = 0; k < CPT; ++k) acc[k] = acch[k] = 0;
-      for (int m0 = 0; m0 < B; m0 += kChunk) {
-        uint32_t xf[kChunk][NDW];
+      auto accumulate = [&](uint32_t (&xf)[kChunk][NDW], int m0) {
         int gm[kChunk];
 #pragma unroll
-        for (int r = 0; r < kChunk; ++r) {
-          load_frag(xf[r], idx[min(m0 + r, B - 1)]);
-          gm[r] = m0 + r < B ? s_gam[m0 + r] : 0;
-        }
+        for (int r = 0; r < kChunk; ++r) gm[r] = m0 + r < B ? s_gam[min(m0 + r, kMaxB - 1)] : 0;
+        if (BITS == 16) {
+          // Two rows at a time: v_perm puts coordinate j of both rows into one register, one
+          // v_dot2 against the pair of gammas then serves both rows.  gamma = 256 gh + gl with
+          // gl in [0, 255]: 64 products of each part stay below 2^31.
 #pragma unroll
-        for (int r = 0; r < kChunk; ++r) {
-          const int gl = BITS == 8 ? gm[r] : (gm[r] & 0xFF), gh = gm[r] >> 8;
+          for (int r = 0; r < kChunk; r += 2) {
+            const uint32_t glp = (uint32_t)(gm[r] & 0xFF) | ((uint32_t)(gm[r + 1] & 0xFF) << 16);
+            const uint32_t ghp = (uint32_t)((gm[r] >> 8) & 0xFFFF) | ((uint32_t)(gm[r + 1] >> 8) << 16);
+            const short2v gl2 = __builtin_bit_cast(short2v, glp), gh2 = __builtin_bit_cast(short2v, ghp);
 #pragma unroll
-          for (int k = 0; k < CPT; ++k) {
-            const uint32_t xv = xf[r][k / EPD];
-            const int sh = (k % EPD) * BITS;
-            const int x = BITS == 8 ? (int)(int8_t)(xv >> sh) : (int)(int16_t)(xv >> sh);
-            acc[k] = mad24(gl, x, acc[k]);
-            if (BITS == 16) acch[k] = mad24(gh, x, acch[k]);
+            for (int q = 0; q < NDW; ++q) {
+              const uint32_t xr0 = xf[r][q], xr1 = xf[r + 1][q];
+              // (row r, row r + 1) of the even and of the odd coordinate of this dword
+              const short2v pe = __builtin_bit_cast(short2v, __builtin_amdgcn_perm(xr1, xr0, 0x05040100u));
+              const short2v po = __builtin_bit_cast(short2v, __builtin_amdgcn_perm(xr1, xr0, 0x07060302u));
+              acc[(2 * q) % CPT] = __builtin_amdgcn_sdot2(pe, gl2, acc[(2 * q) % CPT], false);
+              acch[(2 * q) % CPT] = __builtin_amdgcn_sdot2(pe, gh2, acch[(2 * q) % CPT], false);
+              acc[(2 * q + 1) % CPT] = __builtin_amdgcn_sdot2(po, gl2, acc[(2 * q + 1) % CPT], false);
+              acch[(2 * q + 1) % CPT] = __builtin_amdgcn_sdot2(po, gh2, acch[(2 * q + 1) % CPT], false);
+            }
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < kChunk; ++r) {
+#pragma unroll
+            for (int k = 0; k < CPT; ++k) {
+              const uint32_t xv = xf[r][k / EPD];
+              const int x = (int)(int8_t)(xv >> ((k % EPD) * 8));
+              acc[k] = mad24(gm[r], x, acc[k]);
+            }
           }
         }
+      };
+      const int* idn = s_idx[(t + 1) & 3];
+      for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
+        load_chunk(xb, idx, m0 + kChunk);
+        accumulate(xa, m0);
+        if (m0 + 2 * kChunk < B) load_chunk(xa, idx, m0 + 2 * kChunk);
+        else load_chunk(xa, idn, 0);
+        accumulate(xb, m0 + kChunk);
       }
       // ---- u = z - sum gamma x - h~ - c_lambda z in (delta_i, 2b); z = Q_(delta_m, b)(u)
       const int cl = use_reg ? s_cl : 0;
 #pragma unroll
       for (int k = 0; k < CPT; ++k) {
-        const U4& blk = zr[k / CT];
-        const uint32_t field = zround_field(blk, (uint32_t)t);
+        // the strip's 16-bit field of this step: half (t % 2) of word (t % 8) / 2 of its block
+        const uint32_t field = kPark ? (zw[(k / CT) % (kPark ? UPL : 1)] >> (16u * (uint32_t)(t & 1))) & 0xFFFFu
+                                     : zround_field(zr[kPark ? 0 : k / CT], (uint32_t)t);
         const long long re = (long long)((field >> ((k % CT) * BITS)) & ((1u << BITS) - 1u));
         const long long gsum = (long long)acc[k] + (BITS == 16 ? (long long)acch[k] * 256 : 0);
         const long long v = -(long long)hv[k] - (long long)cl * (long long)z[k] - gsum;
@@ -296,6 +383,17 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
   }
   __syncthreads();
   if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
+}
+
+template <int BITS, int NDW, int KT>
+int launch_kt(const InArgs& a, int nwk, dim3 grid, dim3 block, size_t smem, hipStream_t s) {
+  auto kern = inner_batch_kernel<BITS, NDW, KT>;
+  if (smem > 0 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)smem) != hipSuccess)
+    return HALP_ERR_HIP;
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk);
+  return hip_ok(hipGetLastError());
 }
 
 struct BtShape {
@@ -342,17 +440,14 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const InArgs a = make_inner_args(h, epoch);
   const BtShape sh = pick_shape(p, h.buf.ldxq * (p.b / 8));
   const dim3 grid(p.R), block(64 * (sh.nwk + 1));
-#define HALP_BT(BITS_, NDW_)                                                                   \
-  if (p.b == BITS_ && sh.ndw == NDW_) {                                                        \
-    if (sh.nwk + 1 <= 4)                                                                       \
-      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 4>), grid, block, 0, s, a, sh.nwk);  \
-    else if (sh.nwk + 1 <= 8)                                                                  \
-      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 8>), grid, block, 0, s, a, sh.nwk);  \
-    else if (sh.nwk + 1 <= 12)                                                                 \
-      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 12>), grid, block, 0, s, a, sh.nwk); \
-    else                                                                                       \
-      hipLaunchKernelGGL((inner_batch_kernel<BITS_, NDW_, 16>), grid, block, 0, s, a, sh.nwk); \
-    return hip_ok(hipGetLastError());                                                          \
+  // parked Philox blocks: 128 bytes per worker thread at 8 strips per thread (120 KB at most)
+  const size_t smem = sh.ndw == 4 ? (size_t)64 * sh.nwk * 128 : 0;
+#define HALP_BT(BITS_, NDW_)                                                     \
+  if (p.b == BITS_ && sh.ndw == NDW_) {                                          \
+    if (sh.nwk + 1 <= 4) return launch_kt<BITS_, NDW_, 4>(a, sh.nwk, grid, block, smem, s);   \
+    if (sh.nwk + 1 <= 8) return launch_kt<BITS_, NDW_, 8>(a, sh.nwk, grid, block, smem, s);   \
+    if (sh.nwk + 1 <= 12) return launch_kt<BITS_, NDW_, 12>(a, sh.nwk, grid, block, smem, s); \
+    return launch_kt<BITS_, NDW_, 16>(a, sh.nwk, grid, block, smem, s);          \
   }
   HALP_BT(8, 1) HALP_BT(8, 2) HALP_BT(8, 4)
   HALP_BT(16, 1) HALP_BT(16, 2) HALP_BT(16, 4)
