@@ -1,9 +1,9 @@
 // Inner loop of Algorithm 4 (LM-HALP) with a minibatch of B rows per step (K = 1):
 // all rows of a step see the same z, each has its own gamma, z is quantized once per step.
 //
-// One workgroup per chain: worker waves and one service wave.
+// One workgroup per chain.
 //
-// A worker thread owns the coordinates of one 4/8/16-byte fragment of a row (CPT of them)
+// A thread owns the coordinates of one 4/8/16-byte fragment of a row (CPT of them)
 // with z, h~ and the window's Philox words in registers.  The B rows of a step (B d b/8
 // bytes: 512 KB at B = 64, d = 4096, b = 16 — the size of a CU's register file) cannot stay
 // on chip between the dot products and the update, so they are read twice: once from HBM
@@ -11,12 +11,12 @@
 //   pass 1   per row: packed integer dot of the fragment with z (v_dot4 at 8 bits; at 16
 //            bits v_dot2 against a low and a high part of z separately, so that
 //            32-bit sums stay exact), DPP fold, one LDS slot per wave and row      | barrier
-//   service  one row per lane: D_m, beta_m, gamma_m = Q_(delta_s,b)(beta_m) into LDS     | barrier
+//   scalars  wave 0, one row per lane: D_m, beta_m, gamma_m = Q_(delta_s,b)(beta_m) into LDS | barrier
 //   pass 2   per row: sum_m gamma_m x_m accumulated per coordinate (gamma split into its
 //            low and high byte at 16 bits), then the rounding of z
-// The service wave also draws the indices two steps ahead and gathers the margins and
-// labels of the next step's rows; its loads stay in flight across the barriers, which
-// wait for LDS only.
+// Wave 0 also draws the indices two steps ahead and gathers the margins and labels of the
+// next step's rows.  Rows travel in chunks of 8 through two register buffers, the next chunk
+// being in flight across passes, steps and barriers (the barriers wait for LDS only).
 #include "halp_device.hpp"
 #include "inner_args.hpp"
 
@@ -63,7 +63,7 @@ __device__ __forceinline__ double logistic_dl(double a, double y) {
   return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
 }
 
-// NDW: dwords of a row per worker thread; KT: most waves of the workgroup (workers + 1)
+// NDW: dwords of a row per thread; KT: most waves of the workgroup
 template <int BITS, int NDW, int KT>
 __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
@@ -100,77 +100,33 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
   const bool use_reg = a.lambda > 0;
   const bool lp = a.lp != 0;
 
-  if (wave == nwk) {
-    // ===================================================================== service wave
-    const uint32_t N = (uint32_t)a.N;
-    const float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
-    const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
-    const double delta_m = sc[0], inv_s = sc[5];
-    const double dscale = __dmul_rn(a.delta_d, delta_m);
-    const double aB = __ddiv_rn(a.alpha, (double)B);
-    const double al = __dmul_rn(a.alpha, a.lambda);
-    const bool row = lane < B;
-    const bool need_phi = a.loss != HALP_LOSS_SQUARED || lp;
-    unsigned int n_gclamp = 0, n_reg = 0;
-    auto draw_idx = [&](int64_t t) {  // row `lane` of step t (any t names a valid row)
-      const uint64_t n = (uint64_t)t * (uint64_t)B + (uint64_t)min(lane, B - 1);
-      const U4 r = stream_block(seed, kIdx, a.epoch, n >> 2);
-      return (int)__umulhi(pick(r, (uint32_t)(n & 3)), N);
-    };
-    int i0 = draw_idx(0), i1 = draw_idx(1);
+  // ---- scalar duties, carried by wave 0 beside its share of z (one row of the step per lane)
+  const bool svc = wave == 0;
+  const uint32_t N = (uint32_t)a.N;
+  const float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
+  const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
+  const double inv_s = sc[5];
+  const double dscale = __dmul_rn(a.delta_d, sc[0]);
+  const double aB = __ddiv_rn(a.alpha, (double)B);
+  const double al = __dmul_rn(a.alpha, a.lambda);
+  const bool row = lane < B;
+  const bool need_phi = a.loss != HALP_LOSS_SQUARED || lp;
+  unsigned int n_gclamp = 0, n_reg = 0;
+  auto draw_idx = [&](int64_t t) {  // row `lane` of step t (any t names a valid row)
+    const uint64_t n = (uint64_t)t * (uint64_t)B + (uint64_t)min(lane, B - 1);
+    const U4 r = stream_block(seed, kIdx, a.epoch, n >> 2);
+    return (int)__umulhi(pick(r, (uint32_t)(n & 3)), N);
+  };
+  float phi_c = 0.f, y_c = 0.f;
+  int i_next = 0;
+  if (svc) {
+    const int i0 = draw_idx(0), i1 = draw_idx(1);
     if (row) { s_idx[0][lane] = i0; s_idx[1][lane] = i1; }
-    float phi_c = need_phi ? phi[i0] : 0.f;
-    float y_c = a.loss == HALP_LOSS_LOGISTIC ? y[i0] : 0.f;
-    __syncthreads();
-    int i_next = i1;
-    for (int64_t t = 0; t < T; ++t) {
-      // margins and labels of the next step's rows: requested now, used after the next barrier pair
-      const float phi_n = need_phi ? phi[i_next] : 0.f;
-      const float y_n = a.loss == HALP_LOSS_LOGISTIC ? y[i_next] : 0.f;
-      // the rounding word of gamma_m and the L2 draw do not depend on the dots either
-      const uint64_t n = (uint64_t)t * (uint64_t)B + (uint64_t)min(lane, B - 1);
-      const uint32_t rw = pick(stream_block(seed, kGamma, a.epoch, n >> 2), (uint32_t)(n & 3));
-      int cl = 0;
-      if (use_reg) {
-        const uint32_t rr = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
-        cl = (int)quantize_real(al, (double)(1 << BITS), rr, 0.0, (double)QMAX, nullptr);
-        n_reg += (lane == 0 && cl != 0) ? 1u : 0u;
-      }
-      lds_barrier();  // the partial dots of this step are in LDS
-      long long D = 0;
-      for (int w2 = 0; w2 < nwk; ++w2) {
-        const long long lo = s_part[0][w2][min(lane, B - 1)];
-        const long long hi = BITS == 8 ? 0 : s_part[1][w2][min(lane, B - 1)];
-        D += lo + hi * 256;
-      }
-      // beta_m = (alpha / B) (l'(phi_m + x_m^T z) - l'(phi_m)), gamma_m = Q_(delta_s, b)(beta_m)
-      const double delta = __dmul_rn(dscale, (double)D);
-      const double a0 = (double)phi_c, yi = (double)y_c;
-      double diff;
-      if (a.loss == HALP_LOSS_LOGISTIC) {
-        const double a1 = lp ? delta : __dadd_rn(a0, delta);
-        diff = __dadd_rn(logistic_dl(a1, yi), -logistic_dl(a0, yi));
-      } else {
-        diff = lp ? __dadd_rn(delta, -a0) : delta;
-      }
-      const double beta = __dmul_rn(aB, diff);
-      bool hit = false;
-      const int gq = (int)quantize_real(beta, inv_s, rw, (double)QMIN, (double)QMAX, &hit);
-      if (row) {
-        s_gam[lane] = gq;
-        n_gclamp += hit ? 1u : 0u;
-      }
-      if (lane == 0) s_cl = cl;
-      lds_barrier();  // gamma is out; the workers update z
-      // indices two steps ahead (slot (t + 2) % 4 was last read in step t - 2)
-      const int i2 = draw_idx(t + 2);
-      if (row) s_idx[(t + 2) & 3][lane] = i2;
-      phi_c = phi_n; y_c = y_n;
-      i_next = i2;
-    }
-    if (n_gclamp) atomicAdd(&s_cnt[1], (unsigned long long)n_gclamp);
-    if (n_reg) atomicAdd(&s_cnt[2], (unsigned long long)n_reg);
-  } else {
+    phi_c = need_phi ? phi[i0] : 0.f;
+    y_c = a.loss == HALP_LOSS_LOGISTIC ? y[i0] : 0.f;
+    i_next = i1;
+  }
+  {
     // ========================================================================= worker
     const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + (int64_t)chain * d;
     XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + (int64_t)chain * d;
@@ -196,7 +152,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
     // a thread reads only what it wrote) and the words of two steps are fetched at a time.
     constexpr bool kPark = UPL == 8;
     extern __shared__ __attribute__((aligned(16))) uint4 s_zr[];
-    const int nworkers = 64 * nwk;
+    const int nworkers = 64 * nwk;  // all threads of the workgroup
     U4 zr[kPark ? 1 : UPL];
     uint32_t zw[kPark ? UPL : 1];
     unsigned long long n_zclamp = 0;
@@ -215,13 +171,31 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
     uint32_t xa[kChunk][NDW], xb[kChunk][NDW];
     auto load_chunk = [&](uint32_t (&dst)[kChunk][NDW], const int* idx, int m0) {
 #pragma unroll
-      for (int r = 0; r < kChunk; ++r) load_frag(dst[r], idx[min(m0 + r, B - 1)]);
+      for (int r = 0; r < kChunk; ++r)  // the row number is uniform: scalar address arithmetic
+        load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(m0 + r, B - 1)]));
     };
     __syncthreads();
     load_chunk(xa, s_idx[0], 0);
 
     for (int64_t t = 0; t < T; ++t) {
       const int* idx = s_idx[t & 3];
+      // wave 0: what the scalar stage needs and does not depend on the dots — margins and
+      // labels of the next step's rows (used after the next barrier pair), the rounding word
+      // of gamma_m, the L2 draw
+      float phi_n = 0.f, y_n = 0.f;
+      uint32_t rw = 0;
+      int cl_draw = 0;
+      if (svc) {
+        phi_n = need_phi ? phi[i_next] : 0.f;
+        y_n = a.loss == HALP_LOSS_LOGISTIC ? y[i_next] : 0.f;
+        const uint64_t n = (uint64_t)t * (uint64_t)B + (uint64_t)min(lane, B - 1);
+        rw = pick(stream_block(seed, kGamma, a.epoch, n >> 2), (uint32_t)(n & 3));
+        if (use_reg) {
+          const uint32_t rr = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
+          cl_draw = (int)quantize_real(al, (double)(1 << BITS), rr, 0.0, (double)QMAX, nullptr);
+          n_reg += (lane == 0 && cl_draw != 0) ? 1u : 0u;
+        }
+      }
       if ((t & 7) == 0) {
         if (kPark) {
 #pragma unroll
@@ -300,8 +274,39 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
         load_chunk(xa, idx, m0 + 2 * kChunk < B ? m0 + 2 * kChunk : 0);
         if (m0 + kChunk < B) dots(xb, m0 + kChunk);
       }
-      lds_barrier();
-      lds_barrier();
+      lds_barrier();  // the partial dots of this step are in LDS
+      if (svc) {
+        long long D = 0;
+        for (int w2 = 0; w2 < nwk; ++w2) {
+          const long long lo = s_part[0][w2][min(lane, B - 1)];
+          const long long hi = BITS == 8 ? 0 : s_part[1][w2][min(lane, B - 1)];
+          D += lo + hi * 256;
+        }
+        // beta_m = (alpha / B) (l'(phi_m + x_m^T z) - l'(phi_m)), gamma_m = Q_(delta_s, b)(beta_m)
+        const double delta = __dmul_rn(dscale, (double)D);
+        const double a0 = (double)phi_c, yi = (double)y_c;
+        double diff;
+        if (a.loss == HALP_LOSS_LOGISTIC) {
+          const double a1 = lp ? delta : __dadd_rn(a0, delta);
+          diff = __dadd_rn(logistic_dl(a1, yi), -logistic_dl(a0, yi));
+        } else {
+          diff = lp ? __dadd_rn(delta, -a0) : delta;
+        }
+        const double beta = __dmul_rn(aB, diff);
+        bool hit = false;
+        const int gq = (int)quantize_real(beta, inv_s, rw, (double)QMIN, (double)QMAX, &hit);
+        if (row) {
+          s_gam[lane] = gq;
+          n_gclamp += hit ? 1u : 0u;
+        }
+        if (lane == 0) s_cl = cl_draw;
+        // indices two steps ahead (slot (t + 2) % 4 was last read in step t - 2)
+        const int i2 = draw_idx(t + 2);
+        if (row) s_idx[(t + 2) & 3][lane] = i2;
+        phi_c = phi_n; y_c = y_n;
+        i_next = i2;
+      }
+      lds_barrier();  // gamma is out
       // ---- pass 2: sum_m gamma_m x_m per coordinate (low / high byte of gamma apart at 16 bits)
       int acc[CPT], acch[CPT];
 #pragma unroll
@@ -309,7 +314,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
       auto accumulate = [&](uint32_t (&xf)[kChunk][NDW], int m0) {
         int gm[kChunk];
 #pragma unroll
-        for (int r = 0; r < kChunk; ++r) gm[r] = m0 + r < B ? s_gam[min(m0 + r, kMaxB - 1)] : 0;
+        for (int r = 0; r < kChunk; ++r)
+          gm[r] = m0 + r < B ? __builtin_amdgcn_readfirstlane(s_gam[min(m0 + r, kMaxB - 1)]) : 0;
         if (BITS == 16) {
           // Two rows at a time: v_perm puts coordinate j of both rows into one register, one
           // v_dot2 against the pair of gammas then serves both rows.  gamma = 256 gh + gl with
@@ -380,6 +386,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
       }
     }
     if (n_zclamp) atomicAdd(&s_cnt[0], n_zclamp);
+    if (n_gclamp) atomicAdd(&s_cnt[1], (unsigned long long)n_gclamp);
+    if (n_reg) atomicAdd(&s_cnt[2], (unsigned long long)n_reg);
   }
   __syncthreads();
   if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
@@ -407,7 +415,7 @@ BtShape pick_shape(const halp_params& p, int64_t row_bytes) {
   int ndw = row_bytes % 16 == 0 ? 4 : 2;
   while (ndw > 1 && (p.d + 64 * ndw * epd - 1) / (64 * ndw * epd) < 4) ndw /= 2;
   int nwk = (p.d + 64 * ndw * epd - 1) / (64 * ndw * epd);
-  while (nwk > 15 && ndw < (row_bytes % 16 == 0 ? 4 : 2)) {
+  while (nwk > 16 && ndw < (row_bytes % 16 == 0 ? 4 : 2)) {
     ndw *= 2;
     nwk = (p.d + 64 * ndw * epd - 1) / (64 * ndw * epd);
   }
@@ -416,7 +424,7 @@ BtShape pick_shape(const halp_params& p, int64_t row_bytes) {
 
 }  // namespace
 
-// K = 1, 2 <= B <= 64, squared or logistic loss, up to 15 worker waves of 16-byte fragments
+// K = 1, 2 <= B <= 64, squared or logistic loss, up to 16 waves of 16-byte fragments
 int inner_batch_supported(const halp_handle& h) {
   const halp_params& p = h.p;
   if (p.K != 1 || p.B < 2 || p.B > kMaxB) return HALP_ERR_UNSUPPORTED;
@@ -425,7 +433,7 @@ int inner_batch_supported(const halp_handle& h) {
   if (!h.bound || !h.buf.Xq) return HALP_ERR_NOT_BOUND;
   const int64_t row_bytes = h.buf.ldxq * (p.b / 8);
   const BtShape sh = pick_shape(p, row_bytes);
-  if (sh.nwk > 15) return HALP_ERR_UNSUPPORTED;
+  if (sh.nwk > 16) return HALP_ERR_UNSUPPORTED;
   // every fragment that starts below d must lie inside the row
   const int cpt = sh.ndw * 32 / p.b;
   if ((int64_t)((p.d + cpt - 1) / cpt) * sh.ndw * 4 > row_bytes) return HALP_ERR_UNSUPPORTED;
@@ -439,14 +447,14 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   if (rc != HALP_OK) return rc;
   const InArgs a = make_inner_args(h, epoch);
   const BtShape sh = pick_shape(p, h.buf.ldxq * (p.b / 8));
-  const dim3 grid(p.R), block(64 * (sh.nwk + 1));
+  const dim3 grid(p.R), block(64 * sh.nwk);
   // parked Philox blocks: 128 bytes per worker thread at 8 strips per thread (120 KB at most)
   const size_t smem = sh.ndw == 4 ? (size_t)64 * sh.nwk * 128 : 0;
 #define HALP_BT(BITS_, NDW_)                                                     \
   if (p.b == BITS_ && sh.ndw == NDW_) {                                          \
-    if (sh.nwk + 1 <= 4) return launch_kt<BITS_, NDW_, 4>(a, sh.nwk, grid, block, smem, s);   \
-    if (sh.nwk + 1 <= 8) return launch_kt<BITS_, NDW_, 8>(a, sh.nwk, grid, block, smem, s);   \
-    if (sh.nwk + 1 <= 12) return launch_kt<BITS_, NDW_, 12>(a, sh.nwk, grid, block, smem, s); \
+    if (sh.nwk <= 4) return launch_kt<BITS_, NDW_, 4>(a, sh.nwk, grid, block, smem, s);   \
+    if (sh.nwk <= 8) return launch_kt<BITS_, NDW_, 8>(a, sh.nwk, grid, block, smem, s);   \
+    if (sh.nwk <= 12) return launch_kt<BITS_, NDW_, 12>(a, sh.nwk, grid, block, smem, s); \
     return launch_kt<BITS_, NDW_, 16>(a, sh.nwk, grid, block, smem, s);          \
   }
   HALP_BT(8, 1) HALP_BT(8, 2) HALP_BT(8, 4)
