@@ -123,10 +123,12 @@ typedef struct {
 #define HALP_OPT_INNER_VARIANT 1 /* 0 auto (default), 1 general, 2 register-resident.
                                     Register-resident kernels exist for B = 1 with K = 1 (squared,
                                     logistic; d up to 8 strips of 16 rounding bits per lane and
-                                    16 waves) and for softmax with K <= 15 (a class's row of z
-                                    within 8 strips per lane of one wave, data rows up to 1 KB);
-                                    auto takes them when the shape fits, 2 fails with
-                                    HALP_ERR_UNSUPPORTED when it does not                   */
+                                    16 waves), for K = 1 with 2 <= B <= 64 (same limit on d), and
+                                    for softmax with B = 1, K <= 15 (a class's row of z within 8
+                                    strips per lane of one wave, data rows up to 1 KB); auto takes
+                                    them when the shape fits, 2 fails with HALP_ERR_UNSUPPORTED
+                                    when it does not.  HALP_ALG_SVRG has one fp32 kernel and
+                                    ignores this option                                      */
 #define HALP_OPT_TIMING 2        /* 1: halp_epoch brackets its phases with events on its stream;
                                     setting it restarts the averages of halp_get_stats     */
 #define HALP_OPT_FULLGRAD_BLOCKS 4 /* workgroups per chain of the gradient pass, 0 = auto  */
