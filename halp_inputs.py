@@ -48,6 +48,22 @@ def softmax_sparse(N, d, K, seed=0, zero_frac=0.8):
     return X.astype(np.float32), y.astype(np.int32), W_star.T.copy().astype(np.float32)
 
 
+def linreg_conditioned(N, d, kappa, seed=0, noise=0.01):
+    """Linear regression with a prescribed spectrum (the recipe of the paper's conditioning
+    study): X = U S V^T with U (N x d, orthonormal columns) and V (d x d) random orthogonal,
+    from QR of Gaussian matrices, and S such that the Hessian X^T X / N of the squared loss
+    has eigenvalues spaced geometrically from 1 to kappa.  w* ~ N(0,1), y = X w* + N(0, noise^2).
+    Returns X, y, w* as fp32 and the eigenvalues."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    U, _ = np.linalg.qr(rng.standard_normal((N, d)))
+    V, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    eig = np.geomspace(1.0, float(kappa), d) if d > 1 else np.ones(1)
+    X = (U * np.sqrt(N * eig)) @ V.T
+    w_star = rng.standard_normal(d)
+    y = X @ w_star + noise * rng.standard_normal(N)
+    return X.astype(np.float32), y.astype(np.float32), w_star.astype(np.float32), eig
+
+
 def default_delta_d(X, b):
     """One scalar data scale so that max|X| maps to the largest code."""
     m = float(np.max(np.abs(X)))

@@ -148,6 +148,14 @@ int halp_bind(halp_handle* h, const halp_buffers* buf);
 
 int halp_set_option(halp_handle* h, int32_t option, int64_t value);
 
+/* Step size and mu per chain, for grids of hyper-parameters run as independent chains (the
+ * paper's conditioning study, Appendix "Conditioning Evaluation", searches both).  alpha and
+ * mu are HOST arrays of R entries, copied synchronously into the library's device workspace;
+ * a NULL array means the value of halp_params for every chain.  Chain r then runs Algorithm
+ * 4 (or 2, or 1) with alpha[r] and mu[r] in place of the two parameters, everything else
+ * as before.  Not to be called while work of this handle is in flight.                   */
+int halp_set_chain_hyper(halp_handle* h, const double* alpha, const double* mu);
+
 /* Data in the low-precision representation (delta_d, b) that Algorithm 4 is
  * given: Xq = clamp(round-half-even(X / delta_d), -(2^(b-1)-1), 2^(b-1)-1).
  * Needs X, Xq.                                                                        */

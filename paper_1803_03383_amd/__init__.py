@@ -17,7 +17,8 @@ OPT_INNER_VARIANT, OPT_TIMING, OPT_FULLGRAD_BLOCKS, OPT_INNER_WAVES = 1, 2, 4, 5
 ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_NOT_BOUND, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "halp_create", "halp_destroy", "halp_bind", "halp_set_option", "halp_quantize_data",
+    "halp_create", "halp_destroy", "halp_bind", "halp_set_option", "halp_set_chain_hyper",
+    "halp_quantize_data",
     "halp_full_gradient", "halp_recenter", "halp_inner_loop", "halp_epoch",
     "halp_inner_loop_trace", "halp_get_stats", "halp_debug_stream_words",
     "halp_debug_zround_bits", "halp_strerror", "halp_last_error_detail", "halp_version",
@@ -77,6 +78,7 @@ def lib():
         L.halp_destroy.argtypes = [vp]
         L.halp_bind.argtypes = [vp, C.POINTER(Buffers)]
         L.halp_set_option.argtypes = [vp, i32, i64]
+        L.halp_set_chain_hyper.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.halp_quantize_data.argtypes = [vp, vp]
         L.halp_full_gradient.argtypes = [vp, vp]
         L.halp_recenter.argtypes = [vp, i64, vp]
@@ -159,6 +161,17 @@ class Halp:
 
     def set_option(self, option, value):
         _check(lib().halp_set_option(self._h, option, value), "halp_set_option")
+
+    def set_chain_hyper(self, alpha=None, mu=None):
+        """Per-chain step size and mu (sequences of R floats, or None for the handle's)."""
+        def arr(v):
+            if v is None:
+                return None
+            v = [float(x) for x in v]
+            if len(v) != self.params.R:
+                raise ValueError("one value per chain expected")
+            return (C.c_double * len(v))(*v)
+        _check(lib().halp_set_chain_hyper(self._h, arr(alpha), arr(mu)), "halp_set_chain_hyper")
 
     def quantize_data(self, stream=None):
         _check(lib().halp_quantize_data(self._h, _stream(stream)), "halp_quantize_data")

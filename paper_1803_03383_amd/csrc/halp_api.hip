@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "halp_internal.hpp"
 
@@ -146,6 +147,11 @@ int halp_create(halp_handle** out, const halp_params* p) {
       return HALP_ERR_HIP;
     }
   }
+  // every chain starts with the step size and mu of the parameters
+  if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->hyper), sizeof(double) * 2 * (size_t)p->R),
+               "hipMalloc(hyper)")) { halp_destroy(h); return HALP_ERR_HIP; }
+  rc = halp_set_chain_hyper(h, nullptr, nullptr);
+  if (rc != HALP_OK) { halp_destroy(h); return rc; }
   for (auto& quad : h->ev)
     for (auto& e : quad)
       if (hip_fail(hipEventCreate(&e), "hipEventCreate")) { halp_destroy(h); return HALP_ERR_HIP; }
@@ -157,10 +163,29 @@ int halp_destroy(halp_handle* h) {
   if (!h) return HALP_ERR_NULL;
   if (h->partial_g) (void)hipFree(h->partial_g);
   if (h->partial_loss) (void)hipFree(h->partial_loss);
+  if (h->hyper) (void)hipFree(h->hyper);
   for (auto& quad : h->ev)
     for (auto& e : quad)
       if (e) (void)hipEventDestroy(e);
   delete h;
+  return HALP_OK;
+}
+
+int halp_set_chain_hyper(halp_handle* h, const double* alpha, const double* mu) {
+  if (!h) return HALP_ERR_NULL;
+  const halp_params& p = h->p;
+  std::vector<double> host(2 * (size_t)p.R);
+  for (int r = 0; r < p.R; ++r) {
+    const double av = alpha ? alpha[r] : p.alpha;
+    const double mv = mu ? mu[r] : p.mu;
+    if (!(av > 0) || !std::isfinite(av)) return HALP_ERR_INVALID;
+    if (p.algorithm == HALP_ALG_HALP && (!(mv > 0) || !std::isfinite(mv))) return HALP_ERR_INVALID;
+    host[2 * (size_t)r] = av;
+    host[2 * (size_t)r + 1] = mv;
+  }
+  if (hip_fail(hipMemcpy(h->hyper, host.data(), sizeof(double) * host.size(), hipMemcpyHostToDevice),
+               "hipMemcpy(hyper)"))
+    return HALP_ERR_HIP;
   return HALP_OK;
 }
 

@@ -22,6 +22,7 @@ struct halp_handle {
   double* partial_loss = nullptr;  // [R][parts]
   int parts = 0;                 // workgroups per chain the workspace was sized for
   size_t partial_g_bytes = 0;
+  double* hyper = nullptr;       // [R][2] step size and mu of each chain (device)
   int last_inner_variant = 0;
   // timing: a ring of event quadruples, one per halp_epoch call since timing was switched on
   static constexpr int kTimedEpochs = 32;

@@ -15,12 +15,13 @@ struct InArgs {
   void* z;              // [R][K][d] int8 / int16
   float* w;             // [R][K][d]
   const double* scales; // [R][8]
+  const double* hyper;  // [R][2] step size and mu of each chain
   uint64_t* counters;   // [R][4]
   int64_t N, ldxq, T;
   int64_t xq_chain_stride, y_chain_stride;  // elements; 0 when chains share the data
   int d, K, B, loss;
   int lp;  // 1: LP-SVRG (Algorithm 2): z is the model itself, the margin is x^T z alone
-  double alpha, lambda, delta_d;
+  double lambda, delta_d;
   uint64_t seed;
   uint32_t epoch;
   TraceBufs tr;
@@ -30,13 +31,13 @@ inline InArgs make_inner_args(const halp_handle& h, uint32_t epoch) {
   const halp_params& p = h.p;
   InArgs a;
   a.Xq = h.buf.Xq; a.phi = h.buf.phi; a.y = h.buf.y; a.h = h.buf.h; a.z = h.buf.z; a.w = h.buf.w;
-  a.scales = h.buf.scales; a.counters = h.buf.counters;
+  a.scales = h.buf.scales; a.counters = h.buf.counters; a.hyper = h.hyper;
   a.N = p.N; a.ldxq = h.buf.ldxq; a.T = p.T;
   a.xq_chain_stride = p.share_data ? 0 : p.N * h.buf.ldxq;
   a.y_chain_stride = p.share_data ? 0 : p.N;
   a.d = p.d; a.K = p.K; a.B = p.B; a.loss = p.loss;
   a.lp = p.algorithm == HALP_ALG_LPSVRG;
-  a.alpha = p.alpha; a.lambda = p.lambda; a.delta_d = p.delta_d;
+  a.lambda = p.lambda; a.delta_d = p.delta_d;
   a.seed = p.seed; a.epoch = epoch;
   return a;
 }

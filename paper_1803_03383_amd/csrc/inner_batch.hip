@@ -107,8 +107,9 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
   const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
   const double inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, sc[0]);
-  const double aB = __ddiv_rn(a.alpha, (double)B);
-  const double al = __dmul_rn(a.alpha, a.lambda);
+  const double alpha = a.hyper[2 * chain];
+  const double aB = __ddiv_rn(alpha, (double)B);
+  const double al = __dmul_rn(alpha, a.lambda);
   const bool row = lane < B;
   const bool need_phi = a.loss != HALP_LOSS_SQUARED || lp;
   unsigned int n_gclamp = 0, n_reg = 0;

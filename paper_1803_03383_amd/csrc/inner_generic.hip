@@ -66,7 +66,8 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
 
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
-  const double aB = __ddiv_rn(a.alpha, (double)B);
+  const double alpha = a.hyper[2 * chain];
+  const double aB = __ddiv_rn(alpha, (double)B);
   const bool lp = a.lp != 0;
   // the margin after the move: Algorithm 4 adds x^T z to phi, in Algorithm 2 x^T w is all of it
   auto after_margin = [&](double a0, long long D) {
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
     }
     if (tid == 0 && a.lambda > 0) {  // c_lambda = Q_(2^-b, b)(alpha lambda)
       const uint32_t r = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
-      const int cl = (int)quantize_real(__dmul_rn(a.alpha, a.lambda), (double)(1 << BITS), r, 0.0,
+      const int cl = (int)quantize_real(__dmul_rn(alpha, a.lambda), (double)(1 << BITS), r, 0.0,
                                         qmaxd, nullptr);
       s_clambda = cl;
       if (cl != 0) s_cnt[2] += 1;

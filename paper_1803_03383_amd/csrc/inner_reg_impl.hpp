@@ -96,12 +96,12 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
 
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
-  const double aB = a.alpha;  // B = 1: alpha / 1
+  const double aB = a.hyper[2 * chain];  // B = 1: alpha / 1
   const bool use_reg = a.lambda > 0;
   constexpr bool logistic = LOSS == HALP_LOSS_LOGISTIC;
   constexpr bool need_phi = LOSS != HALP_LOSS_SQUARED;  // logistic, or squared loss of LP-SVRG
   const bool lp = a.lp != 0;
-  const double al = __dmul_rn(a.alpha, a.lambda);
+  const double al = __dmul_rn(aB, a.lambda);
 
   // ---- per-lane state
   const int s0 = (wave * 64 + lane) * UPL;  // first strip of the lane

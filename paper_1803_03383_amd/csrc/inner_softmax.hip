@@ -122,8 +122,8 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     const float* __restrict__ phi = a.phi + (int64_t)chain * a.N * K;
     const double delta_m = sc[0], inv_s = sc[5];
     const double dscale = __dmul_rn(a.delta_d, delta_m);
-    const double aB = a.alpha;  // B = 1
-    const double al = __dmul_rn(a.alpha, a.lambda);
+    const double aB = a.hyper[2 * chain];  // alpha / B, B = 1
+    const double al = __dmul_rn(aB, a.lambda);
     unsigned int n_gclamp = 0, n_reg = 0;
 
     // sample index of step tw + (lane & 7): any step number names a valid row, so windows

@@ -28,7 +28,8 @@ struct SvArgs {
   int64_t N, ldx, T;
   int64_t x_chain_stride, y_chain_stride;
   int d, loss;
-  double alpha, lambda;
+  const double* hyper;  // [R][2] step size (and mu, unused here) of each chain
+  double lambda;
   uint64_t seed;
   uint32_t epoch;
 };
@@ -65,6 +66,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_svrg_kernel(SvArgs a) {
   // Rows are padded to a multiple of 4 floats, so the fragment at j0 < d lies inside the row
   // even when it runs past d (the excess is masked); threads past the row re-read its start.
   const int jc = j0 < d ? j0 : 0;
+  const double alpha = a.hyper[2 * chain];
   float w[CPL], wt[CPL], ag[CPL];
   bool keep[CPL];
 #pragma unroll
@@ -72,10 +74,10 @@ __global__ __launch_bounds__(64 * NWT) void inner_svrg_kernel(SvArgs a) {
     const bool ok = j0 + k < d;
     const int j = min(j0 + k, d - 1);
     w[k] = wt[k] = ok ? wg[j] : 0.f;
-    ag[k] = ok ? (float)__dmul_rn(a.alpha, (double)g[j]) : 0.f;
+    ag[k] = ok ? (float)__dmul_rn(alpha, (double)g[j]) : 0.f;
     keep[k] = ok;
   }
-  const float al = (float)__dmul_rn(a.alpha, a.lambda);
+  const float al = (float)__dmul_rn(alpha, a.lambda);
   const bool use_reg = a.lambda > 0;
 
   auto fill_batch = [&](int64_t bb) {
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_svrg_kernel(SvArgs a) {
         double diff;
         if (logistic) diff = __dadd_rn(logistic_dl(a1, (double)y8[s]), -logistic_dl(a0, (double)y8[s]));
         else diff = __dadd_rn(a1, -a0);  // (a1 - y) - (a0 - y)
-        const float c = (float)__dmul_rn(a.alpha, diff);
+        const float c = (float)__dmul_rn(alpha, diff);
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
           float u = __builtin_fmaf(-c, xw[s][k], w[k]) - ag[k];
@@ -251,7 +253,7 @@ int launch_inner_svrg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   a.N = p.N; a.ldx = h.buf.ldx; a.T = p.T;
   a.x_chain_stride = p.share_data ? 0 : p.N * h.buf.ldx;
   a.y_chain_stride = p.share_data ? 0 : p.N;
-  a.d = p.d; a.loss = p.loss; a.alpha = p.alpha; a.lambda = p.lambda;
+  a.d = p.d; a.loss = p.loss; a.hyper = h.hyper; a.lambda = p.lambda;
   a.seed = p.seed; a.epoch = epoch;
   const SvShape sh = pick_shape(h);
 #define HALP_SV(C_, W_) \

@@ -17,7 +17,8 @@ struct RcArgs {
   double* scales;
   int n;  // K*d
   int b;
-  double alpha, mu, delta_d;
+  const double* hyper;  // [R][2] alpha, mu of each chain
+  double delta_d;
   uint64_t seed;
   uint32_t epoch;
 };
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(256) void recenter_kernel(RcArgs a) {
       status = 1;
     } else {
       // Algorithm 4: s~ = ||g~|| / (mu (2^(b-1) - 1)); Algorithm 2: the given delta
-      delta_m = a.lp ? a.delta : __ddiv_rn(nrm, __dmul_rn(a.mu, qmax));
+      delta_m = a.lp ? a.delta : __ddiv_rn(nrm, __dmul_rn(a.hyper[2 * chain + 1], qmax));
       delta_i = __dmul_rn(delta_m, BITS == 8 ? 0x1p-8 : 0x1p-16);
       delta_s = __ddiv_rn(delta_i, a.delta_d);
       inv_i = __ddiv_rn(1.0, delta_i);
@@ -82,6 +83,7 @@ __global__ __launch_bounds__(256) void recenter_kernel(RcArgs a) {
   }
   __syncthreads();
   const double inv_i = s_inv_i;
+  const double alpha = a.hyper[2 * chain];
   const bool live = s_status == 0;
   const double hmax = BITS == 8 ? 32767.0 : 2147483647.0;
   const double hmin = BITS == 8 ? -32768.0 : -2147483648.0;
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(256) void recenter_kernel(RcArgs a) {
       if (k < a.n) {
         long long q = 0;
         if (live)  // h~ = Q_(delta_i, 2b)(alpha g~)
-          q = quantize_real(__dmul_rn(a.alpha, (double)g[k]), inv_i, pick(r, e), hmin, hmax, nullptr);
+          q = quantize_real(__dmul_rn(alpha, (double)g[k]), inv_i, pick(r, e), hmin, hmax, nullptr);
         h[k] = (HT)q;
         int z0 = 0;  // Algorithm 4: z_{k,0} = Q(0) = 0
         if (a.lp) {  // Algorithm 2: w_{k,0} = w~_k in (delta, b), nearest (ties to even)
@@ -165,7 +167,7 @@ int launch_recenter(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const halp_params& p = h.p;
   RcArgs a;
   a.g = h.buf.g; a.h = h.buf.h; a.z = h.buf.z; a.scales = h.buf.scales;
-  a.n = p.K * p.d; a.b = p.b; a.alpha = p.alpha; a.mu = p.mu; a.delta_d = p.delta_d;
+  a.n = p.K * p.d; a.b = p.b; a.hyper = h.hyper; a.delta_d = p.delta_d;
   a.seed = p.seed; a.epoch = epoch;
   a.w = h.buf.w; a.lp = p.algorithm == HALP_ALG_LPSVRG; a.delta = p.delta;
   if (p.b == 8) hipLaunchKernelGGL(recenter_kernel<8>, dim3(p.R), dim3(256), 0, s, a);
