@@ -205,14 +205,69 @@ def softmax_gradient_pass(hp, torch, rows, reps):
     return out
 
 
+def conditioning_sweep(hp, inp, torch, epochs, T):
+    """The conditioning study (appendix "Conditioning Evaluation") as a many-chains workload:
+    linear regression 1000 x 64 with Hessian spectrum 1..kappa, `epochs` epochs of T steps, SVRG
+    against 16-bit and 8-bit HALP, every (kappa, step size, mu) grid point one chain of a single
+    handle per algorithm.  Reports the best final gradient norm per kappa and algorithm, and
+    the time of the whole sweep."""
+    N, d = 1000, 64
+    kappas = [1.0, 10.0, 100.0, 1e3, 1e4, 1e5]
+    alphas = [10.0 ** (-k / 2.0) for k in range(3, 15)]          # 3.2e-2 .. 1e-7
+    mus = [0.5, 2.0, 8.0, 32.0, 128.0, 512.0, 2000.0]
+    data = [inp.linreg_conditioned(N, d, k, seed=1) for k in kappas]
+    out = {"N": N, "d": d, "T": T, "epochs": epochs, "kappas": kappas,
+           "grid": {"alpha": alphas, "mu": mus}, "runs": {}}
+    t_all = 0.0
+    for name, alg, b in [("svrg_fp32", hp.ALG_SVRG, 8), ("halp16", hp.ALG_HALP, 16), ("halp8", hp.ALG_HALP, 8)]:
+        grid = [(a, m) for a in alphas for m in (mus if alg == hp.ALG_HALP else [1.0])]
+        R = len(kappas) * len(grid)
+        X = torch.from_numpy(np.stack([data[i][0] for i in range(len(kappas)) for _ in grid])).cuda()
+        y = torch.from_numpy(np.stack([data[i][1] for i in range(len(kappas)) for _ in grid])).cuda()
+        # one data scale for the handle: the largest entry over all kappas
+        delta_d = float(X.abs().max().item()) / float(2 ** (b - 1) - 1)
+        st = hp.alloc_state(N, d, R=R, b=b)
+        Xq = torch.zeros((R, N, d), dtype=torch.int8 if b == 8 else torch.int16, device="cuda")
+        h = hp.Halp(N, d, R=R, b=b, T=T, alpha=1e-3, mu=1.0, delta_d=delta_d, seed=0, algorithm=alg)
+        h.bind(X=X, Xq=Xq, y=y, **st)
+        h.set_chain_hyper(alpha=[a for _ in kappas for a, _ in grid], mu=[m for _ in kappas for _, m in grid])
+        if alg == hp.ALG_HALP:
+            h.quantize_data()
+        h.full_gradient()
+        torch.cuda.synchronize()
+        g0 = st["g"].double().reshape(R, -1).norm(dim=1).cpu().numpy()
+        t0 = time.perf_counter()
+        for k in range(epochs):
+            h.epoch(k)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        t_all += dt
+        h.full_gradient()
+        torch.cuda.synchronize()
+        gn = st["g"].double().reshape(R, -1).norm(dim=1).cpu().numpy()
+        gn = np.where(np.isfinite(gn), gn, np.inf).reshape(len(kappas), len(grid))
+        best = gn.argmin(axis=1)
+        out["runs"][name] = {
+            "chains": R, "seconds": dt, "inner_variant": h.get_stats(0).inner_variant,
+            "feature_updates_per_s": R * T * d * epochs / dt,
+            "initial_gradient_norm": [float(g0[i * len(grid)]) for i in range(len(kappas))],
+            "best_gradient_norm": [float(gn[i, best[i]]) for i in range(len(kappas))],
+            "best_alpha_mu": [list(grid[best[i]]) for i in range(len(kappas))]}
+        h.close()
+        del X, y, Xq, st
+    out["seconds_total"] = t_all
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c5", "c3grad"],
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c5", "c3grad", "cond"],
                     help="c4 (default), c2, c1: the headline line; c3, c5: inner-loop step rate "
-                         "of the softmax and minibatch configurations")
+                         "of the softmax and minibatch configurations; c3grad: the softmax "
+                         "gradient pass; cond: the conditioning sweep (5 x --steps epochs)")
     ap.add_argument("--inner-steps", type=int, default=2000, help="T for --workload c3 / c5")
     ap.add_argument("--rows", type=int, default=960000, help="N for --workload c3grad")
     ap.add_argument("--algorithm", default="halp", choices=["halp", "lpsvrg", "svrg"],
@@ -246,6 +301,10 @@ def main():
     if args.workload == "c3grad":
         print(json.dumps({"workload": "c3grad",
                           "softmax_gradient_pass": softmax_gradient_pass(hp, torch, args.rows, args.steps)}))
+        return
+    if args.workload == "cond":
+        print(json.dumps({"workload": "cond", "conditioning_sweep":
+                          conditioning_sweep(hp, inp, torch, max(args.steps, 1) * 5, 1000)}))
         return
     if args.workload in ("c3", "c5"):
         print(json.dumps({"workload": args.workload, "side_inner_loop":
