@@ -180,6 +180,124 @@ __global__ __launch_bounds__(256) void fullgrad_k1(FgArgs a) {
   }
 }
 
+// ---- K = 1, narrow rows (d <= 128) ----------------------------------------------
+// A row of up to 4 G floats is held by G lanes (G = 4, 8, 16, 32), so a wave works on 64 / G
+// consecutive rows at once -- one coalesced load of 1 KB at d = 4 G -- instead of leaving most
+// of its lanes idle.  The margin is folded inside the G lanes only.  RB such row groups make
+// a batch; batches are double-buffered as above.
+template <typename T>
+__device__ __forceinline__ T group_sum(T v, int G) {
+  v += dpp_quad_swap1(v);
+  v += dpp_quad_swap2(v);
+  if (G >= 8) v += dpp_half_mirror(v);
+  if (G >= 16) v += dpp_row_mirror(v);
+  if (G >= 32) v += __shfl_xor(v, 16);
+  return v;
+}
+
+template <int G, int RB, int LOSS>
+__global__ __launch_bounds__(256) void fullgrad_k1_narrow(FgArgs a) {
+  constexpr int RW = 64 / G;       // rows per wave and group
+  constexpr int BR = RB * RW;      // rows per batch
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int sub = lane % G, rsel = lane / G;
+  const int chain = blockIdx.y;
+  const float* __restrict__ X = a.X + (int64_t)chain * a.x_chain_stride;
+  const float* __restrict__ y =
+      reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
+  const float* __restrict__ w = a.w + (int64_t)chain * a.d;
+  float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
+  const int d = a.d;
+  const int64_t N = a.N, ldx = a.ldx;
+  const int col = 4 * sub;
+
+  F4 wv = make_f4(0.f, 0.f, 0.f, 0.f), gv = make_f4(0.f, 0.f, 0.f, 0.f);
+  if (col < d) wv.x = w[col];
+  if (col + 1 < d) wv.y = w[col + 1];
+  if (col + 2 < d) wv.z = w[col + 2];
+  if (col + 3 < d) wv.w = w[col + 3];
+  double loss_acc = 0.0;
+
+  const int64_t nblk = (N + BR - 1) / BR;
+  const int64_t stride = (int64_t)a.parts * 4;
+  int64_t bi = (int64_t)blockIdx.x * 4 + wave;
+
+  F4 xa[RB], xb[RB];
+  auto load_batch = [&](F4(&xv)[RB], int64_t blk) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const int64_t row = blk * BR + r * RW + rsel;
+      xv[r] = make_f4(0.f, 0.f, 0.f, 0.f);
+      if (row < N) xv[r] = load_chunk<false>(X + row * ldx, col, d);
+    }
+  };
+  auto reduce_batch = [&](F4(&xv)[RB], int64_t blk) {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const float m = group_sum(dot4(xv[r], wv, 0.f), G);  // phi_i, in all G lanes of the row
+      const int64_t row = blk * BR + r * RW + rsel;
+      const bool ok = row < N;
+      const float yi = ok ? y[row] : 0.f;
+      float rr, li;
+      if (LOSS == HALP_LOSS_SQUARED) {
+        rr = m - yi;
+        li = 0.5f * rr * rr;
+      } else {
+        rr = -yi / (1.0f + expf(yi * m));
+        const float sgn = -yi * m;
+        li = fmaxf(sgn, 0.f) + log1pf(expf(-fabsf(sgn)));
+      }
+      if (ok && sub == 0) {
+        phi[row] = m;
+        loss_acc += (double)li;
+      }
+      axpy4(ok ? rr : 0.f, xv[r], gv);
+    }
+  };
+
+  if (bi < nblk) load_batch(xa, bi);
+  while (bi < nblk) {
+    const int64_t b1 = bi + stride;
+    if (b1 < nblk) load_batch(xb, b1);
+    reduce_batch(xa, bi);
+    if (b1 >= nblk) break;
+    const int64_t b2 = b1 + stride;
+    if (b2 < nblk) load_batch(xa, b2);
+    reduce_batch(xb, b1);
+    bi = b2;
+  }
+
+  // the wave's row groups hold partial gradients of the same columns: add them, group 0 ends
+  // up with the wave's sum (a fixed order), likewise the loss
+#pragma unroll
+  for (int off = 32; off >= G; off >>= 1) {
+    gv.x += __shfl_xor(gv.x, off); gv.y += __shfl_xor(gv.y, off);
+    gv.z += __shfl_xor(gv.z, off); gv.w += __shfl_xor(gv.w, off);
+    loss_acc += __shfl_xor(loss_acc, off);
+  }
+  __shared__ F4 fold[4][G];
+  __shared__ double fold_loss[4];
+  if (lane < G) fold[wave][lane] = gv;
+  if (lane == 0) fold_loss[wave] = loss_acc;
+  __syncthreads();
+  if (wave == 0 && lane < G) {
+#pragma unroll
+    for (int sw = 1; sw < 4; ++sw) {
+      const F4 o = fold[sw][lane];
+      gv.x += o.x; gv.y += o.y; gv.z += o.z; gv.w += o.w;
+    }
+    float* pg = a.partial_g + ((int64_t)chain * a.parts + blockIdx.x) * (int64_t)d;
+    if (col < d) pg[col] = gv.x;
+    if (col + 1 < d) pg[col + 1] = gv.y;
+    if (col + 2 < d) pg[col + 2] = gv.z;
+    if (col + 3 < d) pg[col + 3] = gv.w;
+    if (lane == 0)
+      a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] =
+          ((fold_loss[0] + fold_loss[1]) + fold_loss[2]) + fold_loss[3];
+  }
+}
+
 // ---- second stage: fixed-order sum of the per-workgroup partials --------------
 struct RedArgs {
   const float* partial_g;
@@ -262,7 +380,29 @@ int fullgrad_supported(const halp_params& p) {
   return nv <= 16 ? HALP_OK : HALP_ERR_UNSUPPORTED;  // d <= 4096
 }
 
-static int rows_per_batch(int nv) { return nv >= 16 ? 1 : 16 / nv; }
+// narrow rows: lanes per row (0 = the row-per-wave kernel) and rows per batch
+constexpr int kNarrowGroups = 8;
+static int narrow_lanes(int d) {
+  if (d > 128) return 0;
+  int g = 4;
+  while (4 * g < d) g *= 2;
+  return g;
+}
+static int rows_per_batch(int d) {
+  const int g = narrow_lanes(d);
+  if (g) return kNarrowGroups * (64 / g);
+  const int nv = nv_for(d);
+  return nv >= 16 ? 1 : 16 / nv;
+}
+
+template <int G>
+int launch_narrow(const FgArgs& a, int loss, dim3 grid, hipStream_t s) {
+  if (loss == HALP_LOSS_SQUARED)
+    hipLaunchKernelGGL((fullgrad_k1_narrow<G, kNarrowGroups, HALP_LOSS_SQUARED>), grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((fullgrad_k1_narrow<G, kNarrowGroups, HALP_LOSS_LOGISTIC>), grid, dim3(256), 0, s, a);
+  return hip_ok(hipGetLastError());
+}
 
 int fullgrad_parts(const halp_handle& h) {
   const halp_params& p = h.p;
@@ -273,7 +413,7 @@ int fullgrad_parts(const halp_handle& h) {
     if (parts > tiles) parts = tiles;
     return (int)(parts < 1 ? 1 : parts);
   }
-  const int rb = rows_per_batch(nv_for(p.d));
+  const int rb = rows_per_batch(p.d);
   const int64_t nblk = (p.N + rb - 1) / rb;
   int64_t parts = (2 * (int64_t)h.num_cus + p.R - 1) / p.R;  // two workgroups per CU
   const int64_t most = (nblk + 3) / 4;                        // one batch per wave at least
@@ -297,6 +437,13 @@ int launch_full_gradient(const halp_handle& h, hipStream_t s) {
   const int nv = nv_for(p.d);
   if (p.loss == HALP_LOSS_SOFTMAX) {
     rc = launch_fullgrad_softmax(a, p.R, s);
+  } else if (const int g = narrow_lanes(p.d)) {
+    switch (g) {
+      case 4: rc = launch_narrow<4>(a, p.loss, grid, s); break;
+      case 8: rc = launch_narrow<8>(a, p.loss, grid, s); break;
+      case 16: rc = launch_narrow<16>(a, p.loss, grid, s); break;
+      default: rc = launch_narrow<32>(a, p.loss, grid, s); break;
+    }
   } else {
     const bool exact = p.d == 256 * nv;
     switch (nv) {

@@ -69,6 +69,14 @@ FG_CASES = [
     (hp.LOSS_LOGISTIC, 2500, 1024, 1, 1, 1e-5),
     (hp.LOSS_LOGISTIC, 403, 4096, 1, 2, 1e-5),
     (hp.LOSS_LOGISTIC, 5, 7 * 4, 1, 1, 0.0),
+    # narrow rows (d <= 128): several rows per wave, 4 / 8 / 16 / 32 lanes each
+    (hp.LOSS_SQUARED, 1000, 64, 1, 3, 0.0),
+    (hp.LOSS_SQUARED, 77, 5, 1, 2, 1e-3),
+    (hp.LOSS_SQUARED, 2049, 16, 1, 1, 0.0),
+    (hp.LOSS_LOGISTIC, 130, 33, 1, 2, 1e-5),
+    (hp.LOSS_SQUARED, 513, 100, 1, 2, 1e-3),
+    (hp.LOSS_LOGISTIC, 999, 128, 1, 1, 0.0),
+    (hp.LOSS_SQUARED, 1, 128, 1, 1, 0.0),
     (hp.LOSS_SOFTMAX, 1500, 784, 10, 1, 1e-4),
     (hp.LOSS_SOFTMAX, 333, 100, 3, 2, 1e-4),
     (hp.LOSS_SOFTMAX, 64, 257, 16, 1, 0.0),
