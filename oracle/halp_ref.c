@@ -77,6 +77,12 @@ int64_t halp_ref_sample_index(uint64_t seed, uint32_t epoch, uint64_t t, int32_t
   return (int64_t)(((uint64_t)r * (uint64_t)N) >> 32);
 }
 
+int64_t halp_ref_option2_steps(uint64_t seed, uint32_t epoch, int64_t T) {
+  if (T <= 0) return T;
+  const uint32_t r = halp_ref_stream_word(seed, HALP_REF_PURPOSE_OPT2, epoch, 0);
+  return (int64_t)(((uint64_t)r * (uint64_t)T) >> 32);
+}
+
 /* ------------------------------------------------------------ quantizers */
 
 /* Sec. 3 "Quantization": inside the domain round down to the lattice point

@@ -76,7 +76,8 @@ enum {
   HALP_REF_PURPOSE_GAMMA = 1,  /* rounding of the scalar beta         */
   HALP_REF_PURPOSE_ZROUND = 2, /* rounding of the offset vector z     */
   HALP_REF_PURPOSE_REG = 3,    /* rounding of alpha*lambda            */
-  HALP_REF_PURPOSE_HROUND = 4  /* rounding of alpha*g~ into h~        */
+  HALP_REF_PURPOSE_HROUND = 4, /* rounding of alpha*g~ into h~        */
+  HALP_REF_PURPOSE_OPT2 = 5    /* option II: where an epoch ends      */
 };
 
 typedef struct {
@@ -115,6 +116,11 @@ void halp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32
 /* word n of a purpose's stream: Philox block n/4, word n%4,
  * counter = (lo32(n/4), hi32(n/4), epoch, purpose), key = (lo32 seed, hi32 seed) */
 uint32_t halp_ref_stream_word(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n);
+
+/* Option II of Algorithms 1-3: t uniform on {0, .., T-1}; the epoch ends at the iterate after
+ * t steps (t = 0: the outer iterate does not move).  Word 0 of the purpose's stream of that
+ * epoch, mapped like the sample indices.  The caller runs the inner loop for t steps.       */
+int64_t halp_ref_option2_steps(uint64_t seed, uint32_t epoch, int64_t T);
 
 /* the b rounding bits of coordinate (c,j) at 0-based step t */
 uint32_t halp_ref_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,

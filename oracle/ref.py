@@ -11,7 +11,7 @@ import numpy as np
 from . import build as _build
 
 SQUARED, LOGISTIC, SOFTMAX = 0, 1, 2
-PURPOSE_IDX, PURPOSE_GAMMA, PURPOSE_ZROUND, PURPOSE_REG, PURPOSE_HROUND = 0, 1, 2, 3, 4
+PURPOSE_IDX, PURPOSE_GAMMA, PURPOSE_ZROUND, PURPOSE_REG, PURPOSE_HROUND, PURPOSE_OPT2 = 0, 1, 2, 3, 4, 5
 
 
 class Problem(C.Structure):
@@ -43,6 +43,8 @@ def lib():
         L.halp_ref_zround_bits.restype = C.c_uint32
         L.halp_ref_zround_bits.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32,
                                            C.c_int32, C.c_int32, C.c_int32]
+        L.halp_ref_option2_steps.restype = C.c_int64
+        L.halp_ref_option2_steps.argtypes = [C.c_uint64, C.c_uint32, C.c_int64]
         L.halp_ref_sample_index.restype = C.c_int64
         L.halp_ref_sample_index.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32,
                                             C.c_int32, C.c_int64]
@@ -118,6 +120,11 @@ def zround_bits(seed, epoch, t, d, b, c, j):
 
 def sample_index(seed, epoch, t, B, m, N):
     return int(lib().halp_ref_sample_index(seed, epoch, t, B, m, N))
+
+
+def option2_steps(seed, epoch, T):
+    """option II: the number of inner steps after which the epoch of that number ends"""
+    return int(lib().halp_ref_option2_steps(seed, epoch, T))
 
 
 def quantize_real(x, inv_delta, r32, lo, hi):
@@ -238,9 +245,11 @@ def svrg_inner(prob, X, y, phi32, g32, w, epoch, T):
     return w
 
 
-def svrg_epoch(prob, X, y, w, epoch, T):
+def svrg_epoch(prob, X, y, w, epoch, T, option2=False):
     """one SVRG epoch as the library runs it: fp64 gradient pass rounded to fp32, inner loop,
-    w~ <- fp32(w_T)"""
+    w~ <- fp32(w_T) (option I) or fp32(w_t), t drawn (option II)"""
+    if option2:
+        T = option2_steps(prob.seed, epoch, T)
     phi, g, loss = full_gradient(prob, X, y, np.asarray(w, np.float32).reshape(1, prob.d))
     wT = svrg_inner(prob, X, y, phi.astype(np.float32), g.astype(np.float32),
                     np.asarray(w, np.float32).reshape(prob.d), epoch, T)
@@ -255,8 +264,11 @@ def apply_offset(prob, scales, z, w):
     return w
 
 
-def epoch(prob, X, Xq, y, w, epoch_no, T):
-    """one HALP epoch; returns dict(w, phi, g, scales, h, z, counters)"""
+def epoch(prob, X, Xq, y, w, epoch_no, T, option2=False):
+    """one HALP epoch; returns dict(w, phi, g, scales, h, z, counters).  option2: the epoch ends
+    at the iterate after t steps, t drawn uniformly from {0..T-1} (option II)"""
+    if option2:
+        T = option2_steps(prob.seed, epoch_no, T)
     X = np.ascontiguousarray(X, dtype=np.float32)
     Xq = np.ascontiguousarray(Xq, dtype=xq_dtype(prob.b))
     yy = _ylike(prob, y)

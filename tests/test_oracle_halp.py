@@ -224,6 +224,66 @@ def test_theorem2_linear_rate_integer_form():
         assert gaps[k] <= gam ** k * gaps[0] * 1.05
 
 
+def test_theorem2_linear_rate_integer_form_option2():
+    """Theorem 2 as it is stated: option II ends every epoch at a uniformly drawn iterate."""
+    X, y = _theorem2_instance()
+    _, _, f = lsq_callables(X, y)
+    w_star = np.linalg.lstsq(X, y, rcond=None)[0]
+    b = 8
+    delta_d = np.sqrt(2.0) / 90
+    Xq = np.rint(X / delta_d).astype(np.int8)
+    X32, y32 = X.astype(np.float32), y.astype(np.float32)
+    alpha, T, K, gam = 0.5 / (4 * 2 * 1.5), 97, 4, 0.5
+    gaps = np.zeros(K + 1)
+    seeds = 300
+    for s in range(seeds):
+        prob = ref.make_problem(8, 2, b=b, alpha=alpha, mu=1.0, delta_d=delta_d, seed=900 + s)
+        w = np.zeros((1, 2), np.float32)
+        gaps[0] += f(w[0].astype(np.float64)) - f(w_star)
+        for k in range(K):
+            w = ref.epoch(prob, X32, Xq, y32, w, k, T, option2=True)["w"]
+            gaps[k + 1] += f(w[0].astype(np.float64)) - f(w_star)
+    gaps /= seeds
+    for k in range(1, K + 1):
+        assert gaps[k] <= gam ** k * gaps[0] * 1.05
+
+
+def test_option2_draw_is_uniform_on_0_to_T_minus_1():
+    T = 12
+    draws = np.array([ref.option2_steps(seed, ep, T) for seed in range(300) for ep in range(80)])
+    assert draws.min() == 0 and draws.max() == T - 1          # never T: w_{k,T} is not a candidate
+    counts = np.bincount(draws, minlength=T)
+    chi2 = np.sum((counts - len(draws) / T) ** 2 / (len(draws) / T))
+    assert chi2 < 35.0                                        # 11 degrees of freedom, p ~ 2e-4
+    assert all(ref.option2_steps(s, 0, 1) == 0 for s in range(50))
+    assert ref.option2_steps(3, 0, 0) == 0
+    # its own stream: independent of the index draws of the same epoch
+    idx = np.array([ref.sample_index(seed, 0, 0, 1, 0, T) for seed in range(4000)])
+    d2 = np.array([ref.option2_steps(seed, 0, T) for seed in range(4000)])
+    assert abs(np.corrcoef(idx, d2)[0, 1]) < 0.06
+
+
+def test_option2_epoch_ends_at_a_recorded_iterate():
+    """the epoch's result is the iterate the full run passes through after t steps"""
+    X, y, _ = inp.linreg(80, 12, seed=2)
+    dd = inp.default_delta_d(X, 8)
+    Xq = ref.quantize_data(X, dd, 8)
+    T = 40
+    seen = set()
+    for seed in range(6):
+        prob = ref.make_problem(80, 12, alpha=0.02, mu=0.7, delta_d=dd, seed=seed)
+        w0 = np.zeros((1, 12), np.float32)
+        full = ref.epoch(prob, X, Xq, y, w0, 1, T)
+        tr = ref.inner_loop(prob, Xq, full["phi"], y, full["h"], full["scales"], 1, T, trace_steps=T)
+        t = ref.option2_steps(seed, 1, T)
+        seen.add(t)
+        out = ref.epoch(prob, X, Xq, y, w0, 1, T, option2=True)
+        want = tr["ztraj"][t - 1] if t > 0 else np.zeros_like(out["z"])
+        assert np.array_equal(out["z"], want.reshape(out["z"].shape))
+        assert np.array_equal(out["w"], ref.apply_offset(prob, full["scales"], want.reshape(1, 12), w0))
+    assert len(seen) > 3
+
+
 # -------------------------------------------- HALP beats the fixed lattice
 
 def test_halp_goes_below_the_lp_svrg_floor():
