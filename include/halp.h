@@ -135,6 +135,11 @@ typedef struct {
 #define HALP_OPT_INNER_WAVES 5   /* waves per chain of the register-resident inner loop: 1, 2, 4,
                                     8, 16, or 0 = auto (several when chains are few, one when
                                     they are many); results do not depend on it             */
+#define HALP_OPT_OPTION_II 6     /* 0 (default): option I of Algorithms 1-3, an epoch ends at the
+                                    last iterate.  1: option II, the form the theorems are stated
+                                    for: chain r draws t uniformly from {0, .., T-1} (word 0 of
+                                    stream purpose 5 of that epoch) and the epoch ends at the
+                                    iterate after t steps: w~ <- w~ + delta_m z_t                */
 
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */
@@ -195,7 +200,7 @@ int halp_inner_loop_trace(halp_handle* h, int64_t epoch, int64_t M, int64_t* idx
 int halp_get_stats(halp_handle* h, int32_t chain, void* stream, halp_stats* out);
 
 /* Debug: words n0 .. n0+count-1 of a purpose's random stream (purposes: 0 index,
- * 1 gamma, 3 L2, 4 h~), and the b rounding bits of every coordinate [K][d] of z at
+ * 1 gamma, 3 L2, 4 h~, 5 option II), and the b rounding bits of every coordinate [K][d] of z at
  * step t (purpose 2), written as uint32 to device memory.                             */
 int halp_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
                             int64_t count, uint32_t* out, void* stream);

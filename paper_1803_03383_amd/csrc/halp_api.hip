@@ -224,6 +224,10 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
       h->timing = value != 0;
       h->timed = 0;
       return HALP_OK;
+    case HALP_OPT_OPTION_II:
+      if (value != 0 && value != 1) return HALP_ERR_INVALID;
+      h->option2 = value != 0;
+      return HALP_OK;
     case HALP_OPT_INNER_WAVES:
       if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return HALP_ERR_INVALID;

@@ -10,7 +10,7 @@ namespace halp {
 
 constexpr int kWave = 64;
 
-enum Purpose : uint32_t { kIdx = 0, kGamma = 1, kZround = 2, kReg = 3, kHround = 4 };
+enum Purpose : uint32_t { kIdx = 0, kGamma = 1, kZround = 2, kReg = 3, kHround = 4, kOpt2 = 5 };
 
 struct U4 {
   uint32_t x, y, z, w;
@@ -50,6 +50,14 @@ __device__ __forceinline__ uint32_t pick(const U4& v, uint32_t k) {
 // Rounding bits of z: a row of z is cut into strips 16 rounding bits wide (16/b
 // coordinates: two at b = 8, one at b = 16).  One block serves strip `strip` for the
 // eight steps 8s .. 8s+7; step t reads the 16-bit field t % 8 (half f % 2 of word f / 2).
+// Steps of an epoch.  Option I of Algorithms 1-3 runs all T; option II ends the epoch at the
+// iterate after t steps, t uniform on {0, .., T-1} (word 0 of its own stream, multiply-shift).
+__device__ __forceinline__ int64_t epoch_steps(uint64_t seed, uint32_t epoch, int64_t T, int option2) {
+  if (!option2 || T <= 0) return T;
+  const U4 r = stream_block(seed, kOpt2, epoch, 0);
+  return (int64_t)(((uint64_t)r.x * (uint64_t)T) >> 32);
+}
+
 __device__ __forceinline__ U4 zround_block(uint64_t seed, uint32_t epoch, uint32_t strip,
                                            uint32_t s) {
   return philox4x32_10(U4{strip, s, epoch, (uint32_t)kZround}, (uint32_t)seed,

@@ -16,6 +16,7 @@ struct halp_handle {
   int inner_variant = 0;
   bool timing = false;
   int fullgrad_blocks = 0;
+  bool option2 = false; // option II of Algorithms 1-3 for the end of an epoch
   int inner_waves = 0;  // waves per chain of the register-resident inner loop, 0 = auto
   // library-owned workspace of the gradient pass: per-workgroup partial sums
   float* partial_g = nullptr;    // [R][parts][K*d]

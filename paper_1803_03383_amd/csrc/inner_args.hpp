@@ -20,6 +20,7 @@ struct InArgs {
   int64_t N, ldxq, T;
   int64_t xq_chain_stride, y_chain_stride;  // elements; 0 when chains share the data
   int d, K, B, loss;
+  int option2;  // 1: the epoch ends at a uniformly drawn earlier iterate (option II)
   int lp;  // 1: LP-SVRG (Algorithm 2): z is the model itself, the margin is x^T z alone
   double lambda, delta_d;
   uint64_t seed;
@@ -37,6 +38,7 @@ inline InArgs make_inner_args(const halp_handle& h, uint32_t epoch) {
   a.y_chain_stride = p.share_data ? 0 : p.N;
   a.d = p.d; a.K = p.K; a.B = p.B; a.loss = p.loss;
   a.lp = p.algorithm == HALP_ALG_LPSVRG;
+  a.option2 = h.option2 ? 1 : 0;
   a.lambda = p.lambda; a.delta_d = p.delta_d;
   a.seed = p.seed; a.epoch = epoch;
   return a;

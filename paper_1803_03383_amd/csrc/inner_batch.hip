@@ -78,7 +78,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int d = a.d, B = a.B;
-  const int64_t T = a.T;
+  const int64_t T = epoch_steps(a.seed + (uint64_t)blockIdx.x, a.epoch, a.T, a.option2);
   const int64_t row_bytes = a.ldxq * (BITS / 8);
   const unsigned char* __restrict__ Xq = reinterpret_cast<const unsigned char*>(a.Xq) +
                                          (int64_t)chain * a.xq_chain_stride * (BITS / 8);

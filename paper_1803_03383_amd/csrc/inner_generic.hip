@@ -81,7 +81,8 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
   U4 zcache[kCached];
   const bool cache_blocks = K * U <= kCached * NT;
 
-  for (int64_t t = 0; t < a.T; ++t) {
+  const int64_t T = epoch_steps(seed, a.epoch, a.T, a.option2);
+  for (int64_t t = 0; t < T; ++t) {
     const bool rec = t < a.tr.M;
     // sample i uniformly (with replacement)
     if (tid < B) {

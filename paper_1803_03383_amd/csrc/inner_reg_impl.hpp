@@ -80,6 +80,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   const double* sc = a.scales + (int64_t)chain * 8;
   uint64_t* cnt_out = a.counters + (int64_t)chain * 4;
   const uint64_t seed = a.seed + (uint64_t)chain;
+  const int64_t T = epoch_steps(seed, a.epoch, a.T, a.option2);
 
   if (sc[7] != 0.0) {  // converged or unusable gradient: the epoch is a no-op
     if (tid < 4) cnt_out[tid] = 0;
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   };
 #pragma unroll
   for (int s = 0; s < kWin; ++s) {
-    if (s < a.T) request(xa[s], __builtin_amdgcn_readfirstlane(s_idx[s]));
+    if (s < T) request(xa[s], __builtin_amdgcn_readfirstlane(s_idx[s]));
   }
 
   unsigned int n_zclamp = 0, n_gclamp = 0, n_reg = 0;
@@ -209,7 +210,6 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
                     uint32_t (&xr)[kWin][NDW], uint32_t (&xnext)[kWin][NDW]) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr bool REGW = decltype(reg_tag)::value;  // some step of the window has c_lambda != 0
-    const int64_t T = a.T;
     const int base = (int)(t0 & kMask);  // multiple of 8: the window is contiguous in LDS
     // draws of this window and the row indices of the next one, in a few wide LDS reads
     double rho[kWin];
@@ -333,7 +333,6 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     }
   };
 
-  const int64_t T = a.T;
   int64_t t0 = 0;
   auto refill = [&](int64_t tt) {
     if ((tt & (kBatch - 1)) == 0 && tt > 0) {

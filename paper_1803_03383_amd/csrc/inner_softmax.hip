@@ -88,7 +88,7 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   const int d = a.d, K = a.K;
   const int NTc = 64 * K;  // class-wave threads
   const int U = (d + CT - 1) / CT;
-  const int64_t T = a.T;
+  const int64_t T = epoch_steps(a.seed + (uint64_t)blockIdx.x, a.epoch, a.T, a.option2);
   const int64_t row_bytes = a.ldxq * (BITS / 8);
   const int row_dw = (int)(row_bytes / 4);
   const double* sc = a.scales + (int64_t)chain * 8;

@@ -28,6 +28,7 @@ struct SvArgs {
   int64_t N, ldx, T;
   int64_t x_chain_stride, y_chain_stride;
   int d, loss;
+  int option2;
   const double* hyper;  // [R][2] step size (and mu, unused here) of each chain
   double lambda;
   uint64_t seed;
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_svrg_kernel(SvArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int d = a.d;
   const uint32_t N = (uint32_t)a.N;
-  const int64_t T = a.T;
+  const int64_t T = epoch_steps(a.seed + (uint64_t)blockIdx.x, a.epoch, a.T, a.option2);
   const float* __restrict__ X = a.X + (int64_t)chain * a.x_chain_stride;
   const float* __restrict__ y = a.y + (int64_t)chain * a.y_chain_stride;
   const float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
@@ -253,7 +254,7 @@ int launch_inner_svrg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   a.N = p.N; a.ldx = h.buf.ldx; a.T = p.T;
   a.x_chain_stride = p.share_data ? 0 : p.N * h.buf.ldx;
   a.y_chain_stride = p.share_data ? 0 : p.N;
-  a.d = p.d; a.loss = p.loss; a.hyper = h.hyper; a.lambda = p.lambda;
+  a.d = p.d; a.loss = p.loss; a.hyper = h.hyper; a.lambda = p.lambda; a.option2 = h.option2 ? 1 : 0;
   a.seed = p.seed; a.epoch = epoch;
   const SvShape sh = pick_shape(h);
 #define HALP_SV(C_, W_) \
