@@ -224,6 +224,7 @@ INNER_REG_CASES = [
     (hp.LOSS_SQUARED, 50, 64, 8, 0.0, 1, 1, 0.5),           # a single step
     (hp.LOSS_SQUARED, 50, 64, 8, 0.0, 1, 0, 0.5),           # no step at all
     (hp.LOSS_SQUARED, 64, 64, 8, 0.0, 1, 600, 500.0),       # box far too small: z saturates
+    (hp.LOSS_LOGISTIC, 300, 128, 16, 1e-4, 2, 600, 500.0),  # the same at 16 bits ("Clip")
 ]
 
 
@@ -276,6 +277,7 @@ SOFTMAX_REG_CASES = [
     (100, 64, 2, 8, 0.0, 1, 1, 0.05),         # a single step
     (100, 64, 2, 8, 0.0, 1, 0, 0.05),         # no step at all
     (64, 64, 4, 8, 0.0, 1, 600, 500.0),       # box far too small: z saturates
+    (128, 96, 3, 16, 1e-3, 1, 400, 500.0),    # the same at 16 bits
 ]
 
 
