@@ -4,8 +4,9 @@
 // One workgroup per chain: K class waves and one service wave.
 //
 // Class wave c owns row c of z ([K][d]): lane l holds the UPL consecutive strips
-// (16 rounding bits each) starting at l * UPL, with -h~ and the strips' Philox
-// blocks of the current window of 8 steps, in registers for the whole epoch.
+// (16 rounding bits each; UPL up to 8 at 8 bits, up to 16 at 16 bits) starting at l * UPL,
+// with -h~ and the strips' Philox blocks of the current window of 8 steps, in registers for
+// the whole epoch.
 //
 // The service wave owns everything that does not scale with d: it draws the
 // sample indices, fetches the sampled rows of the quantized data and their margins
@@ -29,7 +30,6 @@ namespace {
 
 constexpr int kWin = 8;   // steps per window
 constexpr int kKC = 16;   // classes are padded to one DPP row
-constexpr int kRowQ = 4;  // dwords of a row per service lane: rows up to 1 KB
 
 __device__ __forceinline__ int mad24(int a, int b, int c) {
   int r;
@@ -80,14 +80,20 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   constexpr int CPL = UPL * CT;
   constexpr int NDW = (UPL + 1) / 2;
   constexpr int PQ = UPL >= 4 ? UPL / 4 : 1;  // 16-byte slots per word of a lane's parked blocks
+  constexpr int BPS = UPL > 8 ? 2 : 1;        // Philox blocks of the next window made per step
+  constexpr int kRowQ = UPL > 8 ? 8 : 4;      // dwords of a row per service lane: rows up to 1 / 2 KB
+  // 16 strips per lane leave no registers for operands prepared ahead of gamma: the sampled
+  // row stays packed and everything else of the update is formed after the second barrier
+  constexpr bool LEAN = UPL > 8;
   constexpr int QMAX = (1 << (BITS - 1)) - 1, QMIN = -(1 << (BITS - 1));
   const int chain = blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int d = a.d, K = a.K;
-  const int NTc = 64 * K;  // class-wave threads
   const int U = (d + CT - 1) / CT;
+  const int NACT = (U + UPL - 1) / UPL;  // lanes of a class wave that hold part of the row
+  const int NP = K * NACT;               // ... of all class waves: slots of the parked blocks
   const int64_t T = epoch_steps(a.seed + (uint64_t)blockIdx.x, a.epoch, a.T, a.option2);
   const int64_t row_bytes = a.ldxq * (BITS / 8);
   const int row_dw = (int)(row_bytes / 4);
@@ -106,12 +112,15 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   __shared__ __attribute__((aligned(16))) AccT s_D[2][kKC];              // x_i^T z_c
   __shared__ int s_ng[2][kKC];                                           // -gamma_c
   __shared__ unsigned long long s_cnt[3];
-  // [2][kWin][row_dw] staged rows, then the parked Philox blocks: [word][slot][class thread]
-  // of 16 bytes, so that a wave reads consecutive addresses; a thread reads only its own
+  // [2][kWin][row_dw] staged rows (coordinates past d staged as zeros), 32 bytes of zeros that
+  // the lanes past the row read instead, then the parked Philox blocks: [word][slot][active
+  // class lane] of 16 bytes, so that a wave reads consecutive addresses; a lane reads only its own
   extern __shared__ __attribute__((aligned(16))) uint32_t s_ring[];
-  uint32_t* s_park = s_ring + 2 * kWin * row_dw;
+  uint32_t* s_zero = s_ring + ((2 * kWin * row_dw + 3) & ~3);
+  uint32_t* s_park = s_zero + 8;
 
   if (tid < 3) s_cnt[tid] = 0;
+  if (tid < 8) s_zero[tid] = 0;
   const bool use_reg = a.lambda > 0;
 
   if (wave == K) {
@@ -135,6 +144,13 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     };
     uint32_t xn[kWin][kRowQ];
     float phin[2];
+    // coordinates of dword lane + 64 q that lie inside the row's d
+    uint32_t smask[kRowQ];
+#pragma unroll
+    for (int q = 0; q < kRowQ; ++q) {
+      const int nv = d - (lane + 64 * q) * (32 / BITS);
+      smask[q] = nv >= 32 / BITS ? 0xFFFFFFFFu : (nv <= 0 ? 0u : (1u << (nv * BITS)) - 1u);
+    }
     // dwords lane, lane + 64, ... of the window's rows; 8K margins, two per lane
     auto request = [&](int idxv) {
 #pragma unroll
@@ -156,7 +172,8 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
       for (int s = 0; s < kWin; ++s)
 #pragma unroll
         for (int q = 0; q < kRowQ; ++q)
-          if (lane + 64 * q < row_dw) s_ring[(buf * kWin + s) * row_dw + lane + 64 * q] = xn[s][q];
+          if (lane + 64 * q < row_dw)
+            s_ring[(buf * kWin + s) * row_dw + lane + 64 * q] = xn[s][q] & smask[q];
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         const int e = lane + 64 * q;
@@ -245,23 +262,20 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     float* __restrict__ wg = a.w + row0;
     const int s0 = lane * UPL;
     const int j0 = s0 * CT;
-    const bool lane_ok = s0 < U;
+    const bool lane_ok = s0 < U;  // = lane < NACT
     int z[CPL];
     int hv[CPL];  // -h~ at b = 8, h~ at b = 16
-    uint32_t xmask[NDW];
-#pragma unroll
-    for (int k = 0; k < NDW; ++k) xmask[k] = 0;
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
       const int j = j0 + k;
       const bool ok = j < d;
       z[k] = ok ? (int)zg[j] : 0;
       hv[k] = ok ? (BITS == 8 ? -(int)hg[j] : (int)hg[j]) : 0;
-      if (ok) xmask[(k * BITS) / 32] |= (BITS == 8 ? 0xFFu : 0xFFFFu) << ((k * BITS) % 32);
     }
     const int frag_dw = lane_ok ? (s0 * 2) >> 2 : 0;  // dword index of the fragment in a row
     const int half_sh = (UPL == 1 && lane_ok) ? ((s0 * 2) & 2) * 8 : 0;
     const uint32_t strip0 = (uint32_t)(cls * U + s0);
+    const int pidx = cls * NACT + lane;  // slot of this lane's parked blocks (lanes on the row only)
     const uint4* park = reinterpret_cast<const uint4*>(s_park);
 
     uint32_t zrw[4][UPL];  // the window's rounding words: [word of the block][strip]
@@ -276,12 +290,12 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     for (int64_t t0 = 0; t0 < T; t0 += kWin) {
       const int buf = (int)((t0 >> 3) & 1);
       const bool more = t0 + kWin < T;
-      if (t0 > 0) {  // the blocks parked during the previous window
+      if (t0 > 0 && lane_ok) {  // the blocks parked during the previous window
 #pragma unroll
         for (int wd = 0; wd < 4; ++wd)
 #pragma unroll
           for (int q = 0; q < PQ; ++q) {
-            const uint4 v = park[(wd * PQ + q) * NTc + tid];
+            const uint4 v = park[(wd * PQ + q) * NP + pidx];
             if (4 * q + 0 < UPL) zrw[wd][(4 * q + 0) % UPL] = v.x;
             if (4 * q + 1 < UPL) zrw[wd][(4 * q + 1) % UPL] = v.y;
             if (4 * q + 2 < UPL) zrw[wd][(4 * q + 2) % UPL] = v.z;
@@ -291,31 +305,49 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
 #pragma unroll
       for (int s = 0; s < kWin; ++s) {
         if (t0 + s < T) {
-          // this lane's fragment of the row, from the ring
+          // this lane's fragment of the row, from the ring (zeros for the lanes past the row)
           uint32_t xw[NDW];
           {
-            const uint32_t* rp = s_ring + (buf * kWin + s) * row_dw + frag_dw;
+            const uint32_t* rp =
+                lane_ok ? s_ring + (buf * kWin + s) * row_dw + frag_dw : s_zero;
             if (NDW == 1) {
               xw[0] = rp[0];
+              if (UPL == 1) xw[0] = (xw[0] >> half_sh) & 0xFFFFu;
             } else if (NDW == 2) {
               const uint2 v = *reinterpret_cast<const uint2*>(rp);
               xw[0] = v.x; xw[NDW > 1 ? 1 : 0] = v.y;
             } else {
-              const uint4 v = *reinterpret_cast<const uint4*>(rp);
-              xw[0] = v.x; xw[NDW > 1 ? 1 : 0] = v.y; xw[NDW > 2 ? 2 : 0] = v.z; xw[NDW > 3 ? 3 : 0] = v.w;
+#pragma unroll
+              for (int q = 0; q < NDW / 4; ++q) {
+                const uint4 v = reinterpret_cast<const uint4*>(rp)[q];
+                xw[4 * q] = v.x; xw[NDW > 1 ? 4 * q + 1 : 0] = v.y;
+                xw[NDW > 2 ? 4 * q + 2 : 0] = v.z; xw[NDW > 3 ? 4 * q + 3 : 0] = v.w;
+              }
             }
-#pragma unroll
-            for (int k = 0; k < NDW; ++k) xw[k] = (UPL == 1 ? xw[k] >> half_sh : xw[k]) & xmask[k];
           }
-          int xe[CPL];
-          AccT part = 0;
-#pragma unroll
-          for (int k = 0; k < CPL; ++k) {
+          auto x_of = [&](int k) {
             const uint32_t xv = xw[(k * BITS) / 32];
             const int xs = (k * BITS) % 32;
-            xe[k] = BITS == 8 ? (int)(int8_t)(xv >> xs) : (int)(int16_t)(xv >> xs);
-            if (BITS == 8) part = (AccT)mad24(xe[k], z[k], (int)part);
-            else part += (AccT)((long long)xe[k] * (long long)z[k]);
+            return BITS == 8 ? (int)(int8_t)(xv >> xs) : (int)(int16_t)(xv >> xs);
+          };
+          int xe[LEAN ? 1 : CPL];
+          AccT part = 0;
+          if (!LEAN) {
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+              xe[LEAN ? 0 : k] = x_of(k);
+              if (BITS == 8) part = (AccT)mad24(xe[LEAN ? 0 : k], z[k], (int)part);
+            }
+          }
+          if (BITS == 16) {
+            // two products of 16-bit factors fit 32 bits; their sums are added in 64
+            if (CPL == 1) {
+              part = (AccT)mad24(x_of(0), z[0], 0);
+            } else {
+#pragma unroll
+              for (int k = 0; k + 1 < CPL; k += 2)
+                part += (AccT)mad24(x_of(k), z[k], mad24(x_of(k + 1), z[k + 1], 0));
+            }
           }
           AccT D;
           if (BITS == 8) D = (AccT)wave_sum_i32((int)part);
@@ -323,20 +355,34 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
           if (lane == 0) s_D[s & 1][cls] = D;
           __syncthreads();
           // While the service wave evaluates the softmax: the part of the update that does
-          // not need gamma, and one Philox block of the next window.
-          int hr[CPL];  // b = 8: -h~ + rounding bits; b = 16: the rounding bits
-#pragma unroll
-          for (int k = 0; k < CPL; ++k) {
+          // not need gamma, and the Philox blocks of the next window.
+          // b = 8: hr = -h~ + rounding bits.  b = 16: with h~ = 2^16 hh + hl, 0 <= hl < 2^16,
+          // floor((-gamma x + bits - h~) / 2^16) = floor((-gamma x + bits - hl) / 2^16) - hh, and
+          // the numerator on the right fits 32 bits; hr = bits - hl.
+          auto hr_of = [&](int k) {
             const uint32_t word = zrw[s >> 1][k / CT];
             const int sh = 16 * (s & 1) + (k % CT) * BITS;
             const int re = (int)((word >> sh) & (BITS == 8 ? 0xFFu : 0xFFFFu));
-            hr[k] = BITS == 8 ? hv[k] + re : re;
+            if (BITS == 16) asm volatile("" : "+v"(hv[k]));  // keeps hl, hh from being hoisted into registers
+            return BITS == 8 ? hv[k] + re : re - (hv[k] & 0xFFFF);
+          };
+          int hr[LEAN ? 1 : CPL];
+          if (!LEAN) {
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) hr[LEAN ? 0 : k] = hr_of(k);
           }
-          if (s < UPL && more) {
-            const U4 r = zround_block(seed, a.epoch, strip0 + (uint32_t)s, (uint32_t)(t0 >> 3) + 1u);
-            uint32_t* slot = s_park + ((size_t)((s / 4) * NTc + tid)) * 4 + (s % 4);
-            const size_t word_stride = (size_t)PQ * NTc * 4;
-            slot[0] = r.x; slot[word_stride] = r.y; slot[2 * word_stride] = r.z; slot[3 * word_stride] = r.w;
+#pragma unroll
+          for (int q = 0; q < BPS; ++q) {
+            if (q > 0) __builtin_amdgcn_sched_barrier(0);  // one block's temporaries at a time
+            const int u = s * BPS + q;
+            if (u < UPL && more) {
+              const U4 r = zround_block(seed, a.epoch, strip0 + (uint32_t)u, (uint32_t)(t0 >> 3) + 1u);
+              if (lane_ok) {
+                uint32_t* slot = s_park + ((size_t)((u / 4) * NP + pidx)) * 4 + (u % 4);
+                const size_t word_stride = (size_t)PQ * NP * 4;
+                slot[0] = r.x; slot[word_stride] = r.y; slot[2 * word_stride] = r.z; slot[3 * word_stride] = r.w;
+              }
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
           __syncthreads();
@@ -346,17 +392,12 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
           auto update = [&](auto with_l2) {
 #pragma unroll
             for (int k = 0; k < CPL; ++k) {
+              int hk = LEAN ? hr_of(k) : hr[LEAN ? 0 : k];
+              if (decltype(with_l2)::value) hk = mad24(-cl, z[k], hk);
+              const int xk = LEAN ? x_of(k) : xe[LEAN ? 0 : k];
               int zu;
-              if (BITS == 8) {
-                int hk = hr[k];
-                if (decltype(with_l2)::value) hk = mad24(-cl, z[k], hk);
-                zu = z[k] + (mad24(ng, xe[k], hk) >> 8);
-              } else {
-                long long hk = (long long)hr[k] - (long long)hv[k];
-                if (decltype(with_l2)::value) hk -= (long long)(cl * z[k]);
-                const long long v = (long long)ng * (long long)xe[k] + hk;
-                zu = z[k] + (int)(v >> 16);
-              }
+              if (BITS == 8) zu = z[k] + (mad24(ng, xk, hk) >> 8);
+              else zu = z[k] + (mad24(ng, xk, hk) >> 16) - (hv[k] >> 16);
               const int zc = min(max(zu, QMIN), QMAX);
               // clamps are counted on the scalar unit: one compare here, the rest is wave-wide
               n_zclamp += (unsigned long long)__builtin_popcountll(__ballot(zu != zc));
@@ -419,6 +460,11 @@ int launch_upl(const InArgs& a, int upl, int R, size_t smem, hipStream_t s) {
   }
 }
 
+// 16 strips per lane exist at 16 bits only (16 coordinates per lane; at 8 bits they would be 32)
+int launch_upl16(const InArgs& a, int R, size_t smem, hipStream_t s) {
+  return launch_kt<16, 16>(a, R, smem, s);
+}
+
 int strips_per_lane(const halp_params& p) {
   const int ct = 16 / p.b;
   const int U = (p.d + ct - 1) / ct;
@@ -428,32 +474,37 @@ int strips_per_lane(const halp_params& p) {
   return u2;
 }
 
-// the ring of staged rows, and the parked Philox blocks (16 bytes per strip, 64 at least,
-// per class thread)
+// the ring of staged rows, 32 bytes of zeros, and the parked Philox blocks (16 bytes per
+// strip, 64 at least, per class lane that holds part of the row)
 size_t dynamic_lds(const halp_params& p, int64_t row_bytes) {
   const int upl = strips_per_lane(p);
-  return (size_t)2 * kWin * (size_t)row_bytes + (size_t)64 * p.K * 16 * (size_t)(upl >= 4 ? upl : 4);
+  const int ct = 16 / p.b;
+  const int U = (p.d + ct - 1) / ct;
+  const int nact = (U + upl - 1) / upl;
+  const size_t ring = (((size_t)2 * kWin * (size_t)row_bytes) + 15) / 16 * 16;
+  return ring + 32 + (size_t)nact * p.K * 16 * (size_t)(upl >= 4 ? upl : 4);
 }
 
 }  // namespace
 
 // softmax, one row per step, at most 15 classes (one wave each, plus the service wave), a
-// class's row of z within one wave (8 strips per lane at most), data rows up to 1 KB
+// class's row of z within one wave (8 strips per lane at most at 8 bits, 16 at 16 bits), data
+// rows up to 1 KB (2 KB at 16 strips per lane), everything staged within the LDS of a CU
 int inner_softmax_supported(const halp_handle& h) {
   const halp_params& p = h.p;
   if (p.loss != HALP_LOSS_SOFTMAX || p.B != 1 || p.K < 2 || p.K > 15) return HALP_ERR_UNSUPPORTED;
   if (p.b == 8 && p.d > 131071) return HALP_ERR_UNSUPPORTED;  // int32 dot product stays exact
   const int upl = strips_per_lane(p);
-  if (upl > 8) return HALP_ERR_UNSUPPORTED;
+  if (upl > (p.b == 16 ? 16 : 8)) return HALP_ERR_UNSUPPORTED;
   if (!h.bound || !h.buf.Xq) return HALP_ERR_NOT_BOUND;
   const int64_t row_bytes = h.buf.ldxq * (p.b / 8);
   const int ct = 16 / p.b;
   const int U = (p.d + ct - 1) / ct;
   // fragments are read whole (2 * UPL bytes, up to 16) from the staged row
-  const int frag = upl == 8 ? 16 : (upl == 4 ? 8 : 4);
-  if (row_bytes % frag != 0 || row_bytes / 4 > 64 * kRowQ) return HALP_ERR_UNSUPPORTED;
+  const int frag = upl >= 8 ? 16 : (upl == 4 ? 8 : 4);
+  if (row_bytes % frag != 0 || row_bytes / 4 > 64 * (upl > 8 ? 8 : 4)) return HALP_ERR_UNSUPPORTED;
   if ((int64_t)((U + upl - 1) / upl) * upl * 2 > row_bytes) return HALP_ERR_UNSUPPORTED;
-  if (dynamic_lds(p, row_bytes) > 150 * 1024) return HALP_ERR_UNSUPPORTED;
+  if (dynamic_lds(p, row_bytes) > 156 * 1024) return HALP_ERR_UNSUPPORTED;  // 160 KB less the static part
   return HALP_OK;
 }
 
@@ -464,6 +515,7 @@ int launch_inner_softmax(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const InArgs a = make_inner_args(h, epoch);
   const int upl = strips_per_lane(p);
   const size_t smem = dynamic_lds(p, h.buf.ldxq * (p.b / 8));
+  if (upl == 16) return launch_upl16(a, p.R, smem, s);
   return p.b == 8 ? launch_upl<8>(a, upl, p.R, smem, s) : launch_upl<16>(a, upl, p.R, smem, s);
 }
 

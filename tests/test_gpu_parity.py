@@ -278,6 +278,9 @@ SOFTMAX_REG_CASES = [
     (100, 64, 2, 8, 0.0, 1, 0, 0.05),         # no step at all
     (64, 64, 4, 8, 0.0, 1, 600, 500.0),       # box far too small: z saturates
     (128, 96, 3, 16, 1e-3, 1, 400, 500.0),    # the same at 16 bits
+    (300, 784, 10, 16, 1e-4, 1, 203, 0.05),   # the 10-class shape at 16 bits: 16 strips per lane, 49 lanes
+    (200, 781, 4, 16, 1e-2, 2, 150, 0.05),    # the same with a ragged last lane, L2 draws
+    (150, 1008, 2, 16, 0.0, 1, 120, 500.0),   # 63 lanes, saturating
 ]
 
 
@@ -303,9 +306,9 @@ def test_inner_loop_softmax_bit_exact(N, d, K, b, lam, R, T, mu, variant):
 
 
 def test_softmax_shapes_outside_the_register_kernel_fall_back():
-    # 784 coordinates at 16 bits need more than 8 strips per lane: the automatic choice is the
+    # 1600 coordinates at 16 bits need more than 16 strips per lane: the automatic choice is the
     # general kernel, and forcing the register kernel is an error, not a wrong answer
-    loss, N, d, K, b, T = hp.LOSS_SOFTMAX, 120, 784, 10, 16, 40
+    loss, N, d, K, b, T = hp.LOSS_SOFTMAX, 120, 1600, 3, 16, 40
     case = _inner_case(loss, N, d, K, 1, b, 0.0, 1, T, 77, mu=0.05)
     P = _run_inner(case, loss, K, 1, b, 0.0, 1, T, 77, 0, mu=0.05)
     P.h.inner_loop(3)
