@@ -125,7 +125,8 @@ typedef struct {
                                     logistic; d up to 8 strips of 16 rounding bits per lane and
                                     16 waves), for K = 1 with 2 <= B <= 64 (same limit on d), and
                                     for softmax with B = 1, K <= 15 (a class's row of z within 8
-                                    strips per lane of one wave, data rows up to 1 KB); auto takes
+                                    strips per lane of one wave at 8 bits, 16 at 16 bits, and
+                                    the staged rows within the LDS of a CU); auto takes
                                     them when the shape fits, 2 fails with HALP_ERR_UNSUPPORTED
                                     when it does not.  HALP_ALG_SVRG has one fp32 kernel and
                                     ignores this option                                      */
