@@ -140,6 +140,21 @@ void halp_ref_quantize_data(const float* X, int64_t n, double delta_d, int b, vo
   }
 }
 
+void halp_ref_quantize_data_scaled(const float* X, int64_t rows, int32_t d, double delta_d,
+                                   const float* s, int b, void* Xq) {
+  const double qmax = (double)(((int64_t)1 << (b - 1)) - 1);
+  for (int64_t i = 0; i < rows; ++i)
+    for (int32_t j = 0; j < d; ++j) {
+      const int64_t k = i * d + j;
+      double q = nearbyint((double)X[k] / (delta_d * (double)s[j]));
+      if (q > qmax) q = qmax;
+      if (q < -qmax) q = -qmax;
+      if (b == 8) ((int8_t*)Xq)[k] = (int8_t)q;
+      else if (b == 16) ((int16_t*)Xq)[k] = (int16_t)q;
+      else ((int32_t*)Xq)[k] = (int32_t)q;
+    }
+}
+
 /* ------------------------------------------------------- scalar losses l_i */
 
 static double logistic_dl(double a, double y) { /* l'(a) for l = log(1+exp(-y a)) */
@@ -264,6 +279,20 @@ int halp_ref_full_gradient(const halp_ref_problem* p, const float* X, int64_t ld
     w2 += (double)w[k] * (double)w[k];
   }
   *loss = total / (double)N + 0.5 * p->lambda * w2;
+  return 0;
+}
+
+int halp_ref_full_gradient_scaled(const halp_ref_problem* p, const float* X, int64_t ldx,
+                                  const void* y, const float* v, const float* s, double* phi,
+                                  double* g, double* loss) {
+  const int64_t n = (int64_t)p->K * p->d;
+  if (p->lambda != 0.0) return -1; /* lambda ||w||^2 is not lambda ||v||^2 */
+  float* w = (float*)calloc((size_t)n + 1, sizeof(float));
+  for (int64_t k = 0; k < n; ++k) w[k] = v[k] / s[k % p->d]; /* the model the data belong to */
+  const int rc = halp_ref_full_gradient(p, X, ldx, y, w, phi, g, loss);
+  free(w);
+  if (rc != 0) return rc;
+  for (int64_t k = 0; k < n; ++k) g[k] = g[k] / (double)s[k % p->d]; /* d f / d v_j */
   return 0;
 }
 

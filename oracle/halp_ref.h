@@ -145,6 +145,18 @@ void halp_ref_exp_array(const double* x, int64_t n, double* out);
  * Xq is int8 when b == 8, int16 when b == 16, int32 for 16 < b <= 24 (CPU only) */
 void halp_ref_quantize_data(const float* X, int64_t n, double delta_d, int b, void* Xq);
 
+/* Per-feature scales (diagonal preconditioning; the remark after Theorem 2 that low precision
+ * should be combined with preconditioning).  The data are represented as x_ij = delta_d s_j q_ij
+ * and the algorithm runs unchanged on q and the scaled model v_j = s_j w_j: the margins are the
+ * same, x_i^T w = delta_d q_i^T v, and the gradient with respect to v is g_j / s_j.
+ *   quantize:  q_ij = clamp(round-half-even(X_ij / (delta_d s_j)))          (rows x d, dense)
+ *   gradient:  w_j = fp32(v_j / s_j), then the plain pass, then g_j / s_j;  lambda must be 0 */
+void halp_ref_quantize_data_scaled(const float* X, int64_t rows, int32_t d, double delta_d,
+                                   const float* s, int b, void* Xq);
+int halp_ref_full_gradient_scaled(const halp_ref_problem* p, const float* X, int64_t ldx,
+                                  const void* y, const float* v, const float* s, double* phi,
+                                  double* g, double* loss);
+
 /* Algorithm 2 in integers, start of an epoch: scales from the fixed p->delta
  * (delta_m = delta), h~ = Q_(delta_i,2b)(alpha g~), z = clamp(rne(w~ / delta)).
  * Same scales[] layout and status codes as halp_ref_recenter.               */

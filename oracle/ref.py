@@ -59,6 +59,12 @@ def lib():
         L.halp_ref_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.halp_ref_quantize_data.restype = None
         L.halp_ref_quantize_data.argtypes = [C.c_void_p, C.c_int64, C.c_double, C.c_int, C.c_void_p]
+        L.halp_ref_quantize_data_scaled.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_double,
+                                                    C.c_void_p, C.c_int, C.c_void_p]
+        L.halp_ref_full_gradient_scaled.restype = C.c_int
+        L.halp_ref_full_gradient_scaled.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                    C.c_void_p]
         L.halp_ref_full_gradient.restype = C.c_int
         L.halp_ref_full_gradient.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -154,6 +160,16 @@ def quantize_data(X, delta_d, b):
     return Xq
 
 
+def quantize_data_scaled(X, delta_d, s, b):
+    """q_ij = clamp(rne(X_ij / (delta_d s_j))): per-feature scales s[d]"""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    assert X.ndim == 2 and s.shape == (X.shape[1],)
+    Xq = np.zeros(X.shape, dtype=xq_dtype(b))
+    lib().halp_ref_quantize_data_scaled(_p(X), X.shape[0], X.shape[1], float(delta_d), _p(s), b, _p(Xq))
+    return Xq
+
+
 def _ylike(prob, y):
     if prob.loss == SOFTMAX:
         return np.ascontiguousarray(y, dtype=np.int32)
@@ -173,6 +189,33 @@ def full_gradient(prob, X, y, w):
     if rc != 0:
         raise ValueError(f"halp_ref_full_gradient rc={rc}")
     return phi, g, float(loss[0])
+
+
+def full_gradient_scaled(prob, X, y, v, s):
+    """the pass for the scaled model v_j = s_j w_j: returns (phi, d f / d v, loss)"""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    v = np.ascontiguousarray(v, dtype=np.float32).reshape(prob.K, prob.d)
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    yy = _ylike(prob, y)
+    phi = np.zeros((prob.N, prob.K), dtype=np.float64)
+    g = np.zeros((prob.K, prob.d), dtype=np.float64)
+    loss = np.zeros(1, dtype=np.float64)
+    rc = lib().halp_ref_full_gradient_scaled(C.addressof(prob), _p(X), X.shape[1], _p(yy), _p(v), _p(s),
+                                             _p(phi), _p(g), _p(loss))
+    if rc != 0:
+        raise ValueError(f"halp_ref_full_gradient_scaled rc={rc}")
+    return phi, g, float(loss[0])
+
+
+def epoch_scaled(prob, X, Xq, y, v, s, epoch_no, T):
+    """one HALP epoch on the scaled model: scaled gradient pass, then the unchanged bit
+    centering, inner loop and update of v"""
+    phi, g, loss = full_gradient_scaled(prob, X, y, v, s)
+    phi32, g32 = phi.astype(np.float32), g.astype(np.float32)
+    scales, h, z = recenter(prob, g32, epoch_no)
+    out = inner_loop(prob, Xq, phi32, y, h, scales, epoch_no, T)
+    v1 = apply_offset(prob, scales, out["z"], v)
+    return dict(w=v1, phi=phi32, g=g32, scales=scales, h=h, z=out["z"], counters=out["counters"], loss=loss)
 
 
 def recenter(prob, g32, epoch):
