@@ -154,6 +154,16 @@ int halp_bind(halp_handle* h, const halp_buffers* buf);
 
 int halp_set_option(halp_handle* h, int32_t option, int64_t value);
 
+/* Per-feature data scales: diagonal preconditioning (the remark after Theorem 2 that low
+ * precision should be combined with preconditioning).  s is a DEVICE array of d positive
+ * floats owned by the caller (NULL switches it off).  The low-precision data are then
+ * x_ij = delta_d s_j q_ij -- halp_quantize_data writes q_ij = round(X_ij / (delta_d s_j)) --
+ * and every algorithm runs unchanged on q and the scaled model v_j = s_j w_j: the buffer w
+ * holds v (the caller divides by s to read the model); halp_full_gradient forms
+ * w_j = v_j / s_j for the margins and hands on d f / d v_j = g_j / s_j in g.  lambda must be
+ * 0 (HALP_ERR_UNSUPPORTED otherwise, and for HALP_ALG_SVRG).                          */
+int halp_set_feature_scale(halp_handle* h, const float* s);
+
 /* Step size and mu per chain, for grids of hyper-parameters run as independent chains (the
  * paper's conditioning study, Appendix "Conditioning Evaluation", searches both).  alpha and
  * mu are HOST arrays of R entries, copied synchronously into the library's device workspace;

@@ -18,6 +18,7 @@ ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_NOT_BOUND, ERR_HIP, ERR_ALIGN = -1, 
 
 EXPORTS = [
     "halp_create", "halp_destroy", "halp_bind", "halp_set_option", "halp_set_chain_hyper",
+    "halp_set_feature_scale",
     "halp_quantize_data",
     "halp_full_gradient", "halp_recenter", "halp_inner_loop", "halp_epoch",
     "halp_inner_loop_trace", "halp_get_stats", "halp_debug_stream_words",
@@ -79,6 +80,7 @@ def lib():
         L.halp_bind.argtypes = [vp, C.POINTER(Buffers)]
         L.halp_set_option.argtypes = [vp, i32, i64]
         L.halp_set_chain_hyper.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.halp_set_feature_scale.argtypes = [vp, vp]
         L.halp_quantize_data.argtypes = [vp, vp]
         L.halp_full_gradient.argtypes = [vp, vp]
         L.halp_recenter.argtypes = [vp, i64, vp]
@@ -151,7 +153,7 @@ class Halp:
     def bind(self, X=None, Xq=None, y=None, w=None, phi=None, g=None, z=None, h=None, scales=None,
              counters=None, ldx=None, ldxq=None):
         self._keep = dict(X=X, Xq=Xq, y=y, w=w, phi=phi, g=g, z=z, h=h, scales=scales,
-                          counters=counters)
+                          counters=counters, fscale=self._keep.get("fscale"))
         b = Buffers()
         b.X, b.Xq, b.y, b.w, b.phi, b.g = _ptr(X), _ptr(Xq), _ptr(y), _ptr(w), _ptr(phi), _ptr(g)
         b.z, b.h, b.scales, b.counters = _ptr(z), _ptr(h), _ptr(scales), _ptr(counters)
@@ -172,6 +174,11 @@ class Halp:
                 raise ValueError("one value per chain expected")
             return (C.c_double * len(v))(*v)
         _check(lib().halp_set_chain_hyper(self._h, arr(alpha), arr(mu)), "halp_set_chain_hyper")
+
+    def set_feature_scale(self, s=None):
+        """Per-feature data scales: a float32 CUDA tensor of d entries, or None to switch off."""
+        self._keep["fscale"] = s
+        _check(lib().halp_set_feature_scale(self._h, _ptr(s)), "halp_set_feature_scale")
 
     def quantize_data(self, stream=None):
         _check(lib().halp_quantize_data(self._h, _stream(stream)), "halp_quantize_data")

@@ -36,6 +36,12 @@ __device__ __forceinline__ void axpy4(float s, const F4& x, F4& g) {
   g.w = __builtin_fmaf(s, x.w, g.w);
 }
 
+// Coordinate j of the model the data belong to: with per-feature scales the buffer holds
+// v_j = s_j w_j (one correctly rounded division, once per workgroup).
+__device__ __forceinline__ float model_coord(const FgArgs& a, const float* w, int j) {
+  return a.fscale ? __fdiv_rn(w[j], a.fscale[j]) : w[j];
+}
+
 // Loads the chunk at column `col` of a row; columns >= d read as 0.  The row
 // stride is a multiple of 4 floats, so a whole F4 is always inside the row.
 template <bool EXACT>
@@ -71,10 +77,10 @@ __global__ __launch_bounds__(256) void fullgrad_k1(FgArgs a) {
   for (int k = 0; k < NV; ++k) {
     const int col = 4 * (lane + 64 * k);
     wv[k] = make_f4(0.f, 0.f, 0.f, 0.f);
-    if (col < d) wv[k].x = w[col];
-    if (col + 1 < d) wv[k].y = w[col + 1];
-    if (col + 2 < d) wv[k].z = w[col + 2];
-    if (col + 3 < d) wv[k].w = w[col + 3];
+    if (col < d) wv[k].x = model_coord(a, w, col);
+    if (col + 1 < d) wv[k].y = model_coord(a, w, col + 1);
+    if (col + 2 < d) wv[k].z = model_coord(a, w, col + 2);
+    if (col + 3 < d) wv[k].w = model_coord(a, w, col + 3);
     gv[k] = make_f4(0.f, 0.f, 0.f, 0.f);
   }
   double loss_acc = 0.0;
@@ -213,10 +219,10 @@ __global__ __launch_bounds__(256) void fullgrad_k1_narrow(FgArgs a) {
   const int col = 4 * sub;
 
   F4 wv = make_f4(0.f, 0.f, 0.f, 0.f), gv = make_f4(0.f, 0.f, 0.f, 0.f);
-  if (col < d) wv.x = w[col];
-  if (col + 1 < d) wv.y = w[col + 1];
-  if (col + 2 < d) wv.z = w[col + 2];
-  if (col + 3 < d) wv.w = w[col + 3];
+  if (col < d) wv.x = model_coord(a, w, col);
+  if (col + 1 < d) wv.y = model_coord(a, w, col + 1);
+  if (col + 2 < d) wv.z = model_coord(a, w, col + 2);
+  if (col + 3 < d) wv.w = model_coord(a, w, col + 3);
   double loss_acc = 0.0;
 
   const int64_t nblk = (N + BR - 1) / BR;
@@ -303,10 +309,12 @@ struct RedArgs {
   const float* partial_g;
   const double* partial_loss;
   const float* w;
+  const float* fscale;  // [d] or null: the gradient is handed on as d f / d v_j = g_j / s_j
   float* g;
   double* scales;
   int64_t N;
   int n;  // K*d
+  int d;
   int parts;
   double lambda;
 };
@@ -332,7 +340,9 @@ __global__ __launch_bounds__(256) void fullgrad_reduce(RedArgs a) {
     double t = gsum[0][e];
 #pragma unroll
     for (int q = 1; q < 8; ++q) t += gsum[q][e];
-    a.g[(int64_t)chain * a.n + k] = (float)(t / (double)a.N + a.lambda * (double)w[k]);
+    double gk = t / (double)a.N + a.lambda * (double)w[k];
+    if (a.fscale) gk = gk / (double)a.fscale[k % a.d];
+    a.g[(int64_t)chain * a.n + k] = (float)gk;
   }
   if (blockIdx.x == 0) {  // f(w~): data term plus lambda/2 ||w~||^2
     __shared__ double red[256];
@@ -432,7 +442,7 @@ int launch_full_gradient(const halp_handle& h, hipStream_t s) {
   a.N = p.N; a.ldx = h.buf.ldx;
   a.x_chain_stride = p.share_data ? 0 : p.N * h.buf.ldx;
   a.y_chain_stride = p.share_data ? 0 : p.N;
-  a.d = p.d; a.K = p.K; a.parts = h.parts;
+  a.d = p.d; a.K = p.K; a.parts = h.parts; a.fscale = h.fscale;
   const dim3 grid(h.parts, p.R);
   const int nv = nv_for(p.d);
   if (p.loss == HALP_LOSS_SOFTMAX) {
@@ -458,6 +468,7 @@ int launch_full_gradient(const halp_handle& h, hipStream_t s) {
   RedArgs r;
   r.partial_g = h.partial_g; r.partial_loss = h.partial_loss; r.w = h.buf.w; r.g = h.buf.g;
   r.scales = h.buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = h.parts; r.lambda = p.lambda;
+  r.fscale = h.fscale; r.d = p.d;
   hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 31) / 32, p.R), dim3(256), 0, s, r);
   return hip_ok(hipGetLastError());
 }

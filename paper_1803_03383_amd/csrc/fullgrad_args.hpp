@@ -11,6 +11,7 @@ struct FgArgs {
   const float* X;
   const void* y;
   const float* w;
+  const float* fscale;  // [d] per-feature data scales s_j, or null: w then holds v_j = s_j w_j
   float* phi;
   float* partial_g;
   double* partial_loss;

@@ -78,6 +78,13 @@ __global__ __launch_bounds__(256, 2) void fullgrad_softmax_mfma(FgArgs a) {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       wreg[m][e] = w[(int64_t)min(li, K - 1) * d + min(cw0 + 16 * m + 4 * lq + e, d - 1)];
+  if (a.fscale) {  // the buffer holds v = s w: one correctly rounded division per coordinate
+#pragma unroll
+    for (int m = 0; m < NT16; ++m)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        wreg[m][e] = __fdiv_rn(wreg[m][e], a.fscale[min(cw0 + 16 * m + 4 * lq + e, d - 1)]);
+  }
 #pragma unroll
   for (int m = 0; m < NT16; ++m)
 #pragma unroll

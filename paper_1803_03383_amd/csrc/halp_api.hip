@@ -189,6 +189,17 @@ int halp_set_chain_hyper(halp_handle* h, const double* alpha, const double* mu) 
   return HALP_OK;
 }
 
+int halp_set_feature_scale(halp_handle* h, const float* s) {
+  if (!h) return HALP_ERR_NULL;
+  if (s) {
+    // lambda ||w||^2 is not uniform in the scaled model; Algorithm 1 here works on X and w directly
+    if (h->p.lambda != 0 || h->p.algorithm == HALP_ALG_SVRG) return HALP_ERR_UNSUPPORTED;
+    if (!aligned(s, 4)) return HALP_ERR_ALIGN;
+  }
+  h->fscale = s;
+  return HALP_OK;
+}
+
 int halp_bind(halp_handle* h, const halp_buffers* b) {
   if (!h || !b) return HALP_ERR_NULL;
   const halp_params& p = h->p;

@@ -23,6 +23,7 @@ struct halp_handle {
   double* partial_loss = nullptr;  // [R][parts]
   int parts = 0;                 // workgroups per chain the workspace was sized for
   size_t partial_g_bytes = 0;
+  const float* fscale = nullptr; // caller's per-feature data scales [d] (device), or null
   double* hyper = nullptr;       // [R][2] step size and mu of each chain (device)
   int last_inner_variant = 0;
   // timing: a ring of event quadruples, one per halp_epoch call since timing was switched on

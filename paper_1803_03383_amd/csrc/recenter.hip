@@ -116,6 +116,7 @@ struct QdArgs {
   int64_t rows, ldx, ldxq;
   int d;
   double delta_d;
+  const float* fscale;  // [d] per-feature scales or null
 };
 
 template <int BITS>
@@ -129,7 +130,8 @@ __global__ __launch_bounds__(256) void quantize_data_kernel(QdArgs a) {
     for (int64_t j = threadIdx.x; j < a.ldxq; j += 256) {
       double q = 0.0;
       if (j < a.d) {
-        q = rint(__ddiv_rn((double)xr[j], a.delta_d));  // ties to even
+        const double dd = a.fscale ? __dmul_rn(a.delta_d, (double)a.fscale[j]) : a.delta_d;
+        q = rint(__ddiv_rn((double)xr[j], dd));  // ties to even
         q = fmin(fmax(q, -qmax), qmax);
       }
       qr[j] = (XT)(int)q;
@@ -180,7 +182,7 @@ int launch_quantize_data(const halp_handle& h, hipStream_t s) {
   QdArgs a;
   a.X = h.buf.X; a.Xq = h.buf.Xq;
   a.rows = (p.share_data ? 1 : (int64_t)p.R) * p.N;
-  a.ldx = h.buf.ldx; a.ldxq = h.buf.ldxq; a.d = p.d; a.delta_d = p.delta_d;
+  a.ldx = h.buf.ldx; a.ldxq = h.buf.ldxq; a.d = p.d; a.delta_d = p.delta_d; a.fscale = h.fscale;
   const int grid = (int)(a.rows < 65536 ? a.rows : 65536);
   if (p.b == 8) hipLaunchKernelGGL(quantize_data_kernel<8>, dim3(grid), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(quantize_data_kernel<16>, dim3(grid), dim3(256), 0, s, a);
