@@ -106,3 +106,37 @@ def test_feature_scale_is_refused_where_it_has_no_meaning():
     with pytest.raises(hp.HalpError):
         P.h.set_feature_scale(s)
     P.h.set_feature_scale(None)
+
+
+def test_feature_scales_rescue_small_columns_end_to_end():
+    """Columns spread over three decades: with one scalar data scale the small columns quantize
+    to zero and the loss stalls; with per-feature scales 8-bit HALP drives it to zero -- on the
+    GPU as on the oracle."""
+    N, d, T, K, b = 800, 32, 1600, 20, 8
+    X0, _, ws = inp.linreg(N, d, seed=5, x_var="inv_d", noise=0.0)
+    col = np.logspace(0, -3, d).astype(np.float32)
+    X = (X0 * col).astype(np.float32)
+    y = (X.astype(np.float64) @ (ws / col)).astype(np.float32)
+    final = {}
+    for mode in ("scalar", "feature"):
+        if mode == "scalar":
+            s, dd = np.ones(d, np.float32), inp.default_delta_d(X, b)
+        else:
+            s, dd = np.abs(X).max(axis=0).astype(np.float32), 1.0 / 127
+        P = GpuProblem(X, None, y, b=b, T=T, alpha=0.1, mu=0.1, delta_d=dd, seed=1)
+        P.h.set_feature_scale(torch.from_numpy(s).cuda())
+        P.h.quantize_data()
+        for k in range(K):
+            P.h.epoch(k)
+        P.h.full_gradient()
+        loss_gpu = float(P.get("scales")[0, 6])
+        prob = ref.make_problem(N, d, b=b, alpha=0.1, mu=0.1, delta_d=dd, seed=1)
+        Xq = ref.quantize_data_scaled(X, dd, s, b)
+        v = np.zeros((1, d), np.float32)
+        for k in range(K):
+            v = ref.epoch_scaled(prob, X, Xq, y, v, s, k, T)["w"]
+        loss_ref = ref.full_gradient_scaled(prob, X, y, v, s)[2]
+        final[mode] = (loss_gpu, loss_ref)
+    assert final["scalar"][0] > 0.1 and final["scalar"][1] > 0.1
+    assert abs(final["scalar"][0] / final["scalar"][1] - 1) < 0.2
+    assert final["feature"][0] < 1e-8 and final["feature"][1] < 1e-8
