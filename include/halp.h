@@ -218,6 +218,12 @@ int halp_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uin
 int halp_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
                            int32_t K, uint32_t* out, void* stream);
 
+/* Measurement aid, not part of the method: one kernel that reads `bytes` (a multiple of 16,
+ * 16-byte aligned DEVICE memory) exactly once with the load pattern of the gradient pass and
+ * writes 2048 uint32 partial checksums to out (DEVICE).  Timed over the example matrix it is
+ * the read-only bandwidth this GPU reaches, the yardstick beside the published HBM peak.  */
+int halp_debug_read_bandwidth(const void* p, int64_t bytes, uint32_t* out, void* stream);
+
 const char* halp_strerror(int code);
 /* Text of the last HIP runtime failure seen by this thread inside the library
  * (which call, and HIP's message); empty if there was none.                            */

@@ -22,7 +22,7 @@ EXPORTS = [
     "halp_quantize_data",
     "halp_full_gradient", "halp_recenter", "halp_inner_loop", "halp_epoch",
     "halp_inner_loop_trace", "halp_get_stats", "halp_debug_stream_words",
-    "halp_debug_zround_bits", "halp_strerror", "halp_last_error_detail", "halp_version",
+    "halp_debug_zround_bits", "halp_debug_read_bandwidth", "halp_strerror", "halp_last_error_detail", "halp_version",
 ]
 
 
@@ -90,6 +90,7 @@ def lib():
         L.halp_get_stats.argtypes = [vp, i32, vp, C.POINTER(Stats)]
         L.halp_debug_stream_words.argtypes = [u64, u32, u32, u64, i64, vp, vp]
         L.halp_debug_zround_bits.argtypes = [u64, u32, u64, i32, i32, i32, vp, vp]
+        L.halp_debug_read_bandwidth.argtypes = [vp, i64, vp, vp]
         for name in EXPORTS:
             getattr(L, name).restype = C.c_int
         L.halp_strerror.restype = C.c_char_p
@@ -239,4 +240,15 @@ def debug_zround_bits(seed, epoch, t, d, b, K, stream=None):
     out = torch.zeros((K, d), dtype=torch.int32, device="cuda")
     _check(lib().halp_debug_zround_bits(seed, epoch, t, d, b, K, _ptr(out), _stream(stream)),
            "halp_debug_zround_bits")
+    return out
+
+
+def debug_read_bandwidth(t, out=None, stream=None):
+    """Reads tensor t (contiguous, a multiple of 16 bytes) once; returns the checksum tensor."""
+    import torch
+    if out is None:
+        out = torch.empty(2048, dtype=torch.int32, device=t.device)
+    nbytes = t.numel() * t.element_size()
+    _check(lib().halp_debug_read_bandwidth(_ptr(t), nbytes, _ptr(out), _stream(stream)),
+           "halp_debug_read_bandwidth")
     return out

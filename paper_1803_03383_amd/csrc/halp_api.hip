@@ -402,6 +402,13 @@ int halp_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uin
   return launch_debug_stream_words(seed, purpose, epoch, n0, count, out, as_stream(stream));
 }
 
+int halp_debug_read_bandwidth(const void* p, int64_t bytes, uint32_t* out, void* stream) {
+  if (!p || !out) return HALP_ERR_NULL;
+  if (bytes < 0 || bytes % 16 != 0) return HALP_ERR_INVALID;
+  if (!aligned(p, 16) || !aligned(out, 4)) return HALP_ERR_ALIGN;
+  return launch_debug_read(p, bytes, out, as_stream(stream));
+}
+
 int halp_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
                            int32_t K, uint32_t* out, void* stream) {
   if (!out) return HALP_ERR_NULL;

@@ -60,6 +60,8 @@ int inner_svrg_supported(const halp_handle& h);
 int launch_inner_svrg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int launch_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
                               int64_t count, uint32_t* out, hipStream_t s);
+constexpr int kDebugReadBlocks = 2048;  // workgroups (and partial sums) of the read yardstick
+int launch_debug_read(const void* p, int64_t bytes, uint32_t* out, hipStream_t s);
 int launch_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
                              int32_t K, uint32_t* out, hipStream_t s);
 

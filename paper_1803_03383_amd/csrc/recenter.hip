@@ -163,7 +163,42 @@ __global__ void debug_zround_kernel(uint64_t seed, uint32_t epoch, uint64_t t, i
   }
 }
 
+// Yardstick of the gradient pass: reads n16 16-byte words once (non-temporal, eight loads in
+// flight per thread) and does nothing else; one partial sum per workgroup keeps the loads alive.
+typedef uint32_t UV4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void debug_read_kernel(const UV4* __restrict__ p, int64_t n16,
+                                                         uint32_t* out) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  uint32_t acc = 0;
+  for (; k + 7 * stride < n16; k += 8 * stride) {
+    UV4 v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = __builtin_nontemporal_load(p + k + e * stride);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += v[e].x ^ v[e].y ^ v[e].z ^ v[e].w;
+  }
+  for (; k < n16; k += stride) {
+    const UV4 v = __builtin_nontemporal_load(p + k);
+    acc += v.x ^ v.y ^ v.z ^ v.w;
+  }
+  __shared__ uint32_t red[256];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = red[0];
+}
+
 }  // namespace
+
+int launch_debug_read(const void* p, int64_t bytes, uint32_t* out, hipStream_t s) {
+  hipLaunchKernelGGL(debug_read_kernel, dim3(kDebugReadBlocks), dim3(256), 0, s,
+                     reinterpret_cast<const UV4*>(p), bytes / 16, out);
+  return hip_ok(hipGetLastError());
+}
 
 int launch_recenter(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const halp_params& p = h.p;

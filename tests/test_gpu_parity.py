@@ -57,6 +57,19 @@ def test_quantize_data_bit_exact(b):
     assert not got[..., 100:].any()  # padding columns are zero
 
 
+def test_read_yardstick_reads_every_word_once():
+    import torch
+    rng = np.random.default_rng(0)
+    for n16 in (1, 255, 2048 * 256 * 8 + 12345):
+        a = rng.integers(0, 2 ** 32, size=(n16, 4), dtype=np.uint64).astype(np.uint32)
+        t = torch.from_numpy(a.view(np.int32)).cuda()
+        out = hp.debug_read_bandwidth(t).cpu().numpy().view(np.uint32)
+        want = np.bitwise_xor.reduce(a, axis=1).astype(np.uint64).sum() % 2 ** 32
+        assert int(out.astype(np.uint64).sum() % 2 ** 32) == int(want)
+    with pytest.raises(hp.HalpError):
+        hp.debug_read_bandwidth(torch.zeros(5, dtype=torch.int32, device="cuda"))
+
+
 # ------------------------------------------------------------ full gradient
 
 FG_CASES = [
