@@ -128,3 +128,24 @@ def test_conditioning_grid_reaches_the_oracles_gradient_norm():
     # chain by chain the two agree on which settings work at all
     ok_ref, ok_gpu = gn_ref < 10 * gn_ref.min(), gn_gpu < 10 * gn_gpu.min()
     assert np.sum(ok_ref != ok_gpu) <= 2
+
+
+def test_resume_from_w_epoch_seed_alone():
+    """All randomness is a function of (seed + chain, epoch, step): a run stopped after two
+    epochs and resumed in a new handle from w~ alone ends with the same bits as the unbroken run."""
+    X, y, dd, Xq = _data(10.0, 8, hp.LOSS_LOGISTIC)
+    R, T = 3, 400
+    kw = dict(R=R, loss=hp.LOSS_LOGISTIC, T=T, alpha=2e-3, mu=2.0, delta_d=dd, seed=11, share_data=True)
+    A = GpuProblem(X, Xq, y, **kw)
+    for k in range(4):
+        A.h.epoch(k)
+    B1 = GpuProblem(X, Xq, y, **kw)
+    for k in range(2):
+        B1.h.epoch(k)
+    w_mid = B1.get("w").copy()
+    B2 = GpuProblem(X, Xq, y, w0=w_mid, **kw)
+    for k in range(2, 4):
+        B2.h.epoch(k)
+    assert np.array_equal(A.get("w"), B2.get("w"))
+    assert np.array_equal(A.get("z"), B2.get("z"))
+    assert not np.array_equal(w_mid, A.get("w"))
