@@ -268,18 +268,37 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
       if (FULL || t < T) {
         // low-precision dot product x_i^T z
         int xe[CPL];
-        AccT part = 0;
+        int part = 0, part_hi = 0;
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
           const uint32_t xv = xw[s][(k * BITS) / 32];
           const int sh = (k * BITS) % 32;
           xe[k] = BITS == 8 ? (int)(int8_t)(xv >> sh) : (int)(int16_t)(xv >> sh);
-          if (BITS == 8) part = (AccT)mad24(xe[k], z[k], (int)part);
-          else part += (AccT)((long long)xe[k] * (long long)z[k]);
+          if (BITS == 8) part = mad24(xe[k], z[k], part);
         }
         AccT D;
-        if (BITS == 8) D = (AccT)wave_sum_i32((int)part);
-        else D = (AccT)wave_sum_i64((long long)part);
+        if (BITS == 8) {
+          D = (AccT)wave_sum_i32(part);
+        } else {
+          // 16 bits: a product of two 16-bit factors, or the sum of two, fits 32 bits.  Each is
+          // cut into its low 16 bits and the rest, and the two kinds are summed apart: both
+          // sums stay far inside 32 bits over a whole wave, so two plain folds give the exact
+          // 64-bit dot product.
+          if (CPL == 1) {
+            const int p = mad24(xe[0], z[0], 0);
+            part = p & 0xFFFF;
+            part_hi = p >> 16;
+          } else {
+#pragma unroll
+            for (int k = 0; k + 1 < CPL; k += 2) {
+              const int p = mad24(xe[k], z[k], mad24(xe[k + 1], z[k + 1], 0));
+              part += p & 0xFFFF;
+              part_hi += p >> 16;
+            }
+          }
+          const int lo = wave_sum_i32(part), hi = wave_sum_i32(part_hi);
+          D = (AccT)(((long long)hi << 16) + (long long)lo);
+        }
         if (NWT > 1) {
           if (lane == 0) s_part[s & 1][wave] = D;
           __syncthreads();
@@ -321,9 +340,12 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
             if (REGW) v = mad24(-cl, z[k], v);
             zu = z[k] + (v >> 8);
           } else {
-            long long v = (long long)ng * (long long)xe[k] - (long long)hv[k] + (long long)re;
-            if (REGW) v -= (long long)(cl * z[k]);
-            zu = z[k] + (int)(v >> 16);
+            // with h~ = 2^16 hh + hl, 0 <= hl < 2^16:
+            // floor((-gamma x + r - h~ - c z) / 2^16) = floor((-gamma x + r - hl - c z) / 2^16) - hh,
+            // and the numerator on the right stays below 2^31 in magnitude
+            int v = mad24(ng, xe[k], re - (hv[k] & 0xFFFF));
+            if (REGW) v = mad24(-cl, z[k], v);
+            zu = z[k] + (v >> 16) - (hv[k] >> 16);
           }
           const int zc = min(max(zu, QMIN), QMAX);
           if (COUNT) n_zclamp += (zu != zc) ? 1u : 0u;
