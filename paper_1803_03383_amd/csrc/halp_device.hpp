@@ -47,9 +47,6 @@ __device__ __forceinline__ uint32_t pick(const U4& v, uint32_t k) {
   return k == 0 ? v.x : (k == 1 ? v.y : (k == 2 ? v.z : v.w));
 }
 
-// Rounding bits of z: a row of z is cut into strips 16 rounding bits wide (16/b
-// coordinates: two at b = 8, one at b = 16).  One block serves strip `strip` for the
-// eight steps 8s .. 8s+7; step t reads the 16-bit field t % 8 (half f % 2 of word f / 2).
 // Steps of an epoch.  Option I of Algorithms 1-3 runs all T; option II ends the epoch at the
 // iterate after t steps, t uniform on {0, .., T-1} (word 0 of its own stream, multiply-shift).
 __device__ __forceinline__ int64_t epoch_steps(uint64_t seed, uint32_t epoch, int64_t T, int option2) {
@@ -58,6 +55,9 @@ __device__ __forceinline__ int64_t epoch_steps(uint64_t seed, uint32_t epoch, in
   return (int64_t)(((uint64_t)r.x * (uint64_t)T) >> 32);
 }
 
+// Rounding bits of z: a row of z is cut into strips 16 rounding bits wide (16/b
+// coordinates: two at b = 8, one at b = 16).  One block serves strip `strip` for the
+// eight steps 8s .. 8s+7; step t reads the 16-bit field t % 8 (half f % 2 of word f / 2).
 __device__ __forceinline__ U4 zround_block(uint64_t seed, uint32_t epoch, uint32_t strip,
                                            uint32_t s) {
   return philox4x32_10(U4{strip, s, epoch, (uint32_t)kZround}, (uint32_t)seed,
