@@ -13,7 +13,8 @@ and are resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` is int8 feature-updates per second over whole
 epochs (R*T*d updates per epoch, gradient pass included in the time).
-`roofline` describes the inner-loop kernel (the dominant one), and
+`roofline` describes the inner-loop kernel (the dominant one; `roofline_chip_filled` the
+same kernel with 2048 chains, eight per CU), and
 `roofline_full_gradient` the gradient pass of the same epochs; both durations
 come from HIP events recorded by the library on the launch stream inside the
 timed region.  `full_gradient_c5` is the gradient pass alone on the 16.4 GB
@@ -102,6 +103,30 @@ def cpu_baseline(cfg, X, Xq, y, delta_d, seed, budget_chains):
                 kind="oracle",
                 sample=f"{len(chains)} of the {R} chains, one full epoch each (N={N}, d={d}, T={T}), "
                        f"{dt:.1f} s wall")
+
+
+def chip_filled_inner_loop(hp, inp, torch, cfg, chains=2048, epochs=3):
+    """The inner-loop kernel of the headline workload with 8 chains per CU (the chains share chain
+    0's data and differ in their seeds): the throughput-bound figure beside the latency-bound
+    one of 256 chains."""
+    c = dict(cfg)
+    c["R"], c["share_data"] = chains, True
+    h, X, Xq, y, st, _ = make_problem(hp, inp, torch, c)
+    for k in range(2):
+        h.epoch(k)
+    h.set_option(hp.OPT_TIMING, 1)
+    for k in range(epochs):
+        h.epoch(2 + k)
+    s = h.get_stats(0)
+    upd = chains * c["T"] * c["d"]
+    out = dict(chains=chains, ms=s.ms_inner_loop, feature_updates_per_s=upd / (s.ms_inner_loop * 1e-3),
+               achieved=upd * LANEOPS_PER_UPDATE_B8 / (s.ms_inner_loop * 1e-3) / 1e12,
+               peak=ALU_PEAK_LANEOPS / 1e12, unit="Tlane-op/s",
+               frac=upd * LANEOPS_PER_UPDATE_B8 / (s.ms_inner_loop * 1e-3) / ALU_PEAK_LANEOPS,
+               steps_per_s_per_chain=c["T"] / (s.ms_inner_loop * 1e-3))
+    h.close()
+    del X, Xq, y, st
+    return out
 
 
 def read_ceiling(hp, torch, t, reps=5):
@@ -456,6 +481,8 @@ def main():
     h.close()
     del h, X, Xq, y, st
     torch.cuda.empty_cache()
+    if args.algorithm == "halp" and args.workload == "c4" and args.chains in (0, WORKLOADS["c4"]["R"]):
+        out["roofline_chip_filled"] = chip_filled_inner_loop(hp, inp, torch, WORKLOADS["c4"])
     if not args.no_c5:
         out["full_gradient_c5"] = c5_full_gradient(hp, inp, torch)
     print(json.dumps(out))
