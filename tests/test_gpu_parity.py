@@ -90,6 +90,10 @@ FG_CASES = [
     (hp.LOSS_SQUARED, 513, 100, 1, 2, 1e-3),
     (hp.LOSS_LOGISTIC, 999, 128, 1, 1, 0.0),
     (hp.LOSS_SQUARED, 1, 128, 1, 1, 0.0),
+    (hp.LOSS_SQUARED, 1, 1, 1, 1, 0.0),       # the smallest problem there is
+    (hp.LOSS_LOGISTIC, 3, 2, 1, 2, 1e-3),
+    (hp.LOSS_SOFTMAX, 2, 1, 2, 1, 0.0),
+    (hp.LOSS_SOFTMAX, 37, 3, 16, 1, 1e-4),
     (hp.LOSS_SOFTMAX, 1500, 784, 10, 1, 1e-4),
     (hp.LOSS_SOFTMAX, 333, 100, 3, 2, 1e-4),
     (hp.LOSS_SOFTMAX, 64, 257, 16, 1, 0.0),
@@ -237,6 +241,8 @@ INNER_REG_CASES = [
     (hp.LOSS_SQUARED, 50, 64, 8, 0.0, 1, 1, 0.5),           # a single step
     (hp.LOSS_SQUARED, 50, 64, 8, 0.0, 1, 0, 0.5),           # no step at all
     (hp.LOSS_SQUARED, 64, 64, 8, 0.0, 1, 600, 500.0),       # box far too small: z saturates
+    (hp.LOSS_SQUARED, 1, 1, 8, 0.0, 1, 50, 0.5),            # one example, one feature
+    (hp.LOSS_LOGISTIC, 3, 2, 16, 1e-3, 2, 77, 0.5),
     (hp.LOSS_LOGISTIC, 300, 128, 16, 1e-4, 2, 600, 500.0),  # the same at 16 bits ("Clip")
 ]
 
@@ -289,6 +295,8 @@ SOFTMAX_REG_CASES = [
     (250, 200, 5, 16, 0.0, 1, 520, 0.05),     # crosses two batches of draws
     (100, 64, 2, 8, 0.0, 1, 1, 0.05),         # a single step
     (100, 64, 2, 8, 0.0, 1, 0, 0.05),         # no step at all
+    (2, 1, 2, 8, 0.0, 1, 40, 0.05),           # two examples, one feature
+    (5, 3, 15, 16, 1e-2, 1, 33, 0.05),
     (64, 64, 4, 8, 0.0, 1, 600, 500.0),       # box far too small: z saturates
     (128, 96, 3, 16, 1e-3, 1, 400, 500.0),    # the same at 16 bits
     (300, 784, 10, 16, 1e-4, 1, 203, 0.05),   # the 10-class shape at 16 bits: 16 strips per lane, 49 lanes
@@ -342,6 +350,8 @@ BATCH_CASES = [
     (hp.LOSS_LOGISTIC, 300, 4096, 64, 16, 1e-5, 1, 40),    # the C5 shape: 8 worker waves, 16-byte fragments
     (hp.LOSS_SQUARED, 200, 2048, 33, 16, 0.0, 2, 100),
     (hp.LOSS_SQUARED, 200, 512, 2, 8, 0.0, 1, 1),
+    (hp.LOSS_LOGISTIC, 1, 1, 64, 16, 0.0, 1, 20),          # every row of the batch is the only example
+    (hp.LOSS_SQUARED, 5, 3, 3, 8, 1e-2, 2, 25),
     (hp.LOSS_SQUARED, 64, 64, 16, 8, 0.0, 1, 300),         # box far too small (mu below): z saturates
 ]
 
