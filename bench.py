@@ -165,7 +165,8 @@ def c5_full_gradient(hp, inp, torch, reps=5):
     ceiling = read_ceiling(hp, torch, X)
     out = dict(workload="binary logistic N=1e6 d=4096 fp32 (16.4 GB)", ms=mean, ms_min=float(min(ms)),
                achieved=nbytes / mean / 1e6, peak=HBM_PEAK_GBS, unit="GB/s",
-               frac=nbytes / mean / 1e6 / HBM_PEAK_GBS, read_only_kernel_GBs=ceiling,
+               frac=nbytes / mean / 1e6 / HBM_PEAK_GBS, bytes=nbytes,
+               traffic=measured_traffic("fullgrad_k1", "c5"), read_only_kernel_GBs=ceiling,
                frac_of_read_only_kernel=nbytes / mean / 1e6 / ceiling, loss=h.get_stats(0).loss)
     h.close()
     del X, y, st
