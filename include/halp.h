@@ -108,7 +108,8 @@ typedef struct {
   double* scales;     /* out  [R][8]: delta_m, delta_i, delta_s, ||g~||, 1/delta_i, 1/delta_s,
                          f(w~), status (0 ok, 1 gradient exactly zero, -1 not finite)   */
   uint64_t* counters; /* out  [R][4]: coordinates of z clamped by the last inner loop, gammas
-                         clamped, steps with a non-zero L2 draw, reserved               */
+                         clamped, steps with a non-zero L2 draw, 1 if a cross-workgroup wait
+                         of the split minibatch loop ran out (the result is then invalid)   */
 } halp_buffers;
 
 typedef struct {
@@ -141,6 +142,14 @@ typedef struct {
                                     for: chain r draws t uniformly from {0, .., T-1} (word 0 of
                                     stream purpose 5 of that epoch) and the epoch ends at the
                                     iterate after t steps: w~ <- w~ + delta_m z_t                */
+#define HALP_OPT_INNER_PARTS 7   /* workgroups per chain of the minibatch (B > 1) register inner
+                                    loop: 1, 2, 4, 8 or 0 = auto.  More than one cuts the row
+                                    fragments a CU has to stream per step; the workgroups of a
+                                    chain meet once per step in device memory and wait for each
+                                    other (bounded; a wait that runs out is reported in
+                                    counters[3]), so it is only taken when R times the value is
+                                    at most the number of CUs, and launches of two handles in
+                                    that mode should not overlap.  Results do not depend on it */
 
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */

@@ -147,6 +147,12 @@ int halp_create(halp_handle** out, const halp_params* p) {
       return HALP_ERR_HIP;
     }
   }
+  // exchange buffers of the split minibatch inner loop, where it can apply
+  if (p->K == 1 && p->B > 1 && (int64_t)p->R * 2 <= h->num_cus) {
+    const size_t slots = (size_t)p->R * 2 * kBatchMaxParts;
+    if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->batch_xbuf), slots * 64 * sizeof(long long)),
+                 "hipMalloc(batch_xbuf)")) { halp_destroy(h); return HALP_ERR_HIP; }
+  }
   // every chain starts with the step size and mu of the parameters
   if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->hyper), sizeof(double) * 2 * (size_t)p->R),
                "hipMalloc(hyper)")) { halp_destroy(h); return HALP_ERR_HIP; }
@@ -164,6 +170,7 @@ int halp_destroy(halp_handle* h) {
   if (h->partial_g) (void)hipFree(h->partial_g);
   if (h->partial_loss) (void)hipFree(h->partial_loss);
   if (h->hyper) (void)hipFree(h->hyper);
+  if (h->batch_xbuf) (void)hipFree(h->batch_xbuf);
   for (auto& quad : h->ev)
     for (auto& e : quad)
       if (e) (void)hipEventDestroy(e);
@@ -234,6 +241,10 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
     case HALP_OPT_TIMING:
       h->timing = value != 0;
       h->timed = 0;
+      return HALP_OK;
+    case HALP_OPT_INNER_PARTS:
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return HALP_ERR_INVALID;
+      h->inner_parts = (int)value;
       return HALP_OK;
     case HALP_OPT_OPTION_II:
       if (value != 0 && value != 1) return HALP_ERR_INVALID;

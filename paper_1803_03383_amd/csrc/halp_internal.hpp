@@ -24,6 +24,9 @@ struct halp_handle {
   int parts = 0;                 // workgroups per chain the workspace was sized for
   size_t partial_g_bytes = 0;
   const float* fscale = nullptr; // caller's per-feature data scales [d] (device), or null
+  // minibatch inner loop split over several workgroups per chain: partial dots and tags
+  long long* batch_xbuf = nullptr;   // [R][2][kBatchMaxParts][64] tagged partial dots
+  int inner_parts = 0;               // workgroups per chain of that kernel, 0 = auto
   double* hyper = nullptr;       // [R][2] step size and mu of each chain (device)
   int last_inner_variant = 0;
   // timing: a ring of event quadruples, one per halp_epoch call since timing was switched on
@@ -33,6 +36,8 @@ struct halp_handle {
 };
 
 namespace halp {
+
+constexpr int kBatchMaxParts = 8;  // workgroups per chain of the minibatch inner loop at most
 
 struct TraceBufs {
   int64_t M = 0;

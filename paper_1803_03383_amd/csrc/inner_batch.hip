@@ -1,7 +1,11 @@
 // Inner loop of Algorithm 4 (LM-HALP) with a minibatch of B rows per step (K = 1):
 // all rows of a step see the same z, each has its own gamma, z is quantized once per step.
 //
-// One workgroup per chain.
+// One workgroup per chain, or -- when chains are few -- P workgroups per chain, each holding
+// a slice of the coordinates.  The P partial dots of a row then meet in global memory once
+// per step: every workgroup publishes its 64 partial sums, each tagged with the step, waits
+// (bounded) for the tagged sums of the others, adds them and goes on alone; the update needs
+// nothing from the others.
 //
 // A thread owns the coordinates of one 4/8/16-byte fragment of a row (CPT of them)
 // with z, h~ and the window's Philox words in registers.  The B rows of a step (B d b/8
@@ -25,6 +29,8 @@ namespace {
 
 constexpr int kMaxB = 64;   // rows per step: one per service lane
 constexpr int kChunk = 8;   // rows in flight per worker thread
+constexpr int kMaxParts = kBatchMaxParts;
+constexpr int kSpinLimit = 1 << 20; // polls of the other workgroups' sums before giving up for good
 
 typedef short short2v __attribute__((ext_vector_type(2)));
 
@@ -63,9 +69,12 @@ __device__ __forceinline__ double logistic_dl(double a, double y) {
   return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
 }
 
-// NDW: dwords of a row per thread; KT: most waves of the workgroup
-template <int BITS, int NDW, int KT>
-__global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk) {
+// NDW: dwords of a row per thread; KT: most waves of the workgroup; FS: a thread keeps its
+// fragment of every row of the step in registers, loaded a whole step ahead (then the rows
+// are read from memory once, and a full step of loads is in flight per thread, which is what
+// hides the latency of gathering B rows from HBM)
+template <int BITS, int NDW, int KT, bool FS>
+__global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk, int P, long long* xbuf) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
   constexpr int EPD = 32 / BITS;       // elements per dword
@@ -73,12 +82,13 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
   constexpr int CT = 16 / BITS;        // coordinates per strip of 16 rounding bits
   constexpr int UPL = CPT / CT;        // strips per thread (= 2 NDW)
   constexpr int QMAX = (1 << (BITS - 1)) - 1, QMIN = -(1 << (BITS - 1));
-  const int chain = blockIdx.x;
+  const int chain = (int)blockIdx.x / P;         // P workgroups per chain, nwk waves of z each
+  const int part = (int)blockIdx.x - chain * P;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int d = a.d, B = a.B;
-  const int64_t T = epoch_steps(a.seed + (uint64_t)blockIdx.x, a.epoch, a.T, a.option2);
+  const int64_t T = epoch_steps(a.seed + (uint64_t)chain, a.epoch, a.T, a.option2);
   const int64_t row_bytes = a.ldxq * (BITS / 8);
   const unsigned char* __restrict__ Xq = reinterpret_cast<const unsigned char*>(a.Xq) +
                                          (int64_t)chain * a.xq_chain_stride * (BITS / 8);
@@ -90,6 +100,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
     if (tid < 4) cnt_out[tid] = 0;
     return;
   }
+  unsigned int n_timeout = 0;
 
   __shared__ int s_idx[4][kMaxB];            // sampled rows of steps t .. t+2, slot = step % 4
   __shared__ int s_part[2][16][kMaxB];       // per wave and row: low / high partial dot
@@ -100,8 +111,13 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
   const bool use_reg = a.lambda > 0;
   const bool lp = a.lp != 0;
 
-  // ---- scalar duties, carried by wave 0 beside its share of z (one row of the step per lane)
+  // ---- scalar duties (one row of the step per lane): wave 0, beside its share of z in the
+  // chunked form.  In the full-step form wave 0 holds no coordinates: what it reads from
+  // memory inside a step (margins, the other workgroups' sums) must not queue behind a share
+  // of the next step's rows.
   const bool svc = wave == 0;
+  const int wv = FS ? wave - 1 : wave;  // this wave's place among the nwk waves that hold z
+  const bool worker = wv >= 0;
   const uint32_t N = (uint32_t)a.N;
   const float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
   const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
@@ -132,7 +148,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
     const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + (int64_t)chain * d;
     XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + (int64_t)chain * d;
     float* __restrict__ wg = a.w + (int64_t)chain * d;
-    const int j0 = tid * CPT;
+    const int j0 = worker ? (part * 64 * nwk + wv * 64 + lane) * CPT : d;
     const bool active = j0 < d;
     // Rows are padded to whole 8-byte groups; a 16-byte fragment is only used when rows are
     // 16-byte multiples (checked on the host), so a fragment that starts below d lies inside
@@ -175,11 +191,23 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
       for (int r = 0; r < kChunk; ++r)  // the row number is uniform: scalar address arithmetic
         load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(m0 + r, B - 1)]));
     };
+    // FS: the fragments of all rows of this step and of the next one
+    uint32_t xc[FS ? kMaxB : 1][NDW], xn[FS ? kMaxB : 1][NDW];
+    auto load_step = [&](uint32_t (&dst)[FS ? kMaxB : 1][NDW], const int* idx) {
+#pragma unroll
+      for (int r = 0; r < (FS ? kMaxB : 1); ++r)  // rows past B repeat the last one and are not used
+        load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(r, B - 1)]));
+    };
     __syncthreads();
-    load_chunk(xa, s_idx[0], 0);
+    if (FS) {
+      if (worker) load_step(xc, s_idx[0]);
+    } else {
+      load_chunk(xa, s_idx[0], 0);
+    }
 
-    for (int64_t t = 0; t < T; ++t) {
+    auto one_step = [&](int64_t t, uint32_t (&cur)[FS ? kMaxB : 1][NDW], uint32_t (&nxt)[FS ? kMaxB : 1][NDW]) {
       const int* idx = s_idx[t & 3];
+      if (FS && worker) load_step(nxt, s_idx[(t + 1) & 3]);  // the whole next step, in flight for a step
       // wave 0: what the scalar stage needs and does not depend on the dots — margins and
       // labels of the next step's rows (used after the next barrier pair), the rounding word
       // of gamma_m, the L2 draw
@@ -265,15 +293,23 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
         const int slo = wave_sums8_i32(lo, lane);  // row m0 + lane % 8
         const int shi = BITS == 16 ? wave_sums8_i32(hi, lane) : 0;
         if (lane < kChunk && m0 + lane < B) {
-          s_part[0][wave][m0 + lane] = slo;
-          if (BITS == 16) s_part[1][wave][m0 + lane] = shi;
+          s_part[0][wv][m0 + lane] = slo;
+          if (BITS == 16) s_part[1][wv][m0 + lane] = shi;
         }
       };
-      for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
-        load_chunk(xb, idx, m0 + kChunk);
-        dots(xa, m0);
-        load_chunk(xa, idx, m0 + 2 * kChunk < B ? m0 + 2 * kChunk : 0);
-        if (m0 + kChunk < B) dots(xb, m0 + kChunk);
+      if constexpr (FS) {
+        if (worker) {
+#pragma unroll
+          for (int m0 = 0; m0 < kMaxB; m0 += kChunk)
+            if (m0 < B) dots(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[m0]), m0);
+        }
+      } else {
+        for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
+          load_chunk(xb, idx, m0 + kChunk);
+          dots(xa, m0);
+          load_chunk(xa, idx, m0 + 2 * kChunk < B ? m0 + 2 * kChunk : 0);
+          if (m0 + kChunk < B) dots(xb, m0 + kChunk);
+        }
       }
       lds_barrier();  // the partial dots of this step are in LDS
       if (svc) {
@@ -282,6 +318,38 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
           const long long lo = s_part[0][w2][min(lane, B - 1)];
           const long long hi = BITS == 8 ? 0 : s_part[1][w2][min(lane, B - 1)];
           D += lo + hi * 256;
+        }
+        if (P > 1) {
+          // The other workgroups' shares of the dots.  A share travels as one 64-bit word, the
+          // sum in its low 46 bits and a tag of the step above them, written and read with
+          // device-scope atomics: a word that carries the step's tag is that step's sum, so no
+          // fence (and no write-back or invalidation of a whole L2) is needed.  A word is
+          // rewritten two steps later, which its writer only reaches after every workgroup of
+          // the chain has read it.
+          const unsigned long long tag = (unsigned long long)((t >> 1) % 262143) + 1ull;
+          unsigned long long* xb = reinterpret_cast<unsigned long long*>(xbuf) +
+                                   (((int64_t)chain * 2 + (int64_t)(t & 1)) * kMaxParts) * kMaxB;
+          __hip_atomic_store(&xb[part * kMaxB + lane],
+                             (tag << 46) | ((unsigned long long)D & ((1ull << 46) - 1ull)), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+          long long tot = D;
+          for (int spin = 0; n_timeout == 0; ++spin) {  // after one wait ran out, none is tried again
+            bool miss = false;
+            tot = 0;
+            for (int p2 = 0; p2 < P; ++p2) {
+              const unsigned long long wd =
+                  __hip_atomic_load(&xb[p2 * kMaxB + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              miss |= (wd >> 46) != tag;
+              tot += (long long)(wd << 18) >> 18;
+            }
+            if (__ballot(miss) == 0) break;
+            if (spin >= kSpinLimit) {  // only if a workgroup of the chain never ran: give up
+              n_timeout = 1;
+              break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+          }
+          D = tot;
         }
         // beta_m = (alpha / B) (l'(phi_m + x_m^T z) - l'(phi_m)), gamma_m = Q_(delta_s, b)(beta_m)
         const double delta = __dmul_rn(dscale, (double)D);
@@ -350,13 +418,21 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
           }
         }
       };
-      const int* idn = s_idx[(t + 1) & 3];
-      for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
-        load_chunk(xb, idx, m0 + kChunk);
-        accumulate(xa, m0);
-        if (m0 + 2 * kChunk < B) load_chunk(xa, idx, m0 + 2 * kChunk);
-        else load_chunk(xa, idn, 0);
-        accumulate(xb, m0 + kChunk);
+      if constexpr (FS) {
+        if (worker) {
+#pragma unroll
+          for (int m0 = 0; m0 < kMaxB; m0 += kChunk)
+            if (m0 < B) accumulate(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[m0]), m0);
+        }
+      } else {
+        const int* idn = s_idx[(t + 1) & 3];
+        for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
+          load_chunk(xb, idx, m0 + kChunk);
+          accumulate(xa, m0);
+          if (m0 + 2 * kChunk < B) load_chunk(xa, idx, m0 + 2 * kChunk);
+          else load_chunk(xa, idn, 0);
+          accumulate(xb, m0 + kChunk);
+        }
       }
       // ---- u = z - sum gamma x - h~ - c_lambda z in (delta_i, 2b); z = Q_(delta_m, b)(u)
       const int cl = use_reg ? s_cl : 0;
@@ -373,6 +449,16 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
         n_zclamp += (ok[k] && zu != zc) ? 1u : 0u;
         z[k] = ok[k] ? (int)zc : 0;
       }
+    };
+    if (FS) {  // the two register sets trade places from step to step
+      int64_t t = 0;
+      for (; t + 1 < T; t += 2) {
+        one_step(t, xc, xn);
+        one_step(t + 1, xn, xc);
+      }
+      if (t < T) one_step(t, xc, xn);
+    } else {
+      for (int64_t t = 0; t < T; ++t) one_step(t, xc, xn);
     }
 
     // ---- w~ <- w~ + delta_m z (option I; Algorithm 2: w~ = delta z); hand z out
@@ -391,17 +477,33 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk)
     if (n_reg) atomicAdd(&s_cnt[2], (unsigned long long)n_reg);
   }
   __syncthreads();
-  if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
+  if (P == 1) {
+    if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
+  } else {
+    // counters were cleared before the launch: clamped coordinates add up over the parts, the
+    // scalar counts are the same in every part, a timed-out wait is flagged in the last word
+    if (tid == 0 && s_cnt[0]) atomicAdd(reinterpret_cast<unsigned long long*>(&cnt_out[0]), s_cnt[0]);
+    if (part == 0 && (tid == 1 || tid == 2)) cnt_out[tid] = s_cnt[tid];
+    if (tid == 0 && n_timeout) atomicMax(reinterpret_cast<unsigned long long*>(&cnt_out[3]), 1ull);
+  }
 }
 
-template <int BITS, int NDW, int KT>
-int launch_kt(const InArgs& a, int nwk, dim3 grid, dim3 block, size_t smem, hipStream_t s) {
-  auto kern = inner_batch_kernel<BITS, NDW, KT>;
+// clears what the split launch accumulates into or waits on
+__global__ void batch_split_prepare(long long* xbuf, int nwords, uint64_t* counters, int ncounters) {
+  const int k = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (k < nwords) xbuf[k] = 0;
+  if (k < ncounters) counters[k] = 0;
+}
+
+template <int BITS, int NDW, int KT, bool FS>
+int launch_kt(const InArgs& a, int nwk, int P, long long* xbuf, dim3 grid, dim3 block, size_t smem,
+              hipStream_t s) {
+  auto kern = inner_batch_kernel<BITS, NDW, KT, FS>;
   if (smem > 0 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                       hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)smem) != hipSuccess)
     return HALP_ERR_HIP;
-  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk);
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk, P, xbuf);
   return hip_ok(hipGetLastError());
 }
 
@@ -442,24 +544,69 @@ int inner_batch_supported(const halp_handle& h) {
   return HALP_OK;
 }
 
+// Launch shape.  Full-step form (4-byte fragments, every row of a step in registers): taken
+// by default whenever the row splits into at most 7 waves of z per workgroup over the
+// workgroups a chain may have.  Otherwise, and whenever HALP_OPT_INNER_PARTS names a count,
+// the chunked form with that many workgroups per chain.  Workgroups of a chain wait for each
+// other, so there are only as many as are surely resident at once (at most one per CU).
+struct BtLaunch {
+  bool fs;
+  int ndw, nwk, P;  // nwk: waves of z per workgroup
+};
+
+static BtLaunch pick_launch(const halp_handle& h, int64_t row_bytes) {
+  const halp_params& p = h.p;
+  const BtShape sh = pick_shape(p, row_bytes);
+  int most = 1;
+  if (h.batch_xbuf) {
+    most = kBatchMaxParts;
+    while (most > 1 && (int64_t)p.R * most > h.num_cus) most /= 2;
+  }
+  if (h.inner_parts == 0) {
+    const int epd = 32 / p.b;
+    const int w1 = (p.d + 64 * epd - 1) / (64 * epd);  // waves at one dword per thread
+    int P = 1;
+    while (P < most && (w1 + P - 1) / P > 4) P *= 2;
+    if ((w1 + P - 1) / P <= 7) return BtLaunch{true, 1, (w1 + P - 1) / P, P};
+  }
+  int P = 1;
+  if (h.inner_parts > 0) {
+    while (most > sh.nwk) most /= 2;
+    P = h.inner_parts < most ? h.inner_parts : (most < 1 ? 1 : most);
+  }
+  return BtLaunch{false, sh.ndw, (sh.nwk + P - 1) / P, P};
+}
+
 int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const halp_params& p = h.p;
   const int rc = inner_batch_supported(h);
   if (rc != HALP_OK) return rc;
   const InArgs a = make_inner_args(h, epoch);
-  const BtShape sh = pick_shape(p, h.buf.ldxq * (p.b / 8));
-  const dim3 grid(p.R), block(64 * sh.nwk);
-  // parked Philox blocks: 128 bytes per worker thread at 8 strips per thread (120 KB at most)
-  const size_t smem = sh.ndw == 4 ? (size_t)64 * sh.nwk * 128 : 0;
-#define HALP_BT(BITS_, NDW_)                                                     \
-  if (p.b == BITS_ && sh.ndw == NDW_) {                                          \
-    if (sh.nwk <= 4) return launch_kt<BITS_, NDW_, 4>(a, sh.nwk, grid, block, smem, s);   \
-    if (sh.nwk <= 8) return launch_kt<BITS_, NDW_, 8>(a, sh.nwk, grid, block, smem, s);   \
-    if (sh.nwk <= 12) return launch_kt<BITS_, NDW_, 12>(a, sh.nwk, grid, block, smem, s); \
-    return launch_kt<BITS_, NDW_, 16>(a, sh.nwk, grid, block, smem, s);          \
+  const BtLaunch L = pick_launch(h, h.buf.ldxq * (p.b / 8));
+  const int nwk = L.nwk, P = L.P;
+  const int nwaves = nwk + (L.fs ? 1 : 0);  // the full-step form adds a wave that holds no z
+  const dim3 grid(p.R * P), block(64 * nwaves);
+  if (P > 1) {
+    const int nwords = p.R * 2 * kBatchMaxParts * kMaxB, ncnt = p.R * 4;
+    hipLaunchKernelGGL(batch_split_prepare, dim3((nwords + 255) / 256), dim3(256), 0, s, h.batch_xbuf, nwords,
+                       h.buf.counters, ncnt);
   }
-  HALP_BT(8, 1) HALP_BT(8, 2) HALP_BT(8, 4)
-  HALP_BT(16, 1) HALP_BT(16, 2) HALP_BT(16, 4)
+  // parked Philox blocks: 128 bytes per worker thread at 8 strips per thread (120 KB at most)
+  const size_t smem = L.ndw == 4 ? (size_t)64 * nwk * 128 : 0;
+#define HALP_BT(BITS_, NDW_, FS_)                                                                  \
+  if (p.b == BITS_ && L.ndw == NDW_ && L.fs == FS_) {                                              \
+    if (nwaves <= 4)                                                                               \
+      return launch_kt<BITS_, NDW_, 4, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);         \
+    if (nwaves <= 8)                                                                               \
+      return launch_kt<BITS_, NDW_, 8, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);         \
+    if (FS_) return HALP_ERR_UNSUPPORTED;                                                          \
+    if (nwaves <= 12)                                                                              \
+      return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);        \
+    return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);          \
+  }
+  HALP_BT(8, 1, true) HALP_BT(16, 1, true)
+  HALP_BT(8, 1, false) HALP_BT(8, 2, false) HALP_BT(8, 4, false)
+  HALP_BT(16, 1, false) HALP_BT(16, 2, false) HALP_BT(16, 4, false)
 #undef HALP_BT
   return HALP_ERR_UNSUPPORTED;
 }

@@ -356,13 +356,18 @@ BATCH_CASES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [2, 1])
+# (kernel variant, workgroups per chain of the register kernel: 0 = the library's choice)
+BATCH_KERNELS = [(2, 0), (2, 1), (2, 2), (2, 4), (2, 8), (1, 0)]
+
+
+@pytest.mark.parametrize("variant,parts", BATCH_KERNELS)
 @pytest.mark.parametrize("loss,N,d,B,b,lam,R,T", BATCH_CASES)
-def test_inner_loop_minibatch_bit_exact(loss, N, d, B, b, lam, R, T, variant):
+def test_inner_loop_minibatch_bit_exact(loss, N, d, B, b, lam, R, T, variant, parts):
     seed = 60 + d + B
     mu = 500.0 if (N, d, B) == (64, 64, 16) else 0.05
     case = _inner_case(loss, N, d, 1, B, b, lam, R, T, seed, mu=mu)
     P = _run_inner(case, loss, 1, B, b, lam, R, T, seed, variant, mu=mu)
+    P.h.set_option(hp.OPT_INNER_PARTS, parts)
     P.h.inner_loop(3)
     z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
     assert P.h.get_stats(0).inner_variant == variant
