@@ -101,6 +101,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     return;
   }
   unsigned int n_timeout = 0;
+  constexpr int kWarm = 14;  // cache lines of the widest slice (7 waves of 256 bytes)
+  uint32_t warm[kWarm] = {};  // full-step form: what wave 0 reads to warm the caches, never used
 
   __shared__ int s_idx[4][kMaxB];            // sampled rows of steps t .. t+2, slot = step % 4
   __shared__ int s_part[2][16][kMaxB];       // per wave and row: low / high partial dot
@@ -207,7 +209,6 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
 
     auto one_step = [&](int64_t t, uint32_t (&cur)[FS ? kMaxB : 1][NDW], uint32_t (&nxt)[FS ? kMaxB : 1][NDW]) {
       const int* idx = s_idx[t & 3];
-      if (FS && worker) load_step(nxt, s_idx[(t + 1) & 3]);  // the whole next step, in flight for a step
       // wave 0: what the scalar stage needs and does not depend on the dots — margins and
       // labels of the next step's rows (used after the next barrier pair), the rounding word
       // of gamma_m, the L2 draw
@@ -223,6 +224,25 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           const uint32_t rr = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
           cl_draw = (int)quantize_real(al, (double)(1 << BITS), rr, 0.0, (double)QMAX, nullptr);
           n_reg += (lane == 0 && cl_draw != 0) ? 1u : 0u;
+        }
+        if (FS) {  // wave 0 is free while the others take the dots: the indices two steps ahead now
+          const int i2 = draw_idx(t + 2);
+          if (row) s_idx[(t + 2) & 3][lane] = i2;
+          i_next = i2;
+          // Touch this workgroup's slice of those rows, one row per lane and one load per
+          // cache line: the address translations and the lines are on their way into L2 a step
+          // before the other waves ask for them.  The values are not used (taken up a step
+          // later, so that nothing here waits for them).
+#pragma unroll
+          for (int k = 0; k < kWarm; ++k) asm volatile("" ::"v"(warm[k]));
+          const int64_t part_off = (int64_t)part * 64 * nwk * NDW * 4;
+          const int slice = (int)min((int64_t)64 * nwk * NDW * 4, row_bytes - part_off);
+          if (slice >= 4) {
+            const unsigned char* wp = Xq + (int64_t)i2 * row_bytes + part_off;
+#pragma unroll
+            for (int k = 0; k < kWarm; ++k)  // unconditional, the last line repeated
+              warm[k] = *reinterpret_cast<const uint32_t*>(wp + min(k * 128, slice - 4));
+          }
         }
       }
       if ((t & 7) == 0) {
@@ -302,6 +322,10 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
 #pragma unroll
           for (int m0 = 0; m0 < kMaxB; m0 += kChunk)
             if (m0 < B) dots(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[m0]), m0);
+          // The whole next step, requested once this step's rows have arrived (a wait for older
+          // loads can leave at most 63 newer ones outstanding) and in flight through the scalar
+          // stage and the update.
+          load_step(nxt, s_idx[(t + 1) & 3]);
         }
       } else {
         for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
@@ -369,11 +393,12 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           n_gclamp += hit ? 1u : 0u;
         }
         if (lane == 0) s_cl = cl_draw;
-        // indices two steps ahead (slot (t + 2) % 4 was last read in step t - 2)
-        const int i2 = draw_idx(t + 2);
-        if (row) s_idx[(t + 2) & 3][lane] = i2;
+        if (!FS) {  // indices two steps ahead (slot (t + 2) % 4 was last read in step t - 2)
+          const int i2 = draw_idx(t + 2);
+          if (row) s_idx[(t + 2) & 3][lane] = i2;
+          i_next = i2;
+        }
         phi_c = phi_n; y_c = y_n;
-        i_next = i2;
       }
       lds_barrier();  // gamma is out
       // ---- pass 2: sum_m gamma_m x_m per coordinate (low / high byte of gamma apart at 16 bits)
