@@ -30,6 +30,7 @@ namespace {
 constexpr int kMaxB = 64;   // rows per step: one per service lane
 constexpr int kChunk = 8;   // rows in flight per worker thread
 constexpr int kMaxParts = kBatchMaxParts;
+constexpr int kRowsPerWave = 16;    // full-step form: rows of a step one wave takes at most
 constexpr int kSpinLimit = 1 << 20; // polls of the other workgroups' sums before giving up for good
 
 typedef short short2v __attribute__((ext_vector_type(2)));
@@ -69,10 +70,13 @@ __device__ __forceinline__ double logistic_dl(double a, double y) {
   return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
 }
 
-// NDW: dwords of a row per thread; KT: most waves of the workgroup; FS: a thread keeps its
-// fragment of every row of the step in registers, loaded a whole step ahead (then the rows
-// are read from memory once, and a full step of loads is in flight per thread, which is what
-// hides the latency of gathering B rows from HBM)
+// NDW: dwords of a row per thread; KT: most waves of the workgroup.
+// FS, the full-step form: a workgroup holds ONE slice of 64 NDW dwords of the row, and its
+// nwk waves of z all hold that same slice and split the ROWS of the step between them (16
+// each at most).  A wave keeps its rows' fragments in registers, loaded a whole step ahead, so
+// the rows are read from memory once and a wave's per-row work covers a quarter of the batch.
+// The price: the waves add up their sums over rows through LDS before the update, which each
+// of them then performs on its own copy of z (same inputs, same result).
 template <int BITS, int NDW, int KT, bool FS>
 __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk, int P, long long* xbuf) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
@@ -101,12 +105,13 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     return;
   }
   unsigned int n_timeout = 0;
-  constexpr int kWarm = 14;  // cache lines of the widest slice (7 waves of 256 bytes)
+  constexpr int kWarm = 8;   // cache lines of the widest slice (64 threads of 16 bytes)
   uint32_t warm[kWarm] = {};  // full-step form: what wave 0 reads to warm the caches, never used
 
   __shared__ int s_idx[4][kMaxB];            // sampled rows of steps t .. t+2, slot = step % 4
   __shared__ int s_part[2][16][kMaxB];       // per wave and row: low / high partial dot
   __shared__ int s_gam[kMaxB];               // gamma_m
+  __shared__ int s_acc[FS ? 4 : 1][FS ? 2 * CPT : 1][64];  // full-step form: the waves' sums over their rows
   __shared__ int s_cl;                       // c_lambda of the step
   __shared__ unsigned long long s_cnt[3];
   if (tid < 3) s_cnt[tid] = 0;
@@ -150,7 +155,12 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + (int64_t)chain * d;
     XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + (int64_t)chain * d;
     float* __restrict__ wg = a.w + (int64_t)chain * d;
-    const int j0 = worker ? (part * 64 * nwk + wv * 64 + lane) * CPT : d;
+    // chunked form: the waves of a workgroup (and the workgroups of a chain) hold consecutive
+    // slices; full-step form: one slice per workgroup, the same in all its waves
+    const int j0 = !worker ? d : (FS ? (part * 64 + lane) * CPT : (part * 64 * nwk + wv * 64 + lane) * CPT);
+    // full-step form: the rows of a step are dealt to the waves in runs of 8 or 16
+    const int rpw = FS ? 8 * ((((B + nwk - 1) / nwk) + 7) / 8) : 0;
+    const int row0 = FS && worker ? wv * rpw : 0;
     const bool active = j0 < d;
     // Rows are padded to whole 8-byte groups; a 16-byte fragment is only used when rows are
     // 16-byte multiples (checked on the host), so a fragment that starts below d lies inside
@@ -171,7 +181,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     // a thread reads only what it wrote) and the words of two steps are fetched at a time.
     constexpr bool kPark = UPL == 8;
     extern __shared__ __attribute__((aligned(16))) uint4 s_zr[];
-    const int nworkers = 64 * nwk;  // all threads of the workgroup
+    const int nworkers = 64 * nwk;      // threads that hold z
+    const int wtid = wv * 64 + lane;    // this thread's place among them
     U4 zr[kPark ? 1 : UPL];
     uint32_t zw[kPark ? UPL : 1];
     unsigned long long n_zclamp = 0;
@@ -194,11 +205,12 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(m0 + r, B - 1)]));
     };
     // FS: the fragments of all rows of this step and of the next one
-    uint32_t xc[FS ? kMaxB : 1][NDW], xn[FS ? kMaxB : 1][NDW];
-    auto load_step = [&](uint32_t (&dst)[FS ? kMaxB : 1][NDW], const int* idx) {
+    constexpr int RPW = FS ? kRowsPerWave : 1;
+    uint32_t xc[RPW][NDW], xn[RPW][NDW];
+    auto load_step = [&](uint32_t (&dst)[RPW][NDW], const int* idx) {
 #pragma unroll
-      for (int r = 0; r < (FS ? kMaxB : 1); ++r)  // rows past B repeat the last one and are not used
-        load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(r, B - 1)]));
+      for (int r = 0; r < RPW; ++r)  // rows past B repeat the last one and are not used
+        load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(row0 + r, B - 1)]));
     };
     __syncthreads();
     if (FS) {
@@ -207,7 +219,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       load_chunk(xa, s_idx[0], 0);
     }
 
-    auto one_step = [&](int64_t t, uint32_t (&cur)[FS ? kMaxB : 1][NDW], uint32_t (&nxt)[FS ? kMaxB : 1][NDW]) {
+    auto one_step = [&](int64_t t, uint32_t (&cur)[RPW][NDW], uint32_t (&nxt)[RPW][NDW]) {
       const int* idx = s_idx[t & 3];
       // wave 0: what the scalar stage needs and does not depend on the dots — margins and
       // labels of the next step's rows (used after the next barrier pair), the rounding word
@@ -235,8 +247,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           // later, so that nothing here waits for them).
 #pragma unroll
           for (int k = 0; k < kWarm; ++k) asm volatile("" ::"v"(warm[k]));
-          const int64_t part_off = (int64_t)part * 64 * nwk * NDW * 4;
-          const int slice = (int)min((int64_t)64 * nwk * NDW * 4, row_bytes - part_off);
+          const int64_t part_off = (int64_t)part * 64 * NDW * 4;
+          const int slice = (int)min((int64_t)64 * NDW * 4, row_bytes - part_off);
           if (slice >= 4) {
             const unsigned char* wp = Xq + (int64_t)i2 * row_bytes + part_off;
 #pragma unroll
@@ -245,7 +257,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           }
         }
       }
-      if ((t & 7) == 0) {
+      if (worker && (t & 7) == 0) {
         if (kPark) {
 #pragma unroll
           for (int q = 0; q < UPL / 4; ++q) {
@@ -255,7 +267,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
               blk[u] = zround_block(seed, a.epoch, strip0 + (uint32_t)(4 * q + u), (uint32_t)(t >> 3));
 #pragma unroll
             for (int wd = 0; wd < 4; ++wd)
-              s_zr[(wd * (UPL / 4) + q) * nworkers + tid] =
+              s_zr[(wd * (UPL / 4) + q) * nworkers + wtid] =
                   make_uint4(pick(blk[0], wd), pick(blk[1], wd), pick(blk[2], wd), pick(blk[3], wd));
           }
         } else {
@@ -264,10 +276,10 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
             zr[u] = zround_block(seed, a.epoch, strip0 + (uint32_t)u, (uint32_t)(t >> 3));
         }
       }
-      if (kPark && (t & 1) == 0) {  // the block word that serves steps t and t + 1
+      if (kPark && worker && (t & 1) == 0) {  // the block word that serves steps t and t + 1
 #pragma unroll
         for (int q = 0; q < UPL / 4; ++q) {
-          const uint4 v = s_zr[(((int)(t & 7) >> 1) * (UPL / 4) + q) * nworkers + tid];
+          const uint4 v = s_zr[(((int)(t & 7) >> 1) * (UPL / 4) + q) * nworkers + wtid];
           zw[(4 * q) % UPL] = v.x; zw[(4 * q + 1) % UPL] = v.y;
           zw[(4 * q + 2) % UPL] = v.z; zw[(4 * q + 3) % UPL] = v.w;
         }
@@ -313,15 +325,15 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         const int slo = wave_sums8_i32(lo, lane);  // row m0 + lane % 8
         const int shi = BITS == 16 ? wave_sums8_i32(hi, lane) : 0;
         if (lane < kChunk && m0 + lane < B) {
-          s_part[0][wv][m0 + lane] = slo;
-          if (BITS == 16) s_part[1][wv][m0 + lane] = shi;
+          s_part[0][FS ? 0 : wv][m0 + lane] = slo;  // full-step form: one wave per row, one slot
+          if (BITS == 16) s_part[1][FS ? 0 : wv][m0 + lane] = shi;
         }
       };
       if constexpr (FS) {
         if (worker) {
 #pragma unroll
-          for (int m0 = 0; m0 < kMaxB; m0 += kChunk)
-            if (m0 < B) dots(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[m0]), m0);
+          for (int c0 = 0; c0 < RPW; c0 += kChunk)
+            if (c0 < rpw && row0 + c0 < B) dots(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[c0]), row0 + c0);
           // The whole next step, requested once this step's rows have arrived (a wait for older
           // loads can leave at most 63 newer ones outstanding) and in flight through the scalar
           // stage and the update.
@@ -338,7 +350,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       lds_barrier();  // the partial dots of this step are in LDS
       if (svc) {
         long long D = 0;
-        for (int w2 = 0; w2 < nwk; ++w2) {
+        for (int w2 = 0; w2 < (FS ? 1 : nwk); ++w2) {
           const long long lo = s_part[0][w2][min(lane, B - 1)];
           const long long hi = BITS == 8 ? 0 : s_part[1][w2][min(lane, B - 1)];
           D += lo + hi * 256;
@@ -446,8 +458,27 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       if constexpr (FS) {
         if (worker) {
 #pragma unroll
-          for (int m0 = 0; m0 < kMaxB; m0 += kChunk)
-            if (m0 < B) accumulate(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[m0]), m0);
+          for (int c0 = 0; c0 < RPW; c0 += kChunk)
+            if (c0 < rpw && row0 + c0 < B)
+              accumulate(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[c0]), row0 + c0);
+          // this wave's sums over its rows, for the other waves
+#pragma unroll
+          for (int k = 0; k < CPT; ++k) {
+            s_acc[wv][k][lane] = acc[k];
+            if (BITS == 16) s_acc[wv][CPT + k][lane] = acch[k];
+          }
+        }
+        lds_barrier();  // every wave's sums are in LDS
+        if (worker) {
+#pragma unroll
+          for (int k = 0; k < CPT; ++k) {
+            acc[k] = 0;
+            acch[k] = 0;
+            for (int g = 0; g < nwk; ++g) {  // the same order in every wave
+              acc[k] += s_acc[g][k][lane];
+              if (BITS == 16) acch[k] += s_acc[g][CPT + k][lane];
+            }
+          }
         }
       } else {
         const int* idn = s_idx[(t + 1) & 3];
@@ -471,7 +502,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         const long long v = -(long long)hv[k] - (long long)cl * (long long)z[k] - gsum;
         const long long zu = (long long)z[k] + ((v + re) >> BITS);
         const long long zc = zu > QMAX ? QMAX : (zu < QMIN ? QMIN : zu);
-        n_zclamp += (ok[k] && zu != zc) ? 1u : 0u;
+        n_zclamp += (ok[k] && zu != zc && (!FS || wv == 0)) ? 1u : 0u;  // the copies of z count once
         z[k] = ok[k] ? (int)zc : 0;
       }
     };
@@ -490,7 +521,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     const double delta_m = sc[0];
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
-      if (ok[k]) {
+      if (ok[k] && (!FS || wv == 0)) {
         const int j = j0 + k;
         zg[j] = (XT)z[k];
         const double step = __dmul_rn(delta_m, (double)z[k]);
@@ -569,9 +600,9 @@ int inner_batch_supported(const halp_handle& h) {
   return HALP_OK;
 }
 
-// Launch shape.  Full-step form (4-byte fragments, every row of a step in registers): taken
-// by default whenever the row splits into at most 7 waves of z per workgroup over the
-// workgroups a chain may have.  Otherwise, and whenever HALP_OPT_INNER_PARTS names a count,
+// Launch shape.  Full-step form (one slice of the row per workgroup, the rows of a step dealt
+// to its waves and kept in registers): taken by default whenever the slices of a row are few
+// enough for one workgroup each.  Otherwise, and whenever HALP_OPT_INNER_PARTS names a count,
 // the chunked form with that many workgroups per chain.  Workgroups of a chain wait for each
 // other, so there are only as many as are surely resident at once (at most one per CU).
 struct BtLaunch {
@@ -587,12 +618,26 @@ static BtLaunch pick_launch(const halp_handle& h, int64_t row_bytes) {
     most = kBatchMaxParts;
     while (most > 1 && (int64_t)p.R * most > h.num_cus) most /= 2;
   }
+  int most_any = 1;  // any count up to the exchange buffer's 8 slots
+  if (h.batch_xbuf) {
+    most_any = (int)(h.num_cus / p.R);
+    if (most_any > kBatchMaxParts) most_any = kBatchMaxParts;
+    if (most_any < 1) most_any = 1;
+  }
   if (h.inner_parts == 0) {
+    // full-step form: the widest fragment the alignment allows whose slices (one workgroup
+    // each) are few enough to be resident together; up to 4 waves share the rows of a step
     const int epd = 32 / p.b;
-    const int w1 = (p.d + 64 * epd - 1) / (64 * epd);  // waves at one dword per thread
-    int P = 1;
-    while (P < most && (w1 + P - 1) / P > 4) P *= 2;
-    if ((w1 + P - 1) / P <= 7) return BtLaunch{true, 1, (w1 + P - 1) / P, P};
+    const bool al16 = row_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(h.buf.Xq) % 16 == 0;
+    for (int ndw = al16 ? 4 : 2; ndw >= 1; ndw /= 2) {
+      const int cpt = ndw * epd;
+      const int P = (p.d + 64 * cpt - 1) / (64 * cpt);
+      if (P > most_any) continue;
+      if ((int64_t)((p.d + cpt - 1) / cpt) * ndw * 4 > row_bytes) continue;  // fragments inside the row
+      int rg = (p.B + 7) / 8;
+      if (rg > 4) rg = 4;
+      return BtLaunch{true, ndw, rg, P};
+    }
   }
   int P = 1;
   if (h.inner_parts > 0) {
@@ -629,7 +674,8 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
       return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);        \
     return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);          \
   }
-  HALP_BT(8, 1, true) HALP_BT(16, 1, true)
+  HALP_BT(8, 1, true) HALP_BT(8, 2, true) HALP_BT(8, 4, true)
+  HALP_BT(16, 1, true) HALP_BT(16, 2, true) HALP_BT(16, 4, true)
   HALP_BT(8, 1, false) HALP_BT(8, 2, false) HALP_BT(8, 4, false)
   HALP_BT(16, 1, false) HALP_BT(16, 2, false) HALP_BT(16, 4, false)
 #undef HALP_BT
