@@ -118,13 +118,11 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
   const bool use_reg = a.lambda > 0;
   const bool lp = a.lp != 0;
 
-  // ---- scalar duties (one row of the step per lane): wave 0, beside its share of z in the
-  // chunked form.  In the full-step form wave 0 holds no coordinates: what it reads from
-  // memory inside a step (margins, the other workgroups' sums) must not queue behind a share
-  // of the next step's rows.
+  // ---- scalar duties (one row of the step per lane): wave 0, beside its share of z.  (A wave
+  // of its own for them would put two waves on one SIMD and halve every wave's registers.)
   const bool svc = wave == 0;
-  const int wv = FS ? wave - 1 : wave;  // this wave's place among the nwk waves that hold z
-  const bool worker = wv >= 0;
+  const int wv = wave;        // this wave's place among the nwk waves that hold z
+  const bool worker = true;
   const uint32_t N = (uint32_t)a.N;
   const float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
   const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
@@ -334,10 +332,6 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
 #pragma unroll
           for (int c0 = 0; c0 < RPW; c0 += kChunk)
             if (c0 < rpw && row0 + c0 < B) dots(reinterpret_cast<uint32_t(&)[kChunk][NDW]>(cur[c0]), row0 + c0);
-          // The whole next step, requested once this step's rows have arrived (a wait for older
-          // loads can leave at most 63 newer ones outstanding) and in flight through the scalar
-          // stage and the update.
-          load_step(nxt, s_idx[(t + 1) & 3]);
         }
       } else {
         for (int m0 = 0; m0 < B; m0 += 2 * kChunk) {
@@ -413,6 +407,10 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         phi_c = phi_n; y_c = y_n;
       }
       lds_barrier();  // gamma is out
+      // Full-step form: this wave's rows of the next step, requested only now -- what wave 0
+      // read from memory for the scalar stage (margins, the other workgroups' sums) must not
+      // queue behind them -- and in flight through the update and the next step's start.
+      if (FS) load_step(nxt, s_idx[(t + 1) & 3]);
       // ---- pass 2: sum_m gamma_m x_m per coordinate (low / high byte of gamma apart at 16 bits)
       int acc[CPT], acch[CPT];
 #pragma unroll
@@ -629,10 +627,12 @@ static BtLaunch pick_launch(const halp_handle& h, int64_t row_bytes) {
     // each) are few enough to be resident together; up to 4 waves share the rows of a step
     const int epd = 32 / p.b;
     const bool al16 = row_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(h.buf.Xq) % 16 == 0;
-    for (int ndw = al16 ? 4 : 2; ndw >= 1; ndw /= 2) {
+    for (int ndw = (al16 && p.b == 16) ? 4 : 2; ndw >= 1; ndw /= 2) {  // 8 coordinates per thread at most
       const int cpt = ndw * epd;
       const int P = (p.d + 64 * cpt - 1) / (64 * cpt);
       if (P > most_any) continue;
+      // several workgroups pay ~3 us per step for their exchange: only for steps that move a lot
+      if (P > 1 && (int64_t)p.B * row_bytes < 256 * 1024) continue;
       if ((int64_t)((p.d + cpt - 1) / cpt) * ndw * 4 > row_bytes) continue;  // fragments inside the row
       int rg = (p.B + 7) / 8;
       if (rg > 4) rg = 4;
@@ -654,7 +654,7 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const InArgs a = make_inner_args(h, epoch);
   const BtLaunch L = pick_launch(h, h.buf.ldxq * (p.b / 8));
   const int nwk = L.nwk, P = L.P;
-  const int nwaves = nwk + (L.fs ? 1 : 0);  // the full-step form adds a wave that holds no z
+  const int nwaves = nwk;
   const dim3 grid(p.R * P), block(64 * nwaves);
   if (P > 1) {
     const int nwords = p.R * 2 * kBatchMaxParts * kMaxB, ncnt = p.R * 4;
