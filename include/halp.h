@@ -143,13 +143,15 @@ typedef struct {
                                     stream purpose 5 of that epoch) and the epoch ends at the
                                     iterate after t steps: w~ <- w~ + delta_m z_t                */
 #define HALP_OPT_INNER_PARTS 7   /* workgroups per chain of the minibatch (B > 1) register inner
-                                    loop: 1, 2, 4, 8 or 0 = auto.  More than one cuts the row
-                                    fragments a CU has to stream per step; the workgroups of a
-                                    chain meet once per step in device memory and wait for each
-                                    other (bounded; a wait that runs out is reported in
-                                    counters[3]), so it is only taken when R times the value is
-                                    at most the number of CUs, and launches of two handles in
-                                    that mode should not overlap.  Results do not depend on it */
+                                    loop.  0 (default): the library's choice, the full-step form
+                                    (the row cut across up to 8 workgroups, rows of a step held in
+                                    registers) where it applies; 1, 2, 4, 8: the chunked form with
+                                    that many workgroups.  The workgroups of a chain meet once per
+                                    step in device memory and wait for each other (bounded; a wait
+                                    that runs out is reported in counters[3]), so more than one
+                                    is only taken when R times the count is at most the number of
+                                    CUs, and launches of two handles in that mode should not
+                                    overlap.  Results do not depend on it                       */
 
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */
