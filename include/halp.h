@@ -152,6 +152,11 @@ typedef struct {
                                     is only taken when R times the count is at most the number of
                                     CUs, and launches of two handles in that mode should not
                                     overlap.  Results do not depend on it                       */
+#define HALP_OPT_EXCHANGE_SPIN_LIMIT 8 /* polls after which a workgroup of the split minibatch
+                                    loop stops waiting for the others for good (default 2^20,
+                                    about a second); -1: never wait.  The launch then ends
+                                    normally with counters[3] = 1 and an invalid result: for
+                                    tests of that path                                    */
 
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */

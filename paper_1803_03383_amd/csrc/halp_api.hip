@@ -246,6 +246,10 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
       if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return HALP_ERR_INVALID;
       h->inner_parts = (int)value;
       return HALP_OK;
+    case HALP_OPT_EXCHANGE_SPIN_LIMIT:
+      if (value < -1 || value > (int64_t(1) << 30)) return HALP_ERR_INVALID;
+      h->spin_limit = (int)value;
+      return HALP_OK;
     case HALP_OPT_OPTION_II:
       if (value != 0 && value != 1) return HALP_ERR_INVALID;
       h->option2 = value != 0;

@@ -27,6 +27,7 @@ struct halp_handle {
   // minibatch inner loop split over several workgroups per chain: partial dots and tags
   long long* batch_xbuf = nullptr;   // [R][2][kBatchMaxParts][64] tagged partial dots
   int inner_parts = 0;               // workgroups per chain of that kernel, 0 = auto
+  int spin_limit = 1 << 20;          // polls before a workgroup stops waiting for the others
   double* hyper = nullptr;       // [R][2] step size and mu of each chain (device)
   int last_inner_variant = 0;
   // timing: a ring of event quadruples, one per halp_epoch call since timing was switched on

@@ -31,7 +31,6 @@ constexpr int kMaxB = 64;   // rows per step: one per service lane
 constexpr int kChunk = 8;   // rows in flight per worker thread
 constexpr int kMaxParts = kBatchMaxParts;
 constexpr int kRowsPerWave = 16;    // full-step form: rows of a step one wave takes at most
-constexpr int kSpinLimit = 1 << 20; // polls of the other workgroups' sums before giving up for good
 
 typedef short short2v __attribute__((ext_vector_type(2)));
 
@@ -78,7 +77,8 @@ __device__ __forceinline__ double logistic_dl(double a, double y) {
 // The price: the waves add up their sums over rows through LDS before the update, which each
 // of them then performs on its own copy of z (same inputs, same result).
 template <int BITS, int NDW, int KT, bool FS>
-__global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk, int P, long long* xbuf) {
+__global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk, int P, long long* xbuf,
+                                                              int spin_limit) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
   constexpr int EPD = 32 / BITS;       // elements per dword
@@ -104,7 +104,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     if (tid < 4) cnt_out[tid] = 0;
     return;
   }
-  unsigned int n_timeout = 0;
+  // polls of the other workgroups' sums before a wait is given up for good; below 0: never wait
+  unsigned int n_timeout = spin_limit < 0 ? 1u : 0u;
   constexpr int kWarm = 8;   // cache lines of the widest slice (64 threads of 16 bytes)
   uint32_t warm[kWarm] = {};  // full-step form: what wave 0 reads to warm the caches, never used
 
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
               tot += (long long)(wd << 18) >> 18;
             }
             if (__ballot(miss) == 0) break;
-            if (spin >= kSpinLimit) {  // only if a workgroup of the chain never ran: give up
+            if (spin >= spin_limit) {  // only if a workgroup of the chain never ran: give up
               n_timeout = 1;
               break;
             }
@@ -550,14 +551,14 @@ __global__ void batch_split_prepare(long long* xbuf, int nwords, uint64_t* count
 }
 
 template <int BITS, int NDW, int KT, bool FS>
-int launch_kt(const InArgs& a, int nwk, int P, long long* xbuf, dim3 grid, dim3 block, size_t smem,
-              hipStream_t s) {
+int launch_kt(const InArgs& a, int nwk, int P, long long* xbuf, int spin_limit, dim3 grid, dim3 block,
+              size_t smem, hipStream_t s) {
   auto kern = inner_batch_kernel<BITS, NDW, KT, FS>;
   if (smem > 0 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                       hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)smem) != hipSuccess)
     return HALP_ERR_HIP;
-  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk, P, xbuf);
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk, P, xbuf, spin_limit);
   return hip_ok(hipGetLastError());
 }
 
@@ -666,13 +667,13 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
 #define HALP_BT(BITS_, NDW_, FS_)                                                                  \
   if (p.b == BITS_ && L.ndw == NDW_ && L.fs == FS_) {                                              \
     if (nwaves <= 4)                                                                               \
-      return launch_kt<BITS_, NDW_, 4, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);         \
+      return launch_kt<BITS_, NDW_, 4, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
     if (nwaves <= 8)                                                                               \
-      return launch_kt<BITS_, NDW_, 8, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);         \
+      return launch_kt<BITS_, NDW_, 8, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
     if (FS_) return HALP_ERR_UNSUPPORTED;                                                          \
     if (nwaves <= 12)                                                                              \
-      return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);        \
-    return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, grid, block, smem, s);          \
+      return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);        \
+    return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);          \
   }
   HALP_BT(8, 1, true) HALP_BT(8, 2, true) HALP_BT(8, 4, true)
   HALP_BT(16, 1, true) HALP_BT(16, 2, true) HALP_BT(16, 4, true)

@@ -480,3 +480,25 @@ def test_missing_buffers_and_bad_calls_are_errors():
     with pytest.raises(hp.HalpError) as e:
         P.h.bind(X=P.X[:, :, 1:], ldx=16, **P.st)  # misaligned base pointer
     assert e.value.code == hp.ERR_ALIGN
+
+
+def test_minibatch_exchange_wait_is_bounded_and_reported():
+    """Several workgroups per chain wait for each other's sums; told never to wait, the launch
+    must still end, report it in counters[3], and leave the handle usable."""
+    loss, N, d, B, b, T = hp.LOSS_LOGISTIC, 300, 4096, 64, 16, 40
+    seed = 60 + d + B
+    case = _inner_case(loss, N, d, 1, B, b, 1e-5, 1, T, seed, mu=0.05)
+    P = _run_inner(case, loss, 1, B, b, 1e-5, 1, T, seed, 2, mu=0.05)
+    P.h.set_option(hp.OPT_INNER_PARTS, 4)
+    P.h.set_option(hp.OPT_EXCHANGE_SPIN_LIMIT, -1)
+    P.h.inner_loop(3)
+    assert int(P.get("counters")[0, 3]) == 1
+    # with the default limit the same handle gives the oracle's result again
+    P.h.set_option(hp.OPT_EXCHANGE_SPIN_LIMIT, 1 << 20)
+    P.put("w", case["w"]); P.st["z"].zero_()
+    P.h.inner_loop(3)
+    out = _oracle_inner(case, 0, T)
+    assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
+    assert int(P.get("counters")[0, 3]) == 0
+    with pytest.raises(hp.HalpError):
+        P.h.set_option(hp.OPT_EXCHANGE_SPIN_LIMIT, -2)
