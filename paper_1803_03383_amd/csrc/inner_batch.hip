@@ -218,6 +218,20 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       load_chunk(xa, s_idx[0], 0);
     }
 
+    // wave 0: the rounding word of gamma_m and the L2 draw of a step, made a step ahead
+    uint32_t rw_next = 0;
+    int cl_next = 0;
+    auto draw_scalars = [&](int64_t tn) {
+      const uint64_t n = (uint64_t)tn * (uint64_t)B + (uint64_t)min(lane, B - 1);
+      rw_next = pick(stream_block(seed, kGamma, a.epoch, n >> 2), (uint32_t)(n & 3));
+      cl_next = 0;
+      if (use_reg) {
+        const uint32_t rr = pick(stream_block(seed, kReg, a.epoch, (uint64_t)tn >> 2), (uint32_t)(tn & 3));
+        cl_next = (int)quantize_real(al, (double)(1 << BITS), rr, 0.0, (double)QMAX, nullptr);
+      }
+    };
+    if (svc) draw_scalars(0);
+
     auto one_step = [&](int64_t t, uint32_t (&cur)[RPW][NDW], uint32_t (&nxt)[RPW][NDW]) {
       const int* idx = s_idx[t & 3];
       // wave 0: what the scalar stage needs and does not depend on the dots — margins and
@@ -229,14 +243,15 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       if (svc) {
         phi_n = need_phi ? phi[i_next] : 0.f;
         y_n = a.loss == HALP_LOSS_LOGISTIC ? y[i_next] : 0.f;
-        const uint64_t n = (uint64_t)t * (uint64_t)B + (uint64_t)min(lane, B - 1);
-        rw = pick(stream_block(seed, kGamma, a.epoch, n >> 2), (uint32_t)(n & 3));
-        if (use_reg) {
-          const uint32_t rr = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
-          cl_draw = (int)quantize_real(al, (double)(1 << BITS), rr, 0.0, (double)QMAX, nullptr);
-          n_reg += (lane == 0 && cl_draw != 0) ? 1u : 0u;
-        }
-        if (FS) {  // wave 0 is free while the others take the dots: the indices two steps ahead now
+        rw = rw_next;  // drawn during the previous step
+        cl_draw = cl_next;
+        n_reg += (lane == 0 && cl_draw != 0) ? 1u : 0u;
+      }
+      // What wave 0 prepares for later steps: with several workgroups per chain it runs while
+      // the wave waits for the others' sums, else here, while the other waves take the dots.
+      auto prepare_ahead = [&]() {
+        draw_scalars(t + 1);
+        if (FS) {  // the indices two steps ahead (slot (t + 2) % 4 was last read in step t - 2)
           const int i2 = draw_idx(t + 2);
           if (row) s_idx[(t + 2) & 3][lane] = i2;
           i_next = i2;
@@ -255,7 +270,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
               warm[k] = *reinterpret_cast<const uint32_t*>(wp + min(k * 128, slice - 4));
           }
         }
-      }
+      };
+      if (svc && P == 1) prepare_ahead();
       if (worker && (t & 7) == 0) {
         if (kPark) {
 #pragma unroll
@@ -363,6 +379,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           __hip_atomic_store(&xb[part * kMaxB + lane],
                              (tag << 46) | ((unsigned long long)D & ((1ull << 46) - 1ull)), __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
+          prepare_ahead();
           long long tot = D;
           for (int spin = 0; n_timeout == 0; ++spin) {  // after one wait ran out, none is tried again
             bool miss = false;
