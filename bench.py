@@ -18,7 +18,8 @@ same kernel with 2048 chains, eight per CU), and
 `roofline_full_gradient` the gradient pass of the same epochs; both durations
 come from HIP events recorded by the library on the launch stream inside the
 timed region.  `full_gradient_c5` is the gradient pass alone on the 16.4 GB
-logistic configuration (N=1e6, d=4096).  `cpu_baseline` is the oracle timed on
+logistic configuration (N=1e6, d=4096), with the step rate of that configuration's
+minibatch inner loop (B=64, b=16) beside it.  `cpu_baseline` is the oracle timed on
 the host cores on a bounded sample of the same workload.
 """
 import argparse
@@ -169,7 +170,26 @@ def c5_full_gradient(hp, inp, torch, reps=5):
                traffic=measured_traffic("fullgrad_k1", "c5"), read_only_kernel_GBs=ceiling,
                frac_of_read_only_kernel=nbytes / mean / 1e6 / ceiling, loss=h.get_stats(0).loss)
     h.close()
-    del X, y, st
+    # the same configuration's minibatch inner loop (B=64, b=16) at a reduced step count
+    T = 2000
+    delta_d = float(X.abs().max().item()) / 32767.0
+    Xq = torch.zeros((1, N, d), dtype=torch.int16, device="cuda")
+    h = hp.Halp(N, d, loss=hp.LOSS_LOGISTIC, b=16, B=64, T=T, alpha=0.05, mu=0.01, lam=1e-5,
+                delta_d=delta_d, seed=0)
+    h.bind(X=X, Xq=Xq, y=y, **st)
+    h.quantize_data()
+    h.set_option(hp.OPT_TIMING, 1)
+    for k in range(3):
+        h.epoch(k)
+    s = h.get_stats(0)
+    out["inner_loop"] = dict(B=64, b=16, T=T, inner_variant=s.inner_variant, ms=s.ms_inner_loop,
+                             steps_per_s=T / (s.ms_inner_loop * 1e-3),
+                             us_per_step=s.ms_inner_loop / T * 1e3,
+                             row_bytes_per_step=64 * d * 2,
+                             traffic=measured_traffic("inner_batch_kernel", "c5"),
+                             exchange_timeouts=int(st["counters"][:, 3].sum().item()))
+    h.close()
+    del X, y, st, Xq
     torch.cuda.empty_cache()
     return out
 
