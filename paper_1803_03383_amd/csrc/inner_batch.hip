@@ -8,19 +8,21 @@
 // nothing from the others.
 //
 // A thread owns the coordinates of one 4/8/16-byte fragment of a row (CPT of them)
-// with z, h~ and the window's Philox words in registers.  The B rows of a step (B d b/8
-// bytes: 512 KB at B = 64, d = 4096, b = 16 — the size of a CU's register file) cannot stay
-// on chip between the dot products and the update, so they are read twice: once from HBM
-// for the dots, once more (from L2) for the update.
+// with z, h~ and the window's Philox words in registers.  A step:
 //   pass 1   per row: packed integer dot of the fragment with z (v_dot4 at 8 bits; at 16
 //            bits v_dot2 against a low and a high part of z separately, so that
-//            32-bit sums stay exact), DPP fold, one LDS slot per wave and row      | barrier
-//   scalars  wave 0, one row per lane: D_m, beta_m, gamma_m = Q_(delta_s,b)(beta_m) into LDS | barrier
+//            32-bit sums stay exact), eight wave sums at a time, one LDS slot per row | barrier
+//   scalars  wave 0, one row per lane: D_m (with the other workgroups' shares), beta_m,
+//            gamma_m = Q_(delta_s,b)(beta_m) into LDS                               | barrier
 //   pass 2   per row: sum_m gamma_m x_m accumulated per coordinate (gamma split into its
 //            low and high byte at 16 bits), then the rounding of z
 // Wave 0 also draws the indices two steps ahead and gathers the margins and labels of the
-// next step's rows.  Rows travel in chunks of 8 through two register buffers, the next chunk
-// being in flight across passes, steps and barriers (the barriers wait for LDS only).
+// next step's rows.  The barriers wait for LDS only, loads stay in flight across them.
+//
+// Chunked form: the waves of a workgroup sit side by side along the row.  The B rows of a
+// step (512 KB at B = 64, d = 4096, b = 16: a CU's register file) cannot stay on chip, so
+// they travel twice, in chunks of 8 through two register buffers: from HBM for the dots,
+// from L2 for the update.  Full-step form: see the kernel template below.
 #include "halp_device.hpp"
 #include "inner_args.hpp"
 
