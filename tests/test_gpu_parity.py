@@ -349,6 +349,9 @@ BATCH_CASES = [
     (hp.LOSS_LOGISTIC, 500, 256, 8, 16, 1e-5, 1, 300),
     (hp.LOSS_LOGISTIC, 300, 4096, 64, 16, 1e-5, 1, 40),    # the C5 shape: 8 worker waves, 16-byte fragments
     (hp.LOSS_SQUARED, 200, 2048, 33, 16, 0.0, 2, 100),
+    (hp.LOSS_LOGISTIC, 200, 3000, 64, 16, 0.0, 1, 30),     # full-step form on six workgroups, ragged last slice
+    (hp.LOSS_SQUARED, 120, 4096, 64, 8, 1e-3, 1, 25),      # ... on eight, 8-byte fragments, L2 draws
+    (hp.LOSS_SQUARED, 150, 512, 40, 16, 0.0, 3, 60),       # ... one workgroup per chain, rows dealt 16-16-8
     (hp.LOSS_SQUARED, 200, 512, 2, 8, 0.0, 1, 1),
     (hp.LOSS_LOGISTIC, 1, 1, 64, 16, 0.0, 1, 20),          # every row of the batch is the only example
     (hp.LOSS_SQUARED, 5, 3, 3, 8, 1e-2, 2, 25),
