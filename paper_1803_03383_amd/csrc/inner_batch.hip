@@ -201,17 +201,20 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     };
     uint32_t xa[kChunk][NDW], xb[kChunk][NDW];
     auto load_chunk = [&](uint32_t (&dst)[kChunk][NDW], const int* idx, int m0) {
+      const int mine = idx[min(m0 + (lane & (kChunk - 1)), B - 1)];  // lane r: row m0 + r, one LDS read
 #pragma unroll
       for (int r = 0; r < kChunk; ++r)  // the row number is uniform: scalar address arithmetic
-        load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(m0 + r, B - 1)]));
+        load_frag(dst[r], __builtin_amdgcn_readlane(mine, r));
     };
     // FS: the fragments of all rows of this step and of the next one
     constexpr int RPW = FS ? kRowsPerWave : 1;
     uint32_t xc[RPW][NDW], xn[RPW][NDW];
     auto load_step = [&](uint32_t (&dst)[RPW][NDW], const int* idx) {
+      // lane r fetches the index of the wave's row r (one LDS read for all); rows past B
+      // repeat the last one and are not used
+      const int mine = idx[min(row0 + (lane & (RPW - 1)), B - 1)];
 #pragma unroll
-      for (int r = 0; r < RPW; ++r)  // rows past B repeat the last one and are not used
-        load_frag(dst[r], __builtin_amdgcn_readfirstlane(idx[min(row0 + r, B - 1)]));
+      for (int r = 0; r < RPW; ++r) load_frag(dst[r], __builtin_amdgcn_readlane(mine, r));
     };
     __syncthreads();
     if (FS) {
@@ -386,11 +389,17 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           for (int spin = 0; n_timeout == 0; ++spin) {  // after one wait ran out, none is tried again
             bool miss = false;
             tot = 0;
-            for (int p2 = 0; p2 < P; ++p2) {
-              const unsigned long long wd =
-                  __hip_atomic_load(&xb[p2 * kMaxB + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              miss |= (wd >> 46) != tag;
-              tot += (long long)(wd << 18) >> 18;
+            unsigned long long wd[kMaxParts];
+#pragma unroll
+            for (int p2 = 0; p2 < kMaxParts; ++p2)  // all in flight at once; slots past P repeat the last
+              wd[p2] = __hip_atomic_load(&xb[min(p2, P - 1) * kMaxB + lane], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int p2 = 0; p2 < kMaxParts; ++p2) {
+              if (p2 < P) {
+                miss |= (wd[p2] >> 46) != tag;
+                tot += (long long)(wd[p2] << 18) >> 18;
+              }
             }
             if (__ballot(miss) == 0) break;
             if (spin >= spin_limit) {  // only if a workgroup of the chain never ran: give up
@@ -437,9 +446,9 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       for (int k = 0; k < CPT; ++k) acc[k] = acch[k] = 0;
       auto accumulate = [&](uint32_t (&xf)[kChunk][NDW], int m0) {
         int gm[kChunk];
+        const int gmine = s_gam[min(m0 + (lane & (kChunk - 1)), kMaxB - 1)];  // lane r: row m0 + r
 #pragma unroll
-        for (int r = 0; r < kChunk; ++r)
-          gm[r] = m0 + r < B ? __builtin_amdgcn_readfirstlane(s_gam[min(m0 + r, kMaxB - 1)]) : 0;
+        for (int r = 0; r < kChunk; ++r) gm[r] = m0 + r < B ? __builtin_amdgcn_readlane(gmine, r) : 0;
         if (BITS == 16) {
           // Two rows at a time: v_perm puts coordinate j of both rows into one register, one
           // v_dot2 against the pair of gammas then serves both rows.  gamma = 256 gh + gl with
@@ -490,11 +499,20 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         if (worker) {
 #pragma unroll
           for (int k = 0; k < CPT; ++k) {
+            int pa[4], ph[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {  // every group's slot is read (unused ones hold old sums)
+              pa[g] = s_acc[g][k][lane];
+              ph[g] = BITS == 16 ? s_acc[g][CPT + k][lane] : 0;
+            }
             acc[k] = 0;
             acch[k] = 0;
-            for (int g = 0; g < nwk; ++g) {  // the same order in every wave
-              acc[k] += s_acc[g][k][lane];
-              if (BITS == 16) acch[k] += s_acc[g][CPT + k][lane];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {  // the same order in every wave
+              if (g < nwk) {
+                acc[k] += pa[g];
+                acch[k] += ph[g];
+              }
             }
           }
         }
