@@ -116,6 +116,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
   __shared__ int s_gam[kMaxB];               // gamma_m
   __shared__ int s_acc[FS ? 4 : 1][FS ? 2 * CPT : 1][64];  // full-step form: the waves' sums over their rows
   __shared__ int s_cl;                       // c_lambda of the step
+  __shared__ uint32_t s_rw[2][kMaxB];        // full-step form: rounding words of gamma_m and the L2
+  __shared__ int s_cln[2];                   // draw of the next step, made by wave 1 for wave 0
   __shared__ unsigned long long s_cnt[3];
   if (tid < 3) s_cnt[tid] = 0;
   const bool use_reg = a.lambda > 0;
@@ -126,6 +128,10 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
   const bool svc = wave == 0;
   const int wv = wave;        // this wave's place among the nwk waves that hold z
   const bool worker = true;
+  // Full-step form with more than one wave: what can be drawn ahead (the next step's rounding
+  // words, the indices two steps ahead) is drawn by wave 1 while wave 0 runs the scalar stage.
+  const bool helper = FS && nwk > 1 && wave == 1;
+  const bool self_prepare = !(FS && nwk > 1);
   const uint32_t N = (uint32_t)a.N;
   const float* __restrict__ phi = a.phi + (int64_t)chain * a.N;
   const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
@@ -246,10 +252,16 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       uint32_t rw = 0;
       int cl_draw = 0;
       if (svc) {
-        phi_n = need_phi ? phi[i_next] : 0.f;
-        y_n = a.loss == HALP_LOSS_LOGISTIC ? y[i_next] : 0.f;
-        rw = rw_next;  // drawn during the previous step
-        cl_draw = cl_next;
+        const int inx = self_prepare ? i_next : s_idx[(t + 1) & 3][min(lane, B - 1)];
+        phi_n = need_phi ? phi[inx] : 0.f;
+        y_n = a.loss == HALP_LOSS_LOGISTIC ? y[inx] : 0.f;
+        if (self_prepare || t == 0) {  // drawn during the previous step (or before the first)
+          rw = rw_next;
+          cl_draw = cl_next;
+        } else {
+          rw = s_rw[t & 1][lane];
+          cl_draw = s_cln[t & 1];
+        }
         n_reg += (lane == 0 && cl_draw != 0) ? 1u : 0u;
       }
       // What wave 0 prepares for later steps: with several workgroups per chain it runs while
@@ -276,7 +288,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           }
         }
       };
-      if (svc && P == 1) prepare_ahead();
+      if (svc && P == 1 && self_prepare) prepare_ahead();
       if (worker && (t & 7) == 0) {
         if (kPark) {
 #pragma unroll
@@ -364,6 +376,11 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         }
       }
       lds_barrier();  // the partial dots of this step are in LDS
+      if (helper) {
+        prepare_ahead();
+        s_rw[(t + 1) & 1][lane] = rw_next;
+        if (lane == 0) s_cln[(t + 1) & 1] = cl_next;
+      }
       if (svc) {
         long long D = 0;
         for (int w2 = 0; w2 < (FS ? 1 : nwk); ++w2) {
@@ -384,7 +401,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           __hip_atomic_store(&xb[part * kMaxB + lane],
                              (tag << 46) | ((unsigned long long)D & ((1ull << 46) - 1ull)), __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
-          prepare_ahead();
+          if (self_prepare) prepare_ahead();
           long long tot = D;
           for (int spin = 0; n_timeout == 0; ++spin) {  // after one wait ran out, none is tried again
             bool miss = false;
