@@ -79,8 +79,8 @@ __device__ __forceinline__ double logistic_dl(double a, double y) {
 // The price: the waves add up their sums over rows through LDS before the update, which each
 // of them then performs on its own copy of z (same inputs, same result).
 template <int BITS, int NDW, int KT, bool FS>
-__global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk, int P, int R,
-                                                              long long* xbuf, int spin_limit) {
+__global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk, int P, long long* xbuf,
+                                                              int spin_limit) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
   constexpr int EPD = 32 / BITS;       // elements per dword
@@ -88,17 +88,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
   constexpr int CT = 16 / BITS;        // coordinates per strip of 16 rounding bits
   constexpr int UPL = CPT / CT;        // strips per thread (= 2 NDW)
   constexpr int QMAX = (1 << (BITS - 1)) - 1, QMIN = -(1 << (BITS - 1));
-  // P workgroups per chain, nwk waves of z each.  Workgroups go to the eight XCDs in turn, and
-  // the workgroups of a chain trade their sums through memory every step: with P > 1 the grid is
-  // laid out so that all of a chain's workgroups have the same index modulo 8, and with it the
-  // same XCD and L2 (a placement the result does not depend on).
-  int chain = (int)blockIdx.x, part = 0;
-  if (P > 1) {
-    const int q = (int)blockIdx.x >> 3;
-    chain = 8 * (q / P) + ((int)blockIdx.x & 7);
-    part = q % P;
-    if (chain >= R) return;
-  }
+  const int chain = (int)blockIdx.x / P;         // P workgroups per chain, nwk waves of z each
+  const int part = (int)blockIdx.x - chain * P;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -614,14 +605,14 @@ __global__ void batch_split_prepare(long long* xbuf, int nwords, uint64_t* count
 }
 
 template <int BITS, int NDW, int KT, bool FS>
-int launch_kt(const InArgs& a, int nwk, int P, int R, long long* xbuf, int spin_limit, dim3 grid, dim3 block,
+int launch_kt(const InArgs& a, int nwk, int P, long long* xbuf, int spin_limit, dim3 grid, dim3 block,
               size_t smem, hipStream_t s) {
   auto kern = inner_batch_kernel<BITS, NDW, KT, FS>;
   if (smem > 0 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                       hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)smem) != hipSuccess)
     return HALP_ERR_HIP;
-  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk, P, R, xbuf, spin_limit);
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk, P, xbuf, spin_limit);
   return hip_ok(hipGetLastError());
 }
 
@@ -675,16 +666,14 @@ struct BtLaunch {
 static BtLaunch pick_launch(const halp_handle& h, int64_t row_bytes) {
   const halp_params& p = h.p;
   const BtShape sh = pick_shape(p, row_bytes);
-  // the workgroups of a chain share an XCD, which takes every eighth chain
-  const int cus_per_xcd = h.num_cus / 8 > 0 ? h.num_cus / 8 : 1, chains_per_xcd = (p.R + 7) / 8;
   int most = 1;
   if (h.batch_xbuf) {
     most = kBatchMaxParts;
-    while (most > 1 && (int64_t)chains_per_xcd * most > cus_per_xcd) most /= 2;
+    while (most > 1 && (int64_t)p.R * most > h.num_cus) most /= 2;
   }
   int most_any = 1;  // any count up to the exchange buffer's 8 slots
   if (h.batch_xbuf) {
-    most_any = cus_per_xcd / chains_per_xcd;
+    most_any = (int)(h.num_cus / p.R);
     if (most_any > kBatchMaxParts) most_any = kBatchMaxParts;
     if (most_any < 1) most_any = 1;
   }
@@ -721,8 +710,7 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const BtLaunch L = pick_launch(h, h.buf.ldxq * (p.b / 8));
   const int nwk = L.nwk, P = L.P;
   const int nwaves = nwk;
-  // with several workgroups per chain: 8 P workgroups for every 8 chains (see the kernel)
-  const dim3 grid(P > 1 ? 8 * P * ((p.R + 7) / 8) : p.R), block(64 * nwaves);
+  const dim3 grid(p.R * P), block(64 * nwaves);
   if (P > 1) {
     const int nwords = p.R * 2 * kBatchMaxParts * kMaxB, ncnt = p.R * 4;
     hipLaunchKernelGGL(batch_split_prepare, dim3((nwords + 255) / 256), dim3(256), 0, s, h.batch_xbuf, nwords,
@@ -733,13 +721,13 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
 #define HALP_BT(BITS_, NDW_, FS_)                                                                  \
   if (p.b == BITS_ && L.ndw == NDW_ && L.fs == FS_) {                                              \
     if (nwaves <= 4)                                                                               \
-      return launch_kt<BITS_, NDW_, 4, FS_>(a, nwk, P, p.R, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
+      return launch_kt<BITS_, NDW_, 4, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
     if (nwaves <= 8)                                                                               \
-      return launch_kt<BITS_, NDW_, 8, FS_>(a, nwk, P, p.R, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
+      return launch_kt<BITS_, NDW_, 8, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
     if (FS_) return HALP_ERR_UNSUPPORTED;                                                          \
     if (nwaves <= 12)                                                                              \
-      return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, p.R, h.batch_xbuf, h.spin_limit, grid, block, smem, s);        \
-    return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, p.R, h.batch_xbuf, h.spin_limit, grid, block, smem, s);          \
+      return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);        \
+    return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);          \
   }
   HALP_BT(8, 1, true) HALP_BT(8, 2, true) HALP_BT(8, 4, true)
   HALP_BT(16, 1, true) HALP_BT(16, 2, true) HALP_BT(16, 4, true)
