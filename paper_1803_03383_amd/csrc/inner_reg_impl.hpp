@@ -202,6 +202,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   }
 
   unsigned int n_zclamp = 0, n_gclamp = 0, n_reg = 0;
+  unsigned int n_zclamp_wave = 0;  // the same count kept for the whole wave (uniform)
   U4 zr[UPL];  // the strips' rounding blocks for the current window
 
   // One window of 8 steps starting at t0 (a multiple of 8).  FULL: all 8 steps
@@ -348,7 +349,12 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
             zu = z[k] + (v >> 16) - (hv[k] >> 16);
           }
           const int zc = min(max(zu, QMIN), QMAX);
-          if (COUNT) n_zclamp += (zu != zc) ? 1u : 0u;
+          if (COUNT) {
+            // one wave per chain is the shape of many chains per SIMD, where a count on the
+            // scalar unit (lanes of the compare's mask) frees a vector issue slot
+            if (NWT == 1) n_zclamp_wave += (unsigned int)__builtin_popcountll(__ballot(zu != zc));
+            else n_zclamp += (zu != zc) ? 1u : 0u;
+          }
           z[k] = zc;
         }
       }
@@ -405,6 +411,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     }
   }
   if (COUNT && n_zclamp) atomicAdd(&s_cnt[0], (unsigned long long)n_zclamp);
+  if (COUNT && lane == 0 && n_zclamp_wave) atomicAdd(&s_cnt[0], (unsigned long long)n_zclamp_wave);
   if (tid == 0) {
     s_cnt[1] = n_gclamp;  // gamma is uniform over the workgroup: count it once
     s_cnt[2] = n_reg;
