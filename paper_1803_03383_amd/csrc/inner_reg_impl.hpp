@@ -47,6 +47,8 @@ __device__ __forceinline__ int mad24(int a, int b, int c) {
   return r;
 }
 
+typedef short short2r __attribute__((ext_vector_type(2)));  // the two coordinates of an 8-bit strip
+
 // squared loss whose step needs the margin phi_i of w~ (LP-SVRG); a value apart from HALP_LOSS_*
 constexpr int kLossSquaredWithMargins = 3;
 
@@ -121,6 +123,30 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     hv[k] = ok ? (BITS == 8 ? -(int)hg[j] : (int)hg[j]) : 0;
     if (ok) xmask[(k * BITS) / 32] |= (BITS == 8 ? 0xFFu : 0xFFFFu) << ((k * BITS) % 32);
   }
+
+  // 8 bits: between windows z lives packed, the two coordinates of a strip as the 16-bit
+  // halves of one register, next to -h~ = 256 hh + hl cut the same way (0 <= hl < 256).
+  // Windows without an L2 draw run on these with packed 16-bit arithmetic.
+  short2r zp[UPL], hlp[UPL], hhp[UPL];
+#pragma unroll
+  for (int u = 0; u < UPL; ++u) {
+    const int k0 = BITS == 8 ? 2 * u : 0, k1 = BITS == 8 ? 2 * u + 1 : 0;
+    zp[u] = short2r{(short)z[k0], (short)z[k1]};
+    hlp[u] = short2r{(short)(hv[k0] & 0xFF), (short)(hv[k1] & 0xFF)};
+    hhp[u] = short2r{(short)(hv[k0] >> 8), (short)(hv[k1] >> 8)};
+  }
+  auto unpack_z = [&]() {
+    if (BITS == 8) {
+#pragma unroll
+      for (int k = 0; k < CPL; ++k) z[k] = (int)zp[(k / 2) % UPL][k % 2];
+    }
+  };
+  auto pack_z = [&]() {
+    if (BITS == 8) {
+#pragma unroll
+      for (int u = 0; u < UPL; ++u) zp[u] = short2r{(short)z[(2 * u) % CPL], (short)z[(2 * u + 1) % CPL]};
+    }
+  };
 
   // ---- draws that depend on the step number only, 256 steps per batch
   auto fill_batch = [&](int64_t bb) {
@@ -211,6 +237,11 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
                     uint32_t (&xr)[kWin][NDW], uint32_t (&xnext)[kWin][NDW]) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr bool REGW = decltype(reg_tag)::value;  // some step of the window has c_lambda != 0
+    // Packed arithmetic on zp: fewer instructions per strip but a longer dependent chain, so
+    // it is for one wave per chain, the shape of many chains per SIMD, where issue slots are
+    // what runs out; several waves per chain wait on the chain and keep the scalar form.
+    constexpr bool PK = BITS == 8 && !REGW && NWT == 1;
+    if (!PK) unpack_z();
     const int base = (int)(t0 & kMask);  // multiple of 8: the window is contiguous in LDS
     // draws of this window and the row indices of the next one, in a few wide LDS reads
     double rho[kWin];
@@ -269,13 +300,25 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
       if (FULL || t < T) {
         // low-precision dot product x_i^T z
         int xe[CPL];
+        short2r xp[UPL];
         int part = 0, part_hi = 0;
+        if (PK) {
+          // the strip's two bytes go to the high bytes of the two halves and are shifted back
+          // down with their signs; one packed dot per strip
 #pragma unroll
-        for (int k = 0; k < CPL; ++k) {
-          const uint32_t xv = xw[s][(k * BITS) / 32];
-          const int sh = (k * BITS) % 32;
-          xe[k] = BITS == 8 ? (int)(int8_t)(xv >> sh) : (int)(int16_t)(xv >> sh);
-          if (BITS == 8) part = mad24(xe[k], z[k], part);
+          for (int u = 0; u < UPL; ++u) {
+            const uint32_t up = __builtin_amdgcn_perm(0u, xw[s][u / 2], (u & 1) ? 0x030C020Cu : 0x010C000Cu);
+            xp[u] = __builtin_bit_cast(short2r, up) >> (short2r)(8);
+            part = __builtin_amdgcn_sdot2(xp[u], zp[u], part, false);
+          }
+        } else {
+#pragma unroll
+          for (int k = 0; k < CPL; ++k) {
+            const uint32_t xv = xw[s][(k * BITS) / 32];
+            const int sh = (k * BITS) % 32;
+            xe[k] = BITS == 8 ? (int)(int8_t)(xv >> sh) : (int)(int16_t)(xv >> sh);
+            if (BITS == 8) part = mad24(xe[k], z[k], part);
+          }
         }
         AccT D;
         if (BITS == 8) {
@@ -330,8 +373,35 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
           n_reg += cl != 0 ? 1u : 0u;
         }
         // u = z - gamma x - h~ (- c_lambda z), z = Q_(delta_m, b)(u)
+        if (PK) {
+          // per half: floor((-gamma x + r + hl) / 256) + hh + z.  |gamma x| <= 128 * 128 and
+          // r + hl < 512, so the numerator fits 16 bits, and so does the sum that is clamped.
+          const short2r ngp = short2r{(short)ng, (short)ng};
+          short2r zu[UPL];
+          uint32_t moved = 0;  // bits in which some clamp changed a value
 #pragma unroll
-        for (int k = 0; k < CPL; ++k) {
+          for (int u = 0; u < UPL; ++u) {
+            const uint32_t word = pick(zr[u], (uint32_t)(s >> 1));
+            const uint32_t rp = __builtin_amdgcn_perm(0u, word, (s & 1) ? 0x0C030C02u : 0x0C010C00u);
+            short2r v = xp[u] * ngp + (__builtin_bit_cast(short2r, rp) + hlp[u]);
+            v = (v >> (short2r)(8)) + hhp[u] + zp[u];
+            const short2r zc = __builtin_elementwise_min(__builtin_elementwise_max(v, (short2r)(QMIN)),
+                                                         (short2r)(QMAX));
+            moved |= __builtin_bit_cast(uint32_t, v) ^ __builtin_bit_cast(uint32_t, zc);
+            zu[u] = v;
+            zp[u] = zc;
+          }
+          if (COUNT && __ballot(moved != 0) != 0) {  // rare: count the clamped coordinates exactly
+#pragma unroll
+            for (int u = 0; u < UPL; ++u) {
+              const uint32_t df = __builtin_bit_cast(uint32_t, zu[u]) ^ __builtin_bit_cast(uint32_t, zp[u]);
+              n_zclamp_wave += (unsigned int)__builtin_popcountll(__ballot((df & 0xFFFFu) != 0)) +
+                               (unsigned int)__builtin_popcountll(__ballot((df >> 16) != 0));
+            }
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < (PK ? 0 : CPL); ++k) {
           const uint32_t word = pick(zr[k / CT], (uint32_t)(s >> 1));
           const int sh = 16 * (s & 1) + (k % CT) * BITS;
           const int re = (int)((word >> sh) & (BITS == 8 ? 0xFFu : 0xFFFFu));
@@ -359,6 +429,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
         }
       }
     }
+    if (!PK) pack_z();
   };
 
   int64_t t0 = 0;
@@ -401,6 +472,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   }
 
   // ---- w~ <- w~ + delta_m z (option I); hand z out
+  unpack_z();
 #pragma unroll
   for (int k = 0; k < CPL; ++k) {
     const int j = j0 + k;
