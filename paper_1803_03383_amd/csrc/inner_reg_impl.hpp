@@ -384,7 +384,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
             const uint32_t word = pick(zr[u], (uint32_t)(s >> 1));
             const uint32_t rp = __builtin_amdgcn_perm(0u, word, (s & 1) ? 0x0C030C02u : 0x0C010C00u);
             short2r v = xp[u] * ngp + (__builtin_bit_cast(short2r, rp) + hlp[u]);
-            v = (v >> (short2r)(8)) + hhp[u] + zp[u];
+            v = (v >> (short2r)(8)) + (hhp[u] + zp[u]);  // the sum in brackets does not wait for gamma
             const short2r zc = __builtin_elementwise_min(__builtin_elementwise_max(v, (short2r)(QMIN)),
                                                          (short2r)(QMAX));
             moved |= __builtin_bit_cast(uint32_t, v) ^ __builtin_bit_cast(uint32_t, zc);
