@@ -158,6 +158,12 @@ typedef struct {
                                     normally with counters[3] = 1 and an invalid result: for
                                     tests of that path                                    */
 
+#define HALP_OPT_INNER_PACKED 9  /* register-resident inner loop at 8 bits with one wave per chain:
+                                    the form that updates the two coordinates of a strip as packed
+                                    16-bit halves.  0 (default): taken when every SIMD holds two
+                                    chains or more; 1: wherever that shape is launched; 2: never.
+                                    Results do not depend on it                                */
+
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */
 int halp_create(halp_handle** out, const halp_params* p);

@@ -254,6 +254,10 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
       if (value != 0 && value != 1) return HALP_ERR_INVALID;
       h->option2 = value != 0;
       return HALP_OK;
+    case HALP_OPT_INNER_PACKED:
+      if (value < 0 || value > 2) return HALP_ERR_INVALID;
+      h->inner_packed = (int)value;
+      return HALP_OK;
     case HALP_OPT_INNER_WAVES:
       if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return HALP_ERR_INVALID;

@@ -5,7 +5,7 @@
 
 namespace halp {
 
-int launch_inner_reg_b8(const InArgs& a, int nw, int upl, int R, hipStream_t s);
+int launch_inner_reg_b8(const InArgs& a, int nw, int upl, int R, bool packed, hipStream_t s);
 int launch_inner_reg_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
 
 namespace {
@@ -81,7 +81,11 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
     sh.upl /= 2;
   }
   if (!launchable(sh)) return HALP_ERR_UNSUPPORTED;
-  return p.b == 8 ? launch_inner_reg_b8(a, sh.nw, sh.upl, p.R, s)
+  // 8 bits, one wave per chain: the packed form once every SIMD holds two chains or more (its
+  // steps issue fewer instructions but take longer alone), or as HALP_OPT_INNER_PACKED says
+  const bool many = (int64_t)p.R >= 8 * (int64_t)h.num_cus;
+  const bool packed = p.b == 8 && sh.nw == 1 && (h.inner_packed == 1 || (h.inner_packed == 0 && many));
+  return p.b == 8 ? launch_inner_reg_b8(a, sh.nw, sh.upl, p.R, packed, s)
                   : launch_inner_reg_b16(a, sh.nw, sh.upl, p.R, s);
 }
 

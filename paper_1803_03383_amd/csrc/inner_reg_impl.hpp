@@ -52,8 +52,10 @@ typedef short short2r __attribute__((ext_vector_type(2)));  // the two coordinat
 // squared loss whose step needs the margin phi_i of w~ (LP-SVRG); a value apart from HALP_LOSS_*
 constexpr int kLossSquaredWithMargins = 3;
 
-template <int BITS, int LOSS, int UPL, int NWT>
+// PKF: the 8-bit strips are updated as packed 16-bit halves (one wave per chain only).
+template <int BITS, int LOSS, int UPL, int NWT, bool PKF = false>
 __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
+  static_assert(!PKF || (BITS == 8 && NWT == 1), "the packed form is built for 8 bits, one wave per chain");
   constexpr bool COUNT = true;  // clamped coordinates are always counted
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     if (ok) xmask[(k * BITS) / 32] |= (BITS == 8 ? 0xFFu : 0xFFFFu) << ((k * BITS) % 32);
   }
 
-  // 8 bits: between windows z lives packed, the two coordinates of a strip as the 16-bit
+  // Packed form: between windows z lives packed, the two coordinates of a strip as the 16-bit
   // halves of one register, next to -h~ = 256 hh + hl cut the same way (0 <= hl < 256).
   // Windows without an L2 draw run on these with packed 16-bit arithmetic.
   short2r zp[UPL], hlp[UPL], hhp[UPL];
@@ -136,13 +138,13 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
     hhp[u] = short2r{(short)(hv[k0] >> 8), (short)(hv[k1] >> 8)};
   }
   auto unpack_z = [&]() {
-    if (BITS == 8) {
+    if (PKF) {
 #pragma unroll
       for (int k = 0; k < CPL; ++k) z[k] = (int)zp[(k / 2) % UPL][k % 2];
     }
   };
   auto pack_z = [&]() {
-    if (BITS == 8) {
+    if (PKF) {
 #pragma unroll
       for (int u = 0; u < UPL; ++u) zp[u] = short2r{(short)z[(2 * u) % CPL], (short)z[(2 * u + 1) % CPL]};
     }
@@ -237,10 +239,10 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
                     uint32_t (&xr)[kWin][NDW], uint32_t (&xnext)[kWin][NDW]) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr bool REGW = decltype(reg_tag)::value;  // some step of the window has c_lambda != 0
-    // Packed arithmetic on zp: fewer instructions per strip but a longer dependent chain, so
-    // it is for one wave per chain, the shape of many chains per SIMD, where issue slots are
-    // what runs out; several waves per chain wait on the chain and keep the scalar form.
-    constexpr bool PK = BITS == 8 && !REGW && NWT == 1;
+    // Packed arithmetic on zp: fewer instructions per strip but a longer dependent chain and a
+    // branch per step, so it is for many chains per SIMD, where issue slots are what runs out;
+    // chains that wait on their own dependent chain keep the scalar form.
+    constexpr bool PK = PKF && !REGW;
     if (!PK) unpack_z();
     const int base = (int)(t0 & kMask);  // multiple of 8: the window is contiguous in LDS
     // draws of this window and the row indices of the next one, in a few wide LDS reads
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
           if (COUNT) {
             // one wave per chain is the shape of many chains per SIMD, where a count on the
             // scalar unit (lanes of the compare's mask) frees a vector issue slot
-            if (NWT == 1) n_zclamp_wave += (unsigned int)__builtin_popcountll(__ballot(zu != zc));
+            if (PKF) n_zclamp_wave += (unsigned int)__builtin_popcountll(__ballot(zu != zc));
             else n_zclamp += (zu != zc) ? 1u : 0u;
           }
           z[k] = zc;
@@ -493,8 +495,19 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
 }
 
 template <int BITS, int UPL, int NWT>
-int launch_one(const InArgs& a, int R, hipStream_t s) {
+int launch_one(const InArgs& a, int R, bool packed, hipStream_t s) {
   const dim3 grid(R), block(64 * NWT);
+  if constexpr (BITS == 8 && NWT == 1) {
+    if (packed) {
+      if (a.loss == HALP_LOSS_SQUARED && a.lp)
+        hipLaunchKernelGGL((inner_reg_kernel<BITS, kLossSquaredWithMargins, UPL, NWT, true>), grid, block, 0, s, a);
+      else if (a.loss == HALP_LOSS_SQUARED)
+        hipLaunchKernelGGL((inner_reg_kernel<BITS, HALP_LOSS_SQUARED, UPL, NWT, true>), grid, block, 0, s, a);
+      else
+        hipLaunchKernelGGL((inner_reg_kernel<BITS, HALP_LOSS_LOGISTIC, UPL, NWT, true>), grid, block, 0, s, a);
+      return hip_ok(hipGetLastError());
+    }
+  }
   if (a.loss == HALP_LOSS_SQUARED && a.lp)
     hipLaunchKernelGGL((inner_reg_kernel<BITS, kLossSquaredWithMargins, UPL, NWT>), grid, block, 0, s, a);
   else if (a.loss == HALP_LOSS_SQUARED)
@@ -506,9 +519,9 @@ int launch_one(const InArgs& a, int R, hipStream_t s) {
 
 // every (strips per lane, waves per chain) pair the library launches
 template <int BITS>
-int launch_bits(const InArgs& a, int nw, int upl, int R, hipStream_t s) {
+int launch_bits(const InArgs& a, int nw, int upl, int R, bool packed, hipStream_t s) {
 #define HALP_CASE(U_, W_) \
-  if (upl == U_ && nw == W_) return launch_one<BITS, U_, W_>(a, R, s);
+  if (upl == U_ && nw == W_) return launch_one<BITS, U_, W_>(a, R, packed, s);
   HALP_CASE(1, 1) HALP_CASE(2, 1) HALP_CASE(4, 1) HALP_CASE(8, 1)
   HALP_CASE(1, 2) HALP_CASE(2, 2) HALP_CASE(4, 2) HALP_CASE(8, 2)
   HALP_CASE(1, 4) HALP_CASE(2, 4) HALP_CASE(4, 4) HALP_CASE(8, 4)

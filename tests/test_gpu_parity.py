@@ -272,6 +272,65 @@ def test_inner_loop_bit_exact(loss, N, d, b, lam, R, T, mu, variant, waves):
         assert cnt[0, 0] > 0  # the saturating case really saturates
 
 
+@pytest.mark.parametrize("loss,N,d,b,lam,R,T,mu", [c for c in INNER_REG_CASES if c[3] == 8 and c[2] <= 1024])
+def test_inner_loop_packed_form_bit_exact(loss, N, d, b, lam, R, T, mu):
+    """The 8-bit form on packed 16-bit halves (the library's choice only when chains are many),
+    forced on the same cases: one wave per chain, 1 to 8 strips per lane, L2 draws, saturation."""
+    seed = 40 + d + T
+    case = _inner_case(loss, N, d, 1, 1, b, lam, R, T, seed, mu=mu)
+    P = _run_inner(case, loss, 1, 1, b, lam, R, T, seed, 2, mu=mu)
+    P.h.set_option(hp.OPT_INNER_WAVES, 1)
+    P.h.set_option(hp.OPT_INNER_PACKED, 1)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    for r in range(R):
+        out = _oracle_inner(case, r, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        assert np.array_equal(w[r], ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r]))
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    if mu > 100:
+        assert cnt[0, 0] > 0
+    for bad in (-1, 3):
+        with pytest.raises(hp.HalpError) as e:
+            P.h.set_option(hp.OPT_INNER_PACKED, bad)
+        assert e.value.code == hp.ERR_INVALID
+
+
+def test_many_chains_take_the_packed_form_by_themselves():
+    """2048 chains over shared data (every SIMD holds two): the default launch and the one with
+    the packed form switched off agree bit for bit, and sampled chains match the oracle."""
+    N, d, b, T, R, seed = 256, 512, 8, 203, 2048, 77
+    X, y, _ = inp.linreg(N, d, seed=5, x_var="inv_d")
+    dd = inp.default_delta_d(X, b)
+    Xq = ref.quantize_data(X, dd, b)
+    rng = np.random.default_rng(2)
+    w1 = (0.05 * rng.standard_normal((1, d))).astype(np.float32)
+    probs = [ref.make_problem(N, d, b=b, alpha=0.02, mu=0.05, delta_d=dd, seed=seed + r) for r in range(R)]
+    phi, g, _ = ref.full_gradient(probs[0], X, y, w1)   # the same for every chain
+    phi, g = phi.astype(np.float32), g.astype(np.float32)
+    rec = [ref.recenter(pr, g, 1) for pr in probs]       # h~ differs: its rounding is the chain's
+    res = []
+    for packed in (0, 2):
+        P = GpuProblem(X, Xq, y, R=R, b=b, T=T, alpha=0.02, mu=0.05, delta_d=dd, seed=seed, share_data=True,
+                       w0=np.repeat(w1[None], R, axis=0))
+        P.put("phi", np.repeat(phi.reshape(1, -1), R, axis=0))
+        P.put("h", np.stack([h for _, h, _ in rec]))
+        P.put("scales", np.stack([s for s, _, _ in rec]))
+        P.st["z"].zero_()
+        P.h.set_option(hp.OPT_INNER_PACKED, packed)
+        P.h.inner_loop(1)
+        res.append({k: P.get(k).copy() for k in ("z", "w", "counters")})
+    a, c = res
+    assert np.array_equal(a["z"], c["z"]) and np.array_equal(a["w"], c["w"])
+    assert np.array_equal(a["counters"], c["counters"])
+    for r in (0, 1, 1023, 2047):
+        s_ref, h_ref, _ = rec[r]
+        out = ref.inner_loop(probs[r], Xq, phi, y, h_ref, s_ref, 1, T)
+        assert np.array_equal(a["z"][r].astype(np.int32), out["z"]), f"chain {r}"
+        assert np.array_equal(a["counters"][r].astype(np.uint64), out["counters"])
+    assert len({a["z"][r].tobytes() for r in (0, 1, 1023, 2047)}) == 4   # the chains do differ
+
+
 _ORACLE_CACHE = {}
 
 
