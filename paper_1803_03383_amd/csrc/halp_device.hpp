@@ -117,6 +117,17 @@ __device__ __forceinline__ int wave_sum_i32(int v) {
   return __builtin_amdgcn_readlane(v, 63);
 }
 
+// the same fold without the read-out: lane 63 holds the sum, the other lanes partial sums
+__device__ __forceinline__ int wave_fold_i32(int v) {
+  v += dpp_quad_swap1(v);
+  v += dpp_quad_swap2(v);
+  v += dpp_half_mirror(v);
+  v += dpp_row_mirror(v);
+  v += dpp_bcast15(v);
+  v += dpp_bcast31(v);
+  return v;
+}
+
 __device__ __forceinline__ float wave_sum_f32(float v) {
   v += dpp_quad_swap1(v);
   v += dpp_quad_swap2(v);

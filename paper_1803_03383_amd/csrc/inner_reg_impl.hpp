@@ -98,6 +98,10 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   __shared__ __attribute__((aligned(16))) float s_y[2 * kBatch];    // of the sampled rows
   __shared__ __attribute__((aligned(16))) AccT s_part[2][16];
   __shared__ unsigned long long s_cnt[3];
+  __shared__ int s_dump[NWT > 1 ? 64 * NWT : 1];  // where lanes 0..62 of a wave put their partial folds
+  using LdsInt = __attribute__((address_space(3))) int;
+  LdsInt* const slot0 = (LdsInt*)((NWT > 1 && lane != 63) ? &s_dump[tid] : reinterpret_cast<int*>(&s_part[0][wave]));
+  LdsInt* const slot1 = (LdsInt*)((NWT > 1 && lane != 63) ? &s_dump[tid] : reinterpret_cast<int*>(&s_part[1][wave]));
 
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
@@ -323,7 +327,11 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
           }
         }
         AccT D;
-        if (BITS == 8) {
+        if (BITS == 8 && NWT > 1) {
+          // the fold leaves the wave's sum in lane 63, which hands it to the other waves itself
+          // (see below): no lane read, no scalar register on the way
+          D = (AccT)wave_fold_i32(part);
+        } else if (BITS == 8) {
           D = (AccT)wave_sum_i32(part);
         } else {
           // 16 bits: a product of two 16-bit factors, or the sum of two, fits 32 bits.  Each is
@@ -346,7 +354,11 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
           D = (AccT)(((long long)hi << 16) + (long long)lo);
         }
         if (NWT > 1) {
-          if (lane == 0) s_part[s & 1][wave] = D;
+          // every lane stores, so no lane mask is set up: at 8 bits lane 63 (the holder of the
+          // sum) into the wave's slot and the others into a dump row, at 16 bits all the same
+          // value into the slot
+          if (BITS == 8) *((s & 1) ? slot1 : slot0) = (int)D;
+          else s_part[s & 1][wave] = D;
           __syncthreads();
           AccT tot = 0;
 #pragma unroll
