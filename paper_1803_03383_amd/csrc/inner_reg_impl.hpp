@@ -98,10 +98,10 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
   __shared__ __attribute__((aligned(16))) float s_y[2 * kBatch];    // of the sampled rows
   __shared__ __attribute__((aligned(16))) AccT s_part[2][16];
   __shared__ unsigned long long s_cnt[3];
-  __shared__ int s_dump[NWT > 1 ? 64 * NWT : 1];  // where lanes 0..62 of a wave put their partial folds
-  using LdsInt = __attribute__((address_space(3))) int;
-  LdsInt* const slot0 = (LdsInt*)((NWT > 1 && lane != 63) ? &s_dump[tid] : reinterpret_cast<int*>(&s_part[0][wave]));
-  LdsInt* const slot1 = (LdsInt*)((NWT > 1 && lane != 63) ? &s_dump[tid] : reinterpret_cast<int*>(&s_part[1][wave]));
+  __shared__ AccT s_dump[NWT > 1 ? 64 * NWT : 1];  // where lanes 0..62 of a wave put their partial folds
+  using LdsAcc = __attribute__((address_space(3))) AccT;
+  LdsAcc* const slot0 = (LdsAcc*)((NWT > 1 && lane != 63) ? &s_dump[tid] : &s_part[0][wave]);
+  LdsAcc* const slot1 = (LdsAcc*)((NWT > 1 && lane != 63) ? &s_dump[tid] : &s_part[1][wave]);
 
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
         AccT D;
         if (BITS == 8 && NWT > 1) {
           // the fold leaves the wave's sum in lane 63, which hands it to the other waves itself
-          // (see below): no lane read, no scalar register on the way
+          // (see below): no lane read, no scalar register on the way (the same at 16 bits)
           D = (AccT)wave_fold_i32(part);
         } else if (BITS == 8) {
           D = (AccT)wave_sum_i32(part);
@@ -350,20 +350,24 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
               part_hi += p >> 16;
             }
           }
-          const int lo = wave_sum_i32(part), hi = wave_sum_i32(part_hi);
+          const int lo = NWT > 1 ? wave_fold_i32(part) : wave_sum_i32(part);
+          const int hi = NWT > 1 ? wave_fold_i32(part_hi) : wave_sum_i32(part_hi);
           D = (AccT)(((long long)hi << 16) + (long long)lo);
         }
         if (NWT > 1) {
-          // every lane stores, so no lane mask is set up: at 8 bits lane 63 (the holder of the
-          // sum) into the wave's slot and the others into a dump row, at 16 bits all the same
-          // value into the slot
-          if (BITS == 8) *((s & 1) ? slot1 : slot0) = (int)D;
-          else s_part[s & 1][wave] = D;
+          // every lane stores, so no lane mask is set up: lane 63 (the holder of the sum) into
+          // the wave's slot, the others into a dump row
+          *((s & 1) ? slot1 : slot0) = D;
           __syncthreads();
-          AccT tot = 0;
+          AccT q[NWT];
 #pragma unroll
-          for (int w2 = 0; w2 < NWT; ++w2) tot += s_part[s & 1][w2];
-          D = tot;
+          for (int w2 = 0; w2 < NWT; ++w2) q[w2] = s_part[s & 1][w2];
+#pragma unroll
+          for (int w = NWT / 2; w >= 1; w /= 2) {  // pairwise: two levels of adds for four waves
+#pragma unroll
+            for (int k = 0; k < w; ++k) q[k] += q[k + w];
+          }
+          D = q[0];
         }
         // beta = alpha (l'(phi_i + x_i^T z) - l'(phi_i)), gamma = Q_(delta_s, b)(beta)
         const double delta = __dmul_rn(dscale, (double)D);
