@@ -155,6 +155,21 @@ __device__ __forceinline__ long long wave_sum_i64(long long v) {
   return (long long)(((uint64_t)hi << 32) | lo);
 }
 
+// exact 64-bit fold without the read-out: lane 63 holds the sum
+__device__ __forceinline__ long long wave_fold_i64(long long v) {
+  auto step = [](long long x, auto mv) {
+    const int lo = mv((int)(uint32_t)x), hi = mv((int)(x >> 32));
+    return x + (long long)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+  };
+  v = step(v, [](int t) { return dpp_quad_swap1(t); });
+  v = step(v, [](int t) { return dpp_quad_swap2(t); });
+  v = step(v, [](int t) { return dpp_half_mirror(t); });
+  v = step(v, [](int t) { return dpp_row_mirror(t); });
+  v = step(v, [](int t) { return dpp_bcast15(t); });
+  v = step(v, [](int t) { return dpp_bcast31(t); });
+  return v;
+}
+
 // ---- exp of the inner loop's scalar path -----------------------------------------
 // l'(phi + x^T z) - l'(phi) is rounded to the integer gamma (Algorithm 4), so the last bit of
 // exp can decide an integer.  The library fixes exp as this sequence of correctly rounded

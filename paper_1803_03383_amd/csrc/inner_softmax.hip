@@ -111,6 +111,7 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   __shared__ int s_creg[2][kWin];                                        // c_lambda
   __shared__ __attribute__((aligned(16))) AccT s_D[2][kKC];              // x_i^T z_c
   __shared__ int s_ng[2][kKC];                                           // -gamma_c
+  __shared__ AccT s_dumpD[64];  // partial folds of lanes 0..62 of every class wave (never read)
   __shared__ unsigned long long s_cnt[3];
   // [2][kWin][row_dw] staged rows (coordinates past d staged as zeros), 32 bytes of zeros that
   // the lanes past the row read instead, then the parked Philox blocks: [word][slot][active
@@ -276,6 +277,9 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     const int half_sh = (UPL == 1 && lane_ok) ? ((s0 * 2) & 2) * 8 : 0;
     const uint32_t strip0 = (uint32_t)(cls * U + s0);
     const int pidx = cls * NACT + lane;  // slot of this lane's parked blocks (lanes on the row only)
+    using LdsAcc = __attribute__((address_space(3))) AccT;
+    LdsAcc* const slotD0 = (LdsAcc*)(lane == 63 ? &s_D[0][cls] : &s_dumpD[lane]);
+    LdsAcc* const slotD1 = (LdsAcc*)(lane == 63 ? &s_D[1][cls] : &s_dumpD[lane]);
     const uint4* park = reinterpret_cast<const uint4*>(s_park);
 
     uint32_t zrw[4][UPL];  // the window's rounding words: [word of the block][strip]
@@ -349,10 +353,12 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
                 part += (AccT)mad24(x_of(k), z[k], mad24(x_of(k + 1), z[k + 1], 0));
             }
           }
+          // the fold leaves the sum in lane 63, which stores it; the other lanes store their
+          // partial folds into a dump row, so that no lane mask is set up and no lane is read
           AccT D;
-          if (BITS == 8) D = (AccT)wave_sum_i32((int)part);
-          else D = (AccT)wave_sum_i64((long long)part);
-          if (lane == 0) s_D[s & 1][cls] = D;
+          if (BITS == 8) D = (AccT)wave_fold_i32((int)part);
+          else D = (AccT)wave_fold_i64((long long)part);
+          *((s & 1) ? slotD1 : slotD0) = D;
           __syncthreads();
           // While the service wave evaluates the softmax: the part of the update that does
           // not need gamma, and the Philox blocks of the next window.
@@ -386,7 +392,7 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
           }
           __builtin_amdgcn_sched_barrier(0);
           __syncthreads();
-          const int ng = __builtin_amdgcn_readfirstlane(s_ng[s & 1][cls]);
+          const int ng = s_ng[s & 1][cls];
           const int cl = use_reg ? __builtin_amdgcn_readfirstlane(s_creg[buf][s]) : 0;
           // u = z - gamma x - h~ (- c_lambda z), z = Q_(delta_m, b)(u)
           auto update = [&](auto with_l2) {
