@@ -138,6 +138,16 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+__device__ __forceinline__ float wave_fold_f32(float v) {  // lane 63 holds the sum
+  v += dpp_quad_swap1(v);
+  v += dpp_quad_swap2(v);
+  v += dpp_half_mirror(v);
+  v += dpp_row_mirror(v);
+  v += dpp_bcast15(v);
+  v += dpp_bcast31(v);
+  return v;
+}
+
 __device__ __forceinline__ long long wave_sum_i64(long long v) {
   // exact 64-bit sum: move both halves with the same DPP pattern, add as a pair
   auto step = [](long long x, auto mv) {

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(64 * NWT) void inner_svrg_kernel(SvArgs a) {
   const int chain = blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = NWT > 1 ? tid >> 6 : 0;
   const int d = a.d;
   const uint32_t N = (uint32_t)a.N;
   const int64_t T = epoch_steps(a.seed + (uint64_t)blockIdx.x, a.epoch, a.T, a.option2);
@@ -61,6 +61,10 @@ __global__ __launch_bounds__(64 * NWT) void inner_svrg_kernel(SvArgs a) {
   __shared__ __attribute__((aligned(16))) float s_phi[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_y[2 * kBatch];
   __shared__ float s_part[2][16];
+  __shared__ float s_dump[NWT > 1 ? 64 * NWT : 1];
+  using LdsF = __attribute__((address_space(3))) float;
+  LdsF* const slot0 = (LdsF*)((NWT > 1 && lane != 63) ? &s_dump[tid] : &s_part[0][wave]);
+  LdsF* const slot1 = (LdsF*)((NWT > 1 && lane != 63) ? &s_dump[tid] : &s_part[1][wave]);
 
   // ---- per-thread state; coordinates past d hold zeros and never change
   const int j0 = tid * CPL;
@@ -160,9 +164,11 @@ __global__ __launch_bounds__(64 * NWT) void inner_svrg_kernel(SvArgs a) {
         float part = 0.f;
 #pragma unroll
         for (int k = 0; k < CPL; ++k) part = __builtin_fmaf(xw[s][k], w[k], part);
-        float dot = wave_sum_f32(part);
+        // several waves: lane 63, where the fold leaves the sum, stores it; the other lanes store
+        // into a dump row, so that no lane mask is set up and no lane is read
+        float dot = NWT > 1 ? wave_fold_f32(part) : wave_sum_f32(part);
         if (NWT > 1) {
-          if (lane == 0) s_part[s & 1][wave] = dot;
+          *((s & 1) ? slot1 : slot0) = dot;
           __syncthreads();
           float tot = 0.f;
 #pragma unroll
