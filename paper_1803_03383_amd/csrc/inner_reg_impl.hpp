@@ -382,9 +382,12 @@ __global__ __launch_bounds__(64 * NWT) void inner_reg_kernel(InArgs a) {
         }
         const double beta = __dmul_rn(aB, diff);
         const double f = floor(__dadd_rn(__dmul_rn(beta, inv_s), rho[s]));
-        const double fc = fmin(fmax(f, (double)QMIN), (double)QMAX);
-        n_gclamp += (f != fc) ? 1u : 0u;
-        const int ng = (int)(-fc);
+        // -gamma = clamp(-f) taken in integers: the conversion saturates at the ends of int32,
+        // far outside [-QMAX, -QMIN], so one integer median does what two fp64 ops did
+        int nf;
+        asm("v_cvt_i32_f64 %0, -%1" : "=v"(nf) : "v"(f));
+        const int ng = min(max(nf, -QMAX), -QMIN);
+        n_gclamp += (nf != ng) ? 1u : 0u;
         int cl = 0;
         if (REGW) {
           cl = __builtin_amdgcn_readfirstlane(creg[s]);
