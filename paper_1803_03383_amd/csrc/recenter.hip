@@ -119,22 +119,76 @@ struct QdArgs {
   const float* fscale;  // [d] per-feature scales or null
 };
 
+// Four columns per thread (halp_bind guarantees rows whose strides and bases allow 16-byte
+// loads and one packed store per thread).  A row takes tpr = 2^lg threads (the power of two
+// at or above its column groups, 256 at most), a workgroup 256 / tpr rows per pass, and a
+// thread keeps four rows in flight.  One scale for all columns: x / delta_d is taken as
+// x * (1 / delta_d) wherever that cannot round differently -- further than 2^-24 from a
+// half-integer, while the two quotients differ by less than 2^-35 below the clamp and both
+// clamp above it -- and by the division otherwise.  Per-feature scales keep the division.
 template <int BITS>
-__global__ __launch_bounds__(256) void quantize_data_kernel(QdArgs a) {
-  using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
+__device__ __forceinline__ int quantize_one(float x, double dd, double inv, bool fast, double qmax) {
+  const double xd = (double)x;
+  double q;
+  if (fast) {
+    q = __dmul_rn(xd, inv);
+    const double fr = __dadd_rn(q, -floor(q));
+    if (fabs(__dadd_rn(fr, -0.5)) < 0x1p-24) q = __ddiv_rn(xd, dd);
+  } else {
+    q = __ddiv_rn(xd, dd);
+  }
+  q = rint(q);  // ties to even
+  q = fmin(fmax(q, -qmax), qmax);
+  return (int)q;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_data_kernel(QdArgs a, int lg) {
+  typedef float F4 __attribute__((ext_vector_type(4)));
   const double qmax = (double)((1 << (BITS - 1)) - 1);
-  XT* __restrict__ Xq = reinterpret_cast<XT*>(a.Xq);
-  for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
-    const float* xr = a.X + row * a.ldx;
-    XT* qr = Xq + row * a.ldxq;
-    for (int64_t j = threadIdx.x; j < a.ldxq; j += 256) {
-      double q = 0.0;
-      if (j < a.d) {
-        const double dd = a.fscale ? __dmul_rn(a.delta_d, (double)a.fscale[j]) : a.delta_d;
-        q = rint(__ddiv_rn((double)xr[j], dd));  // ties to even
-        q = fmin(fmax(q, -qmax), qmax);
+  const int groups = (int)(a.ldxq / 4);
+  const bool fast = a.fscale == nullptr;
+  const double inv = __ddiv_rn(1.0, a.delta_d);
+  const int tpr = 1 << lg, rpb = 256 >> lg;
+  const int g0 = (int)threadIdx.x & (tpr - 1);
+  const int64_t rstep = (int64_t)gridDim.x * rpb;
+  constexpr int kFlight = 4;
+  for (int64_t row0 = (int64_t)blockIdx.x * rpb + ((int)threadIdx.x >> lg); row0 < a.rows;
+       row0 += kFlight * rstep) {
+    for (int g = g0; g < groups; g += tpr) {
+      const int j = 4 * g;
+      F4 xv[kFlight];
+#pragma unroll
+      for (int e = 0; e < kFlight; ++e) {
+        const int64_t row = row0 + e * rstep;
+        xv[e] = F4{0.f, 0.f, 0.f, 0.f};
+        if (row < a.rows && j < a.d) xv[e] = __builtin_nontemporal_load(reinterpret_cast<const F4*>(a.X + row * a.ldx + j));
       }
-      qr[j] = (XT)(int)q;
+#pragma unroll
+      for (int e = 0; e < kFlight; ++e) {
+        const int64_t row = row0 + e * rstep;
+        if (row >= a.rows) break;
+        int q[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int col = j + c;
+          q[c] = 0;
+          if (col < a.d) {
+            const double dd = fast ? a.delta_d : __dmul_rn(a.delta_d, (double)a.fscale[col]);
+            q[c] = quantize_one<BITS>(xv[e][c], dd, inv, fast, qmax);
+          }
+        }
+        if (BITS == 8) {
+          const uint32_t w = (uint32_t)(q[0] & 0xFF) | ((uint32_t)(q[1] & 0xFF) << 8) |
+                             ((uint32_t)(q[2] & 0xFF) << 16) | ((uint32_t)(q[3] & 0xFF) << 24);
+          *reinterpret_cast<uint32_t*>(reinterpret_cast<int8_t*>(a.Xq) + row * a.ldxq + j) = w;
+        } else {
+          uint2 w;
+          w.x = (uint32_t)(q[0] & 0xFFFF) | ((uint32_t)(q[1] & 0xFFFF) << 16);
+          w.y = (uint32_t)(q[2] & 0xFFFF) | ((uint32_t)(q[3] & 0xFFFF) << 16);
+          *reinterpret_cast<uint2*>(reinterpret_cast<int16_t*>(a.Xq) + row * a.ldxq + j) = w;
+        }
+      }
     }
   }
 }
@@ -218,9 +272,20 @@ int launch_quantize_data(const halp_handle& h, hipStream_t s) {
   a.X = h.buf.X; a.Xq = h.buf.Xq;
   a.rows = (p.share_data ? 1 : (int64_t)p.R) * p.N;
   a.ldx = h.buf.ldx; a.ldxq = h.buf.ldxq; a.d = p.d; a.delta_d = p.delta_d; a.fscale = h.fscale;
-  const int grid = (int)(a.rows < 65536 ? a.rows : 65536);
-  if (p.b == 8) hipLaunchKernelGGL(quantize_data_kernel<8>, dim3(grid), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(quantize_data_kernel<16>, dim3(grid), dim3(256), 0, s, a);
+  // what the kernel's 16-byte loads and packed stores assume (halp_bind has checked it)
+  const size_t xq_align = p.b == 8 ? 4 : 8;
+  if (a.ldx % 4 != 0 || a.ldxq % 4 != 0 || reinterpret_cast<uintptr_t>(a.X) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(a.Xq) % xq_align != 0 || a.ldx < a.d)
+    return HALP_ERR_ALIGN;
+  const int64_t groups = a.ldxq / 4;
+  int lg = 0;
+  while (lg < 8 && (1 << lg) < groups) ++lg;  // threads per row: 2^lg >= groups, 256 at most
+  const int rpb = 256 >> lg;
+  int64_t blocks = (a.rows + 4 * rpb - 1) / (4 * rpb);
+  if (blocks > 16384) blocks = 16384;
+  if (blocks < 1) blocks = 1;
+  if (p.b == 8) hipLaunchKernelGGL(quantize_data_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, s, a, lg);
+  else hipLaunchKernelGGL(quantize_data_kernel<16>, dim3((unsigned)blocks), dim3(256), 0, s, a, lg);
   return hip_ok(hipGetLastError());
 }
 

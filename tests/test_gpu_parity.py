@@ -10,7 +10,7 @@ import torch
 import halp_inputs as inp
 import paper_1803_03383_amd as hp
 from oracle import ref
-from gpu_util import GpuProblem, rel_l2
+from gpu_util import DEV, GpuProblem, rel_l2, xq_ld, xq_torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -55,6 +55,39 @@ def test_quantize_data_bit_exact(b):
     want = ref.quantize_data(X, dd, b)
     assert np.array_equal(got[..., :100], want)
     assert not got[..., 100:].any()  # padding columns are zero
+
+
+@pytest.mark.parametrize("b,dd", [(8, 0.25), (8, 0.0371), (16, 2.0 ** -9), (16, 1.7e-4)])
+@pytest.mark.parametrize("ldx_pad", [0, 8])
+def test_quantize_data_ties(b, dd, ldx_pad):
+    """Half-integers of x / delta_d (exact ones when delta_d is a power of two), their fp32
+    neighbours and values around the clamp; rows of 203 columns with and without extra padding."""
+    N, d = 257, 203
+    rng = np.random.default_rng(b + ldx_pad)
+    qmax = 2 ** (b - 1) - 1
+    k = rng.integers(-qmax - 3, qmax + 3, size=(N, d)).astype(np.float64)
+    X = ((k + 0.5) * dd).astype(np.float32)
+    X[1::3] = np.nextafter(X[1::3], np.float32(np.inf))
+    X[2::3] = np.nextafter(X[2::3], np.float32(-np.inf))
+    X[:, ::7] = (rng.standard_normal((N, (d + 6) // 7)) * dd * 50).astype(np.float32)
+    X[0, :4] = [np.float32(1e30), np.float32(-1e30), 0.0, np.float32(dd * 0.5)]
+    ldx = (d + 3) // 4 * 4 + ldx_pad
+    ldxq = xq_ld(d, b) + ldx_pad
+    Xt = torch.zeros((1, N, ldx), dtype=torch.float32, device=DEV)
+    Xt[0, :, :d] = torch.from_numpy(X).to(DEV)
+    Xq = torch.full((1, N, ldxq), 77, dtype=xq_torch_dtype(b), device=DEV)
+    yt = torch.zeros((1, N), dtype=torch.float32, device=DEV)
+    st = hp.alloc_state(N, d, b=b, device=DEV)
+    h = hp.Halp(N, d, b=b, T=1, alpha=0.1, mu=1.0, delta_d=dd, seed=0)
+    h.bind(X=Xt, Xq=Xq, y=yt, ldx=ldx, ldxq=ldxq, **st)
+    h.quantize_data()
+    torch.cuda.synchronize()
+    got = Xq.cpu().numpy()[0]
+    want = ref.quantize_data(X, dd, b)
+    assert np.array_equal(got[:, :d], want)
+    assert not got[:, d:].any()
+    assert (np.abs(want) == qmax).any() and (np.abs(want) < qmax).any()
+    h.close()
 
 
 def test_read_yardstick_reads_every_word_once():
