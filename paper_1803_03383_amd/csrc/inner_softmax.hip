@@ -85,6 +85,10 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   // 16 strips per lane leave no registers for operands prepared ahead of gamma: the sampled
   // row stays packed and everything else of the update is formed after the second barrier
   constexpr bool LEAN = UPL > 8;
+  // 8 bits: the two coordinates of a strip are kept and updated as the 16-bit halves of one
+  // register (the class waves share their SIMDs three deep and are bound by issue slots)
+  constexpr bool PK = BITS == 8 && !LEAN;
+  typedef short S2 __attribute__((ext_vector_type(2)));
   constexpr int QMAX = (1 << (BITS - 1)) - 1, QMIN = -(1 << (BITS - 1));
   const int chain = blockIdx.x;
   const int tid = threadIdx.x;
@@ -273,6 +277,17 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
       z[k] = ok ? (int)zg[j] : 0;
       hv[k] = ok ? (BITS == 8 ? -(int)hg[j] : (int)hg[j]) : 0;
     }
+    // packed form: z, and -h~ = 256 hh + hl with 0 <= hl < 256, two coordinates per register
+    S2 zp[PK ? UPL : 1], hlp[PK ? UPL : 1], hhp[PK ? UPL : 1];
+    if (PK) {
+#pragma unroll
+      for (int u = 0; u < UPL; ++u) {
+        const int k0 = (2 * u) % CPL, k1 = (2 * u + 1) % CPL;
+        zp[PK ? u : 0] = S2{(short)z[k0], (short)z[k1]};
+        hlp[PK ? u : 0] = S2{(short)(hv[k0] & 0xFF), (short)(hv[k1] & 0xFF)};
+        hhp[PK ? u : 0] = S2{(short)(hv[k0] >> 8), (short)(hv[k1] >> 8)};
+      }
+    }
     const int frag_dw = lane_ok ? (s0 * 2) >> 2 : 0;  // dword index of the fragment in a row
     const int half_sh = (UPL == 1 && lane_ok) ? ((s0 * 2) & 2) * 8 : 0;
     const uint32_t strip0 = (uint32_t)(cls * U + s0);
@@ -335,8 +350,18 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
             return BITS == 8 ? (int)(int8_t)(xv >> xs) : (int)(int16_t)(xv >> xs);
           };
           int xe[LEAN ? 1 : CPL];
+          S2 xp[PK ? UPL : 1];
           AccT part = 0;
-          if (!LEAN) {
+          if (PK) {
+            // the strip's two bytes go to the high bytes of the halves and come back down with
+            // their signs; one packed dot per strip
+#pragma unroll
+            for (int u = 0; u < UPL; ++u) {
+              const uint32_t up = __builtin_amdgcn_perm(0u, xw[u / 2], (u & 1) ? 0x030C020Cu : 0x010C000Cu);
+              xp[PK ? u : 0] = __builtin_bit_cast(S2, up) >> (S2)(8);
+              part = (AccT)__builtin_amdgcn_sdot2(xp[PK ? u : 0], zp[PK ? u : 0], (int)part, false);
+            }
+          } else if (!LEAN) {
 #pragma unroll
             for (int k = 0; k < CPL; ++k) {
               xe[LEAN ? 0 : k] = x_of(k);
@@ -373,7 +398,15 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
             return BITS == 8 ? hv[k] + re : re - (hv[k] & 0xFFFF);
           };
           int hr[LEAN ? 1 : CPL];
-          if (!LEAN) {
+          S2 crp[PK ? UPL : 1], zh[PK ? UPL : 1];
+          if (PK) {
+#pragma unroll
+            for (int u = 0; u < UPL; ++u) {
+              const uint32_t rp = __builtin_amdgcn_perm(0u, zrw[s >> 1][u], (s & 1) ? 0x0C030C02u : 0x0C010C00u);
+              crp[PK ? u : 0] = __builtin_bit_cast(S2, rp) + hlp[PK ? u : 0];  // rounding bits + hl
+              zh[PK ? u : 0] = hhp[PK ? u : 0] + zp[PK ? u : 0];
+            }
+          } else if (!LEAN) {
 #pragma unroll
             for (int k = 0; k < CPL; ++k) hr[LEAN ? 0 : k] = hr_of(k);
           }
@@ -410,7 +443,40 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
               z[k] = zc;
             }
           };
-          if (cl != 0) update(std::true_type{});  // the L2 term is rare: c_lambda is mostly 0
+          if (PK && cl == 0) {
+            // per half: floor((-gamma x + r + hl) / 256) + hh + z; |gamma x| <= 2^14 and
+            // r + hl < 512, so every intermediate fits 16 bits
+            const S2 ngp = S2{(short)ng, (short)ng};
+            S2 vu[PK ? UPL : 1];
+            uint32_t moved = 0;
+#pragma unroll
+            for (int u = 0; u < (PK ? UPL : 0); ++u) {
+              S2 v = xp[u] * ngp + crp[u];
+              v = (v >> (S2)(8)) + zh[u];
+              const S2 zc = __builtin_elementwise_min(__builtin_elementwise_max(v, (S2)(QMIN)), (S2)(QMAX));
+              moved |= __builtin_bit_cast(uint32_t, v) ^ __builtin_bit_cast(uint32_t, zc);
+              vu[u] = v;
+              zp[u] = zc;
+            }
+            if (__ballot(moved != 0) != 0) {  // rare: count the clamped coordinates exactly
+#pragma unroll
+              for (int u = 0; u < (PK ? UPL : 0); ++u) {
+                const uint32_t df = __builtin_bit_cast(uint32_t, vu[u]) ^ __builtin_bit_cast(uint32_t, zp[u]);
+                n_zclamp += (unsigned long long)__builtin_popcountll(__ballot((df & 0xFFFFu) != 0)) +
+                            (unsigned long long)__builtin_popcountll(__ballot((df >> 16) != 0));
+              }
+            }
+          } else if (PK) {  // a step with an L2 draw: unpack, the scalar form, pack again
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+              z[k] = (int)zp[(k / 2) % UPL][k % 2];
+              xe[LEAN ? 0 : k] = (int)xp[(k / 2) % UPL][k % 2];
+              hr[LEAN ? 0 : k] = hr_of(k);
+            }
+            update(std::true_type{});
+#pragma unroll
+            for (int u = 0; u < (PK ? UPL : 0); ++u) zp[u] = S2{(short)z[(2 * u) % CPL], (short)z[(2 * u + 1) % CPL]};
+          } else if (cl != 0) update(std::true_type{});  // the L2 term is rare: c_lambda is mostly 0
           else update(std::false_type{});
         }
         __builtin_amdgcn_sched_barrier(0);  // keep one step's temporaries from overlapping the next's
@@ -418,6 +484,10 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     }
 
     // ---- w~ <- w~ + delta_m z (option I); hand z out
+    if (PK) {
+#pragma unroll
+      for (int k = 0; k < CPL; ++k) z[k] = (int)zp[(k / 2) % UPL][k % 2];
+    }
     const double delta_m = sc[0];
     float wv[CPL];
 #pragma unroll
