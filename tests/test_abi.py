@@ -33,6 +33,22 @@ def test_library_exports_every_declared_symbol():
     assert sorted(hp.EXPORTS) == _declared()   # the binding wraps exactly the header
 
 
+def test_binding_constants_follow_the_header():
+    """Every HALP_ERR_*, HALP_LOSS_*, HALP_ALG_* and HALP_OPT_* macro has the same value under the
+    same name (without the prefix) in the binding, and the binding has no option the header lacks."""
+    text = open(os.path.join(ROOT, "include", "halp.h")).read()
+    macros = {m.group(1): int(m.group(2)) for m in
+              re.finditer(r"^#define HALP_((?:ERR|LOSS|ALG|OPT)_\w+)\s+\(?(-?\d+)\)?", text, flags=re.M)}
+    assert len(macros) >= 20 and "OPT_INNER_PACKED" in macros
+    for name, value in macros.items():
+        assert getattr(hp, name) == value, name
+    for name in dir(hp):
+        if name.startswith(("OPT_", "ERR_", "LOSS_", "ALG_")):
+            assert name in macros, f"{name} is not in include/halp.h"
+    opts = [v for k, v in macros.items() if k.startswith("OPT_")]
+    assert len(set(opts)) == len(opts)
+
+
 def test_error_strings_and_version():
     for code in (hp.ERR_NULL, hp.ERR_INVALID, hp.ERR_UNSUPPORTED, hp.ERR_NOT_BOUND, hp.ERR_HIP, hp.ERR_ALIGN, 0):
         assert len(hp.strerror(code)) >= 2
