@@ -130,6 +130,9 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
 
   if (wave == K) {
     // ===================================================================== service wave
+    // every class wave waits for this one at the step's second barrier: it goes first
+    // wherever it shares a SIMD with class waves
+    __builtin_amdgcn_s_setprio(3);
     const uint32_t N = (uint32_t)a.N;
     const unsigned char* __restrict__ Xq = reinterpret_cast<const unsigned char*>(a.Xq) +
                                            (int64_t)chain * a.xq_chain_stride * (BITS / 8);
