@@ -232,6 +232,25 @@ static void softmax_p_inner(const double* a, int K, double* prob) {
   for (int c = 0; c < K; ++c) prob[c] = prob[c] / v[0];
 }
 
+/* l'(a1) - l'(a0) per class, the bracket of Algorithm 4's beta line.  lin is the squared
+ * loss's difference, formed by the caller without cancellation.  path selects the leg:
+ * PLAIN is the definition (libm exp, normaliser summed left to right: the functions of the
+ * full-precision pass), FIXED the reproducible reading above. */
+static void scalar_difference(int loss, int path, int K, const double* a0, const double* a1,
+                              double yi, double lin, double* out) {
+  if (loss == HALP_REF_LOGISTIC) {
+    out[0] = path == HALP_REF_SCALAR_PLAIN ? logistic_dl(a1[0], yi) - logistic_dl(a0[0], yi)
+                                           : logistic_dl_inner(a1[0], yi) - logistic_dl_inner(a0[0], yi);
+  } else if (loss == HALP_REF_SOFTMAX) {
+    double q0[64], q1[64];
+    if (path == HALP_REF_SCALAR_PLAIN) { softmax_p(a0, K, q0); softmax_p(a1, K, q1); }
+    else { softmax_p_inner(a0, K, q0); softmax_p_inner(a1, K, q1); }
+    for (int c = 0; c < K; ++c) out[c] = q1[c] - q0[c];
+  } else {
+    out[0] = lin;
+  }
+}
+
 /* --------------------------------------------------- Algorithm 4, outer part */
 
 int halp_ref_full_gradient(const halp_ref_problem* p, const float* X, int64_t ldx, const void* y,
@@ -381,7 +400,7 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
   int64_t* idx = (int64_t*)malloc(sizeof(int64_t) * (size_t)B);
   int64_t* gam = (int64_t*)malloc(sizeof(int64_t) * (size_t)B * (size_t)K);
   int64_t* znew = (int64_t*)malloc(sizeof(int64_t) * (size_t)K * (size_t)d);
-  double a0[64], a1[64], p0[64], p1[64];
+  double a0[64], a1[64], p0[64], p1[64], p2[64];
   for (int64_t t = 0; t < T; ++t) {
     const int rec = trace && t < trace->M;
     /* sample i uniformly */
@@ -401,19 +420,11 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
         if (rec && trace->D) trace->D[(t * B + m) * K + c] = D;
         p0[c] = dscale * (double)D; /* kept for the squared loss */
       }
-      if (p->loss == HALP_REF_LOGISTIC) {
-        const double yi = ((const float*)y)[i];
-        p1[0] = logistic_dl_inner(a1[0], yi) - logistic_dl_inner(a0[0], yi);
-      } else if (p->loss == HALP_REF_SOFTMAX) {
-        double q0[64], q1[64];
-        softmax_p_inner(a0, K, q0);
-        softmax_p_inner(a1, K, q1);
-        for (int c = 0; c < K; ++c) p1[c] = q1[c] - q0[c];
-      } else {
-        /* Algorithm 4: (phi + D - y) - (phi - y) = D without cancellation;
-         * Algorithm 2: (x^T w - y) - (phi - y) */
-        p1[0] = lp ? p0[0] - a0[0] : p0[0];
-      }
+      const double yi = p->loss == HALP_REF_LOGISTIC ? (double)((const float*)y)[i] : 0.0;
+      const double lin = lp ? p0[0] - a0[0] : p0[0];
+      scalar_difference(p->loss, p->scalar_path, K, a0, a1, yi, lin, p1);
+      const int other = rec && (trace->beta_other || trace->gamma_other);
+      if (other) scalar_difference(p->loss, !p->scalar_path, K, a0, a1, yi, lin, p2);
       for (int c = 0; c < K; ++c) {
         const double beta = aB * p1[c];
         const uint64_t n = ((uint64_t)t * (uint64_t)B + (uint64_t)m) * (uint64_t)K + (uint64_t)c;
@@ -424,6 +435,12 @@ int halp_ref_inner_loop(const halp_ref_problem* p, const void* Xq, int64_t ldxq,
         if (counters) counters[1] += (uint64_t)hit;
         if (rec && trace->beta) trace->beta[(t * B + m) * K + c] = beta;
         if (rec && trace->gamma) trace->gamma[(t * B + m) * K + c] = (int32_t)gq;
+        if (other) { /* the other leg, same state and same draw */
+          const double beta2 = aB * p2[c];
+          const int64_t gq2 = halp_ref_quantize_real(beta2, inv_s, r, qmin, qmax, 0);
+          if (trace->beta_other) trace->beta_other[(t * B + m) * K + c] = beta2;
+          if (trace->gamma_other) trace->gamma_other[(t * B + m) * K + c] = (int32_t)gq2;
+        }
       }
     }
     /* L2: the variance-reduced difference contributes lambda z */

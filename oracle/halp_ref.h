@@ -42,7 +42,9 @@
  *     exp is a fixed sequence of correctly rounded double operations
  *     (halp_ref_exp, within 1 ulp of exp) and the softmax normaliser is summed
  *     pairwise over adjacent classes; the full-precision pass uses libm and
- *     plain loops.
+ *     plain loops.  The plain definition of the same scalar path (libm exp, the
+ *     normaliser added from left to right) is the oracle's second leg,
+ *     HALP_REF_SCALAR_PLAIN; the two legs are compared step by step in the tests.
  *
  *   - LP-SVRG (Algorithm 2) for linear models, which the paper says can be put in
  *     integers "using a similar technique" without printing it: the model w itself
@@ -69,6 +71,13 @@ extern "C" {
 
 enum { HALP_REF_SQUARED = 0, HALP_REF_LOGISTIC = 1, HALP_REF_SOFTMAX = 2 };
 enum { HALP_REF_ALG_HALP = 0, HALP_REF_ALG_LPSVRG = 1, HALP_REF_ALG_SVRG = 2 };
+/* Two legs of the inner loop's scalar path (Algorithm 4, the beta line).  PLAIN is the
+ * definition written out: l' through the C library's exp, the softmax normaliser added class by
+ * class from left to right -- the same code as the full-precision pass.  FIXED is the reading
+ * that makes the integer gamma reproducible on any IEEE machine (halp_ref_exp, pairwise
+ * normaliser); it is what parity with the GPU is held to.  The two differ by rounding only;
+ * tests/test_oracle_scalar_legs.py measures how often that moves a gamma.                    */
+enum { HALP_REF_SCALAR_FIXED = 0, HALP_REF_SCALAR_PLAIN = 1 };
 
 /* purposes of the random streams (counter word 3) */
 enum {
@@ -94,6 +103,8 @@ typedef struct {
   double delta_d; /* scale of the low-precision data (delta_d, b)     */
   uint64_t seed;  /* seed of this chain                               */
   double delta;   /* LP-SVRG only: the fixed scale of the model (delta, b) */
+  int32_t scalar_path; /* how the inner loop evaluates l': HALP_REF_SCALAR_FIXED (0, the
+                          reproducible reading) or HALP_REF_SCALAR_PLAIN (1, the definition) */
 } halp_ref_problem;
 
 /* optional per-step record of the first M steps; any pointer may be NULL */
@@ -104,6 +115,10 @@ typedef struct {
   double* beta;    /* [M][B][K]                                        */
   int32_t* gamma;  /* [M][B][K]                                        */
   int32_t* ztraj;  /* [M][K][d]     z after the step                   */
+  /* what the other leg of the scalar path (see HALP_REF_SCALAR_*) gives at the same state z,
+   * the same sampled row and the same rounding draw; the trajectory follows p->scalar_path  */
+  double* beta_other;   /* [M][B][K] */
+  int32_t* gamma_other; /* [M][B][K] */
 } halp_ref_trace;
 
 /* scales[8]: 0 delta_m, 1 delta_i, 2 delta_s, 3 ||g~||, 4 1/delta_i,

@@ -20,13 +20,15 @@ class Problem(C.Structure):
         ("b", C.c_int32), ("B", C.c_int32), ("algorithm", C.c_int32),
         ("alpha", C.c_double), ("mu", C.c_double), ("lam", C.c_double),
         ("delta_d", C.c_double), ("seed", C.c_uint64), ("delta", C.c_double),
+        ("scalar_path", C.c_int32),
     ]
 
 
 class Trace(C.Structure):
     _fields_ = [
         ("M", C.c_int64), ("idx", C.c_void_p), ("D", C.c_void_p), ("beta", C.c_void_p),
-        ("gamma", C.c_void_p), ("ztraj", C.c_void_p),
+        ("gamma", C.c_void_p), ("ztraj", C.c_void_p), ("beta_other", C.c_void_p),
+        ("gamma_other", C.c_void_p),
     ]
 
 
@@ -100,12 +102,14 @@ def xq_dtype(b):
 
 
 ALG_HALP, ALG_LPSVRG, ALG_SVRG = 0, 1, 2
+# legs of the inner loop's scalar path: the reproducible reading / the plain definition
+SCALAR_FIXED, SCALAR_PLAIN = 0, 1
 
 
 def make_problem(N, d, K=1, loss=SQUARED, b=8, B=1, alpha=0.01, mu=1.0, lam=0.0, delta_d=1.0,
-                 seed=0, algorithm=ALG_HALP, delta=0.0):
+                 seed=0, algorithm=ALG_HALP, delta=0.0, scalar_path=SCALAR_FIXED):
     return Problem(N=N, d=d, K=K, loss=loss, b=b, B=B, algorithm=algorithm, alpha=alpha, mu=mu,
-                   lam=lam, delta_d=delta_d, seed=seed, delta=delta)
+                   lam=lam, delta_d=delta_d, seed=seed, delta=delta, scalar_path=scalar_path)
 
 
 def philox4x32_10(ctr, key):
@@ -243,8 +247,11 @@ def lp_begin(prob, g32, w, epoch):
     return scales, h, z
 
 
-def inner_loop(prob, Xq, phi32, y, h, scales, epoch, T, z0=None, trace_steps=0):
-    """returns dict(z=..., counters=..., and trace arrays when trace_steps > 0)"""
+def inner_loop(prob, Xq, phi32, y, h, scales, epoch, T, z0=None, trace_steps=0, trace_z=True,
+               trace_other=False):
+    """returns dict(z=..., counters=..., and trace arrays when trace_steps > 0).  trace_other adds
+    beta_other / gamma_other: what the other leg of the scalar path gives at each recorded step
+    (same state, same draw)"""
     Xq = np.ascontiguousarray(Xq, dtype=xq_dtype(prob.b))
     phi32 = np.ascontiguousarray(phi32, dtype=np.float32)
     yy = _ylike(prob, y)
@@ -260,10 +267,16 @@ def inner_loop(prob, Xq, phi32, y, h, scales, epoch, T, z0=None, trace_steps=0):
         out["D"] = np.zeros((M, B, K), dtype=np.int64)
         out["beta"] = np.zeros((M, B, K), dtype=np.float64)
         out["gamma"] = np.zeros((M, B, K), dtype=np.int32)
-        out["ztraj"] = np.zeros((M, K, d), dtype=np.int32)
+        if trace_z:
+            out["ztraj"] = np.zeros((M, K, d), dtype=np.int32)
+        if trace_other:
+            out["beta_other"] = np.zeros((M, B, K), dtype=np.float64)
+            out["gamma_other"] = np.zeros((M, B, K), dtype=np.int32)
         tr = Trace(M=M, idx=out["idx"].ctypes.data, D=out["D"].ctypes.data,
                    beta=out["beta"].ctypes.data, gamma=out["gamma"].ctypes.data,
-                   ztraj=out["ztraj"].ctypes.data)
+                   ztraj=out["ztraj"].ctypes.data if trace_z else None,
+                   beta_other=out["beta_other"].ctypes.data if trace_other else None,
+                   gamma_other=out["gamma_other"].ctypes.data if trace_other else None)
     rc = lib().halp_ref_inner_loop(C.addressof(prob), _p(Xq), Xq.shape[1], _p(phi32), _p(yy), _p(h),
                                    _p(scales), epoch, T, _p(z),
                                    C.addressof(tr) if tr is not None else None, _p(counters))
