@@ -47,6 +47,7 @@ extern "C" {
 #define HALP_ERR_NOT_BOUND (-4)   /* halp_bind has not been called / lacks a buffer     */
 #define HALP_ERR_HIP (-5)         /* a HIP runtime call failed                          */
 #define HALP_ERR_ALIGN (-6)       /* pointer or stride alignment requirement not met    */
+#define HALP_ERR_TOO_LARGE (-7)   /* beyond the fixed scratch of halp_full_gradient_static */
 
 /* scalar loss l_i of the linear model (Sec. 4); labels y as noted */
 #define HALP_LOSS_SQUARED 0  /* l(a) = (a - y)^2 / 2,        y: float               */
@@ -203,6 +204,23 @@ int halp_quantize_data(halp_handle* h, void* stream);
  * g~ = (1/N) sum_i l_i'(phi_i) x_i + lambda w~, in fp32 with X read once;
  * also f(w~) into scales[6].  Needs X, y, w, phi, g, scales.                          */
 int halp_full_gradient(halp_handle* h, void* stream);
+
+/* halp_full_gradient for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  No handle (halp_create
+ * allocates): the parameters and the caller's buffers are passed directly, with the meaning,
+ * layout and alignment rules of halp_params / halp_buffers (needs X, ldx, y, w, phi, g, scales;
+ * T, B, b, mu, delta_d, seed are not used).  The per-workgroup partial sums that
+ * halp_full_gradient keeps in workspace from halp_create live here in a fixed device array of
+ * HALP_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends;
+ * its address is looked up on the first call on a device.  The call itself allocates and frees
+ * nothing.  Fewer workgroups per chain are launched when their partials would not fit
+ * (results agree to rounding; bandwidth drops); when R (4 K d + 8) bytes, one workgroup per
+ * chain, exceed the array the call fails with HALP_ERR_TOO_LARGE.  No per-feature scales.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (two streams,
+ * two threads) race and give wrong sums -- order them.  Nothing needs clearing between calls:
+ * every launch overwrites the part it reads.                                              */
+#define HALP_STATIC_SCRATCH_BYTES (16u << 20)
+int halp_full_gradient_static(const halp_params* p, const halp_buffers* buf, void* stream);
 
 /* Algorithm 4, the re-scale lines (bit centering, Sec. 4): from g~ computes
  * delta_m = ||g~||_2 / (mu (2^(b-1)-1)), delta_i = 2^-b delta_m,

@@ -16,12 +16,14 @@ ALG_HALP, ALG_LPSVRG, ALG_SVRG = 0, 1, 2
 OPT_INNER_VARIANT, OPT_TIMING, OPT_FULLGRAD_BLOCKS, OPT_INNER_WAVES, OPT_OPTION_II = 1, 2, 4, 5, 6
 OPT_INNER_PARTS, OPT_EXCHANGE_SPIN_LIMIT, OPT_INNER_PACKED = 7, 8, 9
 ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_NOT_BOUND, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6
+ERR_TOO_LARGE = -7
+STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = [
     "halp_create", "halp_destroy", "halp_bind", "halp_set_option", "halp_set_chain_hyper",
     "halp_set_feature_scale",
     "halp_quantize_data",
-    "halp_full_gradient", "halp_recenter", "halp_inner_loop", "halp_epoch",
+    "halp_full_gradient", "halp_full_gradient_static", "halp_recenter", "halp_inner_loop", "halp_epoch",
     "halp_inner_loop_trace", "halp_get_stats", "halp_debug_stream_words",
     "halp_debug_zround_bits", "halp_debug_read_bandwidth", "halp_strerror", "halp_last_error_detail", "halp_version",
 ]
@@ -84,6 +86,7 @@ def lib():
         L.halp_set_feature_scale.argtypes = [vp, vp]
         L.halp_quantize_data.argtypes = [vp, vp]
         L.halp_full_gradient.argtypes = [vp, vp]
+        L.halp_full_gradient_static.argtypes = [C.POINTER(Params), C.POINTER(Buffers), vp]
         L.halp_recenter.argtypes = [vp, i64, vp]
         L.halp_inner_loop.argtypes = [vp, i64, vp]
         L.halp_epoch.argtypes = [vp, i64, vp]
@@ -207,6 +210,16 @@ class Halp:
         s = Stats()
         _check(lib().halp_get_stats(self._h, chain, _stream(stream), C.byref(s)), "halp_get_stats")
         return s
+
+
+def full_gradient_static(params, X, y, w, phi, g, scales, ldx=None, stream=None):
+    """halp_full_gradient without a handle and without any allocation: the partial sums go
+    through the library's fixed device array.  params: a Params; the rest torch CUDA tensors."""
+    b = Buffers()
+    b.X, b.y, b.w, b.phi, b.g, b.scales = _ptr(X), _ptr(y), _ptr(w), _ptr(phi), _ptr(g), _ptr(scales)
+    b.ldx = int(ldx if ldx is not None else X.stride(-2))
+    _check(lib().halp_full_gradient_static(C.byref(params), C.byref(b), _stream(stream)),
+           "halp_full_gradient_static")
 
 
 def alloc_state(N, d, K=1, R=1, b=8, device="cuda"):

@@ -11,6 +11,8 @@
 // wave computes.  Waves of a workgroup fold their partial gradients through
 // LDS; a second small kernel adds the per-workgroup partials in a fixed order
 // (fp64), so the result does not depend on scheduling.
+#include <mutex>
+
 #include "halp_device.hpp"
 #include "fullgrad_args.hpp"
 #include "halp_internal.hpp"
@@ -414,36 +416,52 @@ int launch_narrow(const FgArgs& a, int loss, dim3 grid, hipStream_t s) {
   return hip_ok(hipGetLastError());
 }
 
-int fullgrad_parts(const halp_handle& h) {
-  const halp_params& p = h.p;
-  if (h.fullgrad_blocks > 0) return h.fullgrad_blocks;
+// workgroups per chain when the caller has not fixed the count: two per CU over all chains
+static int fullgrad_auto_parts(const halp_params& p, int num_cus) {
   if (p.loss == HALP_LOSS_SOFTMAX) {  // two workgroups per CU, tiles of 16 rows
-    int64_t parts = (2 * (int64_t)h.num_cus + p.R - 1) / p.R;
+    int64_t parts = (2 * (int64_t)num_cus + p.R - 1) / p.R;
     const int64_t tiles = (p.N + 15) / 16;
     if (parts > tiles) parts = tiles;
     return (int)(parts < 1 ? 1 : parts);
   }
   const int rb = rows_per_batch(p.d);
   const int64_t nblk = (p.N + rb - 1) / rb;
-  int64_t parts = (2 * (int64_t)h.num_cus + p.R - 1) / p.R;  // two workgroups per CU
-  const int64_t most = (nblk + 3) / 4;                        // one batch per wave at least
+  int64_t parts = (2 * (int64_t)num_cus + p.R - 1) / p.R;  // two workgroups per CU
+  const int64_t most = (nblk + 3) / 4;                      // one batch per wave at least
   if (parts > most) parts = most;
   if (parts < 1) parts = 1;
   return (int)parts;
 }
 
-int launch_full_gradient(const halp_handle& h, hipStream_t s) {
-  const halp_params& p = h.p;
+int fullgrad_parts(const halp_handle& h) {
+  if (h.fullgrad_blocks > 0) return h.fullgrad_blocks;
+  return fullgrad_auto_parts(h.p, h.num_cus);
+}
+
+// What a gradient pass needs beyond the parameters: the caller's buffers and a workspace of
+// per-workgroup partial sums ([R][parts][K d] floats, [R][parts] doubles).
+struct FgPlan {
+  const halp_params* p;
+  const halp_buffers* buf;
+  const float* fscale;
+  float* partial_g;
+  double* partial_loss;
+  int parts;
+};
+
+static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
+  const halp_params& p = *f.p;
+  const halp_buffers& buf = *f.buf;
   int rc = fullgrad_supported(p);
   if (rc != HALP_OK) return rc;
   FgArgs a;
-  a.X = h.buf.X; a.y = h.buf.y; a.w = h.buf.w; a.phi = h.buf.phi;
-  a.partial_g = h.partial_g; a.partial_loss = h.partial_loss;
-  a.N = p.N; a.ldx = h.buf.ldx;
-  a.x_chain_stride = p.share_data ? 0 : p.N * h.buf.ldx;
+  a.X = buf.X; a.y = buf.y; a.w = buf.w; a.phi = buf.phi;
+  a.partial_g = f.partial_g; a.partial_loss = f.partial_loss;
+  a.N = p.N; a.ldx = buf.ldx;
+  a.x_chain_stride = p.share_data ? 0 : p.N * buf.ldx;
   a.y_chain_stride = p.share_data ? 0 : p.N;
-  a.d = p.d; a.K = p.K; a.parts = h.parts; a.fscale = h.fscale;
-  const dim3 grid(h.parts, p.R);
+  a.d = p.d; a.K = p.K; a.parts = f.parts; a.fscale = f.fscale;
+  const dim3 grid(f.parts, p.R);
   const int nv = nv_for(p.d);
   if (p.loss == HALP_LOSS_SOFTMAX) {
     rc = launch_fullgrad_softmax(a, p.R, s);
@@ -466,11 +484,79 @@ int launch_full_gradient(const halp_handle& h, hipStream_t s) {
   }
   if (rc != HALP_OK) return rc;
   RedArgs r;
-  r.partial_g = h.partial_g; r.partial_loss = h.partial_loss; r.w = h.buf.w; r.g = h.buf.g;
-  r.scales = h.buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = h.parts; r.lambda = p.lambda;
-  r.fscale = h.fscale; r.d = p.d;
+  r.partial_g = f.partial_g; r.partial_loss = f.partial_loss; r.w = buf.w; r.g = buf.g;
+  r.scales = buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = f.parts; r.lambda = p.lambda;
+  r.fscale = f.fscale; r.d = p.d;
   hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 31) / 32, p.R), dim3(256), 0, s, r);
   return hip_ok(hipGetLastError());
+}
+
+int launch_full_gradient(const halp_handle& h, hipStream_t s) {
+  const FgPlan f{&h.p, &h.buf, h.fscale, h.partial_g, h.partial_loss, h.parts};
+  return launch_full_gradient_plan(f, s);
+}
+
+// ---- allocation-free form -------------------------------------------------------
+// The workspace of per-workgroup partial sums lives in a file-scope device array instead of
+// memory from hipMalloc.  Every GPU holds its own copy of the array at its own address; the
+// name below is only a host-side stand-in for it, so the address is looked up once per device
+// and that pointer is what the kernels get.  Every launch overwrites the part of the array it
+// uses (each workgroup stores its whole partial, zero or not), so nothing has to be cleared;
+// two calls in flight on one GPU at once would share the array and race.
+static __device__ __align__(256) unsigned char scratch[HALP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct DeviceScratch {
+  unsigned char* ptr = nullptr;
+  int cus = 0;
+};
+std::mutex g_scratch_mu;
+DeviceScratch g_scratch[kMaxDevices];
+
+// address of this device's copy of `scratch` and its CU count, looked up on first use
+int device_scratch(DeviceScratch* out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return HALP_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return HALP_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  DeviceScratch& e = g_scratch[dev];
+  if (!e.ptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return HALP_ERR_HIP;
+    }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+      (void)hipGetLastError();
+      return HALP_ERR_HIP;
+    }
+    e.cus = cus > 0 ? cus : 256;
+    e.ptr = static_cast<unsigned char*>(ptr);
+  }
+  *out = e;
+  return HALP_OK;
+}
+}  // namespace
+
+int launch_full_gradient_static(const halp_params& p, const halp_buffers& buf, hipStream_t s) {
+  int rc = fullgrad_supported(p);
+  if (rc != HALP_OK) return rc;
+  // bytes one workgroup's partial takes per chain: K d floats and a double
+  const size_t n = (size_t)p.K * (size_t)p.d;
+  const size_t per_part = (size_t)p.R * (n * sizeof(float) + sizeof(double));
+  const size_t budget = (size_t)HALP_STATIC_SCRATCH_BYTES - 256;  // the doubles start 256-aligned
+  if (per_part > budget) return HALP_ERR_TOO_LARGE;
+  DeviceScratch ds;
+  if ((rc = device_scratch(&ds)) != HALP_OK) return rc;
+  int64_t parts = fullgrad_auto_parts(p, ds.cus);
+  if ((size_t)parts > budget / per_part) parts = (int64_t)(budget / per_part);
+  const size_t g_bytes = ((size_t)p.R * (size_t)parts * n * sizeof(float) + 255) / 256 * 256;
+  float* partial_g = reinterpret_cast<float*>(ds.ptr);
+  double* partial_loss = reinterpret_cast<double*>(ds.ptr + g_bytes);
+  const FgPlan f{&p, &buf, nullptr, partial_g, partial_loss, (int)parts};
+  return launch_full_gradient_plan(f, s);
 }
 
 }  // namespace halp

@@ -308,6 +308,18 @@ int halp_full_gradient(halp_handle* h, void* stream) {
   return launch_full_gradient(*h, as_stream(stream));
 }
 
+int halp_full_gradient_static(const halp_params* p, const halp_buffers* b, void* stream) {
+  if (!p || !b) return HALP_ERR_NULL;
+  int rc = check_params(*p);
+  if (rc != HALP_OK) return rc;
+  if (!b->X || !b->y || !b->w || !b->phi || !b->g || !b->scales) return HALP_ERR_NOT_BOUND;
+  if (b->ldx < p->d) return HALP_ERR_INVALID;
+  if (b->ldx % 4 != 0 || !aligned(b->X, 16) || !aligned(b->w, 4) || !aligned(b->phi, 4) ||
+      !aligned(b->g, 4) || !aligned(b->y, 4) || !aligned(b->scales, 8))
+    return HALP_ERR_ALIGN;
+  return launch_full_gradient_static(*p, *b, as_stream(stream));
+}
+
 int halp_recenter(halp_handle* h, int64_t epoch, void* stream) {
   if (!h) return HALP_ERR_NULL;
   if (h->p.algorithm == HALP_ALG_SVRG) return HALP_ERR_INVALID;
@@ -444,6 +456,8 @@ const char* halp_strerror(int code) {
     case HALP_ERR_NOT_BOUND: return "a buffer this call needs has not been bound";
     case HALP_ERR_HIP: return "a HIP runtime call failed";
     case HALP_ERR_ALIGN: return "pointer or stride alignment requirement not met";
+    case HALP_ERR_TOO_LARGE:
+      return "the problem does not fit the fixed scratch of the allocation-free entry point";
     default: return "unknown error code";
   }
 }

@@ -55,6 +55,8 @@ int launch_quantize_data(const halp_handle& h, hipStream_t s);
 int fullgrad_supported(const halp_params& p);
 int fullgrad_parts(const halp_handle& h);  // workgroups per chain for this shape
 int launch_full_gradient(const halp_handle& h, hipStream_t s);
+// the same pass with its workspace in the library's fixed device array: no allocation
+int launch_full_gradient_static(const halp_params& p, const halp_buffers& buf, hipStream_t s);
 int launch_recenter(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_reg_supported(const halp_params& p);
 int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s);

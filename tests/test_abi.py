@@ -50,9 +50,10 @@ def test_binding_constants_follow_the_header():
 
 
 def test_error_strings_and_version():
-    for code in (hp.ERR_NULL, hp.ERR_INVALID, hp.ERR_UNSUPPORTED, hp.ERR_NOT_BOUND, hp.ERR_HIP, hp.ERR_ALIGN, 0):
+    for code in (hp.ERR_NULL, hp.ERR_INVALID, hp.ERR_UNSUPPORTED, hp.ERR_NOT_BOUND, hp.ERR_HIP, hp.ERR_ALIGN,
+                 hp.ERR_TOO_LARGE, 0):
         assert len(hp.strerror(code)) >= 2
-    assert len({hp.strerror(c) for c in range(-6, 1)}) == 7
+    assert len({hp.strerror(c) for c in range(-7, 1)}) == 8
     assert hp.version()
 
 
@@ -92,3 +93,27 @@ def test_null_arguments():
     assert L.halp_bind(None, None) == hp.ERR_NULL
     assert L.halp_set_option(None, hp.OPT_TIMING, 1) == hp.ERR_NULL
     assert L.halp_set_chain_hyper(None, None, None) == hp.ERR_NULL
+
+
+def test_allocation_free_gradient_pass_checks_on_the_host():
+    """halp_full_gradient_static answers bad arguments, and a problem beyond its fixed scratch,
+    before it touches a device (the pointers here are never dereferenced)."""
+    L = hp.lib()
+    fake = 0x10000
+    def bufs(**kw):
+        b = hp.Buffers(X=fake, ldx=8, y=fake, w=fake, phi=fake, g=fake, scales=fake)
+        for k, v in kw.items():
+            setattr(b, k, v)
+        return b
+    ok = _params()
+    assert L.halp_full_gradient_static(None, C.byref(bufs()), None) == hp.ERR_NULL
+    assert L.halp_full_gradient_static(C.byref(ok), None, None) == hp.ERR_NULL
+    assert L.halp_full_gradient_static(C.byref(_params(N=0)), C.byref(bufs()), None) == hp.ERR_INVALID
+    assert L.halp_full_gradient_static(C.byref(ok), C.byref(bufs(g=None)), None) == hp.ERR_NOT_BOUND
+    assert L.halp_full_gradient_static(C.byref(ok), C.byref(bufs(ldx=4)), None) == hp.ERR_INVALID
+    assert L.halp_full_gradient_static(C.byref(ok), C.byref(bufs(ldx=10)), None) == hp.ERR_ALIGN
+    assert L.halp_full_gradient_static(C.byref(ok), C.byref(bufs(X=fake + 4)), None) == hp.ERR_ALIGN
+    # one workgroup per chain needs R (4 K d + 8) bytes: 4096 chains of 16 x 1024 do not fit 16 MiB
+    big = _params(R=4096, loss=hp.LOSS_SOFTMAX, K=16, d=1024)
+    assert 4096 * (4 * 16 * 1024 + 8) > hp.STATIC_SCRATCH_BYTES
+    assert L.halp_full_gradient_static(C.byref(big), C.byref(bufs(ldx=1024)), None) == hp.ERR_TOO_LARGE
