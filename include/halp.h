@@ -48,6 +48,9 @@ extern "C" {
 #define HALP_ERR_HIP (-5)         /* a HIP runtime call failed                          */
 #define HALP_ERR_ALIGN (-6)       /* pointer or stride alignment requirement not met    */
 #define HALP_ERR_TOO_LARGE (-7)   /* beyond the fixed scratch of halp_full_gradient_static */
+#define HALP_ERR_EXCHANGE_TIMEOUT (-8) /* halp_get_stats: a cross-workgroup wait of the split
+                                     minibatch inner loop ran out; that chain's w~ was left as
+                                     it was before the loop (status -2)                    */
 
 /* scalar loss l_i of the linear model (Sec. 4); labels y as noted */
 #define HALP_LOSS_SQUARED 0  /* l(a) = (a - y)^2 / 2,        y: float               */
@@ -107,19 +110,26 @@ typedef struct {
   void* z;            /* out  [R][K][d] int8 / int16 offset in (delta_m, b)             */
   void* h;            /* out  [R][K][d] int16 / int32 h~ in (delta_i, 2b)               */
   double* scales;     /* out  [R][8]: delta_m, delta_i, delta_s, ||g~||, 1/delta_i, 1/delta_s,
-                         f(w~), status (0 ok, 1 gradient exactly zero, -1 not finite)   */
+                         f(w~), status (0 ok, 1 gradient exactly zero, -1 not finite, -2 a wait
+                         between the workgroups of the split minibatch loop ran out: w~ was not
+                         updated)                                                       */
   uint64_t* counters; /* out  [R][4]: coordinates of z clamped by the last inner loop, gammas
                          clamped, steps with a non-zero L2 draw, 1 if a cross-workgroup wait
-                         of the split minibatch loop ran out (the result is then invalid)   */
+                         of the split minibatch loop ran out (z is then invalid, w~ is left
+                         unchanged and the status becomes -2)                              */
 } halp_buffers;
 
 typedef struct {
   double delta_m, delta_i, delta_s, grad_norm, loss;
-  int32_t status;         /* 0 ok, 1 converged (gradient exactly zero), -1 gradient not finite */
+  int32_t status;         /* 0 ok, 1 converged (gradient exactly zero), -1 gradient not finite,
+                             -2 exchange wait ran out (w~ unchanged)                        */
   int32_t inner_variant;  /* kernel that ran the last inner loop: 1 generic, 2 register-resident */
   uint64_t n_clamped_z, n_clamped_gamma, n_reg_draws;
   float ms_full_gradient, ms_recenter, ms_inner_loop; /* mean per halp_epoch over timed_epochs */
   int32_t timed_epochs;   /* halp_epoch calls averaged (the last 32 at most since timing was set) */
+  uint64_t n_exchange_timeouts; /* 1 if a cross-workgroup wait of the last split minibatch loop
+                             ran out (counters[3]); halp_get_stats then returns
+                             HALP_ERR_EXCHANGE_TIMEOUT with every field filled in           */
 } halp_stats;
 
 #define HALP_OPT_INNER_VARIANT 1 /* 0 auto (default), 1 general, 2 register-resident.
@@ -156,8 +166,8 @@ typedef struct {
 #define HALP_OPT_EXCHANGE_SPIN_LIMIT 8 /* polls after which a workgroup of the split minibatch
                                     loop stops waiting for the others for good (default 2^20,
                                     about a second); -1: never wait.  The launch then ends
-                                    normally with counters[3] = 1 and an invalid result: for
-                                    tests of that path                                    */
+                                    normally with counters[3] = 1, status -2 and w~ unchanged:
+                                    for tests of that path                                */
 
 #define HALP_OPT_INNER_PACKED 9  /* register-resident inner loop at 8 bits with one wave per chain:
                                     the form that updates the two coordinates of a strip as packed
@@ -247,7 +257,9 @@ int halp_epoch(halp_handle* h, int64_t epoch, void* stream);
 int halp_inner_loop_trace(halp_handle* h, int64_t epoch, int64_t M, int64_t* idx, int64_t* D,
                           double* beta, int32_t* gamma, int32_t* ztraj, void* stream);
 
-/* Synchronizes stream, then reads chain r's scales and counters.                      */
+/* Synchronizes stream, then reads chain r's scales and counters.  Returns
+ * HALP_ERR_EXCHANGE_TIMEOUT (out is still filled in) when that chain's last inner loop gave up
+ * a wait between its workgroups.                                                       */
 int halp_get_stats(halp_handle* h, int32_t chain, void* stream, halp_stats* out);
 
 /* Debug: words n0 .. n0+count-1 of a purpose's random stream (purposes: 0 index,

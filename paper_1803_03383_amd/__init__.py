@@ -17,6 +17,7 @@ OPT_INNER_VARIANT, OPT_TIMING, OPT_FULLGRAD_BLOCKS, OPT_INNER_WAVES, OPT_OPTION_
 OPT_INNER_PARTS, OPT_EXCHANGE_SPIN_LIMIT, OPT_INNER_PACKED = 7, 8, 9
 ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_NOT_BOUND, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6
 ERR_TOO_LARGE = -7
+ERR_EXCHANGE_TIMEOUT = -8
 STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = [
@@ -60,6 +61,7 @@ class Stats(C.Structure):
         ("inner_variant", C.c_int32), ("n_clamped_z", C.c_uint64), ("n_clamped_gamma", C.c_uint64),
         ("n_reg_draws", C.c_uint64), ("ms_full_gradient", C.c_float), ("ms_recenter", C.c_float),
         ("ms_inner_loop", C.c_float), ("timed_epochs", C.c_int32),
+        ("n_exchange_timeouts", C.c_uint64),
     ]
 
 
@@ -208,7 +210,12 @@ class Halp:
 
     def get_stats(self, chain=0, stream=None):
         s = Stats()
-        _check(lib().halp_get_stats(self._h, chain, _stream(stream), C.byref(s)), "halp_get_stats")
+        rc = lib().halp_get_stats(self._h, chain, _stream(stream), C.byref(s))
+        if rc == ERR_EXCHANGE_TIMEOUT:  # the statistics are complete; the caller sees both
+            err = HalpError(rc, "halp_get_stats")
+            err.stats = s
+            raise err
+        _check(rc, "halp_get_stats")
         return s
 
 

@@ -114,7 +114,7 @@ int need_inner(const halp_handle& h, int variant) {
     return HALP_ERR_NOT_BOUND;
   if (h.p.loss == HALP_LOSS_LOGISTIC && !h.buf.y) return HALP_ERR_NOT_BOUND;
   if (variant == 2) return reg_supported(h);
-  return HALP_OK;
+  return inner_generic_supported(h.p);  // so that halp_epoch refuses before its first launch
 }
 
 }  // namespace
@@ -401,6 +401,7 @@ int halp_get_stats(halp_handle* h, int32_t chain, void* stream, halp_stats* out)
         hipSuccess)
       return HALP_ERR_HIP;
     out->n_clamped_z = c[0]; out->n_clamped_gamma = c[1]; out->n_reg_draws = c[2];
+    out->n_exchange_timeouts = c[3];
   }
   if (h->timing && h->timed > 0) {  // mean over the recorded epochs (the last 32 at most)
     const int64_t n = h->timed < halp_handle::kTimedEpochs ? h->timed : halp_handle::kTimedEpochs;
@@ -423,7 +424,7 @@ int halp_get_stats(halp_handle* h, int32_t chain, void* stream, halp_stats* out)
     }
     out->timed_epochs = (int32_t)ok;
   }
-  return HALP_OK;
+  return out->n_exchange_timeouts ? HALP_ERR_EXCHANGE_TIMEOUT : HALP_OK;
 }
 
 int halp_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, uint64_t n0,
@@ -456,6 +457,8 @@ const char* halp_strerror(int code) {
     case HALP_ERR_NOT_BOUND: return "a buffer this call needs has not been bound";
     case HALP_ERR_HIP: return "a HIP runtime call failed";
     case HALP_ERR_ALIGN: return "pointer or stride alignment requirement not met";
+    case HALP_ERR_EXCHANGE_TIMEOUT:
+      return "a wait between the workgroups of the split minibatch loop ran out; w~ was not updated";
     case HALP_ERR_TOO_LARGE:
       return "the problem does not fit the fixed scratch of the allocation-free entry point";
     default: return "unknown error code";

@@ -62,6 +62,7 @@ int inner_reg_supported(const halp_params& p);
 int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_softmax_supported(const halp_handle& h);
 int launch_inner_softmax(const halp_handle& h, uint32_t epoch, hipStream_t s);
+int inner_generic_supported(const halp_params& p);
 int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s);
 int inner_batch_supported(const halp_handle& h);
 int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s);

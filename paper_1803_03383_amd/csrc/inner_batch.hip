@@ -577,8 +577,10 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       if (ok[k] && (!FS || wv == 0)) {
         const int j = j0 + k;
         zg[j] = (XT)z[k];
-        const double step = __dmul_rn(delta_m, (double)z[k]);
-        wg[j] = lp ? (float)step : (float)__dadd_rn((double)wg[j], step);
+        if (P == 1) {  // several workgroups per chain: batch_split_finish applies the offset
+          const double step = __dmul_rn(delta_m, (double)z[k]);
+          wg[j] = lp ? (float)step : (float)__dadd_rn((double)wg[j], step);
+        }
       }
     }
     if (n_zclamp) atomicAdd(&s_cnt[0], n_zclamp);
@@ -595,6 +597,26 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     if (part == 0 && (tid == 1 || tid == 2)) cnt_out[tid] = s_cnt[tid];
     if (tid == 0 && n_timeout) atomicMax(reinterpret_cast<unsigned long long*>(&cnt_out[3]), 1ull);
   }
+}
+
+// Several workgroups per chain: w~ <- w~ + delta_m z is applied here, after the launch, and only
+// for chains none of whose workgroups gave up a wait.  A chain with a wait that ran out keeps
+// its w~ (its z is then not a trajectory of the method) and gets status -2 in scales[7].
+template <int BITS>
+__global__ __launch_bounds__(256) void batch_split_finish(InArgs a, double* scales) {
+  using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
+  const int chain = blockIdx.y;
+  const int j = (int)(blockIdx.x * 256 + threadIdx.x);
+  double* sc = scales + (int64_t)chain * 8;
+  if (a.counters[(int64_t)chain * 4 + 3] != 0) {
+    if (j == 0) sc[7] = -2.0;
+    return;
+  }
+  if (sc[7] != 0.0 || j >= a.d) return;  // a gradient of zero or not finite: the loop did not run
+  const XT* zg = reinterpret_cast<const XT*>(a.z) + (int64_t)chain * a.d;
+  float* wg = a.w + (int64_t)chain * a.d;
+  const double step = __dmul_rn(sc[0], (double)zg[j]);
+  wg[j] = a.lp ? (float)step : (float)__dadd_rn((double)wg[j], step);
 }
 
 // clears what the split launch accumulates into or waits on
@@ -729,12 +751,20 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
       return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);        \
     return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);          \
   }
-  HALP_BT(8, 1, true) HALP_BT(8, 2, true) HALP_BT(8, 4, true)
-  HALP_BT(16, 1, true) HALP_BT(16, 2, true) HALP_BT(16, 4, true)
-  HALP_BT(8, 1, false) HALP_BT(8, 2, false) HALP_BT(8, 4, false)
-  HALP_BT(16, 1, false) HALP_BT(16, 2, false) HALP_BT(16, 4, false)
+  auto launch_loop = [&]() -> int {
+    HALP_BT(8, 1, true) HALP_BT(8, 2, true) HALP_BT(8, 4, true)
+    HALP_BT(16, 1, true) HALP_BT(16, 2, true) HALP_BT(16, 4, true)
+    HALP_BT(8, 1, false) HALP_BT(8, 2, false) HALP_BT(8, 4, false)
+    HALP_BT(16, 1, false) HALP_BT(16, 2, false) HALP_BT(16, 4, false)
+    return HALP_ERR_UNSUPPORTED;
+  };
 #undef HALP_BT
-  return HALP_ERR_UNSUPPORTED;
+  const int lrc = launch_loop();
+  if (lrc != HALP_OK || P == 1) return lrc;
+  const dim3 fgrid((p.d + 255) / 256, p.R);
+  if (p.b == 8) hipLaunchKernelGGL(batch_split_finish<8>, fgrid, dim3(256), 0, s, a, h.buf.scales);
+  else hipLaunchKernelGGL(batch_split_finish<16>, fgrid, dim3(256), 0, s, a, h.buf.scales);
+  return hip_ok(hipGetLastError());
 }
 
 }  // namespace halp

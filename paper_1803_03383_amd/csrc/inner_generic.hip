@@ -301,14 +301,24 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
 
 }  // namespace
 
+// LDS the kernel needs: z and h~ as int32, and per row of the step its index, dots, scalars
+static size_t generic_smem(const halp_params& p) {
+  const int64_t n = (int64_t)p.K * p.d;
+  return (size_t)(2 * n + (n & 1)) * 4 + (size_t)p.B * 8 + (size_t)p.B * p.K * 8 +
+         (size_t)p.B * p.K * 16 + (size_t)p.B * 32 + (size_t)p.B * p.K * 4;
+}
+
+// the model and a step's scalars must fit the LDS of one CU; at most 512 rows per step
+int inner_generic_supported(const halp_params& p) {
+  return (generic_smem(p) > 150 * 1024 || p.B > 512) ? HALP_ERR_UNSUPPORTED : HALP_OK;
+}
+
 int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s) {
   const halp_params& p = h.p;
   InArgs a = make_inner_args(h, epoch);
   a.tr = tr;
-  const int64_t n = (int64_t)p.K * p.d;
-  const size_t smem = (size_t)(2 * n + (n & 1)) * 4 + (size_t)p.B * 8 + (size_t)p.B * p.K * 8 +
-                      (size_t)p.B * p.K * 16 + (size_t)p.B * 32 + (size_t)p.B * p.K * 4;
-  if (smem > 150 * 1024 || p.B > 512) return HALP_ERR_UNSUPPORTED;
+  if (inner_generic_supported(p) != HALP_OK) return HALP_ERR_UNSUPPORTED;
+  const size_t smem = generic_smem(p);
   const int threads = 512;
   hipError_t e;
   if (p.b == 8) {

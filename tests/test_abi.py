@@ -51,9 +51,9 @@ def test_binding_constants_follow_the_header():
 
 def test_error_strings_and_version():
     for code in (hp.ERR_NULL, hp.ERR_INVALID, hp.ERR_UNSUPPORTED, hp.ERR_NOT_BOUND, hp.ERR_HIP, hp.ERR_ALIGN,
-                 hp.ERR_TOO_LARGE, 0):
+                 hp.ERR_TOO_LARGE, hp.ERR_EXCHANGE_TIMEOUT, 0):
         assert len(hp.strerror(code)) >= 2
-    assert len({hp.strerror(c) for c in range(-7, 1)}) == 8
+    assert len({hp.strerror(c) for c in range(-8, 1)}) == 9
     assert hp.version()
 
 

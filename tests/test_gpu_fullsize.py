@@ -96,8 +96,9 @@ def test_config2_single_chain_full_size():
 @pytest.mark.parametrize("b", [8, 16])
 def test_config3_softmax_full_size(b):
     """N=60000, d=784, K=10, lambda=1e-4, alpha=1e-2: gradient pass on the whole set, then
-    200 inner steps (general kernel) against the oracle."""
-    N, d, K, T = 60000, 784, 10, 200
+    603 inner steps on the register-resident softmax kernel against the oracle: two refills of
+    the 256-step batches of step-only draws and a ragged last window of 8 steps."""
+    N, d, K, T = 60000, 784, 10, 603
     alpha, mu, lam, seed = 1e-2, 2.5, 1e-4, 4
     X, y, _ = inp.softmax_sparse(N, d, K, seed=seed)
     delta_d = inp.default_delta_d(X, b)
@@ -126,6 +127,7 @@ def test_config3_softmax_full_size(b):
     h.recenter(1)
     h.inner_loop(1)
     torch.cuda.synchronize()
+    assert h.get_stats(0).inner_variant == 2  # not the general kernel
     sc, hh, _ = ref.recenter(prob, g_ref.astype(np.float32), 1)
     out = ref.inner_loop(prob, Xq_ref, phi_ref.astype(np.float32), y, hh, sc, 1, T)
     assert np.array_equal(st["h"][0].cpu().numpy().astype(np.int64), hh)
@@ -134,10 +136,12 @@ def test_config3_softmax_full_size(b):
 
 
 def test_config5_logistic_full_size():
-    """N=1e6, d=4096 fp32 (16.4 GB), lambda=1e-5, b=16, B=64.  Gradient pass: margins of 2000
-    sampled rows against the oracle's definition; the gradient and loss against an fp64
-    recomputation with torch's matmul in row blocks (a library cross-check: the oracle cannot
-    stream 16 GB in seconds).  Inner loop: 48 minibatch steps against the oracle."""
+    """N=1e6, d=4096 fp32 (16.4 GB), lambda=1e-5, b=16, B=64.  Gradient pass: every margin, the
+    gradient and the loss against the oracle run once over the whole matrix on the host (the
+    one slow test: a 16 GB download and some ten seconds of single-threaded fp64), so that row
+    offsets beyond 4 GB are held to the oracle; beside it an fp64 recomputation with torch's
+    matmul in row blocks as a library cross-check.  Inner loop: 48 minibatch steps against the
+    oracle, counters included."""
     N, d, B, T = 1_000_000, 4096, 64, 48
     alpha, mu, lam, seed = 0.05, 0.01, 1e-5, 0
     X, y, _ = inp.logistic_device(N, d, seed=seed)
@@ -177,11 +181,24 @@ def test_config5_logistic_full_size():
     assert rel_l2(st["g"][0, 0].cpu().numpy(), g64.cpu().numpy()) <= TOL
     assert abs(st["scales"][0, 6].item() - loss64.item()) <= TOL * abs(loss64.item())
     del Xb, yb, a, r
+    # the oracle over all 1e6 rows
+    X_h = X.cpu().numpy()
+    y_h = y.cpu().numpy()
+    prob_g = ref.make_problem(N, d, loss=ref.LOGISTIC, b=16, B=B, alpha=alpha, mu=mu, lam=lam,
+                              delta_d=delta_d, seed=seed)
+    phi_ref, g_ref, loss_ref = ref.full_gradient(prob_g, X_h, y_h, w.cpu().numpy().reshape(1, d))
+    phi_gpu = st["phi"][0, :, 0].cpu().numpy()
+    assert rel_l2(phi_gpu, phi_ref[:, 0]) <= TOL
+    assert rel_l2(phi_gpu[-200000:], phi_ref[-200000:, 0]) <= TOL  # rows past the 4 GB offsets
+    assert np.max(np.abs(phi_gpu - phi_ref[:, 0])) <= 1e-4 * np.max(np.abs(phi_ref))
+    assert rel_l2(st["g"][0, 0].cpu().numpy(), g_ref[0]) <= TOL
+    assert abs(st["scales"][0, 6].item() - loss_ref) <= TOL * abs(loss_ref)
+    assert rel_l2(g64.cpu().numpy(), g_ref[0]) <= 1e-9  # the two references agree
     # minibatch inner loop: oracle on the host copy of the quantized data
     Xq_h = Xq[0].cpu().numpy()
-    X_first = X[:4096].cpu().numpy()
-    assert np.array_equal(Xq_h[:4096], ref.quantize_data(X_first, delta_d, 16))
-    y_h = y.cpu().numpy()
+    assert np.array_equal(Xq_h[:4096], ref.quantize_data(X_h[:4096], delta_d, 16))
+    assert np.array_equal(Xq_h[-4096:], ref.quantize_data(X_h[-4096:], delta_d, 16))
+    del X_h
     rng = np.random.default_rng(5)
     phi32 = rng.standard_normal(N).astype(np.float32)          # any margins will do for parity
     g32 = (1e-3 * rng.standard_normal((1, d))).astype(np.float32)
@@ -198,3 +215,5 @@ def test_config5_logistic_full_size():
     assert np.array_equal(st["h"][0].cpu().numpy().astype(np.int64), hh)
     assert np.array_equal(st["z"][0].cpu().numpy().astype(np.int32), out["z"])
     assert np.array_equal(st["w"][0].cpu().numpy(), ref.apply_offset(prob, sc, out["z"], w_before))
+    assert np.array_equal(st["counters"][0].cpu().numpy().astype(np.uint64), out["counters"])
+    assert h.get_stats(0).inner_variant == 2 and h.get_stats(0).n_exchange_timeouts == 0

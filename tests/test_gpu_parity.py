@@ -586,8 +586,17 @@ def test_minibatch_exchange_wait_is_bounded_and_reported():
     P = _run_inner(case, loss, 1, B, b, 1e-5, 1, T, seed, 2, mu=0.05)
     P.h.set_option(hp.OPT_INNER_PARTS, 4)
     P.h.set_option(hp.OPT_EXCHANGE_SPIN_LIMIT, -1)
+    w_before = P.get("w").copy()
     P.h.inner_loop(3)
     assert int(P.get("counters")[0, 3]) == 1
+    # the model is left as it was, the status says why, and the statistics call reports it
+    assert np.array_equal(P.get("w"), w_before)
+    assert P.get("scales")[0, 7] == -2.0
+    with pytest.raises(hp.HalpError) as e:
+        P.h.get_stats(0)
+    assert e.value.code == hp.ERR_EXCHANGE_TIMEOUT
+    assert e.value.stats.status == -2 and e.value.stats.n_exchange_timeouts == 1
+    P.st["scales"][0, 7] = 0.0  # what the next halp_recenter would do
     # with the default limit the same handle gives the oracle's result again
     P.h.set_option(hp.OPT_EXCHANGE_SPIN_LIMIT, 1 << 20)
     P.put("w", case["w"]); P.st["z"].zero_()
@@ -595,5 +604,24 @@ def test_minibatch_exchange_wait_is_bounded_and_reported():
     out = _oracle_inner(case, 0, T)
     assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
     assert int(P.get("counters")[0, 3]) == 0
+    assert np.array_equal(P.get("w")[0], ref.apply_offset(case["mk"](0), case["scales"][0], out["z"], case["w"][0]))
+    assert P.h.get_stats(0).n_exchange_timeouts == 0
     with pytest.raises(hp.HalpError):
         P.h.set_option(hp.OPT_EXCHANGE_SPIN_LIMIT, -2)
+
+
+def test_epoch_refuses_a_shape_no_inner_kernel_covers_before_launching_anything():
+    """A step of 600 rows fits no inner-loop kernel (the general one stops at 512): halp_epoch
+    says so before the gradient pass or the re-scaling have written anything."""
+    N, d, K, B = 700, 20, 3, 600
+    X, y, _ = inp.softmax_sparse(N, d, K, seed=4)
+    P = GpuProblem(X, ref.quantize_data(X, 1 / 127, 8), y, K=K, loss=hp.LOSS_SOFTMAX, B=B, T=5,
+                   delta_d=1 / 127, w0=np.full((1, K, d), 0.25, np.float32))
+    P.st["g"].fill_(7.0); P.st["h"].fill_(3); P.st["scales"].fill_(5.0)
+    with pytest.raises(hp.HalpError) as e:
+        P.h.epoch(0)
+    assert e.value.code == hp.ERR_UNSUPPORTED
+    assert float(P.get("g").min()) == 7.0 and int(P.get("h").min()) == 3
+    assert float(P.get("scales").min()) == 5.0 and float(P.get("w").max()) == 0.25
+    P.h.full_gradient()  # the gradient pass alone still covers the shape
+    assert float(P.get("g").max()) != 7.0
