@@ -217,3 +217,46 @@ def test_config5_logistic_full_size():
     assert np.array_equal(st["w"][0].cpu().numpy(), ref.apply_offset(prob, sc, out["z"], w_before))
     assert np.array_equal(st["counters"][0].cpu().numpy().astype(np.uint64), out["counters"])
     assert h.get_stats(0).inner_variant == 2 and h.get_stats(0).n_exchange_timeouts == 0
+
+
+def test_config2_shape_makes_progress_like_the_oracle():
+    """Configuration 2's regime (d=1024, b=8, alpha=1e-3, T=1e5, kappa ~ 1e3: outside Theorem
+    2's bit condition, so the box of bit centering clips every epoch) on a reduced N with the
+    mu the benchmark uses: three whole epochs through halp_epoch.  The loss falls every epoch
+    and follows the oracle's own run of the same epochs (the two differ in the last bits of
+    the fp32 gradient, hence in a few roundings of h~, not in the trend)."""
+    N, d, T, epochs = 20000, 1024, 100000, 3
+    alpha, mu, seed = 1e-3, 0.3, 3
+    X, y, _ = inp.linreg(N, d, seed=seed, x_var="inv_d", noise=0.1)
+    delta_d = inp.default_delta_d(X, 8)
+    Xq_ref = ref.quantize_data(X, delta_d, 8)
+    st = hp.alloc_state(N, d, b=8)
+    Xd, yd = torch.from_numpy(X).cuda()[None], torch.from_numpy(y).cuda()[None]
+    Xq = torch.zeros((1, N, d), dtype=torch.int8, device="cuda")
+    h = hp.Halp(N, d, b=8, T=T, alpha=alpha, mu=mu, delta_d=delta_d, seed=seed)
+    h.bind(X=Xd, Xq=Xq, y=yd, **st)
+    h.quantize_data()
+    gpu_loss, gpu_clamped = [], []
+    for k in range(epochs):
+        h.epoch(k)
+        s = h.get_stats(0)
+        gpu_loss.append(s.loss); gpu_clamped.append(s.n_clamped_z)
+    h.full_gradient()
+    gpu_loss.append(h.get_stats(0).loss)
+    assert np.array_equal(Xq[0].cpu().numpy(), Xq_ref)
+    prob = ref.make_problem(N, d, b=8, alpha=alpha, mu=mu, delta_d=delta_d, seed=seed)
+    w = np.zeros((1, d), np.float32)
+    ref_loss, ref_clamped = [], []
+    for k in range(epochs):
+        out = ref.epoch(prob, X, Xq_ref, y, w, k, T)
+        ref_loss.append(float(out["scales"][6])); ref_clamped.append(int(out["counters"][0]))
+        w = out["w"]
+    ref_loss.append(ref.full_gradient(prob, X, y, w)[2])
+    assert all(b < a for a, b in zip(gpu_loss, gpu_loss[1:])), gpu_loss
+    assert all(b < a for a, b in zip(ref_loss, ref_loss[1:])), ref_loss
+    assert gpu_loss[-1] < 0.9 * gpu_loss[0]
+    assert abs(gpu_loss[0] - ref_loss[0]) <= TOL * ref_loss[0]   # same start: the fp32 pass
+    for a, b in zip(gpu_loss[1:], ref_loss[1:]):
+        assert abs(a - b) <= 0.01 * b, (gpu_loss, ref_loss)
+    for a, b in zip(gpu_clamped, ref_clamped):                      # the box binds on both sides
+        assert a > 0 and abs(a - b) <= 0.2 * b, (gpu_clamped, ref_clamped)
