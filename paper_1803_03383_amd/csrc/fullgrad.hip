@@ -418,8 +418,9 @@ int launch_narrow(const FgArgs& a, int loss, dim3 grid, hipStream_t s) {
 
 // workgroups per chain when the caller has not fixed the count: two per CU over all chains
 static int fullgrad_auto_parts(const halp_params& p, int num_cus) {
-  if (p.loss == HALP_LOSS_SOFTMAX) {  // two workgroups per CU, tiles of 16 rows
-    int64_t parts = (2 * (int64_t)num_cus + p.R - 1) / p.R;
+  if (p.loss == HALP_LOSS_SOFTMAX) {  // tiles of 16 rows; one (pipelined form) or two workgroups per CU
+    const int per_cu = fullgrad_softmax_pipelined(p.d) ? 1 : 2;
+    int64_t parts = (per_cu * (int64_t)num_cus + p.R - 1) / p.R;
     const int64_t tiles = (p.N + 15) / 16;
     if (parts > tiles) parts = tiles;
     return (int)(parts < 1 ? 1 : parts);

@@ -23,5 +23,7 @@ struct FgArgs {
 // softmax: margins and gradient as two matrix products on the matrix cores
 int fullgrad_softmax_supported(const halp_params& p);
 int launch_fullgrad_softmax(const FgArgs& a, int R, hipStream_t s);
+// true where the pipelined form runs: one workgroup per CU instead of two
+bool fullgrad_softmax_pipelined(int d);
 
 }  // namespace halp

@@ -17,6 +17,8 @@
 // by 256 threads (one per row and class; a row of 16 classes is a DPP row), and the
 // residuals go back through LDS, transposed, as the A operand of the second product.
 // Per-workgroup partial gradients and losses are summed by the common second-stage kernel.
+#include <type_traits>
+
 #include "fullgrad_args.hpp"
 #include "halp_device.hpp"
 
@@ -240,6 +242,432 @@ __global__ __launch_bounds__(256, 2) void fullgrad_softmax_mfma(FgArgs a) {
   }
 }
 
+// ---- pipelined form (d <= 800): specialised waves, three tiles in LDS ---------------------
+// One workgroup of eight waves per CU.  Waves 0-3 do nothing but the two products (one per
+// SIMD, so the matrix pipe of every SIMD has one instruction stream); waves 4-7 move data and
+// take the softmax.  The work on a tile is spread over three periods, a period being two halves
+// closed by a barrier each:
+//                      half A                               half B
+//   matrix waves       margins of tile k (first product)    gradient sum of tile k-1 (second product)
+//   helper waves       start tile k+1 on its way to LDS     softmax of tile k -> residuals of tile k
+// so the matrix waves never wait for a softmax or for memory, and the three tiles in flight
+// (k-1, k, k+1) take three buffers of 16 rows in LDS.  Rows that are whole float4s travel from
+// memory straight into LDS (global_load_lds, 1 KB per instruction, no registers and no LDS
+// stores from the helper waves; the tile has a whole period to land); other rows go through
+// registers, two tiles ahead, and are masked on their way into LDS.
+// Columns are dealt to the matrix waves in groups of 32 (group g to wave g % 4): d = 784 = 24.5
+// groups costs the half group only, not a padding of every wave's share.  The group count of a
+// wave is a compile-time constant of its loop, so that all operand reads of a tile are issued
+// before its first product and the products follow back to back.
+// What bounds it: a helper wave that shares a SIMD with a wave issuing fp32 matrix products gets
+// about one instruction through per product (~30 cycles each, whatever the instruction), and a
+// tile's loads are accepted by the memory pipeline over ~1.4 us; both are longer than the 0.85 us
+// the products of a half take, so the period is set by the helper waves.
+// The compiler may not move instructions across the borders of a phase: left to itself it
+// spreads a phase's LDS traffic and address arithmetic into its neighbours, where they queue
+// behind the other role's work (measured: 0.80 ms against 0.71 ms at N = 960000).
+#define HALP_PHASE_BORDER() __builtin_amdgcn_sched_barrier(0)
+constexpr int kPipeMaxD = 800;
+constexpr int kPipeGroups = 7;   // groups of 32 columns per matrix wave: 4 x 7 x 32 = 896 >= 800
+constexpr int kPipeSlots = 13;   // float4 slots per helper thread and tile: 16 x 200 / 256 = 12.5
+
+__global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool matrix_wave = wave < 4;
+  const int chain = blockIdx.y;
+  const int d = a.d, K = a.K;
+  const int64_t N = a.N, ldx = a.ldx;
+  const float* __restrict__ X = a.X + (int64_t)chain * a.x_chain_stride;
+  const int32_t* __restrict__ y =
+      reinterpret_cast<const int32_t*>(a.y) + (int64_t)chain * a.y_chain_stride;
+  const float* __restrict__ w = a.w + (int64_t)chain * K * d;
+  float* __restrict__ phi = a.phi + (int64_t)chain * N * K;
+
+  // Tiles in dynamic LDS; the small arrays are objects of their own, so that a read of them is
+  // known not to touch a tile that is still on its way from memory into LDS.
+  extern __shared__ __attribute__((aligned(16))) float s_x[];                       // [3][kRows][LDT]
+  __shared__ __attribute__((aligned(16))) float s_pphi[4 * kRows * 16];             // partial margins per matrix wave
+  __shared__ __attribute__((aligned(16))) float s_rt[2 * 16 * kRtStride];           // residuals [2][class][row]
+  const int tile_floats = kRows * LDT;
+
+  const int li = lane & 15, lq = lane >> 4;
+  const int64_t tiles = (N + kRows - 1) / kRows;
+  const int64_t step = a.parts;
+  // local tile k is global tile blockIdx.x + k step, k = 0 .. n-1
+  const int n = blockIdx.x < tiles ? (int)((tiles - blockIdx.x + step - 1) / step) : 0;
+  auto tile_of = [&](int k) { return (int64_t)blockIdx.x + (int64_t)k * step; };
+
+  // columns [d, LDT) of every buffer stay zero for the whole pass (staging writes below d only)
+  for (int k = tid; k < 3 * kRows * (LDT - d); k += 512) {
+    const int r = k / (LDT - d), c = k - r * (LDT - d);
+    s_x[r * LDT + d + c] = 0.f;
+  }
+  // a matrix wave that narrow rows leave without columns never writes its partial margins
+  for (int k = tid; k < 4 * kRows * 16; k += 512) s_pphi[k] = 0.f;
+
+  // ---------------------------------------------------------------- matrix waves: set-up
+  const int ngr = matrix_wave ? max(0, ((d + 31) / 32 - wave + 3) / 4) : 0;  // groups wave, wave+4, ..
+  float wreg[kPipeGroups][2][4];
+  F4 gacc[kPipeGroups][2];
+  // ---------------------------------------------------------------- helper waves: set-up
+  const int ht = tid - 256;
+  const int nf4 = (d + 3) / 4;
+  double loss_acc = 0.0;
+  if (matrix_wave) {
+    // every load unconditional, from a clamped address, and all issued before the first is used
+    auto wcol = [&](int i, int c2, int e) { return 32 * (wave + 4 * i) + 16 * c2 + 4 * lq + e; };
+#pragma unroll
+    for (int i = 0; i < kPipeGroups; ++i)
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          wreg[i][c2][e] = w[(int64_t)min(li, K - 1) * d + min(wcol(i, c2, e), d - 1)];
+    if (a.fscale) {  // the buffer holds v = s w: one correctly rounded division per coordinate
+#pragma unroll
+      for (int i = 0; i < kPipeGroups; ++i)
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            wreg[i][c2][e] = __fdiv_rn(wreg[i][c2][e], a.fscale[min(wcol(i, c2, e), d - 1)]);
+    }
+#pragma unroll
+    for (int i = 0; i < kPipeGroups; ++i)
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          asm volatile("" : "+v"(wreg[i][c2][e]));
+          if (li >= K || wcol(i, c2, e) >= d) wreg[i][c2][e] = 0.f;
+        }
+#pragma unroll
+    for (int i = 0; i < kPipeGroups; ++i) gacc[i][0] = gacc[i][1] = F4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // matrix waves, first product: partial margins [16 rows] x [16 classes] of this wave's columns.
+  // The group count is a compile-time constant (the loop over groups has no branches), so that
+  // every operand read of a tile is issued ahead of the products that use it.
+  auto margins = [&](auto ngr_c, int buf) {
+    constexpr int NGR = decltype(ngr_c)::value;
+    const float* xr = s_x + buf * tile_floats + li * LDT + 32 * wave + 4 * lq;
+    F4 x0[NGR], x1[NGR];
+#pragma unroll
+    for (int i = 0; i < NGR; ++i) {
+      x0[i] = *reinterpret_cast<const F4*>(xr + 128 * i);
+      x1[i] = *reinterpret_cast<const F4*>(xr + 128 * i + 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // all reads are in flight before the first product
+    F4 pa = F4{0.f, 0.f, 0.f, 0.f}, pb = F4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NGR; ++i) {
+      pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[i].x, wreg[i][0][0], pa, 0, 0, 0);
+      pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[i].y, wreg[i][0][1], pb, 0, 0, 0);
+      pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[i].z, wreg[i][0][2], pa, 0, 0, 0);
+      pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[i].w, wreg[i][0][3], pb, 0, 0, 0);
+      pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].x, wreg[i][1][0], pa, 0, 0, 0);
+      pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].y, wreg[i][1][1], pb, 0, 0, 0);
+      pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].z, wreg[i][1][2], pa, 0, 0, 0);
+      pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].w, wreg[i][1][3], pb, 0, 0, 0);
+    }
+    // component r of lane (j, q) is row 4 q + r, class j
+    float* pp = s_pphi + wave * kRows * 16 + (4 * lq) * 16 + li;
+    pp[0] = pa.x + pb.x;
+    pp[16] = pa.y + pb.y;
+    pp[32] = pa.z + pb.z;
+    pp[48] = pa.w + pb.w;
+  };
+  // matrix waves, second product: G[:, this wave's columns] += R^T X, contraction over the rows
+  auto gradient = [&](auto ngr_c, int buf, int par) {
+    constexpr int NGR = decltype(ngr_c)::value;
+    typedef float F2 __attribute__((ext_vector_type(2)));
+    const float* xc = s_x + buf * tile_floats + (4 * lq) * LDT + 32 * wave + 2 * li;
+    const F4 rt = *reinterpret_cast<const F4*>(s_rt + par * 16 * kRtStride + li * kRtStride + 4 * lq);
+    F2 xb[NGR][4];
+#pragma unroll
+    for (int i = 0; i < NGR; ++i)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) xb[i][kk] = *reinterpret_cast<const F2*>(xc + kk * LDT + 128 * i);
+    const float rtk[4] = {rt.x, rt.y, rt.z, rt.w};
+    __builtin_amdgcn_sched_barrier(0);  // all reads are in flight before the first product
+#pragma unroll
+    for (int i = 0; i < NGR; ++i)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        gacc[i][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(rtk[kk], xb[i][kk].x, gacc[i][0], 0, 0, 0);
+        gacc[i][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(rtk[kk], xb[i][kk].y, gacc[i][1], 0, 0, 0);
+      }
+  };
+  // helper waves: thread (row ht / 16, class ht % 16).  Every instruction here competes with
+  // the matrix waves for the SIMD, so the transcendental steps are single hardware instructions
+  // (2^x, log2, reciprocal: 1 ulp each, far inside the pass's 1e-5) and nothing branches.
+  const int phi_off = (ht >> 4) * K + (ht & 15);
+  auto softmax = [&](int64_t tile, int par, int ycur) {
+    const int r = ht >> 4, c = ht & 15;
+    const bool valid = c < K;
+    const float* pp = s_pphi + r * 16 + c;
+    const float logit = ((pp[0] + pp[kRows * 16]) + pp[2 * kRows * 16]) + pp[3 * kRows * 16];
+    const float mx = row_fold(valid ? logit : -INFINITY, [](float x, float y2) { return fmaxf(x, y2); });
+    const float e = valid ? __builtin_amdgcn_exp2f((logit - mx) * 1.4426950408889634f) : 0.f;
+    const float se = row_fold(e, [](float x, float y2) { return x + y2; });
+    const bool live = valid && tile * kRows + r < N;
+    const bool mine = c == ycur;
+    const float rc = live ? e * __builtin_amdgcn_rcpf(se) - (mine ? 1.0f : 0.f) : 0.f;
+    if (live) (phi + tile * kRows * K)[phi_off] = logit;
+    loss_acc += (live && mine) ? (double)(__builtin_amdgcn_logf(se) * 0.6931471805599453f + mx - logit) : 0.0;
+    s_rt[par * 16 * kRtStride + c * kRtStride + r] = rc;
+  };
+
+  // Two loops, one per role, with the same barriers at the same places: the registers of the
+  // two roles (W~ slice and gradient accumulators there, a tile in flight here) never live together.
+  if (matrix_wave) {
+    auto periods = [&](auto ngr_c) {
+      int bprev = 1, bcur = 2, bnext = 0;  // buffers of tiles k - 1, k, k + 1 (tile k in buffer k mod 3)
+      for (int k = -1; k <= n; ++k) {
+        HALP_PHASE_BORDER();
+        if (k >= 0 && k < n) margins(ngr_c, bcur);
+        HALP_PHASE_BORDER();
+        __syncthreads();
+        HALP_PHASE_BORDER();
+        if (k >= 1) gradient(ngr_c, bprev, (k - 1) & 1);
+        HALP_PHASE_BORDER();
+        __syncthreads();
+        HALP_PHASE_BORDER();
+        const int t = bprev; bprev = bcur; bcur = bnext; bnext = t;
+      }
+    };
+    switch (ngr) {  // same barriers in every case
+      case 7: periods(std::integral_constant<int, 7>{}); break;
+      case 6: periods(std::integral_constant<int, 6>{}); break;
+      case 5: periods(std::integral_constant<int, 5>{}); break;
+      case 4: periods(std::integral_constant<int, 4>{}); break;
+      case 3: periods(std::integral_constant<int, 3>{}); break;
+      case 2: periods(std::integral_constant<int, 2>{}); break;
+      case 1: periods(std::integral_constant<int, 1>{}); break;
+      default:  // narrow rows leave this wave without columns: it only keeps the barriers
+        for (int k = -1; k <= n; ++k) {
+          __syncthreads();
+          __syncthreads();
+        }
+        break;
+    }
+    // partial gradient of this workgroup
+    float* pg = a.partial_g + ((int64_t)chain * a.parts + blockIdx.x) * (int64_t)K * d;
+#pragma unroll
+    for (int i = 0; i < kPipeGroups; ++i)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int col = 32 * (wave + 4 * i) + 2 * li + e;
+        if (col < d) {
+          if (4 * lq + 0 < K) pg[(int64_t)(4 * lq + 0) * d + col] = gacc[i][e].x;
+          if (4 * lq + 1 < K) pg[(int64_t)(4 * lq + 1) * d + col] = gacc[i][e].y;
+          if (4 * lq + 2 < K) pg[(int64_t)(4 * lq + 2) * d + col] = gacc[i][e].z;
+          if (4 * lq + 3 < K) pg[(int64_t)(4 * lq + 3) * d + col] = gacc[i][e].w;
+        }
+      }
+  } else {
+    // A tile is 16 nf4 float4s, row after row; thread ht moves float4 number ht + 256 s for
+    // s < NS (a wave reads 1 KB of consecutive addresses per instruction; slots past the tile
+    // repeat its last float4: the same data to the same place).  Tile k + 1 is staged in period k
+    // from register set (k + 1) mod 2, which then takes the request for tile k + 3: two tiles
+    // are always on their way from memory.  Offsets are bytes from a base that is the same for
+    // the whole wave, so a load or a store is one instruction.
+    auto helper = [&](auto ns_c) {
+      constexpr int NS = decltype(ns_c)::value;
+      uint32_t gofs[NS], lofs[NS];
+#pragma unroll
+      for (int s2 = 0; s2 < NS; ++s2) {
+        const int f = min(ht + 256 * s2, kRows * nf4 - 1);
+        const int r = f / nf4, c4 = f - r * nf4;
+        gofs[s2] = (uint32_t)(r * (int)ldx + 4 * c4) * 4u;
+        lofs[s2] = (uint32_t)(r * LDT + 4 * c4) * 4u;
+      }
+      F4 xn[2][NS];
+      int y_req[2] = {0, 0}, y_staged = 0, y_soft = 0;  // labels of row ht / 16: tiles requested / staged / in softmax
+      const uint32_t row_bytes = (uint32_t)ldx * 4u, lds_row_bytes = (uint32_t)LDT * 4u;
+      auto request = [&](auto set_c, int64_t tile) {
+        constexpr int S = decltype(set_c)::value;
+        const char* tb = reinterpret_cast<const char*>(X + tile * kRows * ldx);
+        const int rows_in = (int)min((int64_t)kRows, N - tile * kRows);
+        if (rows_in == kRows) {
+#pragma unroll
+          for (int s2 = 0; s2 < NS; ++s2)
+            xn[S][s2] = __builtin_nontemporal_load(reinterpret_cast<const F4*>(tb + gofs[s2]));
+        } else {  // the last tile: rows past N read row N - 1 (zeroed when staged)
+#pragma unroll
+          for (int s2 = 0; s2 < NS; ++s2) {
+            const int r = (int)(lofs[s2] / lds_row_bytes);
+            const uint32_t back = r >= rows_in ? (uint32_t)(r - (rows_in - 1)) * row_bytes : 0u;
+            xn[S][s2] = __builtin_nontemporal_load(reinterpret_cast<const F4*>(tb + (gofs[s2] - back)));
+          }
+        }
+        y_req[S] = y[min(tile * kRows + (ht >> 4), N - 1)];
+      };
+      auto stage = [&](auto set_c, int buf, int64_t tile) {
+        constexpr int S = decltype(set_c)::value;
+        char* dst = reinterpret_cast<char*>(s_x + buf * tile_floats);
+        const int rows_in = (int)min((int64_t)kRows, N - tile * kRows);
+        if ((d & 3) == 0 && rows_in == kRows) {
+#pragma unroll
+          for (int s2 = 0; s2 < NS; ++s2) *reinterpret_cast<F4*>(dst + lofs[s2]) = xn[S][s2];
+        } else {
+#pragma unroll
+          for (int s2 = 0; s2 < NS; ++s2) {
+            const int r = (int)(lofs[s2] / lds_row_bytes);
+            const int c0 = (int)(lofs[s2] - (uint32_t)r * lds_row_bytes) / 4;
+            F4 v = xn[S][s2];
+            if (r >= rows_in) v = F4{0.f, 0.f, 0.f, 0.f};
+            if (c0 + 1 >= d) v.y = 0.f;
+            if (c0 + 2 >= d) v.z = 0.f;
+            if (c0 + 3 >= d) v.w = 0.f;
+            *reinterpret_cast<F4*>(dst + lofs[s2]) = v;
+          }
+        }
+      };
+      // Requests are unconditional (past this workgroup's last tile they re-read the matrix's last
+      // tile and are never staged), so that the number of loads in flight is the same in every
+      // period and a wait for the older set does not have to wait for the younger one as well.
+      auto clamped = [&](int k) { return min(tile_of(k), tiles - 1); };
+      request(std::integral_constant<int, 0>{}, clamped(0));
+      request(std::integral_constant<int, 1>{}, clamped(1));
+      int bnext = 0;
+      auto period = [&](auto set_c, int k) {
+        y_soft = y_staged;
+        if (k + 1 < n) {
+          stage(set_c, bnext, tile_of(k + 1));
+          y_staged = y_req[decltype(set_c)::value];
+        }
+        request(set_c, clamped(k + 3));
+        __syncthreads();
+        if (k >= 0 && k < n) softmax(tile_of(k), k & 1, y_soft);
+        __syncthreads();
+        bnext = bnext == 2 ? 0 : bnext + 1;
+      };
+      for (int k = -1; k <= n; k += 2) {
+        period(std::integral_constant<int, 0>{}, k);
+        if (k + 1 <= n) period(std::integral_constant<int, 1>{}, k + 1);
+      }
+    };
+    // Rows that are whole float4s go from memory straight into LDS (no registers, no stores
+    // from this wave): a padded tile is cut into blocks of 64 float4 slots = 1 KB of LDS; helper
+    // wave hw moves blocks hw, hw + 4, ..; a lane's slot names the float4 of the matrix it holds
+    // (a slot in a row's padding repeats the row's last float4, so the padding holds finite
+    // numbers; the padding meets zeros of W~ in the first product and columns that are never
+    // stored in the second).  One tile is on its way while the two before it are multiplied; it has
+    // landed when the period's closing barrier (which waits for it) is passed.
+    auto helper_dma = [&]() {
+      const int row_f4 = LDT / 4, total = kRows * row_f4;
+      const int nblocks = (total + 63) / 64;
+      const int hw = wave - 4;
+      const uint32_t row_bytes = (uint32_t)ldx * 4u;
+      uint32_t gofs[kPipeSlots];
+#pragma unroll
+      for (int s2 = 0; s2 < kPipeSlots; ++s2) {
+        const int q = min(64 * (hw + 4 * s2) + lane, total - 1);
+        const int r = q / row_f4, c4 = min(q - r * row_f4, nf4 - 1);
+        gofs[s2] = (uint32_t)(r * (int)ldx + 4 * c4) * 4u;
+      }
+      typedef __attribute__((address_space(1))) const void* GPtr;
+      typedef __attribute__((address_space(3))) void* LPtr;
+      const int nbw = max(0, (nblocks - hw + 3) / 4);  // blocks of this wave
+      // lanes of this wave's last block that lie inside the tile (64: all)
+      const int last_lanes = nbw > 0 ? min(64, total - 64 * (hw + 4 * (nbw - 1))) : 0;
+      // the block count is a compile-time constant: a whole tile takes one m0 update and one load
+      // per block, with nothing else in between
+      auto run = [&](auto nbw_c) {
+        constexpr int NBW = decltype(nbw_c)::value;
+        auto dma = [&](int buf, int64_t tile) {
+          const char* tb = reinterpret_cast<const char*>(X + tile * kRows * ldx);
+          char* lb = reinterpret_cast<char*>(s_x + buf * tile_floats) + 1024 * hw;
+          const int rows_in = (int)min((int64_t)kRows, N - tile * kRows);
+          if (rows_in == kRows) {
+#pragma unroll
+            for (int s2 = 0; s2 + 1 < NBW; ++s2)
+              __builtin_amdgcn_global_load_lds((GPtr)(tb + gofs[s2]), (LPtr)(lb + 4096 * s2), 16, 0, 2);
+            if (NBW > 0 && lane < last_lanes)
+              __builtin_amdgcn_global_load_lds((GPtr)(tb + gofs[NBW > 0 ? NBW - 1 : 0]),
+                                               (LPtr)(lb + 4096 * (NBW > 0 ? NBW - 1 : 0)), 16, 0, 2);
+          } else {  // the last tile: rows past N repeat row N - 1 (their residuals are 0)
+#pragma unroll
+            for (int s2 = 0; s2 < NBW; ++s2) {
+              uint32_t go = gofs[s2];
+              const int r = (int)(go / row_bytes);
+              if (r >= rows_in) go -= (uint32_t)(r - (rows_in - 1)) * row_bytes;
+              if (s2 + 1 < NBW || lane < last_lanes)
+                __builtin_amdgcn_global_load_lds((GPtr)(tb + go), (LPtr)(lb + 4096 * s2), 16, 0, 2);
+            }
+          }
+        };
+        int y_cur = 0, y_nxt = 0, bnext = 0;
+        for (int k = -1; k <= n; ++k) {
+          HALP_PHASE_BORDER();
+          if (k + 1 < n) {
+            y_nxt = y[min(tile_of(k + 1) * kRows + (ht >> 4), N - 1)];
+            dma(bnext, tile_of(k + 1));
+          }
+          HALP_PHASE_BORDER();
+          // this barrier must not wait for the tile in flight: LDS traffic only
+          __builtin_amdgcn_s_waitcnt(0xc07f);
+          __builtin_amdgcn_s_barrier();
+          HALP_PHASE_BORDER();
+          if (k >= 0 && k < n) softmax(tile_of(k), k & 1, y_cur);
+          HALP_PHASE_BORDER();
+          __syncthreads();  // waits for the tile as well
+          HALP_PHASE_BORDER();
+          y_cur = y_nxt;
+          bnext = bnext == 2 ? 0 : bnext + 1;
+        }
+      };
+      switch (nbw) {
+        case 13: run(std::integral_constant<int, 13>{}); break;
+        case 12: run(std::integral_constant<int, 12>{}); break;
+        case 11: run(std::integral_constant<int, 11>{}); break;
+        case 10: run(std::integral_constant<int, 10>{}); break;
+        case 9: run(std::integral_constant<int, 9>{}); break;
+        case 8: run(std::integral_constant<int, 8>{}); break;
+        case 7: run(std::integral_constant<int, 7>{}); break;
+        case 6: run(std::integral_constant<int, 6>{}); break;
+        case 5: run(std::integral_constant<int, 5>{}); break;
+        case 4: run(std::integral_constant<int, 4>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        default: run(std::integral_constant<int, 0>{}); break;
+      }
+    };
+    const int nslots = (kRows * nf4 + 255) / 256;
+    if ((d & 3) == 0) helper_dma();
+    else if (nslots <= 2) helper(std::integral_constant<int, 2>{});
+    else if (nslots <= 7) helper(std::integral_constant<int, 7>{});
+    else helper(std::integral_constant<int, kPipeSlots>{});
+  }
+  // every read of the margins' LDS lies before the loop's last barrier: it carries the loss terms now
+  double* s_loss = reinterpret_cast<double*>(s_pphi);  // 256 doubles in the 4 KB of the margins
+  if (!matrix_wave) s_loss[ht] = loss_acc;
+  __syncthreads();
+  if (tid == 256) {
+    double l = 0.0;
+    for (int t = 0; t < 256; ++t) l += s_loss[t];  // fixed order
+    a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] = l;
+  }
+}
+
+#undef HALP_PHASE_BORDER
+
+int launch_pipe(const FgArgs& a, int R, hipStream_t s) {
+  const int LDT = (a.d + 31) / 32 * 32 + 8;  // 8 mod 16: the 8-byte reads of the second product
+                                             // (rows 4 apart per half-wave) do not collide
+  const size_t smem = (size_t)3 * kRows * LDT * sizeof(float);  // 155136 bytes at most; 6.6 KB more are static
+  auto kern = fullgrad_softmax_pipe;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+    return HALP_ERR_HIP;
+  hipLaunchKernelGGL(kern, dim3(a.parts, R), dim3(512), smem, s, a, LDT);
+  return hip_ok(hipGetLastError());
+}
+
 template <int NG>
 int launch_ng(const FgArgs& a, int R, hipStream_t s) {
   const size_t smem = (size_t)kRows * (4 * 32 * NG + 8) * sizeof(float);
@@ -259,7 +687,10 @@ int fullgrad_softmax_supported(const halp_params& p) {
   return HALP_OK;
 }
 
+bool fullgrad_softmax_pipelined(int d) { return d <= kPipeMaxD; }
+
 int launch_fullgrad_softmax(const FgArgs& a, int R, hipStream_t s) {
+  if (fullgrad_softmax_pipelined(a.d)) return launch_pipe(a, R, s);
   const int ng = (a.d + 127) / 128;  // groups of 32 columns per wave
   if (ng <= 1) return launch_ng<1>(a, R, s);
   if (ng <= 2) return launch_ng<2>(a, R, s);

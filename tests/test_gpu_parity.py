@@ -130,6 +130,16 @@ FG_CASES = [
     (hp.LOSS_SOFTMAX, 1500, 784, 10, 1, 1e-4),
     (hp.LOSS_SOFTMAX, 333, 100, 3, 2, 1e-4),
     (hp.LOSS_SOFTMAX, 64, 257, 16, 1, 0.0),
+    # the pipelined softmax pass (d <= 800): several periods per workgroup, ragged last tile,
+    # a row that is not a whole number of 16-byte pieces, waves without columns, its widest row
+    (hp.LOSS_SOFTMAX, 20011, 784, 10, 1, 1e-4),
+    (hp.LOSS_SOFTMAX, 9000, 799, 7, 2, 0.0),
+    (hp.LOSS_SOFTMAX, 5000, 800, 16, 1, 1e-4),
+    (hp.LOSS_SOFTMAX, 4100, 33, 4, 3, 0.0),
+    (hp.LOSS_SOFTMAX, 17, 96, 2, 1, 0.0),
+    # beyond it, the form with a quarter of the columns per wave
+    (hp.LOSS_SOFTMAX, 700, 801, 10, 1, 1e-4),
+    (hp.LOSS_SOFTMAX, 300, 1024, 16, 2, 0.0),
 ]
 
 
