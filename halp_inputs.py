@@ -48,6 +48,18 @@ def softmax_sparse(N, d, K, seed=0, zero_frac=0.8):
     return X.astype(np.float32), y.astype(np.int32), W_star.T.copy().astype(np.float32)
 
 
+def softmax_dense(N, d, K, seed=0, margin=4.0):
+    """K-class data with dense Gaussian features, the shape of a synthetic classification set
+    with many informative features: X ~ N(0, I/d), W* ~ N(0,1)^{d x K},
+    labels = argmax(margin X W* + Gumbel)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    X = (rng.standard_normal((N, d)) / np.sqrt(d)).astype(np.float32)
+    W_star = rng.standard_normal((d, K)).astype(np.float32)
+    logits = margin * (X @ W_star) + rng.gumbel(size=(N, K))
+    y = np.argmax(logits, axis=1)
+    return X, y.astype(np.int32), W_star.T.copy()
+
+
 def linreg_conditioned(N, d, kappa, seed=0, noise=0.01):
     """Linear regression with a prescribed spectrum (the recipe of the paper's conditioning
     study): X = U S V^T with U (N x d, orthonormal columns) and V (d x d) random orthogonal,

@@ -77,7 +77,7 @@ typedef struct halp_handle halp_handle; /* opaque, library-owned */
 /* The "given" lists of Algorithm 4 plus the problem sizes of eq. (1). */
 typedef struct {
   int64_t N;          /* examples per chain, 1 <= N < 2^31                             */
-  int32_t d;          /* features, >= 1                                                */
+  int32_t d;          /* features, >= 1 (gradient pass: <= 16384 for one-class losses)      */
   int32_t K;          /* classes: 1 for squared / logistic, 2..16 for softmax          */
   int32_t R;          /* independent chains (seeds / problem instances), >= 1          */
   int32_t loss;       /* HALP_LOSS_*                                                   */

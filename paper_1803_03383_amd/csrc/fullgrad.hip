@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void fullgrad_k1(FgArgs a) {
       if (col + 3 < d) pg[col + 3] = gv[k].w;
     }
     if (lane == 0)
-      a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] =
+      a.partial_loss[(int64_t)chain * max(a.parts, a.loss_parts) + blockIdx.x] =
           ((fold_loss[0] + fold_loss[1]) + fold_loss[2]) + fold_loss[3];
   }
 }
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void fullgrad_k1_narrow(FgArgs a) {
     if (col + 2 < d) pg[col + 2] = gv.z;
     if (col + 3 < d) pg[col + 3] = gv.w;
     if (lane == 0)
-      a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] =
+      a.partial_loss[(int64_t)chain * max(a.parts, a.loss_parts) + blockIdx.x] =
           ((fold_loss[0] + fold_loss[1]) + fold_loss[2]) + fold_loss[3];
   }
 }
@@ -310,6 +310,8 @@ __global__ __launch_bounds__(256) void fullgrad_k1_narrow(FgArgs a) {
 struct RedArgs {
   const float* partial_g;
   const double* partial_loss;
+  int loss_parts;       // partial losses per chain (a row of partial_loss has parts_stride entries)
+  int loss_stride;
   const float* w;
   const float* fscale;  // [d] or null: the gradient is handed on as d f / d v_j = g_j / s_j
   float* g;
@@ -358,7 +360,7 @@ __global__ __launch_bounds__(256) void fullgrad_reduce(RedArgs a) {
     }
     if (threadIdx.x == 0) {
       double l = 0.0;
-      for (int p = 0; p < a.parts; ++p) l += a.partial_loss[(int64_t)chain * a.parts + p];
+      for (int p = 0; p < a.loss_parts; ++p) l += a.partial_loss[(int64_t)chain * a.loss_stride + p];
       a.scales[(int64_t)chain * 8 + 6] = l / (double)a.N + 0.5 * a.lambda * red[0];
     }
   }
@@ -386,10 +388,10 @@ int launch_k1(const FgArgs& a, int loss, bool exact, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
+// K = 1: a row per wave up to d = 4096, a row across a workgroup's waves up to 16384
 int fullgrad_supported(const halp_params& p) {
-  const int nv = nv_for(p.d);
   if (p.loss == HALP_LOSS_SOFTMAX) return fullgrad_softmax_supported(p);
-  return nv <= 16 ? HALP_OK : HALP_ERR_UNSUPPORTED;  // d <= 4096
+  return p.d <= fullgrad_k1_wide_max_d() ? HALP_OK : HALP_ERR_UNSUPPORTED;
 }
 
 // narrow rows: lanes per row (0 = the row-per-wave kernel) and rows per batch
@@ -401,6 +403,7 @@ static int narrow_lanes(int d) {
   return g;
 }
 static int rows_per_batch(int d) {
+  if (d > 4096) return fullgrad_k1_wide_rows_per_batch();
   const int g = narrow_lanes(d);
   if (g) return kNarrowGroups * (64 / g);
   const int nv = nv_for(d);
@@ -419,24 +422,50 @@ int launch_narrow(const FgArgs& a, int loss, dim3 grid, hipStream_t s) {
 // workgroups per chain when the caller has not fixed the count: two per CU over all chains
 static int fullgrad_auto_parts(const halp_params& p, int num_cus) {
   if (p.loss == HALP_LOSS_SOFTMAX) {  // tiles of 16 rows; one (pipelined form) or two workgroups per CU
-    const int per_cu = fullgrad_softmax_pipelined(p.d) ? 1 : 2;
-    int64_t parts = (per_cu * (int64_t)num_cus + p.R - 1) / p.R;
     const int64_t tiles = (p.N + 15) / 16;
+    int64_t parts;
+    if (!fullgrad_softmax_one_pass(p.d)) {  // second pass: a workgroup per row split and column block
+      const int ncb = (p.d + kSoftmaxWideBlock - 1) / kSoftmaxWideBlock;
+      parts = (2 * (int64_t)num_cus + (int64_t)ncb * p.R - 1) / ((int64_t)ncb * p.R);
+    } else {
+      const int per_cu = fullgrad_softmax_pipelined(p.d) ? 1 : 2;
+      parts = (per_cu * (int64_t)num_cus + p.R - 1) / p.R;
+    }
     if (parts > tiles) parts = tiles;
     return (int)(parts < 1 ? 1 : parts);
   }
   const int rb = rows_per_batch(p.d);
   const int64_t nblk = (p.N + rb - 1) / rb;
-  int64_t parts = (2 * (int64_t)num_cus + p.R - 1) / p.R;  // two workgroups per CU
-  const int64_t most = (nblk + 3) / 4;                      // one batch per wave at least
+  const bool wide = p.d > 4096;  // a workgroup of up to 16 waves per CU
+  int64_t parts = ((wide ? 1 : 2) * (int64_t)num_cus + p.R - 1) / p.R;  // two workgroups per CU
+  const int64_t most = wide ? nblk : (nblk + 3) / 4;                     // one batch per wave at least
   if (parts > most) parts = most;
   if (parts < 1) parts = 1;
   return (int)parts;
 }
 
+// workgroups that write a partial loss: the first pass of the two-pass softmax form has its own
+// count (two per CU); everywhere else every workgroup of the one kernel writes one
+static int fullgrad_auto_loss_parts(const halp_params& p, int num_cus, int parts) {
+  if (p.loss != HALP_LOSS_SOFTMAX || fullgrad_softmax_one_pass(p.d)) return parts;
+  const int64_t tiles = (p.N + 15) / 16;
+  int64_t lp = (2 * (int64_t)num_cus + p.R - 1) / p.R;
+  if (lp > tiles) lp = tiles;
+  return (int)(lp < 1 ? 1 : lp);
+}
+
 int fullgrad_parts(const halp_handle& h) {
   if (h.fullgrad_blocks > 0) return h.fullgrad_blocks;
   return fullgrad_auto_parts(h.p, h.num_cus);
+}
+
+bool fullgrad_needs_resid(const halp_params& p) {
+  return p.loss == HALP_LOSS_SOFTMAX && !fullgrad_softmax_one_pass(p.d);
+}
+
+int fullgrad_loss_parts(const halp_handle& h) {
+  if (h.fullgrad_blocks > 0) return h.fullgrad_blocks;
+  return fullgrad_auto_loss_parts(h.p, h.num_cus, fullgrad_parts(h));
 }
 
 // What a gradient pass needs beyond the parameters: the caller's buffers and a workspace of
@@ -448,6 +477,8 @@ struct FgPlan {
   float* partial_g;
   double* partial_loss;
   int parts;
+  int loss_parts;  // entries per chain of partial_loss in use (its rows are max(parts, loss_parts) long)
+  float* resid;    // [R][N][16] for the two-pass softmax form, else unused
 };
 
 static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
@@ -462,10 +493,13 @@ static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
   a.x_chain_stride = p.share_data ? 0 : p.N * buf.ldx;
   a.y_chain_stride = p.share_data ? 0 : p.N;
   a.d = p.d; a.K = p.K; a.parts = f.parts; a.fscale = f.fscale;
+  a.loss_parts = f.loss_parts; a.resid = f.resid;
   const dim3 grid(f.parts, p.R);
   const int nv = nv_for(p.d);
   if (p.loss == HALP_LOSS_SOFTMAX) {
     rc = launch_fullgrad_softmax(a, p.R, s);
+  } else if (p.d > 4096) {
+    rc = launch_fullgrad_k1_wide(a, p.loss, p.R, s);
   } else if (const int g = narrow_lanes(p.d)) {
     switch (g) {
       case 4: rc = launch_narrow<4>(a, p.loss, grid, s); break;
@@ -488,12 +522,13 @@ static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
   r.partial_g = f.partial_g; r.partial_loss = f.partial_loss; r.w = buf.w; r.g = buf.g;
   r.scales = buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = f.parts; r.lambda = p.lambda;
   r.fscale = f.fscale; r.d = p.d;
+  r.loss_parts = f.loss_parts; r.loss_stride = f.parts > f.loss_parts ? f.parts : f.loss_parts;
   hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 31) / 32, p.R), dim3(256), 0, s, r);
   return hip_ok(hipGetLastError());
 }
 
 int launch_full_gradient(const halp_handle& h, hipStream_t s) {
-  const FgPlan f{&h.p, &h.buf, h.fscale, h.partial_g, h.partial_loss, h.parts};
+  const FgPlan f{&h.p, &h.buf, h.fscale, h.partial_g, h.partial_loss, h.parts, h.loss_parts, h.resid};
   return launch_full_gradient_plan(f, s);
 }
 
@@ -544,6 +579,8 @@ int device_scratch(DeviceScratch* out) {
 int launch_full_gradient_static(const halp_params& p, const halp_buffers& buf, hipStream_t s) {
   int rc = fullgrad_supported(p);
   if (rc != HALP_OK) return rc;
+  // the two-pass softmax form keeps N x 16 residuals between its passes: not in the fixed array
+  if (p.loss == HALP_LOSS_SOFTMAX && !fullgrad_softmax_one_pass(p.d)) return HALP_ERR_UNSUPPORTED;
   // bytes one workgroup's partial takes per chain: K d floats and a double
   const size_t n = (size_t)p.K * (size_t)p.d;
   const size_t per_part = (size_t)p.R * (n * sizeof(float) + sizeof(double));
@@ -556,7 +593,7 @@ int launch_full_gradient_static(const halp_params& p, const halp_buffers& buf, h
   const size_t g_bytes = ((size_t)p.R * (size_t)parts * n * sizeof(float) + 255) / 256 * 256;
   float* partial_g = reinterpret_cast<float*>(ds.ptr);
   double* partial_loss = reinterpret_cast<double*>(ds.ptr + g_bytes);
-  const FgPlan f{&p, &buf, nullptr, partial_g, partial_loss, (int)parts};
+  const FgPlan f{&p, &buf, nullptr, partial_g, partial_loss, (int)parts, (int)parts, nullptr};
   return launch_full_gradient_plan(f, s);
 }
 

@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256, 2) void fullgrad_softmax_mfma(FgArgs a) {
   if (tid == 0) {
     double l = 0.0;
     for (int t = 0; t < 256; ++t) l += s_loss[t];  // fixed order
-    a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] = l;
+    a.partial_loss[(int64_t)chain * max(a.parts, a.loss_parts) + blockIdx.x] = l;
   }
 }
 
@@ -650,7 +650,7 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
   if (tid == 256) {
     double l = 0.0;
     for (int t = 0; t < 256; ++t) l += s_loss[t];  // fixed order
-    a.partial_loss[(int64_t)chain * a.parts + blockIdx.x] = l;
+    a.partial_loss[(int64_t)chain * max(a.parts, a.loss_parts) + blockIdx.x] = l;
   }
 }
 
@@ -681,15 +681,19 @@ int launch_ng(const FgArgs& a, int R, hipStream_t s) {
 
 }  // namespace
 
-// K <= 16 classes, d <= 1024 (a wave's quarter of the columns stays in registers)
+// K <= 16 classes; d <= 1024 in one pass (a wave's quarter of the columns stays in registers),
+// wider rows in two
 int fullgrad_softmax_supported(const halp_params& p) {
-  if (p.K < 2 || p.K > 16 || p.d > 1024) return HALP_ERR_UNSUPPORTED;
+  if (p.K < 2 || p.K > 16) return HALP_ERR_UNSUPPORTED;
   return HALP_OK;
 }
+
+bool fullgrad_softmax_one_pass(int d) { return d <= 1024; }
 
 bool fullgrad_softmax_pipelined(int d) { return d <= kPipeMaxD; }
 
 int launch_fullgrad_softmax(const FgArgs& a, int R, hipStream_t s) {
+  if (!fullgrad_softmax_one_pass(a.d)) return launch_fullgrad_softmax_wide(a, R, s);
   if (fullgrad_softmax_pipelined(a.d)) return launch_pipe(a, R, s);
   const int ng = (a.d + 127) / 128;  // groups of 32 columns per wave
   if (ng <= 1) return launch_ng<1>(a, R, s);

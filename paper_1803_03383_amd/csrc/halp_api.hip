@@ -138,11 +138,19 @@ int halp_create(halp_handle** out, const halp_params* p) {
   // workspace of the gradient pass, if a kernel covers this shape
   if (fullgrad_supported(h->p) == HALP_OK) {
     h->parts = fullgrad_parts(*h);
+    h->loss_parts = fullgrad_loss_parts(*h);
+    const size_t loss_row = h->parts > h->loss_parts ? h->parts : h->loss_parts;
     h->partial_g_bytes = sizeof(float) * (size_t)p->R * h->parts * (size_t)p->K * p->d;
     if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->partial_g), h->partial_g_bytes),
                  "hipMalloc(partial_g)") ||
         hip_fail(hipMalloc(reinterpret_cast<void**>(&h->partial_loss),
-                           sizeof(double) * (size_t)p->R * h->parts), "hipMalloc(partial_loss)")) {
+                           sizeof(double) * (size_t)p->R * loss_row), "hipMalloc(partial_loss)")) {
+      halp_destroy(h);
+      return HALP_ERR_HIP;
+    }
+    if (fullgrad_needs_resid(h->p) &&
+        hip_fail(hipMalloc(reinterpret_cast<void**>(&h->resid), sizeof(float) * (size_t)p->R * p->N * 16),
+                 "hipMalloc(resid)")) {
       halp_destroy(h);
       return HALP_ERR_HIP;
     }
@@ -153,6 +161,10 @@ int halp_create(halp_handle** out, const halp_params* p) {
     if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->batch_xbuf), slots * 64 * sizeof(long long)),
                  "hipMalloc(batch_xbuf)")) { halp_destroy(h); return HALP_ERR_HIP; }
   }
+  if (p->algorithm != HALP_ALG_SVRG && inner_generic_supported(*p) == HALP_OK &&
+      inner_generic_needs_workspace(*p) &&
+      hip_fail(hipMalloc(reinterpret_cast<void**>(&h->zh_work), inner_generic_workspace_bytes(*p)),
+               "hipMalloc(zh_work)")) { halp_destroy(h); return HALP_ERR_HIP; }
   // every chain starts with the step size and mu of the parameters
   if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->hyper), sizeof(double) * 2 * (size_t)p->R),
                "hipMalloc(hyper)")) { halp_destroy(h); return HALP_ERR_HIP; }
@@ -169,7 +181,9 @@ int halp_destroy(halp_handle* h) {
   if (!h) return HALP_ERR_NULL;
   if (h->partial_g) (void)hipFree(h->partial_g);
   if (h->partial_loss) (void)hipFree(h->partial_loss);
+  if (h->resid) (void)hipFree(h->resid);
   if (h->hyper) (void)hipFree(h->hyper);
+  if (h->zh_work) (void)hipFree(h->zh_work);
   if (h->batch_xbuf) (void)hipFree(h->batch_xbuf);
   for (auto& quad : h->ev)
     for (auto& e : quad)
@@ -268,13 +282,14 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
       if (fullgrad_supported(h->p) != HALP_OK) return HALP_ERR_UNSUPPORTED;
       const int old = h->fullgrad_blocks;
       h->fullgrad_blocks = (int)value;
-      const int parts = fullgrad_parts(*h);
-      if (parts != h->parts) {  // resize the workspace
+      const int parts = fullgrad_parts(*h), loss_parts = fullgrad_loss_parts(*h);
+      if (parts != h->parts || loss_parts != h->loss_parts) {  // resize the workspace
         float* ng = nullptr;
         double* nl = nullptr;
         const size_t bytes = sizeof(float) * (size_t)h->p.R * parts * (size_t)h->p.K * h->p.d;
+        const size_t loss_row = parts > loss_parts ? parts : loss_parts;
         if (hipMalloc(reinterpret_cast<void**>(&ng), bytes) != hipSuccess ||
-            hipMalloc(reinterpret_cast<void**>(&nl), sizeof(double) * (size_t)h->p.R * parts) !=
+            hipMalloc(reinterpret_cast<void**>(&nl), sizeof(double) * (size_t)h->p.R * loss_row) !=
                 hipSuccess) {
           if (ng) (void)hipFree(ng);
           h->fullgrad_blocks = old;
@@ -287,6 +302,7 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
         h->partial_loss = nl;
         h->partial_g_bytes = bytes;
         h->parts = parts;
+        h->loss_parts = loss_parts;
       }
       return HALP_OK;
     }

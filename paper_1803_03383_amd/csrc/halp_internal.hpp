@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "../../include/halp.h"
@@ -23,6 +24,8 @@ struct halp_handle {
   float* partial_g = nullptr;    // [R][parts][K*d]
   double* partial_loss = nullptr;  // [R][parts]
   int parts = 0;                 // workgroups per chain the workspace was sized for
+  int loss_parts = 0;            // partial losses per chain (rows of partial_loss are max(parts, loss_parts) long)
+  float* resid = nullptr;        // [R][N][16] residuals of the two-pass softmax gradient form, or null
   size_t partial_g_bytes = 0;
   const float* fscale = nullptr; // caller's per-feature data scales [d] (device), or null
   // minibatch inner loop split over several workgroups per chain: partial dots and tags
@@ -30,6 +33,7 @@ struct halp_handle {
   int inner_parts = 0;               // workgroups per chain of that kernel, 0 = auto
   int spin_limit = 1 << 20;          // polls before a workgroup stops waiting for the others
   double* hyper = nullptr;       // [R][2] step size and mu of each chain (device)
+  int32_t* zh_work = nullptr;    // general inner kernel: z and h~ of models too large for LDS
   int last_inner_variant = 0;
   // timing: a ring of event quadruples, one per halp_epoch call since timing was switched on
   static constexpr int kTimedEpochs = 32;
@@ -54,6 +58,8 @@ struct TraceBufs {
 int launch_quantize_data(const halp_handle& h, hipStream_t s);
 int fullgrad_supported(const halp_params& p);
 int fullgrad_parts(const halp_handle& h);  // workgroups per chain for this shape
+int fullgrad_loss_parts(const halp_handle& h);
+bool fullgrad_needs_resid(const halp_params& p);
 int launch_full_gradient(const halp_handle& h, hipStream_t s);
 // the same pass with its workspace in the library's fixed device array: no allocation
 int launch_full_gradient_static(const halp_params& p, const halp_buffers& buf, hipStream_t s);
@@ -63,6 +69,8 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_softmax_supported(const halp_handle& h);
 int launch_inner_softmax(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_generic_supported(const halp_params& p);
+bool inner_generic_needs_workspace(const halp_params& p);
+size_t inner_generic_workspace_bytes(const halp_params& p);
 int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s);
 int inner_batch_supported(const halp_handle& h);
 int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s);

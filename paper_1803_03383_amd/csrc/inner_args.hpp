@@ -17,6 +17,7 @@ struct InArgs {
   const double* scales; // [R][8]
   const double* hyper;  // [R][2] step size and mu of each chain
   uint64_t* counters;   // [R][4]
+  int32_t* zh_work;     // general kernel: z and h~ of models too large for LDS, [R][2][K d] int32, or null
   int64_t N, ldxq, T;
   int64_t xq_chain_stride, y_chain_stride;  // elements; 0 when chains share the data
   int d, K, B, loss;
@@ -33,6 +34,7 @@ inline InArgs make_inner_args(const halp_handle& h, uint32_t epoch) {
   InArgs a;
   a.Xq = h.buf.Xq; a.phi = h.buf.phi; a.y = h.buf.y; a.h = h.buf.h; a.z = h.buf.z; a.w = h.buf.w;
   a.scales = h.buf.scales; a.counters = h.buf.counters; a.hyper = h.hyper;
+  a.zh_work = nullptr;
   a.N = p.N; a.ldxq = h.buf.ldxq; a.T = p.T;
   a.xq_chain_stride = p.share_data ? 0 : p.N * h.buf.ldxq;
   a.y_chain_stride = p.share_data ? 0 : p.N;

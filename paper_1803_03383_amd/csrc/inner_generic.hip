@@ -45,10 +45,14 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
     return;
   }
 
+  // z and h~ as 32-bit integers: in LDS, or -- a model too large for it -- in this chain's part
+  // of a device-memory workspace (the waves of a workgroup share the CU's cache, and every
+  // hand-over between them below is a barrier)
   extern __shared__ unsigned char smem_raw[];
-  int32_t* zs = reinterpret_cast<int32_t*>(smem_raw);
-  int32_t* hs = zs + n;
-  long long* idxs = reinterpret_cast<long long*>(hs + n + (n & 1));
+  const int nz = n + (n & 1);
+  int32_t* zs = a.zh_work ? a.zh_work + (int64_t)chain * 2 * nz : reinterpret_cast<int32_t*>(smem_raw);
+  int32_t* hs = zs + nz;
+  long long* idxs = reinterpret_cast<long long*>(a.zh_work ? smem_raw : smem_raw + sizeof(int32_t) * 2 * nz);
   long long* Ds = idxs + B;
   double* es = reinterpret_cast<double*>(Ds + (int64_t)B * K);  // softmax: exp terms [B*K][2]
   double* rowst = es + 2 * (int64_t)B * K;                       // per row: max0, max1, sum0, sum1
@@ -301,16 +305,26 @@ __global__ __launch_bounds__(512) void inner_generic_kernel(InArgs a) {
 
 }  // namespace
 
-// LDS the kernel needs: z and h~ as int32, and per row of the step its index, dots, scalars
-static size_t generic_smem(const halp_params& p) {
-  const int64_t n = (int64_t)p.K * p.d;
-  return (size_t)(2 * n + (n & 1)) * 4 + (size_t)p.B * 8 + (size_t)p.B * p.K * 8 +
-         (size_t)p.B * p.K * 16 + (size_t)p.B * 32 + (size_t)p.B * p.K * 4;
+// LDS the kernel needs per row of a step (index, dots, scalars), and for z and h~ as int32
+static size_t generic_step_smem(const halp_params& p) {
+  return (size_t)p.B * 8 + (size_t)p.B * p.K * 8 + (size_t)p.B * p.K * 16 + (size_t)p.B * 32 +
+         (size_t)p.B * p.K * 4;
 }
+static size_t generic_model_smem(const halp_params& p) {
+  const int64_t n = (int64_t)p.K * p.d;
+  return (size_t)(2 * (n + (n & 1))) * 4;
+}
+constexpr size_t kGenericSmemCap = 150 * 1024;
 
-// the model and a step's scalars must fit the LDS of one CU; at most 512 rows per step
+// a model that does not fit LDS beside a step's scalars lives in device memory
+bool inner_generic_needs_workspace(const halp_params& p) {
+  return generic_step_smem(p) + generic_model_smem(p) > kGenericSmemCap;
+}
+size_t inner_generic_workspace_bytes(const halp_params& p) { return (size_t)p.R * generic_model_smem(p); }
+
+// at most 512 rows per step, and their scalars must fit the LDS of one CU
 int inner_generic_supported(const halp_params& p) {
-  return (generic_smem(p) > 150 * 1024 || p.B > 512) ? HALP_ERR_UNSUPPORTED : HALP_OK;
+  return (generic_step_smem(p) > kGenericSmemCap || p.B > 512) ? HALP_ERR_UNSUPPORTED : HALP_OK;
 }
 
 int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& tr, hipStream_t s) {
@@ -318,7 +332,10 @@ int launch_inner_generic(const halp_handle& h, uint32_t epoch, const TraceBufs& 
   InArgs a = make_inner_args(h, epoch);
   a.tr = tr;
   if (inner_generic_supported(p) != HALP_OK) return HALP_ERR_UNSUPPORTED;
-  const size_t smem = generic_smem(p);
+  const bool outside = inner_generic_needs_workspace(p);
+  if (outside && !h.zh_work) return HALP_ERR_UNSUPPORTED;
+  a.zh_work = outside ? h.zh_work : nullptr;
+  const size_t smem = generic_step_smem(p) + (outside ? 0 : generic_model_smem(p));
   const int threads = 512;
   hipError_t e;
   if (p.b == 8) {

@@ -260,3 +260,54 @@ def test_config2_shape_makes_progress_like_the_oracle():
         assert abs(a - b) <= 0.01 * b, (gpu_loss, ref_loss)
     for a, b in zip(gpu_clamped, ref_clamped):                      # the box binds on both sides
         assert a > 0 and abs(a - b) <= 0.2 * b, (gpu_clamped, ref_clamped)
+
+
+def test_ten_class_ten_thousand_feature_epoch():
+    """The shape of the paper's synthetic classification set (Sec. 5.2 and the appendix on
+    clipping: 10 classes, 10 000 features, 7500 examples; the records themselves are not
+    reproduced -- seeded stand-in data): halp_epoch runs it.  Gradient pass (the two-pass
+    softmax form) against the oracle, then -- with the oracle's gradient and margins handed in
+    -- bit centering and 150 inner steps on the general kernel, whose 100 000-coordinate model
+    lives in device memory, bit for bit."""
+    N, d, K, T, b = 7500, 10000, 10, 150, 8
+    alpha, mu, lam, seed = 0.5, 0.1, 1e-4, 9
+    X, y, _ = inp.softmax_sparse(N, d, K, seed=seed, zero_frac=0.5)
+    delta_d = inp.default_delta_d(X, b)
+    Xq_ref = ref.quantize_data(X, delta_d, b)
+    rng = np.random.default_rng(4)
+    W0 = (0.01 * rng.standard_normal((1, K, d))).astype(np.float32)
+    st = hp.alloc_state(N, d, K=K, b=b)
+    st["w"].copy_(torch.from_numpy(W0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    Xq = torch.zeros((1, N, d), dtype=torch.int8, device="cuda")
+    h = hp.Halp(N, d, K=K, loss=hp.LOSS_SOFTMAX, b=b, T=T, alpha=alpha, mu=mu, lam=lam,
+                delta_d=delta_d, seed=seed)
+    h.bind(X=Xd, Xq=Xq, y=yd, **st)
+    h.quantize_data()
+    h.epoch(0)   # the whole outer iteration runs at this shape
+    torch.cuda.synchronize()
+    s0 = h.get_stats(0)
+    assert s0.status == 0 and s0.inner_variant == 1 and np.isfinite(s0.loss)
+    assert np.array_equal(Xq[0].cpu().numpy(), Xq_ref)
+    # phase by phase against the oracle, from the same start
+    st["w"].copy_(torch.from_numpy(W0))
+    h.full_gradient()
+    torch.cuda.synchronize()
+    prob = ref.make_problem(N, d, K=K, loss=ref.SOFTMAX, b=b, alpha=alpha, mu=mu, lam=lam,
+                            delta_d=delta_d, seed=seed)
+    phi_ref, g_ref, loss_ref = ref.full_gradient(prob, X, y, W0[0])
+    assert rel_l2(st["phi"][0].cpu().numpy(), phi_ref) <= TOL
+    assert rel_l2(st["g"][0].cpu().numpy(), g_ref) <= TOL
+    assert abs(st["scales"][0, 6].item() - loss_ref) <= TOL * abs(loss_ref)
+    assert abs(s0.loss - loss_ref) <= TOL * abs(loss_ref)
+    st["g"][0].copy_(torch.from_numpy(g_ref.astype(np.float32)))
+    st["phi"][0].copy_(torch.from_numpy(phi_ref.astype(np.float32)))
+    h.recenter(1)
+    h.inner_loop(1)
+    torch.cuda.synchronize()
+    sc, hh, _ = ref.recenter(prob, g_ref.astype(np.float32), 1)
+    out = ref.inner_loop(prob, Xq_ref, phi_ref.astype(np.float32), y, hh, sc, 1, T)
+    assert np.array_equal(st["h"][0].cpu().numpy().astype(np.int64), hh)
+    assert np.array_equal(st["z"][0].cpu().numpy().astype(np.int32), out["z"])
+    assert np.array_equal(st["counters"][0].cpu().numpy().astype(np.uint64), out["counters"])
+    assert np.any(out["z"] != 0)

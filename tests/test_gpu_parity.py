@@ -137,6 +137,16 @@ FG_CASES = [
     (hp.LOSS_SOFTMAX, 5000, 800, 16, 1, 1e-4),
     (hp.LOSS_SOFTMAX, 4100, 33, 4, 3, 0.0),
     (hp.LOSS_SOFTMAX, 17, 96, 2, 1, 0.0),
+    # rows wider than a wave holds (K = 1: the row cut across the waves of a workgroup)
+    (hp.LOSS_SQUARED, 403, 4097, 1, 1, 0.0),
+    (hp.LOSS_LOGISTIC, 301, 5000, 1, 2, 1e-5),
+    (hp.LOSS_SQUARED, 257, 10000, 1, 1, 1e-3),
+    (hp.LOSS_LOGISTIC, 130, 16384, 1, 1, 0.0),
+    # softmax on rows wider than a tile on chip: two passes
+    (hp.LOSS_SOFTMAX, 333, 1025, 3, 2, 1e-4),
+    (hp.LOSS_SOFTMAX, 260, 4097, 16, 1, 0.0),
+    (hp.LOSS_SOFTMAX, 1001, 5000, 10, 1, 1e-4),
+    (hp.LOSS_SOFTMAX, 515, 10000, 10, 1, 1e-4),
     # beyond it, the form with a quarter of the columns per wave
     (hp.LOSS_SOFTMAX, 700, 801, 10, 1, 1e-4),
     (hp.LOSS_SOFTMAX, 300, 1024, 16, 2, 0.0),
@@ -635,3 +645,19 @@ def test_epoch_refuses_a_shape_no_inner_kernel_covers_before_launching_anything(
     assert float(P.get("scales").min()) == 5.0 and float(P.get("w").max()) == 0.25
     P.h.full_gradient()  # the gradient pass alone still covers the shape
     assert float(P.get("g").max()) != 7.0
+
+
+def test_general_inner_loop_with_the_model_in_device_memory():
+    """K d = 20 000 coordinates of z and h~ do not fit LDS as 32-bit integers: the general kernel
+    keeps them in its device-memory workspace.  Softmax, minibatch of 3, L2 draws; bit-exact."""
+    loss, N, d, K, B, b, lam, T = hp.LOSS_SOFTMAX, 150, 2000, 10, 3, 8, 1e-2, 60
+    seed = 77
+    case = _inner_case(loss, N, d, K, B, b, lam, 2, T, seed, mu=0.05)
+    P = _run_inner(case, loss, K, B, b, lam, 2, T, seed, 1, mu=0.05)
+    P.h.inner_loop(3)
+    assert P.h.get_stats(0).inner_variant == 1
+    for r in range(2):
+        out = _oracle_inner(case, r, T)
+        assert np.array_equal(P.get("z")[r].astype(np.int32), out["z"])
+        assert np.array_equal(P.get("counters")[r].astype(np.uint64), out["counters"])
+        assert np.array_equal(P.get("w")[r], ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r]))
