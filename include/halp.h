@@ -174,6 +174,14 @@ typedef struct {
                                     16-bit halves.  0 (default): taken when every SIMD holds two
                                     chains or more; 1: wherever that shape is launched; 2: never.
                                     Results do not depend on it                                */
+#define HALP_OPT_INNER_HELPERS 10 /* register-resident inner loop with two or four waves per
+                                    chain and at most two strips per lane: a helper wave beside
+                                    every chain wave draws the rounding bits, fetches the sampled
+                                    rows and refills the step-indexed draws, so that the chain
+                                    waves issue the step's dependent chain and little else.
+                                    0 (default): taken while a CU holds at most one chain
+                                    (R <= CUs); 1: wherever that shape is launched; 2: never.
+                                    Results do not depend on it                                */
 
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */

@@ -272,6 +272,10 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
       if (value < 0 || value > 2) return HALP_ERR_INVALID;
       h->inner_packed = (int)value;
       return HALP_OK;
+    case HALP_OPT_INNER_HELPERS:
+      if (value < 0 || value > 2) return HALP_ERR_INVALID;
+      h->inner_helpers = (int)value;
+      return HALP_OK;
     case HALP_OPT_INNER_WAVES:
       if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
         return HALP_ERR_INVALID;

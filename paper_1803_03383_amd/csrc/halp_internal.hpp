@@ -19,6 +19,7 @@ struct halp_handle {
   int fullgrad_blocks = 0;
   bool option2 = false; // option II of Algorithms 1-3 for the end of an epoch
   int inner_waves = 0;  // waves per chain of the register-resident inner loop, 0 = auto
+  int inner_helpers = 0;  // helper waves beside the chain waves of that loop: 0 auto, 1 wherever built, 2 never
   int inner_packed = 0;  // packed 8-bit form of that loop: 0 auto, 1 wherever it exists, 2 never
   // library-owned workspace of the gradient pass: per-workgroup partial sums
   float* partial_g = nullptr;    // [R][parts][K*d]

@@ -7,6 +7,8 @@ namespace halp {
 
 int launch_inner_reg_b8(const InArgs& a, int nw, int upl, int R, bool packed, hipStream_t s);
 int launch_inner_reg_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
+int launch_inner_reg_helped_b8(const InArgs& a, int nw, int upl, int R, hipStream_t s);
+int launch_inner_reg_helped_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
 
 namespace {
 
@@ -81,6 +83,12 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
     sh.upl /= 2;
   }
   if (!launchable(sh)) return HALP_ERR_UNSUPPORTED;
+  // Few chains, two or four waves each: a helper wave beside every chain wave takes whatever
+  // does not depend on z off the step's dependent chain.  Worth it while a CU holds one chain.
+  const bool helped_built = (sh.nw == 2 || sh.nw == 4) && sh.upl <= 2;
+  if (helped_built && (h.inner_helpers == 1 || (h.inner_helpers == 0 && (int64_t)p.R <= h.num_cus)))
+    return p.b == 8 ? launch_inner_reg_helped_b8(a, sh.nw, sh.upl, p.R, s)
+                    : launch_inner_reg_helped_b16(a, sh.nw, sh.upl, p.R, s);
   // 8 bits, one wave per chain: the packed form once every SIMD holds two chains or more (its
   // steps issue fewer instructions but take longer alone), or as HALP_OPT_INNER_PACKED says
   const bool many = (int64_t)p.R >= 8 * (int64_t)h.num_cus;

@@ -1,0 +1,9 @@
+// 16-bit instantiations of the register-resident inner loop with helper waves
+// (see inner_reg_helped_impl.hpp).
+#include "inner_reg_helped_impl.hpp"
+
+namespace halp {
+int launch_inner_reg_helped_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s) {
+  return innerhelp::launch_bits<16>(a, nw, upl, R, s);
+}
+}  // namespace halp

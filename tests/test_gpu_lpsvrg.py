@@ -92,11 +92,13 @@ def test_inner_loop_bit_exact(loss, N, d, K, B, b, R, T, variants):
     outs = [ref.inner_loop(case["mk"](r), case["Xq"][r], case["phi"][r], case["y"][r], case["h"][r],
                            case["scales"][r], 3, T, z0=case["z"][r]) for r in range(R)]
     assert any(not np.array_equal(o["z"], case["z"][r]) for r, o in enumerate(outs))
-    for variant in variants:
+    # the register kernel with the library's choice of helper waves and without them
+    for variant, helpers in [(v, hw) for v in variants for hw in ((0, 2) if v == 2 else (0,))]:
         P = _problem(case, loss, K, B, b, R, T, seed, alpha, delta)
         P.put("phi", case["phi"]); P.put("h", case["h"]); P.put("scales", case["scales"])
         P.put("z", case["z"])
         P.h.set_option(hp.OPT_INNER_VARIANT, variant)
+        P.h.set_option(hp.OPT_INNER_HELPERS, helpers)
         P.h.inner_loop(3)
         z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
         assert P.h.get_stats(0).inner_variant == variant

@@ -302,16 +302,20 @@ INNER_REG_CASES = [
 
 # (kernel variant, waves per chain): the register-resident kernel in every launch shape, then
 # the generic kernel; the result must not depend on the choice
-KERNELS = [(2, 0), (2, 1), (2, 2), (2, 4), (2, 16), (1, 0)]
+# With two or four waves per chain and at most two strips per lane the library puts a helper
+# wave beside every chain wave (third entry 0: its choice, which is "yes" for these few chains);
+# 2 switches the helpers off, so that the plain several-wave kernel stays covered.
+KERNELS = [(2, 0, 0), (2, 1, 0), (2, 2, 0), (2, 4, 0), (2, 2, 2), (2, 4, 2), (2, 16, 0), (1, 0, 0)]
 
 
-@pytest.mark.parametrize("variant,waves", KERNELS)
+@pytest.mark.parametrize("variant,waves,helpers", KERNELS)
 @pytest.mark.parametrize("loss,N,d,b,lam,R,T,mu", INNER_REG_CASES)
-def test_inner_loop_bit_exact(loss, N, d, b, lam, R, T, mu, variant, waves):
+def test_inner_loop_bit_exact(loss, N, d, b, lam, R, T, mu, variant, waves, helpers):
     seed = 40 + d + T
     case = _inner_case(loss, N, d, 1, 1, b, lam, R, T, seed, mu=mu)
     P = _run_inner(case, loss, 1, 1, b, lam, R, T, seed, variant, mu=mu)
     P.h.set_option(hp.OPT_INNER_WAVES, waves)
+    P.h.set_option(hp.OPT_INNER_HELPERS, helpers)
     P.h.inner_loop(3)
     z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
     assert P.h.get_stats(0).inner_variant == variant
@@ -323,6 +327,36 @@ def test_inner_loop_bit_exact(loss, N, d, b, lam, R, T, mu, variant, waves):
         assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
     if mu > 100:
         assert cnt[0, 0] > 0  # the saturating case really saturates
+
+
+@pytest.mark.parametrize("T", [0, 1, 2, 7, 8, 15, 16, 17, 31, 33, 255, 256, 257, 513])
+@pytest.mark.parametrize("loss,d,b,lam,waves", [
+    (hp.LOSS_SQUARED, 512, 8, 0.0, 4),      # one strip per lane, four chain waves
+    (hp.LOSS_SQUARED, 1000, 8, 5e-2, 4),    # two strips per lane, ragged, frequent L2 draws
+    (hp.LOSS_LOGISTIC, 200, 8, 1e-3, 2),    # two chain waves, the second partly filled
+    (hp.LOSS_LOGISTIC, 300, 16, 0.0, 2),    # 16 bits, two strips per lane
+])
+def test_inner_loop_with_helper_waves_every_epoch_length(loss, d, b, lam, waves, T):
+    """The form with helper waves hands records over two steps ahead, requests rows 16 steps
+    ahead and refills the step-indexed draws every 256 steps: epoch lengths around each of
+    those spans, forced on (option 1) so that no other kernel can stand in."""
+    N, R = 150, 2
+    seed = 900 + d + T
+    case = _inner_case(loss, N, d, 1, 1, b, lam, R, T, seed, mu=0.2)
+    P = _run_inner(case, loss, 1, 1, b, lam, R, T, seed, 2, mu=0.2)
+    P.h.set_option(hp.OPT_INNER_WAVES, waves)
+    P.h.set_option(hp.OPT_INNER_HELPERS, 1)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    for r in range(R):
+        out = _oracle_inner(case, r, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        assert np.array_equal(w[r], ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r]))
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    for bad in (-1, 3):
+        with pytest.raises(hp.HalpError) as e:
+            P.h.set_option(hp.OPT_INNER_HELPERS, bad)
+        assert e.value.code == hp.ERR_INVALID
 
 
 @pytest.mark.parametrize("loss,N,d,b,lam,R,T,mu", [c for c in INNER_REG_CASES if c[3] == 8 and c[2] <= 1024])
