@@ -49,6 +49,13 @@ WORKLOADS = {
 }
 
 
+def traffic_source(workload):
+    """Where a `traffic` figure of this line comes from: a committed counter summary, not this run."""
+    rel = f"profiles/{workload}_hbm_traffic.md"
+    return (f"{rel} (rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier run of this workload, "
+            "not measured by this run)") if os.path.exists(os.path.join(ROOT, rel)) else None
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 counter summary, or None."""
     path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")
@@ -131,6 +138,50 @@ def chip_filled_inner_loop(hp, inp, torch, cfg, chains=2048, epochs=3):
     return out
 
 
+def step_latency_floor(hp, torch, T, inner_ms, waves=4, steps=65536):
+    """The dependent chain of one 8-bit step (multiply-adds, DPP fold, one LDS word per wave and
+    a barrier, the fp64 path of gamma, the update) run alone by the library's micro-kernel, one
+    workgroup per CU: the time per step no several-wave kernel with one chain per CU can beat,
+    and the share of it the measured inner loop reaches."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out = torch.empty(cus * waves * 64, dtype=torch.int32, device="cuda")
+    hp.debug_step_latency(waves, 8192, cus, out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = None
+    for _ in range(3):
+        torch.cuda.synchronize()
+        e0.record()
+        hp.debug_step_latency(waves, steps, cus, out)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    ns = best * 1e6 / steps
+    return dict(kernel="step_latency_kernel", waves_per_chain=waves, chain_ns_per_step=ns,
+                bound_ms=ns * T * 1e-6, achieved_ms=inner_ms, frac=ns * T * 1e-6 / inner_ms,
+                what="critical path of a step (dot, DPP fold, LDS word + barrier, fp64 scalar "
+                     "path, update) measured alone; frac = bound_ms / achieved_ms")
+
+
+def c2_inner_loop(hp, inp, torch, T=20000):
+    """Step rate of the single-chain configuration (N=100000, d=1024, b=8) at a reduced number
+    of inner steps per epoch."""
+    cfg = dict(WORKLOADS["c2"])
+    cfg["T"] = T
+    h, X, Xq, y, st, _ = make_problem(hp, inp, torch, cfg)
+    h.set_option(hp.OPT_TIMING, 1)
+    for k in range(3):
+        h.epoch(k)
+    s = h.get_stats(0)
+    out = dict(N=cfg["N"], d=cfg["d"], K=1, b=8, B=1, T=T, T_of_the_configuration=WORKLOADS["c2"]["T"],
+               inner_variant=s.inner_variant, ms_inner_loop=s.ms_inner_loop,
+               ms_full_gradient=s.ms_full_gradient, steps_per_s=T / (s.ms_inner_loop * 1e-3),
+               feature_updates_per_s=T * cfg["d"] / (s.ms_inner_loop * 1e-3), loss=s.loss)
+    h.close()
+    del X, Xq, y, st
+    return out
+
+
 def read_ceiling(hp, torch, t, reps=5):
     """GB/s of the library's read-only yardstick kernel over tensor t (each byte read once)."""
     out = torch.empty(2048, dtype=torch.int32, device=t.device)
@@ -168,7 +219,8 @@ def c5_full_gradient(hp, inp, torch, reps=5):
     out = dict(workload="binary logistic N=1e6 d=4096 fp32 (16.4 GB)", ms=mean, ms_min=float(min(ms)),
                achieved=nbytes / mean / 1e6, peak=HBM_PEAK_GBS, unit="GB/s",
                frac=nbytes / mean / 1e6 / HBM_PEAK_GBS, bytes=nbytes,
-               traffic=measured_traffic("fullgrad_k1", "c5"), read_only_kernel_GBs=ceiling,
+               traffic=measured_traffic("fullgrad_k1", "c5"), traffic_source=traffic_source("c5"),
+               read_only_kernel_GBs=ceiling,
                frac_of_read_only_kernel=nbytes / mean / 1e6 / ceiling, loss=h.get_stats(0).loss)
     h.close()
     # the same configuration's minibatch inner loop (B=64, b=16) at a reduced step count
@@ -188,6 +240,7 @@ def c5_full_gradient(hp, inp, torch, reps=5):
                              us_per_step=s.ms_inner_loop / T * 1e3,
                              row_bytes_per_step=64 * d * 2,
                              traffic=measured_traffic("inner_batch_kernel", "c5"),
+                             traffic_source=traffic_source("c5"),
                              exchange_timeouts=int(st["counters"][:, 3].sum().item()))
     h.close()
     del X, y, st, Xq
@@ -385,6 +438,8 @@ def main():
                     help="model scale of --algorithm lpsvrg (teacher weights are N(0,1))")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
+    ap.add_argument("--no-side", action="store_true",
+                    help="skip the step rates of the other configurations' inner loops")
     ap.add_argument("--cpu-chains", type=int, default=64)
     ap.add_argument("--inner-waves", type=int, default=0, help="waves per chain (0 = library's choice)")
     ap.add_argument("--chains", type=int, default=0,
@@ -459,7 +514,10 @@ def main():
     inner_ms, fg_ms = stats.ms_inner_loop, stats.ms_full_gradient
     # fp32 SVRG: one FMA for the dot, one FMA and one subtraction for the update per coordinate
     laneops = 3.0 if args.algorithm == "svrg" else LANEOPS_PER_UPDATE_B8
-    inner_kernel = "inner_svrg_kernel" if args.algorithm == "svrg" else "inner_reg_kernel"
+    # at the headline shape (few chains, four waves each) the register kernel with helper waves runs
+    helped = args.algorithm != "svrg" and R <= 256 and args.inner_waves in (0, 2, 4) and d <= 1024
+    inner_kernel = "inner_svrg_kernel" if args.algorithm == "svrg" else (
+        "inner_reg_helped_kernel" if helped else "inner_reg_kernel")
     alu_achieved = updates * laneops / (inner_ms * 1e-3)
     fg_bytes = (1 if cfg.get("share_data") else R) * N * (4 * d + 4 + 4) + \
         (R * N * 4 if cfg.get("share_data") else 0)
@@ -480,16 +538,20 @@ def main():
                      "peak": ALU_PEAK_LANEOPS / 1e12, "unit": "Tlane-op/s",
                      "frac": alu_achieved / ALU_PEAK_LANEOPS,
                      "traffic": measured_traffic(inner_kernel, wl_key),
+                     "traffic_source": traffic_source(wl_key),
                      "ms": inner_ms, "feature_updates_per_s": updates / (inner_ms * 1e-3),
                      "steps_per_s_per_chain": T / (inner_ms * 1e-3)},
         "roofline_full_gradient": {"kernel": "fullgrad_k1", "bound": "hbm", "achieved": fg_gbs,
                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fg_gbs / HBM_PEAK_GBS,
-                                   "traffic": measured_traffic("fullgrad_k1", wl_key), "ms": fg_ms, "bytes": fg_bytes},
+                                   "traffic": measured_traffic("fullgrad_k1", wl_key),
+                                   "traffic_source": traffic_source(wl_key), "ms": fg_ms, "bytes": fg_bytes},
         "ms_recenter": stats.ms_recenter,
         "loss_first_timed": loss0, "loss_last": loss1, "clamped_coordinates_last_epoch": clamped,
         "paper_context": "paper reports HALP up to 4x faster per epoch than its AVX2 fp64 SVRG on 56 "
                          "Xeon E7-4850 v3 cores (Table 3); no GPU or bandwidth figure is published",
     }
+    if args.algorithm == "halp" and args.workload == "c4" and args.chains in (0, WORKLOADS["c4"]["R"]):
+        out["roofline"]["latency"] = step_latency_floor(hp, torch, T, inner_ms)
     if args.algorithm == "halp":  # the same matrix through a kernel that only reads
         ceiling = read_ceiling(hp, torch, X)
         out["roofline_full_gradient"]["read_only_kernel_GBs"] = ceiling
@@ -507,6 +569,12 @@ def main():
     torch.cuda.empty_cache()
     if args.algorithm == "halp" and args.workload == "c4" and args.chains in (0, WORKLOADS["c4"]["R"]):
         out["roofline_chip_filled"] = chip_filled_inner_loop(hp, inp, torch, WORKLOADS["c4"])
+    if not args.no_side and args.algorithm == "halp" and args.workload == "c4":
+        # the other configurations' inner loops (reduced step counts) and the softmax gradient pass
+        side = {"c2_b8_B1": c2_inner_loop(hp, inp, torch)}
+        side.update(side_inner_loop(hp, inp, torch, "c3", 2000))
+        out["side_inner_loops"] = side
+        out["softmax_gradient_pass"] = softmax_gradient_pass(hp, torch, 960000, 10)
     if not args.no_c5:
         out["full_gradient_c5"] = c5_full_gradient(hp, inp, torch)
     print(json.dumps(out))

@@ -284,6 +284,16 @@ int halp_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d,
  * the read-only bandwidth this GPU reaches, the yardstick beside the published HBM peak.  */
 int halp_debug_read_bandwidth(const void* p, int64_t bytes, uint32_t* out, void* stream);
 
+/* Measurement aid, not part of the method: the dependent chain of one 8-bit inner-loop step
+ * (Algorithm 4, inner `for t`, one sampled row, two coordinates per lane) with nothing beside
+ * it: multiply-adds, DPP fold, one LDS word per wave and a barrier, the fp64 path of gamma, the
+ * update.  `blocks` workgroups (1 .. 65535) of `waves` waves (1, 2 or 4) run `steps` steps (a
+ * multiple of 8, >= 8) on lane constants; out (DEVICE) receives blocks * waves * 64 uint32.
+ * Its time per step is the latency floor of the several-wave register kernels when a CU holds
+ * one chain.                                                                              */
+int halp_debug_step_latency(int32_t waves, int64_t steps, int32_t blocks, uint32_t* out,
+                            void* stream);
+
 const char* halp_strerror(int code);
 /* Text of the last HIP runtime failure seen by this thread inside the library
  * (which call, and HIP's message); empty if there was none.                            */

@@ -26,7 +26,7 @@ EXPORTS = [
     "halp_quantize_data",
     "halp_full_gradient", "halp_full_gradient_static", "halp_recenter", "halp_inner_loop", "halp_epoch",
     "halp_inner_loop_trace", "halp_get_stats", "halp_debug_stream_words",
-    "halp_debug_zround_bits", "halp_debug_read_bandwidth", "halp_strerror", "halp_last_error_detail", "halp_version",
+    "halp_debug_zround_bits", "halp_debug_read_bandwidth", "halp_debug_step_latency", "halp_strerror", "halp_last_error_detail", "halp_version",
 ]
 
 
@@ -97,6 +97,7 @@ def lib():
         L.halp_debug_stream_words.argtypes = [u64, u32, u32, u64, i64, vp, vp]
         L.halp_debug_zround_bits.argtypes = [u64, u32, u64, i32, i32, i32, vp, vp]
         L.halp_debug_read_bandwidth.argtypes = [vp, i64, vp, vp]
+        L.halp_debug_step_latency.argtypes = [i32, i64, i32, vp, vp]
         for name in EXPORTS:
             getattr(L, name).restype = C.c_int
         L.halp_strerror.restype = C.c_char_p
@@ -272,4 +273,16 @@ def debug_read_bandwidth(t, out=None, stream=None):
     nbytes = t.numel() * t.element_size()
     _check(lib().halp_debug_read_bandwidth(_ptr(t), nbytes, _ptr(out), _stream(stream)),
            "halp_debug_read_bandwidth")
+    return out
+
+
+def debug_step_latency(waves, steps, blocks, out=None, stream=None):
+    """Runs the isolated dependent chain of an 8-bit inner-loop step; returns its output tensor."""
+    import torch
+    if out is None:
+        out = torch.empty(blocks * waves * 64, dtype=torch.int32, device="cuda")
+    if out.numel() < blocks * waves * 64:
+        raise ValueError("out holds fewer than blocks * waves * 64 words")
+    _check(lib().halp_debug_step_latency(waves, steps, blocks, _ptr(out), _stream(stream)),
+           "halp_debug_step_latency")
     return out

@@ -461,6 +461,13 @@ int halp_debug_read_bandwidth(const void* p, int64_t bytes, uint32_t* out, void*
   return launch_debug_read(p, bytes, out, as_stream(stream));
 }
 
+int halp_debug_step_latency(int32_t waves, int64_t steps, int32_t blocks, uint32_t* out,
+                            void* stream) {
+  if (!out || steps < 8 || steps % 8 != 0 || blocks < 1 || blocks > 65535) return HALP_ERR_INVALID;
+  if (waves != 1 && waves != 2 && waves != 4) return HALP_ERR_INVALID;
+  return launch_debug_step_latency(waves, steps, blocks, out, as_stream(stream));
+}
+
 int halp_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
                            int32_t K, uint32_t* out, void* stream) {
   if (!out) return HALP_ERR_NULL;

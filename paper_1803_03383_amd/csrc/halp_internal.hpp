@@ -81,6 +81,7 @@ int launch_debug_stream_words(uint64_t seed, uint32_t purpose, uint32_t epoch, u
                               int64_t count, uint32_t* out, hipStream_t s);
 constexpr int kDebugReadBlocks = 2048;  // workgroups (and partial sums) of the read yardstick
 int launch_debug_read(const void* p, int64_t bytes, uint32_t* out, hipStream_t s);
+int launch_debug_step_latency(int waves, int64_t steps, int blocks, uint32_t* out, hipStream_t s);
 int launch_debug_zround_bits(uint64_t seed, uint32_t epoch, uint64_t t, int32_t d, int32_t b,
                              int32_t K, uint32_t* out, hipStream_t s);
 
