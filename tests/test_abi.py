@@ -117,3 +117,16 @@ def test_allocation_free_gradient_pass_checks_on_the_host():
     big = _params(R=4096, loss=hp.LOSS_SOFTMAX, K=16, d=1024)
     assert 4096 * (4 * 16 * 1024 + 8) > hp.STATIC_SCRATCH_BYTES
     assert L.halp_full_gradient_static(C.byref(big), C.byref(bufs(ldx=1024)), None) == hp.ERR_TOO_LARGE
+
+
+def test_step_latency_probe_checks_its_arguments_on_the_host():
+    """halp_debug_step_latency refuses wave counts it has no kernel for, step counts that are
+    not whole windows and a missing output before any launch."""
+    L = hp.lib()
+    fake = 0x10000
+    assert L.halp_debug_step_latency(4, 64, 1, None, None) == hp.ERR_INVALID
+    assert L.halp_debug_step_latency(3, 64, 1, fake, None) == hp.ERR_INVALID
+    assert L.halp_debug_step_latency(4, 60, 1, fake, None) == hp.ERR_INVALID
+    assert L.halp_debug_step_latency(4, 0, 1, fake, None) == hp.ERR_INVALID
+    assert L.halp_debug_step_latency(4, 64, 0, fake, None) == hp.ERR_INVALID
+    assert L.halp_debug_step_latency(4, 64, 70000, fake, None) == hp.ERR_INVALID

@@ -695,3 +695,16 @@ def test_general_inner_loop_with_the_model_in_device_memory():
         assert np.array_equal(P.get("z")[r].astype(np.int32), out["z"])
         assert np.array_equal(P.get("counters")[r].astype(np.uint64), out["counters"])
         assert np.array_equal(P.get("w")[r], ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r]))
+
+
+def test_step_latency_probe_runs_and_is_deterministic():
+    """The latency micro-kernel of the bench line: same output on every run and for every grid
+    position (all workgroups run the same chain on lane constants)."""
+    import torch
+    outs = [hp.debug_step_latency(w, 64, 3).cpu().numpy() for w in (4, 4, 2, 1)]
+    assert np.array_equal(outs[0], outs[1])
+    for o, w in zip(outs[1:], (4, 2, 1)):
+        o = o.reshape(3, w * 64)
+        assert np.array_equal(o[0], o[1]) and np.array_equal(o[0], o[2])
+    with pytest.raises(ValueError):
+        hp.debug_step_latency(4, 64, 3, out=torch.empty(10, dtype=torch.int32, device="cuda"))
