@@ -183,6 +183,14 @@ typedef struct {
                                     (R <= CUs); 1: wherever that shape is launched; 2: never.
                                     Results do not depend on it                                */
 
+#define HALP_OPT_EXCHANGE_POLL_DELAY 11 /* split minibatch loop: sleeps of 256 cycles between a
+                                    workgroup publishing its sums of a step and its first poll
+                                    for the others' (0 .. 64, default 3).  A word needs about
+                                    17 such units to cross device memory, but delays of 4 and
+                                    more were measured to lengthen the step, so the default
+                                    only skips the polls that cannot succeed for free.
+                                    Results do not depend on it                                 */
+
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */
 int halp_create(halp_handle** out, const halp_params* p);

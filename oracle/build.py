@@ -23,6 +23,21 @@ def build(force: bool = True) -> str:
     return OUT
 
 
+SAN_DIR = os.path.join(HERE, "_san")
+SAN_OUT = os.path.join(SAN_DIR, "halp_ref_san")
+
+
+def build_sanitized() -> str:
+    """The oracle and its driver (sanitize_main.c) as one executable under AddressSanitizer and
+    UndefinedBehaviorSanitizer, every report fatal.  Same floating-point flags as the library."""
+    os.makedirs(SAN_DIR, exist_ok=True)
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           "-Wall", "-Wextra", "-o", SAN_OUT, SRC, os.path.join(HERE, "sanitize_main.c"), "-lm"]
+    subprocess.run(cmd, check=True)
+    return SAN_OUT
+
+
 if __name__ == "__main__":
     print(build(force=True))
     sys.exit(0)

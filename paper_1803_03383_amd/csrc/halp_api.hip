@@ -264,6 +264,10 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
       if (value < -1 || value > (int64_t(1) << 30)) return HALP_ERR_INVALID;
       h->spin_limit = (int)value;
       return HALP_OK;
+    case HALP_OPT_EXCHANGE_POLL_DELAY:
+      if (value < 0 || value > 64) return HALP_ERR_INVALID;
+      h->poll_delay = (int)value;
+      return HALP_OK;
     case HALP_OPT_OPTION_II:
       if (value != 0 && value != 1) return HALP_ERR_INVALID;
       h->option2 = value != 0;

@@ -32,6 +32,7 @@ struct halp_handle {
   // minibatch inner loop split over several workgroups per chain: partial dots and tags
   long long* batch_xbuf = nullptr;   // [R][2][kBatchMaxParts][64] tagged partial dots
   int inner_parts = 0;               // workgroups per chain of that kernel, 0 = auto
+  int poll_delay = 3;                // 256-cycle sleeps between publishing a step's sums and the first poll
   int spin_limit = 1 << 20;          // polls before a workgroup stops waiting for the others
   double* hyper = nullptr;       // [R][2] step size and mu of each chain (device)
   int32_t* zh_work = nullptr;    // general inner kernel: z and h~ of models too large for LDS

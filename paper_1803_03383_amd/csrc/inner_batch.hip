@@ -80,7 +80,7 @@ __device__ __forceinline__ double logistic_dl(double a, double y) {
 // of them then performs on its own copy of z (same inputs, same result).
 template <int BITS, int NDW, int KT, bool FS>
 __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk, int P, long long* xbuf,
-                                                              int spin_limit) {
+                                                              int spin_limit, int poll_delay) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
   constexpr int EPD = 32 / BITS;       // elements per dword
@@ -402,28 +402,45 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
                              (tag << 46) | ((unsigned long long)D & ((1ull << 46) - 1ull)), __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
           if (self_prepare) prepare_ahead();
+          // A published word needs a trip through device memory before another workgroup can
+          // see it, so polls that start at once only add traffic: wait out most of that trip
+          // first.  Later rounds ask only for the parts that have not arrived yet.
+          if (n_timeout == 0) {
+            for (int i = 0; i < poll_delay; ++i) __builtin_amdgcn_s_sleep(4);
+          }
           long long tot = D;
+          long long val[kMaxParts];
+#pragma unroll
+          for (int p2 = 0; p2 < kMaxParts; ++p2) val[p2] = 0;
+          unsigned int missing = (1u << P) - 1u;  // parts whose 64 words do not all carry the tag yet
           for (int spin = 0; n_timeout == 0; ++spin) {  // after one wait ran out, none is tried again
-            bool miss = false;
-            tot = 0;
             unsigned long long wd[kMaxParts];
 #pragma unroll
-            for (int p2 = 0; p2 < kMaxParts; ++p2)  // all in flight at once; slots past P repeat the last
-              wd[p2] = __hip_atomic_load(&xb[min(p2, P - 1) * kMaxB + lane], __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
+            for (int p2 = 0; p2 < kMaxParts; ++p2) {  // all in flight at once
+              wd[p2] = 0;
+              if ((missing >> p2) & 1u)
+                wd[p2] = __hip_atomic_load(&xb[p2 * kMaxB + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
 #pragma unroll
             for (int p2 = 0; p2 < kMaxParts; ++p2) {
-              if (p2 < P) {
-                miss |= (wd[p2] >> 46) != tag;
-                tot += (long long)(wd[p2] << 18) >> 18;
+              if ((missing >> p2) & 1u) {
+                if (__ballot((wd[p2] >> 46) != tag) == 0) {
+                  missing &= ~(1u << p2);
+                  val[p2] = (long long)(wd[p2] << 18) >> 18;
+                }
               }
             }
-            if (__ballot(miss) == 0) break;
+            if (missing == 0) break;
             if (spin >= spin_limit) {  // only if a workgroup of the chain never ran: give up
               n_timeout = 1;
               break;
             }
             __builtin_amdgcn_s_sleep(1);
+          }
+          if (n_timeout == 0) {
+            tot = 0;
+#pragma unroll
+            for (int p2 = 0; p2 < kMaxParts; ++p2) tot += val[p2];
           }
           D = tot;
         }
@@ -627,14 +644,14 @@ __global__ void batch_split_prepare(long long* xbuf, int nwords, uint64_t* count
 }
 
 template <int BITS, int NDW, int KT, bool FS>
-int launch_kt(const InArgs& a, int nwk, int P, long long* xbuf, int spin_limit, dim3 grid, dim3 block,
+int launch_kt(const InArgs& a, int nwk, int P, long long* xbuf, int spin_limit, int poll_delay, dim3 grid, dim3 block,
               size_t smem, hipStream_t s) {
   auto kern = inner_batch_kernel<BITS, NDW, KT, FS>;
   if (smem > 0 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                       hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)smem) != hipSuccess)
     return HALP_ERR_HIP;
-  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk, P, xbuf, spin_limit);
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a, nwk, P, xbuf, spin_limit, poll_delay);
   return hip_ok(hipGetLastError());
 }
 
@@ -743,13 +760,13 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
 #define HALP_BT(BITS_, NDW_, FS_)                                                                  \
   if (p.b == BITS_ && L.ndw == NDW_ && L.fs == FS_) {                                              \
     if (nwaves <= 4)                                                                               \
-      return launch_kt<BITS_, NDW_, 4, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
+      return launch_kt<BITS_, NDW_, 4, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, h.poll_delay, grid, block, smem, s);         \
     if (nwaves <= 8)                                                                               \
-      return launch_kt<BITS_, NDW_, 8, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);         \
+      return launch_kt<BITS_, NDW_, 8, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, h.poll_delay, grid, block, smem, s);         \
     if (FS_) return HALP_ERR_UNSUPPORTED;                                                          \
     if (nwaves <= 12)                                                                              \
-      return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);        \
-    return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, grid, block, smem, s);          \
+      return launch_kt<BITS_, NDW_, 12, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, h.poll_delay, grid, block, smem, s);        \
+    return launch_kt<BITS_, NDW_, 16, FS_>(a, nwk, P, h.batch_xbuf, h.spin_limit, h.poll_delay, grid, block, smem, s);          \
   }
   auto launch_loop = [&]() -> int {
     HALP_BT(8, 1, true) HALP_BT(8, 2, true) HALP_BT(8, 4, true)

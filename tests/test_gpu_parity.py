@@ -708,3 +708,39 @@ def test_step_latency_probe_runs_and_is_deterministic():
         assert np.array_equal(o[0], o[1]) and np.array_equal(o[0], o[2])
     with pytest.raises(ValueError):
         hp.debug_step_latency(4, 64, 3, out=torch.empty(10, dtype=torch.int32, device="cuda"))
+
+
+@pytest.mark.parametrize("d,waves,helpers", [(64, 1, 0), (512, 4, 2), (512, 4, 1), (2048, 4, 0)])
+@pytest.mark.parametrize("alpha_lam", [0.45, 0.7])
+def test_sixteen_bit_update_at_the_edge_of_32_bits(d, waves, helpers, alpha_lam):
+    """The register kernels keep the 16-bit update -gamma x + r - (h~ mod 2^16) - c_lambda z in
+    32 bits, the oracle in 64.  Every term at its largest at once: data quantized to +-32767,
+    a box so small that z sits at its ends and gamma at its clamp, and alpha lambda 2^16 near
+    q_max (0.45: c_lambda ~ 29491 on every step) or beyond it (0.7: clamped to 32767)."""
+    N, T, b, seed = 40, 300, 16, 5
+    rng = np.random.default_rng(seed + d)
+    X = rng.choice(np.array([-1.0, 1.0], np.float32), size=(N, d))
+    y = (X @ rng.standard_normal(d).astype(np.float32) * 50.0).astype(np.float32)
+    dd = 1.0 / 32767.0
+    Xq = ref.quantize_data(X, dd, b)
+    assert np.abs(Xq).min() == 32767
+    alpha, lam, mu = 0.5, alpha_lam / 0.5, 2000.0
+    prob = ref.make_problem(N, d, b=b, alpha=alpha, mu=mu, lam=lam, delta_d=dd, seed=seed)
+    w = (rng.standard_normal((1, d)) * 3.0).astype(np.float32)
+    phi, g, _ = ref.full_gradient(prob, X, y, w)
+    sc, h, _ = ref.recenter(prob, g.astype(np.float32), 3)
+    tr = ref.inner_loop(prob, Xq, phi.astype(np.float32), y, h, sc, 3, T, trace_steps=T)
+    out = ref.inner_loop(prob, Xq, phi.astype(np.float32), y, h, sc, 3, T)
+    assert np.abs(out["z"]).max() == 32768 and out["counters"][0] > 0   # z at the ends of its box
+    assert out["counters"][1] > 0                                        # gamma clamped
+    assert out["counters"][2] == T                                       # an L2 draw on every step
+    assert np.abs(tr["gamma"]).max() >= 32767
+    P = GpuProblem(X, Xq, y, b=b, T=T, alpha=alpha, mu=mu, lam=lam, delta_d=dd, seed=seed, w0=w)
+    P.put("phi", phi.astype(np.float32)); P.put("h", h); P.put("scales", sc)
+    P.st["z"].zero_()
+    P.h.set_option(hp.OPT_INNER_VARIANT, 2)
+    P.h.set_option(hp.OPT_INNER_WAVES, waves)
+    P.h.set_option(hp.OPT_INNER_HELPERS, helpers)
+    P.h.inner_loop(3)
+    assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
+    assert np.array_equal(P.get("counters")[0].astype(np.uint64), out["counters"])
