@@ -61,7 +61,6 @@ int launch_inner(const halp_handle& h, int variant, uint32_t epoch, hipStream_t 
 
 // the register-resident family: one kernel for scalar margins, one for softmax
 int reg_supported(const halp_handle& h) {
-  if (h.p.loss == HALP_LOSS_SOFTMAX && h.p.algorithm == HALP_ALG_LPSVRG) return HALP_ERR_UNSUPPORTED;
   if (h.p.loss != HALP_LOSS_SOFTMAX && h.p.B > 1) return inner_batch_supported(h);
   return h.p.loss == HALP_LOSS_SOFTMAX ? inner_softmax_supported(h) : inner_reg_supported(h.p);
 }

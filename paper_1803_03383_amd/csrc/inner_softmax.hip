@@ -104,6 +104,7 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   const double* sc = a.scales + (int64_t)chain * 8;
   uint64_t* cnt_out = a.counters + (int64_t)chain * 4;
   const uint64_t seed = a.seed + (uint64_t)chain;
+  const bool lp = a.lp != 0;  // Algorithm 2 (LP-SVRG): z is the model itself
 
   if (sc[7] != 0.0) {
     if (tid < 4) cnt_out[tid] = 0;
@@ -232,7 +233,9 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
         uint32_t rw = 0;
         if (live) {
           const double a0 = (double)s_phi[buf][s][lc];
-          val = after ? __dadd_rn(a0, __dmul_rn(dscale, (double)s_D[s & 1][lc])) : a0;
+          // Algorithm 4 moves the margins by x^T z; in Algorithm 2 (LP-SVRG) x^T w is the margin
+          const double moved = __dmul_rn(dscale, (double)s_D[s & 1][lc]);
+          val = after ? (lp ? moved : __dadd_rn(a0, moved)) : a0;
           rw = s_rho[buf][s][lc];
         }
         const double mx = row_max_f64(val);
@@ -500,7 +503,8 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
       const int j = j0 + k;
       if (j < d) {
         zg[j] = (XT)z[k];
-        wg[j] = (float)__dadd_rn((double)wv[k], __dmul_rn(delta_m, (double)z[k]));
+        const double step = __dmul_rn(delta_m, (double)z[k]);
+        wg[j] = lp ? (float)step : (float)__dadd_rn((double)wv[k], step);  // Alg. 2: w~ = delta w
       }
     }
     if (lane == 0 && n_zclamp) atomicAdd(&s_cnt[0], n_zclamp);  // wave-wide count

@@ -80,7 +80,9 @@ LP_CASES = [
     (hp.LOSS_LOGISTIC, 500, 256, 1, 1, 8, 2, 800, (2, 1)),
     (hp.LOSS_LOGISTIC, 300, 128, 1, 1, 16, 1, 400, (2, 1)),
     (hp.LOSS_SQUARED, 300, 64, 1, 8, 8, 1, 300, (1,)),     # minibatch: general kernel
-    (hp.LOSS_SOFTMAX, 300, 100, 3, 1, 8, 1, 300, (1,)),    # softmax: general kernel
+    (hp.LOSS_SOFTMAX, 300, 100, 3, 1, 8, 1, 300, (2, 1)),  # softmax: class waves, and the general kernel
+    (hp.LOSS_SOFTMAX, 200, 784, 10, 1, 8, 2, 203, (2, 1)),  # the 10-class shape, ragged epoch
+    (hp.LOSS_SOFTMAX, 150, 256, 15, 1, 16, 1, 150, (2, 1)),  # 15 classes at 16 bits
 ]
 
 
