@@ -155,7 +155,7 @@ typedef struct {
                                     iterate after t steps: w~ <- w~ + delta_m z_t                */
 #define HALP_OPT_INNER_PARTS 7   /* workgroups per chain of the minibatch (B > 1) register inner
                                     loop.  0 (default): the library's choice, the full-step form
-                                    (the row cut across up to 8 workgroups, rows of a step held in
+                                    (the row cut across up to 16 workgroups, rows of a step held in
                                     registers) where it applies; 1, 2, 4, 8: the chunked form with
                                     that many workgroups.  The workgroups of a chain meet once per
                                     step in device memory and wait for each other (bounded; a wait

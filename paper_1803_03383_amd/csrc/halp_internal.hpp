@@ -45,7 +45,7 @@ struct halp_handle {
 
 namespace halp {
 
-constexpr int kBatchMaxParts = 8;  // workgroups per chain of the minibatch inner loop at most
+constexpr int kBatchMaxParts = 16;  // workgroups per chain of the minibatch inner loop at most
 
 struct TraceBufs {
   int64_t M = 0;

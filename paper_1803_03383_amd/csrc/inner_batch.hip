@@ -412,24 +412,36 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           long long val[kMaxParts];
 #pragma unroll
           for (int p2 = 0; p2 < kMaxParts; ++p2) val[p2] = 0;
-          unsigned int missing = (1u << P) - 1u;  // parts whose 64 words do not all carry the tag yet
+          unsigned long long missing = (1ull << P) - 1ull;  // parts whose 64 words do not all carry the tag yet
           for (int spin = 0; n_timeout == 0; ++spin) {  // after one wait ran out, none is tried again
             unsigned long long wd[kMaxParts];
+            // all loads of a round in flight at once; the upper half of the slots only for
+            // chains cut into more than eight parts
+            auto ask = [&](int lo, int hi) {
 #pragma unroll
-            for (int p2 = 0; p2 < kMaxParts; ++p2) {  // all in flight at once
-              wd[p2] = 0;
-              if ((missing >> p2) & 1u)
-                wd[p2] = __hip_atomic_load(&xb[p2 * kMaxB + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+              for (int p2 = 0; p2 < kMaxParts; ++p2) {
+                if (p2 < lo || p2 >= hi) continue;
+                wd[p2] = 0;
+                if ((missing >> p2) & 1ull)
+                  wd[p2] = __hip_atomic_load(&xb[p2 * kMaxB + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              }
+            };
+            auto take = [&](int lo, int hi) {
 #pragma unroll
-            for (int p2 = 0; p2 < kMaxParts; ++p2) {
-              if ((missing >> p2) & 1u) {
-                if (__ballot((wd[p2] >> 46) != tag) == 0) {
-                  missing &= ~(1u << p2);
-                  val[p2] = (long long)(wd[p2] << 18) >> 18;
+              for (int p2 = 0; p2 < kMaxParts; ++p2) {
+                if (p2 < lo || p2 >= hi) continue;
+                if ((missing >> p2) & 1ull) {
+                  if (__ballot((wd[p2] >> 46) != tag) == 0) {
+                    missing &= ~(1ull << p2);
+                    val[p2] = (long long)(wd[p2] << 18) >> 18;
+                  }
                 }
               }
-            }
+            };
+            ask(0, 8);
+            if (P > 8) ask(8, kMaxParts);
+            take(0, 8);
+            if (P > 8) take(8, kMaxParts);
             if (missing == 0) break;
             if (spin >= spin_limit) {  // only if a workgroup of the chain never ran: give up
               n_timeout = 1;
@@ -710,7 +722,7 @@ static BtLaunch pick_launch(const halp_handle& h, int64_t row_bytes) {
     most = kBatchMaxParts;
     while (most > 1 && (int64_t)p.R * most > h.num_cus) most /= 2;
   }
-  int most_any = 1;  // any count up to the exchange buffer's 8 slots
+  int most_any = 1;  // any count up to the exchange buffer's slots
   if (h.batch_xbuf) {
     most_any = (int)(h.num_cus / p.R);
     if (most_any > kBatchMaxParts) most_any = kBatchMaxParts;
@@ -721,16 +733,30 @@ static BtLaunch pick_launch(const halp_handle& h, int64_t row_bytes) {
     // each) are few enough to be resident together; up to 4 waves share the rows of a step
     const int epd = 32 / p.b;
     const bool al16 = row_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(h.buf.Xq) % 16 == 0;
-    for (int ndw = (al16 && p.b == 16) ? 4 : 2; ndw >= 1; ndw /= 2) {  // 8 coordinates per thread at most
+    const int ndw_max = (al16 && p.b == 16) ? 4 : 2;  // 8 coordinates per thread at most
+    auto fits = [&](int ndw, int& P) {
       const int cpt = ndw * epd;
-      const int P = (p.d + 64 * cpt - 1) / (64 * cpt);
-      if (P > most_any) continue;
-      // several workgroups pay ~3 us per step for their exchange: only for steps that move a lot
-      if (P > 1 && (int64_t)p.B * row_bytes < 256 * 1024) continue;
-      if ((int64_t)((p.d + cpt - 1) / cpt) * ndw * 4 > row_bytes) continue;  // fragments inside the row
-      int rg = (p.B + 7) / 8;
-      if (rg > 4) rg = 4;
-      return BtLaunch{true, ndw, rg, P};
+      P = (p.d + 64 * cpt - 1) / (64 * cpt);
+      if (P > most_any) return false;
+      // several workgroups pay ~2 us per step for their exchange.  Measured: worth it down to
+      // steps of 16 KB of rows (3.3 - 4.6 us split against 3.9 - 5.2 on one workgroup; at 64 - 128 KB
+      // 3.9 - 4.9 against 9.6 - 11.3)
+      if (P > 1 && (int64_t)p.B * row_bytes < 16 * 1024) return false;
+      return (int64_t)((p.d + cpt - 1) / cpt) * ndw * 4 <= row_bytes;  // fragments inside the row
+    };
+    int rg = (p.B + 7) / 8;
+    if (rg > 4) rg = 4;
+    // A chain cut across workgroups: the narrowest fragment of at least four coordinates whose
+    // slices are few enough -- more, narrower slices shorten both passes over the rows of a step
+    // (measured: 4096 x 16 bits 6.6 us with 8 slices, 6.2 with 16; 2048 x 16 bits 5.8 / 4.9 with
+    // 4 / 8; 4096 x 8 bits 5.4 / 5.2 with 8 / 16; two coordinates per thread lose again).
+    for (int ndw = p.b == 16 ? 2 : 1; ndw <= ndw_max; ndw *= 2) {
+      int P;
+      if (fits(ndw, P) && P > 1) return BtLaunch{true, ndw, rg, P};
+    }
+    for (int ndw = ndw_max; ndw >= 1; ndw /= 2) {
+      int P;
+      if (fits(ndw, P)) return BtLaunch{true, ndw, rg, P};
     }
   }
   int P = 1;
