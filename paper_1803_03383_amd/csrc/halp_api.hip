@@ -156,7 +156,7 @@ int halp_create(halp_handle** out, const halp_params* p) {
   }
   // exchange buffers of the split minibatch inner loop, where it can apply
   if (p->K == 1 && p->B > 1 && (int64_t)p->R * 2 <= h->num_cus) {
-    const size_t slots = (size_t)p->R * 2 * kBatchMaxParts;
+    const size_t slots = (size_t)p->R * 2 * kBatchSlots;
     if (hip_fail(hipMalloc(reinterpret_cast<void**>(&h->batch_xbuf), slots * 64 * sizeof(long long)),
                  "hipMalloc(batch_xbuf)")) { halp_destroy(h); return HALP_ERR_HIP; }
   }

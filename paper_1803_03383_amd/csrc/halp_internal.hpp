@@ -30,7 +30,7 @@ struct halp_handle {
   size_t partial_g_bytes = 0;
   const float* fscale = nullptr; // caller's per-feature data scales [d] (device), or null
   // minibatch inner loop split over several workgroups per chain: partial dots and tags
-  long long* batch_xbuf = nullptr;   // [R][2][kBatchMaxParts][64] tagged partial dots
+  long long* batch_xbuf = nullptr;   // [R][2][kBatchSlots][64] tagged partial dots, margins and labels
   int inner_parts = 0;               // workgroups per chain of that kernel, 0 = auto
   int poll_delay = 3;                // 256-cycle sleeps between publishing a step's sums and the first poll
   int spin_limit = 1 << 20;          // polls before a workgroup stops waiting for the others
@@ -45,7 +45,8 @@ struct halp_handle {
 
 namespace halp {
 
-constexpr int kBatchMaxParts = 16;  // workgroups per chain of the minibatch inner loop at most
+constexpr int kBatchMaxParts = 16;
+constexpr int kBatchSlots = kBatchMaxParts + 2;  // exchange words per row, step parity and chain: the parts' sums, margin, label  // workgroups per chain of the minibatch inner loop at most
 
 struct TraceBufs {
   int64_t M = 0;

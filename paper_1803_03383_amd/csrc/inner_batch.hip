@@ -150,12 +150,23 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
   };
   float phi_c = 0.f, y_c = 0.f;
   int i_next = 0;
+  // A chain cut across workgroups: every workgroup evaluates all scalars of a step, but only
+  // part 0 gathers the margins and labels of the sampled rows (a 128-byte line per 4-byte
+  // value and workgroup otherwise).  It does so a step before it needs them and ships them with
+  // the sums of the step in between, as two more tagged words per row.
+  const bool shipper = P > 1 && part == 0;
+  const bool receiver = P > 1 && part != 0;
+  float phi_g = 0.f, y_g = 0.f;  // part 0: margins and labels gathered for the step after this one
   if (svc) {
     const int i0 = draw_idx(0), i1 = draw_idx(1);
     if (row) { s_idx[0][lane] = i0; s_idx[1][lane] = i1; }
     phi_c = need_phi ? phi[i0] : 0.f;
     y_c = a.loss == HALP_LOSS_LOGISTIC ? y[i0] : 0.f;
     i_next = i1;
+    if (shipper) {
+      phi_g = need_phi ? phi[i1] : 0.f;
+      y_g = a.loss == HALP_LOSS_LOGISTIC ? y[i1] : 0.f;
+    }
   }
   {
     // ========================================================================= worker
@@ -252,9 +263,14 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       uint32_t rw = 0;
       int cl_draw = 0;
       if (svc) {
-        const int inx = self_prepare ? i_next : s_idx[(t + 1) & 3][min(lane, B - 1)];
-        phi_n = need_phi ? phi[inx] : 0.f;
-        y_n = a.loss == HALP_LOSS_LOGISTIC ? y[inx] : 0.f;
+        if (P == 1) {
+          const int inx = self_prepare ? i_next : s_idx[(t + 1) & 3][min(lane, B - 1)];
+          phi_n = need_phi ? phi[inx] : 0.f;
+          y_n = a.loss == HALP_LOSS_LOGISTIC ? y[inx] : 0.f;
+        } else if (shipper) {  // gathered after the last step's gamma (before the loop for step 0)
+          phi_n = phi_g;
+          y_n = y_g;
+        }  // the other parts receive them with the sums below
         if (self_prepare || t == 0) {  // drawn during the previous step (or before the first)
           rw = rw_next;
           cl_draw = cl_next;
@@ -397,10 +413,18 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           // the chain has read it.
           const unsigned long long tag = (unsigned long long)((t >> 1) % 262143) + 1ull;
           unsigned long long* xb = reinterpret_cast<unsigned long long*>(xbuf) +
-                                   (((int64_t)chain * 2 + (int64_t)(t & 1)) * kMaxParts) * kMaxB;
+                                   (((int64_t)chain * 2 + (int64_t)(t & 1)) * kBatchSlots) * kMaxB;
           __hip_atomic_store(&xb[part * kMaxB + lane],
                              (tag << 46) | ((unsigned long long)D & ((1ull << 46) - 1ull)), __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
+          const bool logistic = a.loss == HALP_LOSS_LOGISTIC;
+          if (shipper && need_phi)
+            __hip_atomic_store(&xb[kMaxParts * kMaxB + lane], (tag << 46) | (unsigned long long)__float_as_uint(phi_g),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (shipper && logistic)
+            __hip_atomic_store(&xb[(kMaxParts + 1) * kMaxB + lane], (tag << 46) | (unsigned long long)__float_as_uint(y_g),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          bool want_phi = receiver && need_phi, want_y = receiver && logistic;
           if (self_prepare) prepare_ahead();
           // A published word needs a trip through device memory before another workgroup can
           // see it, so polls that start at once only add traffic: wait out most of that trip
@@ -440,9 +464,22 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
             };
             ask(0, 8);
             if (P > 8) ask(8, kMaxParts);
+            unsigned long long wphi = 0, wy = 0;
+            if (want_phi)
+              wphi = __hip_atomic_load(&xb[kMaxParts * kMaxB + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (want_y)
+              wy = __hip_atomic_load(&xb[(kMaxParts + 1) * kMaxB + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             take(0, 8);
             if (P > 8) take(8, kMaxParts);
-            if (missing == 0) break;
+            if (want_phi && __ballot((wphi >> 46) != tag) == 0) {
+              want_phi = false;
+              phi_n = __uint_as_float((uint32_t)wphi);
+            }
+            if (want_y && __ballot((wy >> 46) != tag) == 0) {
+              want_y = false;
+              y_n = __uint_as_float((uint32_t)wy);
+            }
+            if (missing == 0 && !want_phi && !want_y) break;
             if (spin >= spin_limit) {  // only if a workgroup of the chain never ran: give up
               n_timeout = 1;
               break;
@@ -482,6 +519,11 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         phi_c = phi_n; y_c = y_n;
       }
       lds_barrier();  // gamma is out
+      if (svc && shipper) {  // margins and labels of the rows two steps on, shipped with the next step's sums
+        const int i2 = self_prepare ? i_next : s_idx[(t + 2) & 3][min(lane, B - 1)];
+        phi_g = need_phi ? phi[i2] : 0.f;
+        y_g = a.loss == HALP_LOSS_LOGISTIC ? y[i2] : 0.f;
+      }
       // Full-step form: this wave's rows of the next step, requested only now -- what wave 0
       // read from memory for the scalar stage (margins, the other workgroups' sums) must not
       // queue behind them -- and in flight through the update and the next step's start.
@@ -777,7 +819,7 @@ int launch_inner_batch(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const int nwaves = nwk;
   const dim3 grid(p.R * P), block(64 * nwaves);
   if (P > 1) {
-    const int nwords = p.R * 2 * kBatchMaxParts * kMaxB, ncnt = p.R * 4;
+    const int nwords = p.R * 2 * kBatchSlots * kMaxB, ncnt = p.R * 4;
     hipLaunchKernelGGL(batch_split_prepare, dim3((nwords + 255) / 256), dim3(256), 0, s, h.batch_xbuf, nwords,
                        h.buf.counters, ncnt);
   }
