@@ -36,7 +36,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 ALU_PEAK_LANEOPS = 256 * 64 * 2.4e9   # 256 CUs x 64 lanes/clk x 2.4 GHz, 32-bit integer lane-ops/s
-# algorithmic lane-ops per feature-update at b = 8 (see DESIGN.md): 1/4 dot MAC + 1 update
+# algorithmic lane-ops per feature-update at b = 8: 1/4 dot MAC + 1 update
 # multiply-add + 4 (add rounding bits, shift, add z, clamp) + 60/16 Philox4x32-10 share
 LANEOPS_PER_UPDATE_B8 = 0.25 + 1.0 + 4.0 + 60.0 / 16.0
 
@@ -248,7 +248,7 @@ def c5_full_gradient(hp, inp, torch, reps=5):
     return out
 
 
-def side_inner_loop(hp, inp, torch, which, T):
+def side_inner_loop(hp, inp, torch, which, T, poll_delay=-1):
     """Inner-loop step rate of the configurations beside the headline one (softmax K=10 at
     b=8/16; logistic with a minibatch of 64 at b=16), at a reduced step count; `inner_variant`
     says which kernel ran (1 general, 2 register-resident)."""
@@ -273,6 +273,8 @@ def side_inner_loop(hp, inp, torch, which, T):
                     lam=c["lam"], delta_d=delta_d, seed=0)
         h.bind(X=Xd, Xq=Xq, y=yd, **st)
         h.quantize_data()
+        if poll_delay >= 0:
+            h.set_option(hp.OPT_EXCHANGE_POLL_DELAY, poll_delay)
         h.set_option(hp.OPT_TIMING, 1)
         for k in range(3):
             h.epoch(k)
@@ -438,6 +440,9 @@ def main():
                     help="model scale of --algorithm lpsvrg (teacher weights are N(0,1))")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-c5", action="store_true", help="skip the 16 GB gradient-pass measurement")
+    ap.add_argument("--poll-delay", type=int, default=-1,
+                    help="c5 minibatch loop: 256-cycle sleeps before the first poll of a step's exchange "
+                         "(-1: the library's default)")
     ap.add_argument("--no-side", action="store_true",
                     help="skip the step rates of the other configurations' inner loops")
     ap.add_argument("--cpu-chains", type=int, default=64)
@@ -474,7 +479,7 @@ def main():
         return
     if args.workload in ("c3", "c5"):
         print(json.dumps({"workload": args.workload, "side_inner_loop":
-                          side_inner_loop(hp, inp, torch, args.workload, args.inner_steps)}))
+                          side_inner_loop(hp, inp, torch, args.workload, args.inner_steps, args.poll_delay)}))
         return
     cfg = dict(WORKLOADS[args.workload])
     if args.chains > 0 and args.chains != cfg["R"]:
