@@ -311,8 +311,11 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
   const int ngr = matrix_wave ? max(0, ((d + 31) / 32 - wave + 3) / 4) : 0;  // groups wave, wave+4, ..
   float wreg[kPipeGroups][2][4];
   F4 gacc[kPipeGroups][2];
+  // Rows of whole float4s take the serial form of a period (see below): the matrix waves also
+  // take the softmax, of four rows each, so `ht` names a matrix thread there
+  const bool serial = (d & 3) == 0;
   // ---------------------------------------------------------------- helper waves: set-up
-  const int ht = tid - 256;
+  const int ht = (serial && matrix_wave) ? tid : tid - 256;
   const int nf4 = (d + 3) / 4;
   double loss_acc = 0.0;
   if (matrix_wave) {
@@ -367,10 +370,14 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
       pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[i].y, wreg[i][0][1], pb, 0, 0, 0);
       pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[i].z, wreg[i][0][2], pa, 0, 0, 0);
       pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[i].w, wreg[i][0][3], pb, 0, 0, 0);
-      pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].x, wreg[i][1][0], pa, 0, 0, 0);
-      pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].y, wreg[i][1][1], pb, 0, 0, 0);
-      pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].z, wreg[i][1][2], pa, 0, 0, 0);
-      pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].w, wreg[i][1][3], pb, 0, 0, 0);
+      // the upper 16 columns of the row's last group may be padding only (d = 784: the wave
+      // with the most groups): their products are zeros
+      if (i + 1 < NGR || 32 * (wave + 4 * i) + 16 < d) {
+        pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].x, wreg[i][1][0], pa, 0, 0, 0);
+        pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].y, wreg[i][1][1], pb, 0, 0, 0);
+        pa = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].z, wreg[i][1][2], pa, 0, 0, 0);
+        pb = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[i].w, wreg[i][1][3], pb, 0, 0, 0);
+      }
     }
     // component r of lane (j, q) is row 4 q + r, class j
     float* pp = s_pphi + wave * kRows * 16 + (4 * lq) * 16 + li;
@@ -438,6 +445,46 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
         const int t = bprev; bprev = bcur; bcur = bnext; bnext = t;
       }
     };
+    // Serial form (rows that travel by global_load_lds): margins, softmax and gradient sum of a
+    // tile follow each other inside one period, all on the matrix waves (wave w takes the softmax
+    // of rows 4w .. 4w+3).  The matrix pipe idles through the softmax and three barriers, but no
+    // other wave competes with the matrix waves for their SIMDs, and a tile buffer is busy for
+    // one period instead of two: with three buffers a tile has two periods to arrive.
+    auto lds_barrier = [&]() {  // LDS traffic only: never waits for stores or loads in flight
+      HALP_PHASE_BORDER();
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_s_barrier();
+      HALP_PHASE_BORDER();
+    };
+    auto periods_serial = [&](auto ngr_c) {
+      constexpr int NGR = decltype(ngr_c)::value;
+      int y_cur = 0, y_nxt = n > 0 ? y[min(tile_of(0) * kRows + (ht >> 4), N - 1)] : 0;
+      int buf = 0;
+      lds_barrier();  // tile 0 has landed
+      for (int k = 0; k < n; ++k) {
+        y_cur = y_nxt;
+        if (k + 1 < n) y_nxt = y[min(tile_of(k + 1) * kRows + (ht >> 4), N - 1)];
+        if constexpr (NGR > 0) margins(ngr_c, buf);
+        lds_barrier();
+        softmax(tile_of(k), 0, y_cur);
+        lds_barrier();
+        if constexpr (NGR > 0) gradient(ngr_c, buf, 0);
+        lds_barrier();  // the buffer is free, the next tile has landed
+        buf = buf == 2 ? 0 : buf + 1;
+      }
+    };
+    if (serial) {
+      switch (ngr) {
+        case 7: periods_serial(std::integral_constant<int, 7>{}); break;
+        case 6: periods_serial(std::integral_constant<int, 6>{}); break;
+        case 5: periods_serial(std::integral_constant<int, 5>{}); break;
+        case 4: periods_serial(std::integral_constant<int, 4>{}); break;
+        case 3: periods_serial(std::integral_constant<int, 3>{}); break;
+        case 2: periods_serial(std::integral_constant<int, 2>{}); break;
+        case 1: periods_serial(std::integral_constant<int, 1>{}); break;
+        default: periods_serial(std::integral_constant<int, 0>{}); break;
+      }
+    } else
     switch (ngr) {  // same barriers in every case
       case 7: periods(std::integral_constant<int, 7>{}); break;
       case 6: periods(std::integral_constant<int, 6>{}); break;
@@ -600,24 +647,34 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
             }
           }
         };
-        int y_cur = 0, y_nxt = 0, bnext = 0;
-        for (int k = -1; k <= n; ++k) {
+        // s_waitcnt for "at most NBW loads in flight" (the youngest tile), every other counter left alone
+        constexpr int kLeaveOne = (NBW & 0xF) | (0x7 << 4) | (0xF << 8) | ((NBW >> 4) << 14);
+        auto bare_barrier = [&]() {  // never waits for the tiles in flight
           HALP_PHASE_BORDER();
-          if (k + 1 < n) {
-            y_nxt = y[min(tile_of(k + 1) * kRows + (ht >> 4), N - 1)];
-            dma(bnext, tile_of(k + 1));
-          }
-          HALP_PHASE_BORDER();
-          // this barrier must not wait for the tile in flight: LDS traffic only
           __builtin_amdgcn_s_waitcnt(0xc07f);
           __builtin_amdgcn_s_barrier();
           HALP_PHASE_BORDER();
-          if (k >= 0 && k < n) softmax(tile_of(k), k & 1, y_cur);
+        };
+        auto landed = [&](bool younger_in_flight) {  // every tile but the youngest has arrived
           HALP_PHASE_BORDER();
-          __syncthreads();  // waits for the tile as well
+          if (younger_in_flight) __builtin_amdgcn_s_waitcnt(kLeaveOne);
+          else __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
           HALP_PHASE_BORDER();
-          y_cur = y_nxt;
-          bnext = bnext == 2 ? 0 : bnext + 1;
+        };
+        // tile k in buffer k mod 3; tile k + 2 is started at the top of period k, into the buffer
+        // that tile k - 1 left at the end of period k - 1, and has to be there when period k + 1 ends
+        if (n > 0) dma(0, tile_of(0));
+        if (n > 1) dma(1, tile_of(1));
+        landed(n > 1);
+        bare_barrier();
+        int b2 = 2;
+        for (int k = 0; k < n; ++k) {
+          if (k + 2 < n) dma(b2, tile_of(k + 2));
+          bare_barrier();
+          bare_barrier();
+          landed(k + 2 < n);
+          bare_barrier();
+          b2 = b2 == 2 ? 0 : b2 + 1;
         }
       };
       switch (nbw) {
@@ -645,7 +702,7 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
   }
   // every read of the margins' LDS lies before the loop's last barrier: it carries the loss terms now
   double* s_loss = reinterpret_cast<double*>(s_pphi);  // 256 doubles in the 4 KB of the margins
-  if (!matrix_wave) s_loss[ht] = loss_acc;
+  if (serial ? matrix_wave : !matrix_wave) s_loss[ht] = loss_acc;
   __syncthreads();
   if (tid == 256) {
     double l = 0.0;
