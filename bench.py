@@ -17,9 +17,16 @@ epochs (R*T*d updates per epoch, gradient pass included in the time).
 same kernel with 2048 chains, eight per CU), and
 `roofline_full_gradient` the gradient pass of the same epochs; both durations
 come from HIP events recorded by the library on the launch stream inside the
-timed region.  `full_gradient_c5` is the gradient pass alone on the 16.4 GB
-logistic configuration (N=1e6, d=4096), with the step rate of that configuration's
-minibatch inner loop (B=64, b=16) beside it.  `cpu_baseline` is the oracle timed on
+timed region.  `roofline.latency` holds the latency floor of that inner loop (one
+chain per CU: the step's dependent chain run alone by the library's micro-kernel) and
+the share of it the measured loop reaches.  `full_gradient_c5` is the gradient pass
+alone on the 16.4 GB logistic configuration (N=1e6, d=4096), with the step rate of that
+configuration's minibatch inner loop (B=64, b=16; T=2000 of its 1e6 steps per epoch)
+beside it; `side_inner_loops` the inner-loop step rates of the single-chain and the
+10-class configurations at reduced step counts (`inner_variant` 2 = register-resident
+kernel), `softmax_gradient_pass` the 10-class gradient pass at an HBM-resident row
+count.  Every `traffic` field is read from a committed rocprofv3 counter summary
+(`traffic_source`), not measured by the run.  `cpu_baseline` is the oracle timed on
 the host cores on a bounded sample of the same workload.
 """
 import argparse
