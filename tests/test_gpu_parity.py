@@ -744,3 +744,22 @@ def test_sixteen_bit_update_at_the_edge_of_32_bits(d, waves, helpers, alpha_lam)
     P.h.inner_loop(3)
     assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
     assert np.array_equal(P.get("counters")[0].astype(np.uint64), out["counters"])
+
+
+@pytest.mark.parametrize("delay", [0, 16, 64])
+def test_minibatch_result_does_not_depend_on_the_poll_delay(delay):
+    """A chain cut across sixteen workgroups (margins and labels shipped from part 0 with the
+    tagged sums): the same bits whether the first poll of a step's exchange comes at once or late."""
+    loss, N, d, B, b, T = hp.LOSS_LOGISTIC, 300, 4096, 64, 16, 40
+    seed = 60 + d + B
+    case = _inner_case(loss, N, d, 1, B, b, 1e-5, 1, T, seed, mu=0.05)
+    P = _run_inner(case, loss, 1, B, b, 1e-5, 1, T, seed, 2, mu=0.05)
+    P.h.set_option(hp.OPT_EXCHANGE_POLL_DELAY, delay)
+    P.h.inner_loop(3)
+    out = _oracle_inner(case, 0, T)
+    assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
+    assert np.array_equal(P.get("counters")[0].astype(np.uint64), out["counters"])
+    for bad in (-1, 65):
+        with pytest.raises(hp.HalpError) as e:
+            P.h.set_option(hp.OPT_EXCHANGE_POLL_DELAY, bad)
+        assert e.value.code == hp.ERR_INVALID
