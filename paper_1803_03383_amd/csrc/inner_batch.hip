@@ -398,6 +398,12 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         if (lane == 0) s_cln[(t + 1) & 1] = cl_next;
       }
       if (svc) {
+        // l'(phi_m) does not depend on the dots: evaluated here, ahead of the wait for the other
+        // workgroups' sums, so that only l'(phi_m + x_m^T z) follows it
+        const double a0 = (double)phi_c, yi = (double)y_c;
+        double dl0 = 0.0;
+        if (a.loss == HALP_LOSS_LOGISTIC) dl0 = logistic_dl(a0, yi);
+        asm volatile("" : "+v"(dl0));  // stays where it is written
         long long D = 0;
         for (int w2 = 0; w2 < (FS ? 1 : nwk); ++w2) {
           const long long lo = s_part[0][w2][min(lane, B - 1)];
@@ -495,11 +501,10 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         }
         // beta_m = (alpha / B) (l'(phi_m + x_m^T z) - l'(phi_m)), gamma_m = Q_(delta_s, b)(beta_m)
         const double delta = __dmul_rn(dscale, (double)D);
-        const double a0 = (double)phi_c, yi = (double)y_c;
         double diff;
         if (a.loss == HALP_LOSS_LOGISTIC) {
           const double a1 = lp ? delta : __dadd_rn(a0, delta);
-          diff = __dadd_rn(logistic_dl(a1, yi), -logistic_dl(a0, yi));
+          diff = __dadd_rn(logistic_dl(a1, yi), -dl0);
         } else {
           diff = lp ? __dadd_rn(delta, -a0) : delta;
         }
