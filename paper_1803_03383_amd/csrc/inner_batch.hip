@@ -225,7 +225,11 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     };
     // FS: the fragments of all rows of this step and of the next one
     constexpr int RPW = FS ? kRowsPerWave : 1;
-    uint32_t xc[RPW][NDW], xn[RPW][NDW];
+    // Full-step form with fragments of at most 8 bytes: three register sets, the rows of a step
+    // are requested two steps before their dots (a step ahead is less than a trip to memory for
+    // a random row, and a workgroup whose rows are late makes every workgroup of the chain wait)
+    constexpr bool kDeep = FS && NDW <= 2;
+    uint32_t xc[RPW][NDW], xn[RPW][NDW], xf[kDeep ? RPW : 1][NDW];
     auto load_step = [&](uint32_t (&dst)[RPW][NDW], const int* idx) {
       // lane r fetches the index of the wave's row r (one LDS read for all); rows past B
       // repeat the last one and are not used
@@ -236,6 +240,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
     __syncthreads();
     if (FS) {
       if (worker) load_step(xc, s_idx[0]);
+      if (kDeep && worker) load_step(xn, s_idx[1]);
     } else {
       load_chunk(xa, s_idx[0], 0);
     }
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           for (int k = 0; k < kWarm; ++k) asm volatile("" ::"v"(warm[k]));
           const int64_t part_off = (int64_t)part * 64 * NDW * 4;
           const int slice = (int)min((int64_t)64 * NDW * 4, row_bytes - part_off);
-          if (slice >= 4) {
+          if (!kDeep && slice >= 4) {  // kDeep: the rows themselves are requested at that distance
             const unsigned char* wp = Xq + (int64_t)i2 * row_bytes + part_off;
 #pragma unroll
             for (int k = 0; k < kWarm; ++k)  // unconditional, the last line repeated
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
       // Full-step form: this wave's rows of the next step, requested only now -- what wave 0
       // read from memory for the scalar stage (margins, the other workgroups' sums) must not
       // queue behind them -- and in flight through the update and the next step's start.
-      if (FS) load_step(nxt, s_idx[(t + 1) & 3]);
+      if (FS) load_step(nxt, s_idx[(t + (kDeep ? 2 : 1)) & 3]);  // kDeep: `nxt` is the set two steps on
       // ---- pass 2: sum_m gamma_m x_m per coordinate (low / high byte of gamma apart at 16 bits)
       int acc[CPT], acch[CPT];
 #pragma unroll
@@ -635,7 +640,19 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         z[k] = ok[k] ? (int)zc : 0;
       }
     };
-    if (FS) {  // the two register sets trade places from step to step
+    if constexpr (kDeep) {  // three register sets in rotation: rows of steps t, t + 1 and the set being filled
+      auto& x0 = xc;
+      auto& x1 = xn;
+      auto& x2 = reinterpret_cast<uint32_t(&)[RPW][NDW]>(xf);
+      int64_t t = 0;
+      for (; t + 2 < T; t += 3) {
+        one_step(t, x0, x2);
+        one_step(t + 1, x1, x0);
+        one_step(t + 2, x2, x1);
+      }
+      if (t < T) one_step(t, x0, x2);
+      if (t + 1 < T) one_step(t + 1, x1, x0);
+    } else if (FS) {  // the two register sets trade places from step to step
       int64_t t = 0;
       for (; t + 1 < T; t += 2) {
         one_step(t, xc, xn);
