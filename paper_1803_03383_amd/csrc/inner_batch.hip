@@ -406,9 +406,13 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
         // l'(phi_m) does not depend on the dots: evaluated here, ahead of the wait for the other
         // workgroups' sums, so that only l'(phi_m + x_m^T z) follows it
         const double a0 = (double)phi_c, yi = (double)y_c;
+        double rho_m = __dmul_rn((double)rw, 0x1p-32);  // the rounding draw of gamma_m
+        asm volatile("" : "+v"(rho_m));
         double dl0 = 0.0;
-        if (a.loss == HALP_LOSS_LOGISTIC) dl0 = logistic_dl(a0, yi);
-        asm volatile("" : "+v"(dl0));  // stays where it is written
+        if (P == 1) {
+          if (a.loss == HALP_LOSS_LOGISTIC) dl0 = logistic_dl(a0, yi);
+          asm volatile("" : "+v"(dl0));  // stays where it is written
+        }
         long long D = 0;
         for (int w2 = 0; w2 < (FS ? 1 : nwk); ++w2) {
           const long long lo = s_part[0][w2][min(lane, B - 1)];
@@ -436,6 +440,8 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
             __hip_atomic_store(&xb[(kMaxParts + 1) * kMaxB + lane], (tag << 46) | (unsigned long long)__float_as_uint(y_g),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           bool want_phi = receiver && need_phi, want_y = receiver && logistic;
+          if (logistic) dl0 = logistic_dl(a0, yi);  // behind the publish, ahead of the wait
+          asm volatile("" : "+v"(dl0));
           if (self_prepare) prepare_ahead();
           // A published word needs a trip through device memory before another workgroup can
           // see it, so polls that start at once only add traffic: wait out most of that trip
@@ -514,8 +520,13 @@ __global__ __launch_bounds__(64 * KT) void inner_batch_kernel(InArgs a, int nwk,
           diff = lp ? __dadd_rn(delta, -a0) : delta;
         }
         const double beta = __dmul_rn(aB, diff);
-        bool hit = false;
-        const int gq = (int)quantize_real(beta, inv_s, rw, (double)QMIN, (double)QMAX, &hit);
+        // gamma_m = Q_(delta_s, b)(beta_m): floor(beta / delta_s + rho), clamped -- the quantizer of
+        // quantize_real with its draw converted ahead of the wait and the result taken as a
+        // 32-bit integer (it lies in the box after the clamp)
+        const double fq = floor(__dadd_rn(__dmul_rn(beta, inv_s), rho_m));
+        const double fc = fmin(fmax(fq, (double)QMIN), (double)QMAX);
+        const bool hit = fq != fc;
+        const int gq = (int)fc;
         if (row) {
           s_gam[lane] = gq;
           n_gclamp += hit ? 1u : 0u;
