@@ -454,6 +454,9 @@ def main():
                     help="skip the step rates of the other configurations' inner loops")
     ap.add_argument("--cpu-chains", type=int, default=64)
     ap.add_argument("--inner-waves", type=int, default=0, help="waves per chain (0 = library's choice)")
+    ap.add_argument("--inner-helpers", type=int, default=0, choices=[0, 1, 2],
+                    help="helper waves beside the chain waves of the register inner loop: 0 the library's "
+                         "choice, 1 wherever built, 2 never")
     ap.add_argument("--chains", type=int, default=0,
                     help="override the number of chains; above the workload's R the chains share "
                          "chain 0's data and differ in their seeds only")
@@ -501,6 +504,8 @@ def main():
     h, X, Xq, y, st, delta_d = make_problem(hp, inp, torch, cfg)
     if args.inner_waves:
         h.set_option(hp.OPT_INNER_WAVES, args.inner_waves)
+    if args.inner_helpers:
+        h.set_option(hp.OPT_INNER_HELPERS, args.inner_helpers)
 
     for k in range(args.warmup):
         h.epoch(k)
@@ -527,7 +532,8 @@ def main():
     # fp32 SVRG: one FMA for the dot, one FMA and one subtraction for the update per coordinate
     laneops = 3.0 if args.algorithm == "svrg" else LANEOPS_PER_UPDATE_B8
     # at the headline shape (few chains, four waves each) the register kernel with helper waves runs
-    helped = args.algorithm != "svrg" and R <= 256 and args.inner_waves in (0, 2, 4) and d <= 1024
+    helped = (args.algorithm != "svrg" and args.inner_helpers != 2 and args.inner_waves in (0, 2, 4) and d <= 1024
+              and (R <= 5 * 256 or args.inner_helpers == 1))
     inner_kernel = "inner_svrg_kernel" if args.algorithm == "svrg" else (
         "inner_reg_helped_kernel" if helped else "inner_reg_kernel")
     alu_achieved = updates * laneops / (inner_ms * 1e-3)

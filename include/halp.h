@@ -179,8 +179,9 @@ typedef struct {
                                     every chain wave draws the rounding bits, fetches the sampled
                                     rows and refills the step-indexed draws, so that the chain
                                     waves issue the step's dependent chain and little else.
-                                    0 (default): taken while a CU holds at most one chain
-                                    (R <= CUs); 1: wherever that shape is launched; 2: never.
+                                    0 (default): taken while a CU holds at most five chains
+                                    (four chain waves up to two chains per CU, two beyond);
+                                    1: wherever that shape is launched; 2: never.
                                     Results do not depend on it                                */
 
 #define HALP_OPT_EXCHANGE_POLL_DELAY 11 /* split minibatch loop: sleeps of 256 cycles between a

@@ -44,10 +44,30 @@ Shape pick_shape(const halp_params& p, int want_nw) {
   return Shape{nw, upl};
 }
 
+// the form with a helper wave beside every chain wave exists for these shapes
+bool helped_shape(Shape sh) { return (sh.nw == 2 || sh.nw == 4) && sh.upl <= 2; }
+
+// Chains per CU up to which that form pays, by chain waves (measured at d = 512, b = 8, epochs of
+// 16384 steps: four chain waves win up to 2 chains per CU -- 3.0 ms at 256 chains, 3.7 at 512,
+// where one wave per chain takes 5.5 -- two chain waves up to 5 per CU -- 4.2 ms at 576 chains,
+// 6.0 at 1280 against 4.8 and 7.6 -- beyond that one wave per chain and no helpers)
+constexpr int kHelpedChainsPerCu4 = 2, kHelpedChainsPerCu2 = 5;
+
 // waves per chain: use the chip's SIMDs when chains are few, one wave per chain
 // when they are many
 int auto_waves(const halp_handle& h) {
   if (h.inner_waves > 0) return h.inner_waves;
+  if (h.inner_helpers != 2) {
+    const int64_t R = h.p.R, cus = h.num_cus;
+    if (R <= kHelpedChainsPerCu4 * cus) {
+      const Shape sh = pick_shape(h.p, 4);
+      if (sh.nw == 4 && helped_shape(sh)) return 4;
+    }
+    if (R <= kHelpedChainsPerCu2 * cus) {
+      const Shape sh = pick_shape(h.p, 2);
+      if (sh.nw == 2 && helped_shape(sh)) return 2;
+    }
+  }
   const int64_t simds = 4 * (int64_t)h.num_cus;
   int nw = 1;
   while (nw < 4 && (int64_t)h.p.R * nw * 2 <= simds) nw *= 2;
@@ -84,9 +104,10 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   }
   if (!launchable(sh)) return HALP_ERR_UNSUPPORTED;
   // Few chains, two or four waves each: a helper wave beside every chain wave takes whatever
-  // does not depend on z off the step's dependent chain.  Worth it while a CU holds one chain.
-  const bool helped_built = (sh.nw == 2 || sh.nw == 4) && sh.upl <= 2;
-  if (helped_built && (h.inner_helpers == 1 || (h.inner_helpers == 0 && (int64_t)p.R <= h.num_cus)))
+  // does not depend on z off the step's dependent chain.  Worth it while a CU holds a few chains.
+  const bool helped_built = helped_shape(sh);
+  if (helped_built &&
+      (h.inner_helpers == 1 || (h.inner_helpers == 0 && (int64_t)p.R <= (int64_t)kHelpedChainsPerCu2 * h.num_cus)))
     return p.b == 8 ? launch_inner_reg_helped_b8(a, sh.nw, sh.upl, p.R, s)
                     : launch_inner_reg_helped_b16(a, sh.nw, sh.upl, p.R, s);
   // 8 bits, one wave per chain: the packed form once every SIMD holds two chains or more (its
