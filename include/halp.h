@@ -136,9 +136,10 @@ typedef struct {
                                     Register-resident kernels exist for B = 1 with K = 1 (squared,
                                     logistic; d up to 8 strips of 16 rounding bits per lane and
                                     16 waves), for K = 1 with 2 <= B <= 64 (same limit on d), and
-                                    for softmax with B = 1, K <= 15 (a class's row of z within 8
-                                    strips per lane of one wave at 8 bits, 16 at 16 bits, and
-                                    the staged rows within the LDS of a CU); auto takes
+                                    for softmax with B = 1 (a class's row of z within 8
+                                    strips per lane of one wave at 8 bits, 16 at 16 bits -- 8
+                                    at either width for 16 classes, which share waves in
+                                    pairs -- and the staged rows within the LDS of a CU); auto takes
                                     them when the shape fits, 2 fails with HALP_ERR_UNSUPPORTED
                                     when it does not.  HALP_ALG_SVRG has one fp32 kernel and
                                     ignores this option                                      */

@@ -1,7 +1,9 @@
 // Inner loop of Algorithm 4 (LM-HALP) for softmax regression (K classes, one
 // sampled row per step), register-resident form with specialised waves.
 //
-// One workgroup per chain: K class waves and one service wave.
+// One workgroup per chain: K / CPW class waves and one service wave (CPW = 1 up to 15
+// classes; CPW = 2, two rows of z per class wave, for the 16 classes that would need a
+// seventeenth wave).
 //
 // Class wave c owns row c of z ([K][d]): lane l holds the UPL consecutive strips
 // (16 rounding bits each; UPL up to 8 at 8 bits, up to 16 at 16 bits) starting at l * UPL,
@@ -71,7 +73,7 @@ __device__ __forceinline__ double row_max_f64(double v) {
   return row_fold_f64(v, [](double x, double y) { return fmax(x, y); });
 }
 
-template <int BITS, int UPL, int KT>
+template <int BITS, int UPL, int KT, int CPW>
 __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
@@ -80,11 +82,12 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   constexpr int CPL = UPL * CT;
   constexpr int NDW = (UPL + 1) / 2;
   constexpr int PQ = UPL >= 4 ? UPL / 4 : 1;  // 16-byte slots per word of a lane's parked blocks
-  constexpr int BPS = UPL > 8 ? 2 : 1;        // Philox blocks of the next window made per step
+  constexpr int BPS = (CPW * UPL + 7) / 8;    // Philox blocks of the next window made per step
   constexpr int kRowQ = UPL > 8 ? 8 : 4;      // dwords of a row per service lane: rows up to 1 / 2 KB
   // 16 strips per lane leave no registers for operands prepared ahead of gamma: the sampled
   // row stays packed and everything else of the update is formed after the second barrier
-  constexpr bool LEAN = UPL > 8;
+  // (and so does a second row of z per wave)
+  constexpr bool LEAN = UPL > 8 || CPW > 1;
   // 8 bits: the two coordinates of a strip are kept and updated as the 16-bit halves of one
   // register (the class waves share their SIMDs three deep and are bound by issue slots)
   constexpr bool PK = BITS == 8 && !LEAN;
@@ -98,6 +101,7 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   const int U = (d + CT - 1) / CT;
   const int NACT = (U + UPL - 1) / UPL;  // lanes of a class wave that hold part of the row
   const int NP = K * NACT;               // ... of all class waves: slots of the parked blocks
+  const int NCW = K / CPW;               // class waves; wave NCW is the service wave
   const int64_t T = epoch_steps(a.seed + (uint64_t)blockIdx.x, a.epoch, a.T, a.option2);
   const int64_t row_bytes = a.ldxq * (BITS / 8);
   const int row_dw = (int)(row_bytes / 4);
@@ -129,7 +133,7 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
   if (tid < 8) s_zero[tid] = 0;
   const bool use_reg = a.lambda > 0;
 
-  if (wave == K) {
+  if (wave == NCW) {
     // ===================================================================== service wave
     // every class wave waits for this one at the step's second barrier: it goes first
     // wherever it shares a SIMD with class waves
@@ -266,22 +270,25 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     if (n_reg) atomicAdd(&s_cnt[2], (unsigned long long)n_reg);
   } else {
     // ======================================================================= class wave
-    const int cls = wave;
-    const int64_t row0 = ((int64_t)chain * K + cls) * d;
-    const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + row0;
-    XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + row0;
-    float* __restrict__ wg = a.w + row0;
+    // rows cls0 .. cls0 + CPW - 1 of z
+    const int cls0 = wave * CPW;
+    auto row0_of = [&](int cc) { return ((int64_t)chain * K + cls0 + cc) * d; };
     const int s0 = lane * UPL;
     const int j0 = s0 * CT;
     const bool lane_ok = s0 < U;  // = lane < NACT
-    int z[CPL];
-    int hv[CPL];  // -h~ at b = 8, h~ at b = 16
+    int z[CPW][CPL];
+    int hv[CPW][CPL];  // -h~ at b = 8, h~ at b = 16
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-      const int j = j0 + k;
-      const bool ok = j < d;
-      z[k] = ok ? (int)zg[j] : 0;
-      hv[k] = ok ? (BITS == 8 ? -(int)hg[j] : (int)hg[j]) : 0;
+    for (int cc = 0; cc < CPW; ++cc) {
+      const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + row0_of(cc);
+      const XT* __restrict__ zg = reinterpret_cast<const XT*>(a.z) + row0_of(cc);
+#pragma unroll
+      for (int k = 0; k < CPL; ++k) {
+        const int j = j0 + k;
+        const bool ok = j < d;
+        z[cc][k] = ok ? (int)zg[j] : 0;
+        hv[cc][k] = ok ? (BITS == 8 ? -(int)hg[j] : (int)hg[j]) : 0;
+      }
     }
     // packed form: z, and -h~ = 256 hh + hl with 0 <= hl < 256, two coordinates per register
     S2 zp[PK ? UPL : 1], hlp[PK ? UPL : 1], hhp[PK ? UPL : 1];
@@ -289,26 +296,33 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
 #pragma unroll
       for (int u = 0; u < UPL; ++u) {
         const int k0 = (2 * u) % CPL, k1 = (2 * u + 1) % CPL;
-        zp[PK ? u : 0] = S2{(short)z[k0], (short)z[k1]};
-        hlp[PK ? u : 0] = S2{(short)(hv[k0] & 0xFF), (short)(hv[k1] & 0xFF)};
-        hhp[PK ? u : 0] = S2{(short)(hv[k0] >> 8), (short)(hv[k1] >> 8)};
+        zp[PK ? u : 0] = S2{(short)z[0][k0], (short)z[0][k1]};
+        hlp[PK ? u : 0] = S2{(short)(hv[0][k0] & 0xFF), (short)(hv[0][k1] & 0xFF)};
+        hhp[PK ? u : 0] = S2{(short)(hv[0][k0] >> 8), (short)(hv[0][k1] >> 8)};
       }
     }
     const int frag_dw = lane_ok ? (s0 * 2) >> 2 : 0;  // dword index of the fragment in a row
     const int half_sh = (UPL == 1 && lane_ok) ? ((s0 * 2) & 2) * 8 : 0;
-    const uint32_t strip0 = (uint32_t)(cls * U + s0);
-    const int pidx = cls * NACT + lane;  // slot of this lane's parked blocks (lanes on the row only)
+    // first strip of this lane in row cc, and the slot of its parked blocks (lanes on the row only)
+    auto strip0_of = [&](int cc) { return (uint32_t)((cls0 + cc) * U + s0); };
+    auto pidx_of = [&](int cc) { return (cls0 + cc) * NACT + lane; };
     using LdsAcc = __attribute__((address_space(3))) AccT;
-    LdsAcc* const slotD0 = (LdsAcc*)(lane == 63 ? &s_D[0][cls] : &s_dumpD[lane]);
-    LdsAcc* const slotD1 = (LdsAcc*)(lane == 63 ? &s_D[1][cls] : &s_dumpD[lane]);
+    LdsAcc* slotD[CPW][2];
+#pragma unroll
+    for (int cc = 0; cc < CPW; ++cc)
+#pragma unroll
+      for (int par = 0; par < 2; ++par)
+        slotD[cc][par] = (LdsAcc*)(lane == 63 ? &s_D[par][cls0 + cc] : &s_dumpD[lane]);
     const uint4* park = reinterpret_cast<const uint4*>(s_park);
 
-    uint32_t zrw[4][UPL];  // the window's rounding words: [word of the block][strip]
+    uint32_t zrw[CPW][4][UPL];  // the window's rounding words: [row][word of the block][strip]
 #pragma unroll
-    for (int u = 0; u < UPL; ++u) {
-      const U4 r = zround_block(seed, a.epoch, strip0 + (uint32_t)u, 0u);
-      zrw[0][u] = r.x; zrw[1][u] = r.y; zrw[2][u] = r.z; zrw[3][u] = r.w;
-    }
+    for (int cc = 0; cc < CPW; ++cc)
+#pragma unroll
+      for (int u = 0; u < UPL; ++u) {
+        const U4 r = zround_block(seed, a.epoch, strip0_of(cc) + (uint32_t)u, 0u);
+        zrw[cc][0][u] = r.x; zrw[cc][1][u] = r.y; zrw[cc][2][u] = r.z; zrw[cc][3][u] = r.w;
+      }
     unsigned long long n_zclamp = 0;
     __syncthreads();
 
@@ -317,15 +331,17 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
       const bool more = t0 + kWin < T;
       if (t0 > 0 && lane_ok) {  // the blocks parked during the previous window
 #pragma unroll
-        for (int wd = 0; wd < 4; ++wd)
+        for (int cc = 0; cc < CPW; ++cc)
 #pragma unroll
-          for (int q = 0; q < PQ; ++q) {
-            const uint4 v = park[(wd * PQ + q) * NP + pidx];
-            if (4 * q + 0 < UPL) zrw[wd][(4 * q + 0) % UPL] = v.x;
-            if (4 * q + 1 < UPL) zrw[wd][(4 * q + 1) % UPL] = v.y;
-            if (4 * q + 2 < UPL) zrw[wd][(4 * q + 2) % UPL] = v.z;
-            if (4 * q + 3 < UPL) zrw[wd][(4 * q + 3) % UPL] = v.w;
-          }
+          for (int wd = 0; wd < 4; ++wd)
+#pragma unroll
+            for (int q = 0; q < PQ; ++q) {
+              const uint4 v = park[(wd * PQ + q) * NP + pidx_of(cc)];
+              if (4 * q + 0 < UPL) zrw[cc][wd][(4 * q + 0) % UPL] = v.x;
+              if (4 * q + 1 < UPL) zrw[cc][wd][(4 * q + 1) % UPL] = v.y;
+              if (4 * q + 2 < UPL) zrw[cc][wd][(4 * q + 2) % UPL] = v.z;
+              if (4 * q + 3 < UPL) zrw[cc][wd][(4 * q + 3) % UPL] = v.w;
+            }
       }
 #pragma unroll
       for (int s = 0; s < kWin; ++s) {
@@ -357,7 +373,9 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
           };
           int xe[LEAN ? 1 : CPL];
           S2 xp[PK ? UPL : 1];
-          AccT part = 0;
+          AccT part[CPW];
+#pragma unroll
+          for (int cc = 0; cc < CPW; ++cc) part[cc] = 0;
           if (PK) {
             // the strip's two bytes go to the high bytes of the halves and come back down with
             // their signs; one packed dot per strip
@@ -365,65 +383,79 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
             for (int u = 0; u < UPL; ++u) {
               const uint32_t up = __builtin_amdgcn_perm(0u, xw[u / 2], (u & 1) ? 0x030C020Cu : 0x010C000Cu);
               xp[PK ? u : 0] = __builtin_bit_cast(S2, up) >> (S2)(8);
-              part = (AccT)__builtin_amdgcn_sdot2(xp[PK ? u : 0], zp[PK ? u : 0], (int)part, false);
+              part[0] = (AccT)__builtin_amdgcn_sdot2(xp[PK ? u : 0], zp[PK ? u : 0], (int)part[0], false);
             }
           } else if (!LEAN) {
 #pragma unroll
             for (int k = 0; k < CPL; ++k) {
               xe[LEAN ? 0 : k] = x_of(k);
-              if (BITS == 8) part = (AccT)mad24(xe[LEAN ? 0 : k], z[k], (int)part);
+              if (BITS == 8) part[0] = (AccT)mad24(xe[LEAN ? 0 : k], z[0][k], (int)part[0]);
+            }
+          } else if (BITS == 8) {
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+              const int xk = x_of(k);
+#pragma unroll
+              for (int cc = 0; cc < CPW; ++cc) part[cc] = (AccT)mad24(xk, z[cc][k], (int)part[cc]);
             }
           }
           if (BITS == 16) {
             // two products of 16-bit factors fit 32 bits; their sums are added in 64
-            if (CPL == 1) {
-              part = (AccT)mad24(x_of(0), z[0], 0);
-            } else {
 #pragma unroll
-              for (int k = 0; k + 1 < CPL; k += 2)
-                part += (AccT)mad24(x_of(k), z[k], mad24(x_of(k + 1), z[k + 1], 0));
+            for (int cc = 0; cc < CPW; ++cc) {
+              if (CPL == 1) {
+                part[cc] = (AccT)mad24(x_of(0), z[cc][0], 0);
+              } else {
+#pragma unroll
+                for (int k = 0; k + 1 < CPL; k += 2)
+                  part[cc] += (AccT)mad24(x_of(k), z[cc][k], mad24(x_of(k + 1), z[cc][k + 1], 0));
+              }
             }
           }
           // the fold leaves the sum in lane 63, which stores it; the other lanes store their
           // partial folds into a dump row, so that no lane mask is set up and no lane is read
-          AccT D;
-          if (BITS == 8) D = (AccT)wave_fold_i32((int)part);
-          else D = (AccT)wave_fold_i64((long long)part);
-          *((s & 1) ? slotD1 : slotD0) = D;
+#pragma unroll
+          for (int cc = 0; cc < CPW; ++cc) {
+            AccT D;
+            if (BITS == 8) D = (AccT)wave_fold_i32((int)part[cc]);
+            else D = (AccT)wave_fold_i64((long long)part[cc]);
+            *slotD[cc][s & 1] = D;
+          }
           __syncthreads();
           // While the service wave evaluates the softmax: the part of the update that does
           // not need gamma, and the Philox blocks of the next window.
           // b = 8: hr = -h~ + rounding bits.  b = 16: with h~ = 2^16 hh + hl, 0 <= hl < 2^16,
           // floor((-gamma x + bits - h~) / 2^16) = floor((-gamma x + bits - hl) / 2^16) - hh, and
           // the numerator on the right fits 32 bits; hr = bits - hl.
-          auto hr_of = [&](int k) {
-            const uint32_t word = zrw[s >> 1][k / CT];
+          auto hr_of = [&](int cc, int k) {
+            const uint32_t word = zrw[cc][s >> 1][k / CT];
             const int sh = 16 * (s & 1) + (k % CT) * BITS;
             const int re = (int)((word >> sh) & (BITS == 8 ? 0xFFu : 0xFFFFu));
-            if (BITS == 16) asm volatile("" : "+v"(hv[k]));  // keeps hl, hh from being hoisted into registers
-            return BITS == 8 ? hv[k] + re : re - (hv[k] & 0xFFFF);
+            if (BITS == 16) asm volatile("" : "+v"(hv[cc][k]));  // keeps hl, hh from being hoisted into registers
+            return BITS == 8 ? hv[cc][k] + re : re - (hv[cc][k] & 0xFFFF);
           };
           int hr[LEAN ? 1 : CPL];
           S2 crp[PK ? UPL : 1], zh[PK ? UPL : 1];
           if (PK) {
 #pragma unroll
             for (int u = 0; u < UPL; ++u) {
-              const uint32_t rp = __builtin_amdgcn_perm(0u, zrw[s >> 1][u], (s & 1) ? 0x0C030C02u : 0x0C010C00u);
+              const uint32_t rp = __builtin_amdgcn_perm(0u, zrw[0][s >> 1][u], (s & 1) ? 0x0C030C02u : 0x0C010C00u);
               crp[PK ? u : 0] = __builtin_bit_cast(S2, rp) + hlp[PK ? u : 0];  // rounding bits + hl
               zh[PK ? u : 0] = hhp[PK ? u : 0] + zp[PK ? u : 0];
             }
           } else if (!LEAN) {
 #pragma unroll
-            for (int k = 0; k < CPL; ++k) hr[LEAN ? 0 : k] = hr_of(k);
+            for (int k = 0; k < CPL; ++k) hr[LEAN ? 0 : k] = hr_of(0, k);
           }
 #pragma unroll
           for (int q = 0; q < BPS; ++q) {
             if (q > 0) __builtin_amdgcn_sched_barrier(0);  // one block's temporaries at a time
-            const int u = s * BPS + q;
-            if (u < UPL && more) {
-              const U4 r = zround_block(seed, a.epoch, strip0 + (uint32_t)u, (uint32_t)(t0 >> 3) + 1u);
+            const int ub = s * BPS + q;  // block number within the window: row ub / UPL, strip ub % UPL
+            if (ub < CPW * UPL && more) {
+              const int cc = ub / UPL, u = ub % UPL;
+              const U4 r = zround_block(seed, a.epoch, strip0_of(cc) + (uint32_t)u, (uint32_t)(t0 >> 3) + 1u);
               if (lane_ok) {
-                uint32_t* slot = s_park + ((size_t)((u / 4) * NP + pidx)) * 4 + (u % 4);
+                uint32_t* slot = s_park + ((size_t)((u / 4) * NP + pidx_of(cc))) * 4 + (u % 4);
                 const size_t word_stride = (size_t)PQ * NP * 4;
                 slot[0] = r.x; slot[word_stride] = r.y; slot[2 * word_stride] = r.z; slot[3 * word_stride] = r.w;
               }
@@ -431,28 +463,32 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
           }
           __builtin_amdgcn_sched_barrier(0);
           __syncthreads();
-          const int ng = s_ng[s & 1][cls];
+          int ng[CPW];
+#pragma unroll
+          for (int cc = 0; cc < CPW; ++cc) ng[cc] = s_ng[s & 1][cls0 + cc];
           const int cl = use_reg ? __builtin_amdgcn_readfirstlane(s_creg[buf][s]) : 0;
           // u = z - gamma x - h~ (- c_lambda z), z = Q_(delta_m, b)(u)
           auto update = [&](auto with_l2) {
 #pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-              int hk = LEAN ? hr_of(k) : hr[LEAN ? 0 : k];
-              if (decltype(with_l2)::value) hk = mad24(-cl, z[k], hk);
-              const int xk = LEAN ? x_of(k) : xe[LEAN ? 0 : k];
-              int zu;
-              if (BITS == 8) zu = z[k] + (mad24(ng, xk, hk) >> 8);
-              else zu = z[k] + (mad24(ng, xk, hk) >> 16) - (hv[k] >> 16);
-              const int zc = min(max(zu, QMIN), QMAX);
-              // clamps are counted on the scalar unit: one compare here, the rest is wave-wide
-              n_zclamp += (unsigned long long)__builtin_popcountll(__ballot(zu != zc));
-              z[k] = zc;
-            }
+            for (int cc = 0; cc < CPW; ++cc)
+#pragma unroll
+              for (int k = 0; k < CPL; ++k) {
+                int hk = LEAN ? hr_of(cc, k) : hr[LEAN ? 0 : k];
+                if (decltype(with_l2)::value) hk = mad24(-cl, z[cc][k], hk);
+                const int xk = LEAN ? x_of(k) : xe[LEAN ? 0 : k];
+                int zu;
+                if (BITS == 8) zu = z[cc][k] + (mad24(ng[cc], xk, hk) >> 8);
+                else zu = z[cc][k] + (mad24(ng[cc], xk, hk) >> 16) - (hv[cc][k] >> 16);
+                const int zc = min(max(zu, QMIN), QMAX);
+                // clamps are counted on the scalar unit: one compare here, the rest is wave-wide
+                n_zclamp += (unsigned long long)__builtin_popcountll(__ballot(zu != zc));
+                z[cc][k] = zc;
+              }
           };
           if (PK && cl == 0) {
             // per half: floor((-gamma x + r + hl) / 256) + hh + z; |gamma x| <= 2^14 and
             // r + hl < 512, so every intermediate fits 16 bits
-            const S2 ngp = S2{(short)ng, (short)ng};
+            const S2 ngp = S2{(short)ng[0], (short)ng[0]};
             S2 vu[PK ? UPL : 1];
             uint32_t moved = 0;
 #pragma unroll
@@ -475,13 +511,13 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
           } else if (PK) {  // a step with an L2 draw: unpack, the scalar form, pack again
 #pragma unroll
             for (int k = 0; k < CPL; ++k) {
-              z[k] = (int)zp[(k / 2) % UPL][k % 2];
+              z[0][k] = (int)zp[(k / 2) % UPL][k % 2];
               xe[LEAN ? 0 : k] = (int)xp[(k / 2) % UPL][k % 2];
-              hr[LEAN ? 0 : k] = hr_of(k);
+              hr[LEAN ? 0 : k] = hr_of(0, k);
             }
             update(std::true_type{});
 #pragma unroll
-            for (int u = 0; u < (PK ? UPL : 0); ++u) zp[u] = S2{(short)z[(2 * u) % CPL], (short)z[(2 * u + 1) % CPL]};
+            for (int u = 0; u < (PK ? UPL : 0); ++u) zp[u] = S2{(short)z[0][(2 * u) % CPL], (short)z[0][(2 * u + 1) % CPL]};
           } else if (cl != 0) update(std::true_type{});  // the L2 term is rare: c_lambda is mostly 0
           else update(std::false_type{});
         }
@@ -492,19 +528,24 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
     // ---- w~ <- w~ + delta_m z (option I); hand z out
     if (PK) {
 #pragma unroll
-      for (int k = 0; k < CPL; ++k) z[k] = (int)zp[(k / 2) % UPL][k % 2];
+      for (int k = 0; k < CPL; ++k) z[0][k] = (int)zp[(k / 2) % UPL][k % 2];
     }
     const double delta_m = sc[0];
-    float wv[CPL];
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) wv[k] = wg[min(j0 + k, d - 1)];  // all loads in flight at once
+    for (int cc = 0; cc < CPW; ++cc) {
+      XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + row0_of(cc);
+      float* __restrict__ wg = a.w + row0_of(cc);
+      float wv[CPL];
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-      const int j = j0 + k;
-      if (j < d) {
-        zg[j] = (XT)z[k];
-        const double step = __dmul_rn(delta_m, (double)z[k]);
-        wg[j] = lp ? (float)step : (float)__dadd_rn((double)wv[k], step);  // Alg. 2: w~ = delta w
+      for (int k = 0; k < CPL; ++k) wv[k] = wg[min(j0 + k, d - 1)];  // all loads in flight at once
+#pragma unroll
+      for (int k = 0; k < CPL; ++k) {
+        const int j = j0 + k;
+        if (j < d) {
+          zg[j] = (XT)z[cc][k];
+          const double step = __dmul_rn(delta_m, (double)z[cc][k]);
+          wg[j] = lp ? (float)step : (float)__dadd_rn((double)wv[k], step);  // Alg. 2: w~ = delta w
+        }
       }
     }
     if (lane == 0 && n_zclamp) atomicAdd(&s_cnt[0], n_zclamp);  // wave-wide count
@@ -515,19 +556,24 @@ __global__ __launch_bounds__(64 * KT) void inner_softmax_kernel(InArgs a) {
 
 template <int BITS, int UPL>
 int launch_kt(const InArgs& a, int R, size_t smem, hipStream_t s) {
-  const dim3 grid(R), block(64 * (a.K + 1));
-#define HALP_SM(KT_)                                                                              \
+  // one row of z per class wave up to 15 classes; 16 classes: two rows per wave, 8 + 1 waves
+  const int cpw = a.K > 15 ? 2 : 1;
+  const dim3 grid(R), block(64 * (a.K / cpw + 1));
+#define HALP_SM(KT_, CPW_)                                                                        \
   do {                                                                                            \
-    auto kern = inner_softmax_kernel<BITS, UPL, KT_>;                                             \
+    auto kern = inner_softmax_kernel<BITS, UPL, KT_, CPW_>;                                       \
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) \
       return HALP_ERR_HIP;                                                                        \
     hipLaunchKernelGGL(kern, grid, block, smem, s, a);                                            \
   } while (0)
-  if (a.K + 1 <= 4) HALP_SM(4);
-  else if (a.K + 1 <= 8) HALP_SM(8);
-  else if (a.K + 1 <= 12) HALP_SM(12);
-  else HALP_SM(16);
+  if (cpw == 2) {
+    if constexpr (UPL <= 8) HALP_SM(12, 2);
+    else return HALP_ERR_UNSUPPORTED;
+  } else if (a.K + 1 <= 4) HALP_SM(4, 1);
+  else if (a.K + 1 <= 8) HALP_SM(8, 1);
+  else if (a.K + 1 <= 12) HALP_SM(12, 1);
+  else HALP_SM(16, 1);
 #undef HALP_SM
   return hip_ok(hipGetLastError());
 }
@@ -570,15 +616,16 @@ size_t dynamic_lds(const halp_params& p, int64_t row_bytes) {
 
 }  // namespace
 
-// softmax, one row per step, at most 15 classes (one wave each, plus the service wave), a
+// softmax, one row per step, up to 15 classes one wave each plus the service wave, 16 classes
+// two to a wave (8 strips per lane at most then, for the registers of two rows of z), a
 // class's row of z within one wave (8 strips per lane at most at 8 bits, 16 at 16 bits), data
 // rows up to 1 KB (2 KB at 16 strips per lane), everything staged within the LDS of a CU
 int inner_softmax_supported(const halp_handle& h) {
   const halp_params& p = h.p;
-  if (p.loss != HALP_LOSS_SOFTMAX || p.B != 1 || p.K < 2 || p.K > 15) return HALP_ERR_UNSUPPORTED;
+  if (p.loss != HALP_LOSS_SOFTMAX || p.B != 1 || p.K < 2 || p.K > 16) return HALP_ERR_UNSUPPORTED;
   if (p.b == 8 && p.d > 131071) return HALP_ERR_UNSUPPORTED;  // int32 dot product stays exact
   const int upl = strips_per_lane(p);
-  if (upl > (p.b == 16 ? 16 : 8)) return HALP_ERR_UNSUPPORTED;
+  if (upl > (p.b == 16 && p.K <= 15 ? 16 : 8)) return HALP_ERR_UNSUPPORTED;
   if (!h.bound || !h.buf.Xq) return HALP_ERR_NOT_BOUND;
   const int64_t row_bytes = h.buf.ldxq * (p.b / 8);
   const int ct = 16 / p.b;

@@ -83,6 +83,7 @@ LP_CASES = [
     (hp.LOSS_SOFTMAX, 300, 100, 3, 1, 8, 1, 300, (2, 1)),  # softmax: class waves, and the general kernel
     (hp.LOSS_SOFTMAX, 200, 784, 10, 1, 8, 2, 203, (2, 1)),  # the 10-class shape, ragged epoch
     (hp.LOSS_SOFTMAX, 150, 256, 15, 1, 16, 1, 150, (2, 1)),  # 15 classes at 16 bits
+    (hp.LOSS_SOFTMAX, 150, 300, 16, 1, 8, 1, 150, (2, 1)),   # 16 classes: two rows of z per class wave
 ]
 
 

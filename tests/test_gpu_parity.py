@@ -448,6 +448,11 @@ SOFTMAX_REG_CASES = [
     (300, 784, 10, 16, 1e-4, 1, 203, 0.05),   # the 10-class shape at 16 bits: 16 strips per lane, 49 lanes
     (200, 781, 4, 16, 1e-2, 2, 150, 0.05),    # the same with a ragged last lane, L2 draws
     (150, 1008, 2, 16, 0.0, 1, 120, 500.0),   # 63 lanes, saturating
+    (300, 784, 16, 8, 1e-3, 2, 303, 0.05),    # 16 classes: two rows of z per class wave, 8 strips per lane
+    (200, 512, 16, 16, 1e-2, 1, 270, 0.05),   # ... at 16 bits, 8 strips per lane, L2 draws
+    (150, 100, 16, 8, 0.0, 1, 520, 0.05),     # ... one strip per lane, two batches of draws
+    (100, 250, 16, 16, 0.0, 1, 33, 500.0),    # ... four strips per lane, saturating
+    (60, 7, 16, 8, 1e-2, 1, 9, 0.05),         # ... a row inside one lane
 ]
 
 
