@@ -454,7 +454,7 @@ def main():
                     help="skip the step rates of the other configurations' inner loops")
     ap.add_argument("--cpu-chains", type=int, default=64)
     ap.add_argument("--inner-waves", type=int, default=0, help="waves per chain (0 = library's choice)")
-    ap.add_argument("--inner-helpers", type=int, default=0, choices=[0, 1, 2],
+    ap.add_argument("--inner-helpers", type=int, default=0, choices=[0, 1, 2, 3],
                     help="helper waves beside the chain waves of the register inner loop: 0 the library's "
                          "choice, 1 wherever built, 2 never")
     ap.add_argument("--chains", type=int, default=0,

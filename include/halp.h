@@ -182,8 +182,13 @@ typedef struct {
                                     waves issue the step's dependent chain and little else.
                                     0 (default): taken while a CU holds at most five chains
                                     (four chain waves up to two chains per CU, two beyond);
-                                    1: wherever that shape is launched; 2: never.
-                                    Results do not depend on it                                */
+                                    1: wherever that shape is launched; 2: never; 3: the 8-bit
+                                    form with ONE chain wave that holds all of z (two
+                                    coordinates per register, packed 16-bit arithmetic) and
+                                    helper waves on the other SIMDs of the CU, for rows up to
+                                    1024 coordinates (HALP_ERR_UNSUPPORTED elsewhere); 0 takes
+                                    it for rows of 129 .. 256 coordinates at up to one chain
+                                    per CU.  Results do not depend on it                       */
 
 #define HALP_OPT_EXCHANGE_POLL_DELAY 11 /* split minibatch loop: sleeps of 256 cycles between a
                                     workgroup publishing its sums of a step and its first poll

@@ -276,7 +276,7 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
       h->inner_packed = (int)value;
       return HALP_OK;
     case HALP_OPT_INNER_HELPERS:
-      if (value < 0 || value > 2) return HALP_ERR_INVALID;
+      if (value < 0 || value > 3) return HALP_ERR_INVALID;
       h->inner_helpers = (int)value;
       return HALP_OK;
     case HALP_OPT_INNER_WAVES:

@@ -9,6 +9,7 @@ int launch_inner_reg_b8(const InArgs& a, int nw, int upl, int R, bool packed, hi
 int launch_inner_reg_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
 int launch_inner_reg_helped_b8(const InArgs& a, int nw, int upl, int R, hipStream_t s);
 int launch_inner_reg_helped_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
+int launch_inner_reg_lone_b8(const InArgs& a, int upl, int R, hipStream_t s);
 
 namespace {
 
@@ -53,6 +54,28 @@ bool helped_shape(Shape sh) { return (sh.nw == 2 || sh.nw == 4) && sh.upl <= 2; 
 // 6.0 at 1280 against 4.8 and 7.6 -- beyond that one wave per chain and no helpers)
 constexpr int kHelpedChainsPerCu4 = 2, kHelpedChainsPerCu2 = 5;
 
+// Strips per lane of the form with one chain wave and its helpers on the other SIMDs (8 bits,
+// rows up to 1024 coordinates), or 0 if the shape does not fit it.  A helper reads fragments
+// of one or two strips: every fragment that starts inside the row must end inside it.
+int lone_strips(const halp_handle& h) {
+  const halp_params& p = h.p;
+  if (p.b != 8 || p.B != 1 || p.K != 1) return 0;
+  const int U = (p.d + 1) / 2;
+  const int upl = U <= 128 ? 2 : (U <= 256 ? 4 : (U <= 512 ? 8 : 0));
+  if (upl == 0) return 0;
+  const int sph = upl == 8 ? 2 : 1;  // strips of the widest fragment a helper reads
+  if ((int64_t)((U + sph - 1) / sph) * sph * 2 > h.buf.ldxq) return 0;
+  return upl;
+}
+
+// Where the library takes that form by itself: at most one chain per CU, rows of 129 .. 256
+// coordinates (two strips per lane).  Measured per step at 256 chains, 16384 steps: d = 256
+// 317 cycles against 428 with two chain waves and helpers; d = 512 432 against 429 with four,
+// d = 1024 685 against 560 (the single wave issues ~9 instructions per strip and step, at ~6
+// cycles each); up to 128 coordinates one wave without helpers is faster still.
+constexpr int kLoneChainsPerCu = 1;
+bool lone_pays(const halp_handle& h, int upl) { return upl == 2 && h.p.d > 128; }
+
 // waves per chain: use the chip's SIMDs when chains are few, one wave per chain
 // when they are many
 int auto_waves(const halp_handle& h) {
@@ -89,6 +112,12 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   int rc = inner_reg_supported(p);
   if (rc != HALP_OK) return rc;
   const InArgs a = make_inner_args(h, epoch);
+  // 8 bits, at most one chain per CU: one chain wave with all of z, helpers on the other SIMDs
+  const int lone_upl = lone_strips(h);
+  if (lone_upl > 0 && (h.inner_helpers == 3 || (h.inner_helpers == 0 && h.inner_waves == 0 && lone_pays(h, lone_upl) &&
+                                                 (int64_t)p.R <= (int64_t)kLoneChainsPerCu * h.num_cus)))
+    return launch_inner_reg_lone_b8(a, lone_upl, p.R, s);
+  if (h.inner_helpers == 3) return HALP_ERR_UNSUPPORTED;
   Shape sh = pick_shape(p, auto_waves(h));
   const int ct = 16 / p.b;
   const int U = (p.d + ct - 1) / ct;

@@ -353,10 +353,76 @@ def test_inner_loop_with_helper_waves_every_epoch_length(loss, d, b, lam, waves,
         assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
         assert np.array_equal(w[r], ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r]))
         assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
-    for bad in (-1, 3):
+    for bad in (-1, 4):
         with pytest.raises(hp.HalpError) as e:
             P.h.set_option(hp.OPT_INNER_HELPERS, bad)
         assert e.value.code == hp.ERR_INVALID
+
+
+LONE_CASES = [c for c in INNER_REG_CASES if c[3] == 8 and c[2] <= 1024] + [
+    # loss, N, d, b, lam, R, T, mu
+    (hp.LOSS_SQUARED, 300, 1000, 8, 5e-2, 2, 400, 0.2),     # eight strips per lane, ragged, frequent L2 draws
+    (hp.LOSS_LOGISTIC, 200, 130, 8, 1e-3, 1, 300, 0.2),     # two strips per lane, ragged last lane
+    (hp.LOSS_LOGISTIC, 300, 257, 8, 5e-2, 2, 333, 500.0),   # odd width, saturating, L2 draws
+    (hp.LOSS_SQUARED, 100, 1024, 8, 0.0, 1, 100, 500.0),    # every lane full, saturating
+]
+
+
+@pytest.mark.parametrize("loss,N,d,b,lam,R,T,mu", LONE_CASES)
+def test_inner_loop_one_chain_wave_bit_exact(loss, N, d, b, lam, R, T, mu):
+    """The 8-bit form with a single chain wave (packed 16-bit halves) and helper waves on the
+    other SIMDs, forced on (option 3) so that no other kernel can stand in: 2, 4 and 8 strips
+    per lane, ragged rows, L2 draws, saturation."""
+    seed = 40 + d + T
+    case = _inner_case(loss, N, d, 1, 1, b, lam, R, T, seed, mu=mu)
+    P = _run_inner(case, loss, 1, 1, b, lam, R, T, seed, 2, mu=mu)
+    P.h.set_option(hp.OPT_INNER_HELPERS, 3)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    assert P.h.get_stats(0).inner_variant == 2
+    for r in range(R):
+        out = _oracle_inner(case, r, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        w_r = ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r])
+        assert np.array_equal(w[r], w_r)
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    if mu > 100:
+        assert cnt[0, 0] > 0
+
+
+@pytest.mark.parametrize("T", [0, 1, 2, 7, 8, 9, 15, 16, 17, 23, 24, 25, 33, 255, 256, 257, 263, 264, 513])
+@pytest.mark.parametrize("loss,d,lam", [
+    (hp.LOSS_SQUARED, 512, 0.0),      # four strips per lane
+    (hp.LOSS_SQUARED, 1000, 5e-2),    # eight, ragged, frequent L2 draws
+    (hp.LOSS_LOGISTIC, 200, 1e-3),    # two
+])
+def test_inner_loop_one_chain_wave_every_epoch_length(loss, d, lam, T):
+    """Records are handed over a window of 8 steps ahead, rows are requested three windows
+    ahead and the step-indexed draws are refilled every 256 steps: epoch lengths around each
+    of those spans."""
+    N, R = 150, 2
+    seed = 700 + d + T
+    case = _inner_case(loss, N, d, 1, 1, 8, lam, R, T, seed, mu=0.2)
+    P = _run_inner(case, loss, 1, 1, 8, lam, R, T, seed, 2, mu=0.2)
+    P.h.set_option(hp.OPT_INNER_HELPERS, 3)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    for r in range(R):
+        out = _oracle_inner(case, r, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        assert np.array_equal(w[r], ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r]))
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+
+
+def test_one_chain_wave_form_is_refused_where_it_does_not_exist():
+    # 16 bits, and rows of more than 1024 coordinates: forcing the form is an error, not a wrong answer
+    for d, b in ((256, 16), (2048, 8)):
+        case = _inner_case(hp.LOSS_SQUARED, 100, d, 1, 1, b, 0.0, 1, 20, 5, mu=0.2)
+        P = _run_inner(case, hp.LOSS_SQUARED, 1, 1, b, 0.0, 1, 20, 5, 2, mu=0.2)
+        P.h.set_option(hp.OPT_INNER_HELPERS, 3)
+        with pytest.raises(hp.HalpError) as e:
+            P.h.inner_loop(3)
+        assert e.value.code == hp.ERR_UNSUPPORTED
 
 
 @pytest.mark.parametrize("loss,N,d,b,lam,R,T,mu", [c for c in INNER_REG_CASES if c[3] == 8 and c[2] <= 1024])
