@@ -146,10 +146,12 @@ def chip_filled_inner_loop(hp, inp, torch, cfg, chains=2048, epochs=3):
 
 
 def step_latency_floor(hp, torch, T, inner_ms, waves=4, steps=65536):
-    """The dependent chain of one 8-bit step (multiply-adds, DPP fold, one LDS word per wave and
-    a barrier, the fp64 path of gamma, the update) run alone by the library's micro-kernel, one
-    workgroup per CU: the time per step no several-wave kernel with one chain per CU can beat,
-    and the share of it the measured inner loop reaches."""
+    """The dependent chain of one 8-bit step run alone by the library's micro-kernel, one workgroup
+    per CU, and the share of it the measured inner loop reaches.  waves = 4: the several-wave form
+    (multiply-adds, DPP fold, one LDS word per wave and a barrier, the fp64 path of gamma, the
+    update).  waves = 1: the form with one chain wave (a row of 512 coordinates in four strips per
+    lane: packed dots, DPP fold, fp64 path, packed update, one LDS store; records from an LDS
+    ring, one barrier per 8 steps)."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     out = torch.empty(cus * waves * 64, dtype=torch.int32, device="cuda")
     hp.debug_step_latency(waves, 8192, cus, out)
@@ -164,10 +166,14 @@ def step_latency_floor(hp, torch, T, inner_ms, waves=4, steps=65536):
         ms = e0.elapsed_time(e1)
         best = ms if best is None else min(best, ms)
     ns = best * 1e6 / steps
-    return dict(kernel="step_latency_kernel", waves_per_chain=waves, chain_ns_per_step=ns,
+    what = ("critical path of a step (dot, DPP fold, LDS word + barrier, fp64 scalar path, update) "
+            "measured alone" if waves > 1 else
+            "the chain wave's step (packed dots, DPP fold, fp64 scalar path, packed update, LDS store of "
+            "the unclamped strips; records from an LDS ring) measured alone")
+    return dict(kernel="step_latency_kernel" if waves > 1 else "step_latency_lone_kernel",
+                waves_per_chain=waves, chain_ns_per_step=ns,
                 bound_ms=ns * T * 1e-6, achieved_ms=inner_ms, frac=ns * T * 1e-6 / inner_ms,
-                what="critical path of a step (dot, DPP fold, LDS word + barrier, fp64 scalar "
-                     "path, update) measured alone; frac = bound_ms / achieved_ms")
+                what=what + "; frac = bound_ms / achieved_ms")
 
 
 def c2_inner_loop(hp, inp, torch, T=20000):
@@ -532,10 +538,16 @@ def main():
     # fp32 SVRG: one FMA for the dot, one FMA and one subtraction for the update per coordinate
     laneops = 3.0 if args.algorithm == "svrg" else LANEOPS_PER_UPDATE_B8
     # at the headline shape (few chains, four waves each) the register kernel with helper waves runs
-    helped = (args.algorithm != "svrg" and args.inner_helpers != 2 and args.inner_waves in (0, 2, 4) and d <= 1024
-              and (R <= 5 * 256 or args.inner_helpers == 1))
+    # the library's launch rule at 8 bits, restated: one chain wave + helpers on the other SIMDs for
+    # rows of 129 .. 512 coordinates up to two chains per CU; chain waves with a helper beside each
+    # up to five chains per CU; one wave per chain beyond
+    lone = (args.algorithm != "svrg" and d <= 1024 and
+            (args.inner_helpers == 3 or (args.inner_helpers == 0 and args.inner_waves == 0
+                                         and 128 < d <= 512 and R <= 2 * 256)))
+    helped = (not lone and args.algorithm != "svrg" and args.inner_helpers in (0, 1)
+              and args.inner_waves in (0, 2, 4) and d <= 1024 and (R <= 5 * 256 or args.inner_helpers == 1))
     inner_kernel = "inner_svrg_kernel" if args.algorithm == "svrg" else (
-        "inner_reg_helped_kernel" if helped else "inner_reg_kernel")
+        "inner_reg_lone_kernel" if lone else ("inner_reg_helped_kernel" if helped else "inner_reg_kernel"))
     alu_achieved = updates * laneops / (inner_ms * 1e-3)
     fg_bytes = (1 if cfg.get("share_data") else R) * N * (4 * d + 4 + 4) + \
         (R * N * 4 if cfg.get("share_data") else 0)
@@ -569,7 +581,7 @@ def main():
                          "Xeon E7-4850 v3 cores (Table 3); no GPU or bandwidth figure is published",
     }
     if args.algorithm == "halp" and args.workload == "c4" and args.chains in (0, WORKLOADS["c4"]["R"]):
-        out["roofline"]["latency"] = step_latency_floor(hp, torch, T, inner_ms)
+        out["roofline"]["latency"] = step_latency_floor(hp, torch, T, inner_ms, waves=1 if lone else 4)
     if args.algorithm == "halp":  # the same matrix through a kernel that only reads
         ceiling = read_ceiling(hp, torch, X)
         out["roofline_full_gradient"]["read_only_kernel_GBs"] = ceiling

@@ -187,7 +187,7 @@ typedef struct {
                                     coordinates per register, packed 16-bit arithmetic) and
                                     helper waves on the other SIMDs of the CU, for rows up to
                                     1024 coordinates (HALP_ERR_UNSUPPORTED elsewhere); 0 takes
-                                    it for rows of 129 .. 256 coordinates at up to one chain
+                                    it for rows of 129 .. 512 coordinates at up to two chains
                                     per CU.  Results do not depend on it                       */
 
 #define HALP_OPT_EXCHANGE_POLL_DELAY 11 /* split minibatch loop: sleeps of 256 cycles between a
@@ -302,10 +302,13 @@ int halp_debug_read_bandwidth(const void* p, int64_t bytes, uint32_t* out, void*
 /* Measurement aid, not part of the method: the dependent chain of one 8-bit inner-loop step
  * (Algorithm 4, inner `for t`, one sampled row, two coordinates per lane) with nothing beside
  * it: multiply-adds, DPP fold, one LDS word per wave and a barrier, the fp64 path of gamma, the
- * update.  `blocks` workgroups (1 .. 65535) of `waves` waves (1, 2 or 4) run `steps` steps (a
+ * update.  `blocks` workgroups (1 .. 65535) of `waves` waves (2 or 4) run `steps` steps (a
  * multiple of 8, >= 8) on lane constants; out (DEVICE) receives blocks * waves * 64 uint32.
  * Its time per step is the latency floor of the several-wave register kernels when a CU holds
- * one chain.                                                                              */
+ * one chain.  `waves` = 1: the chain of the form with one chain wave instead (a row of 512
+ * coordinates, four strips per lane on packed 16-bit halves: packed dots, DPP fold, fp64 path,
+ * packed update, one LDS store of the unclamped strips; records read from an LDS ring, one
+ * barrier per 8 steps): the floor of that form.                                           */
 int halp_debug_step_latency(int32_t waves, int64_t steps, int32_t blocks, uint32_t* out,
                             void* stream);
 

@@ -68,13 +68,14 @@ int lone_strips(const halp_handle& h) {
   return upl;
 }
 
-// Where the library takes that form by itself: at most one chain per CU, rows of 129 .. 256
-// coordinates (two strips per lane).  Measured per step at 256 chains, 16384 steps: d = 256
-// 317 cycles against 428 with two chain waves and helpers; d = 512 432 against 429 with four,
-// d = 1024 685 against 560 (the single wave issues ~9 instructions per strip and step, at ~6
-// cycles each); up to 128 coordinates one wave without helpers is faster still.
-constexpr int kLoneChainsPerCu = 1;
-bool lone_pays(const halp_handle& h, int upl) { return upl == 2 && h.p.d > 128; }
+// Where the library takes that form by itself: up to two chains per CU, rows of 129 .. 512
+// coordinates (two or four strips per lane).  Measured per epoch of 16384 steps at d = 512 (ms):
+// 128 chains 2.57 against 2.91 for four chain waves with helpers, 256: 2.66 / 3.00, 384: 3.19 /
+// 3.67, 512: 3.26 / 3.69; 768: 5.95 against 4.27 for the library's choice there, 1024: 6.43 / 5.15.
+// d = 256 at 256 chains: 2.10 against 2.91.  d = 1024: 3.97 against 3.79 (the single wave issues
+// ~9 instructions per strip and step); up to 128 coordinates one wave without helpers is faster.
+constexpr int kLoneChainsPerCu = 2;
+bool lone_pays(const halp_handle& h, int upl) { return upl <= 4 && h.p.d > 128; }
 
 // waves per chain: use the chip's SIMDs when chains are few, one wave per chain
 // when they are many

@@ -103,10 +103,14 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
   __shared__ __attribute__((aligned(16))) int s_creg[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_phi[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_y[2 * kBatch];
-  __shared__ unsigned long long s_cnt[3];
+  __shared__ unsigned long long s_cnt[4];
   // records: [half of the ring][step of the window][quad][lane], 16 bytes each
   extern __shared__ __attribute__((aligned(16))) int4r s_rec[];
   auto rec_at = [&](int half, int s, int q) -> int4r* { return s_rec + ((half * kWin + s) * NQ + q) * 64 + lane; };
+  // behind it, what the chain wave hands back: the unclamped strips of every step, [half][step][quad][lane]
+  constexpr int NQV = UPL >= 4 ? UPL / 4 : 1;
+  int4r* const s_vlog = s_rec + 2 * kWin * NQ * 64;
+  auto vlog_at = [&](int half, int s, int q) -> int4r* { return s_vlog + ((half * kWin + s) * NQV + q) * 64 + lane; };
 
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
@@ -120,7 +124,7 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
   const int s0 = lane * UPL;  // first strip of the lane
   const int j0 = s0 * 2;      // first coordinate
 
-  if (tid < 3) s_cnt[tid] = 0;
+  if (tid < 4) s_cnt[tid] = 0;
 
   if (is_service) {
     // ============================ service wave ============================
@@ -159,6 +163,35 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
         *reinterpret_cast<int4*>(&s_creg[half + 4 * lane]) = cv;
       }
     };
+    // Clamped coordinates: the chain wave stores the unclamped strips of a step (one LDS store)
+    // instead of comparing them with the clamped ones; they are counted here, a window later.
+    // A half outside [-128, 127] has a bit set above its low byte once 128 is added.
+    unsigned int n_lane = 0;  // this lane's count
+    auto count_window = [&](int64_t w) {
+      const int half = (int)(w & 1);
+      const int64_t left = T - w * kWin;
+      const short2r k128 = short2r{128, 128};
+      short2r acc = short2r{0, 0};  // at most 8 UPL per half and window
+#pragma unroll
+      for (int s = 0; s < kWin; ++s) {
+        if (s < left) {
+#pragma unroll
+          for (int q = 0; q < NQV; ++q) {
+            const int4r v4 = *vlog_at(half, s, q);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              if (4 * q + k < UPL) {
+                const int vk = v4[k];
+                typedef unsigned short ushort2r __attribute__((ext_vector_type(2)));
+                const ushort2r t = __builtin_bit_cast(ushort2r, __builtin_bit_cast(short2r, vk) + k128) >> (ushort2r)(8);
+                acc += __builtin_bit_cast(short2r, __builtin_elementwise_min(t, (ushort2r)(1)));
+              }
+            }
+          }
+        }
+      }
+      n_lane += (unsigned int)(unsigned short)acc[0] + (unsigned int)(unsigned short)acc[1];
+    };
     fill_batch(0);
     fill_batch(1);
     __syncthreads();  // P0: the first two batches are in place
@@ -166,9 +199,13 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
     for (int64_t w = 0; w < nwin; ++w) {
       // window w = 32 m: every reader has left batch m - 1, whose half takes batch m + 1
       if ((w & (kBatch / kWin - 1)) == 0 && w > 0) fill_batch(w / (kBatch / kWin) + 1);
+      if (w > 0) count_window(w - 1);
       __syncthreads();
     }
-    __syncthreads();  // the chain wave's counters
+    if (nwin > 0) count_window(nwin - 1);
+    const unsigned int total = (unsigned int)wave_sum_i32((int)n_lane);
+    if (lane == 0) s_cnt[0] = total;
+    __syncthreads();  // the counters
     return;
   }
 
@@ -402,30 +439,27 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
         }
         // u = z - gamma x - h~ (- c_lambda z), z = Q_(delta_m, b)(u)
         if (!REGW || cl == 0) {
+          // Clamped coordinates are not looked for here (comparing the strips before and after the
+          // clamp costs 70 of 410 cycles per step at 4 strips per lane): the unclamped strips go to
+          // LDS in one store and the service wave counts a window later.
           const short2r ngp = short2r{(short)ng, (short)ng};
-          short2r zu[UPL];
-          uint32_t moved = 0;  // bits in which some clamp changed a value
+          int4r vq[NQV];
+#pragma unroll
+          for (int q = 0; q < NQV; ++q) vq[q] = int4r{0, 0, 0, 0};
 #pragma unroll
           for (int u = 0; u < UPL; ++u) {
             short2r v = xp[u] * ngp + crp[u];
             v = (v >> (short2r)(8)) + (hhp[u] + zp[u]);  // the sum in brackets does not wait for gamma
-            const short2r zc = __builtin_elementwise_min(__builtin_elementwise_max(v, (short2r)(QMIN)),
-                                                         (short2r)(QMAX));
-            moved |= __builtin_bit_cast(uint32_t, v) ^ __builtin_bit_cast(uint32_t, zc);
-            zu[u] = v;
-            zp[u] = zc;
+            vq[u / 4][u % 4] = __builtin_bit_cast(int, v);
+            zp[u] = __builtin_elementwise_min(__builtin_elementwise_max(v, (short2r)(QMIN)), (short2r)(QMAX));
           }
-          if (__builtin_expect(__ballot(moved != 0) != 0, 0)) {  // rare: count the clamped coordinates exactly
 #pragma unroll
-            for (int u = 0; u < UPL; ++u) {
-              const uint32_t df = __builtin_bit_cast(uint32_t, zu[u]) ^ __builtin_bit_cast(uint32_t, zp[u]);
-              n_zclamp += (unsigned int)__builtin_popcountll(__ballot((df & 0xFFFFu) != 0)) +
-                          (unsigned int)__builtin_popcountll(__ballot((df >> 16) != 0));
-            }
-          }
+          for (int q = 0; q < NQV; ++q) *vlog_at(half, s, q) = vq[q];
         } else {
           // a step with an L2 draw (rare): 32-bit arithmetic on the unpacked halves,
-          // -h~ + r = 256 hh + (hl + r)
+          // -h~ + r = 256 hh + (hl + r); its clamps are counted here and its log entry is empty
+#pragma unroll
+          for (int q = 0; q < NQV; ++q) *vlog_at(half, s, q) = int4r{0, 0, 0, 0};
 #pragma unroll
           for (int u = 0; u < UPL; ++u) {
             int zn2[2];
@@ -480,16 +514,19 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
       }
     }
   if (lane == 0) {
-    s_cnt[0] = n_zclamp;
+    s_cnt[3] = n_zclamp;  // clamps of the steps with an L2 draw; the service wave puts the others into s_cnt[0]
     s_cnt[1] = n_gclamp_v;
     s_cnt[2] = n_reg;
   }
   __syncthreads();
-  if (tid < 4) cnt_out[tid] = tid < 3 ? s_cnt[tid] : 0ull;
+  if (tid < 4) cnt_out[tid] = tid == 0 ? s_cnt[0] + s_cnt[3] : (tid < 3 ? s_cnt[tid] : 0ull);
 }
 
-// the record ring: two windows of 8 steps, 8 UPL bytes per lane and step
-constexpr size_t ring_bytes(int upl) { return (size_t)2 * kWin * (upl / 2) * 64 * 16; }
+// the record ring (two windows of 8 steps, 8 UPL bytes per lane and step) and the log of
+// unclamped strips behind it (4 UPL bytes, 16 at least)
+constexpr size_t ring_bytes(int upl) {
+  return (size_t)2 * kWin * (upl / 2) * 64 * 16 + (size_t)2 * kWin * (upl >= 4 ? upl / 4 : 1) * 64 * 16;
+}
 
 template <int UPL>
 int launch_one(const InArgs& a, int R, hipStream_t s) {
