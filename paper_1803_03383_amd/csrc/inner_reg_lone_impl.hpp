@@ -104,6 +104,7 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
   __shared__ __attribute__((aligned(16))) float s_phi[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_y[2 * kBatch];
   __shared__ unsigned long long s_cnt[4];
+  __shared__ int s_fold;  // 1: the whole of -h~ rides in the records (set by the chain wave before the first barrier)
   // records: [half of the ring][step of the window][quad][lane], 16 bytes each
   extern __shared__ __attribute__((aligned(16))) int4r s_rec[];
   auto rec_at = [&](int half, int s, int q) -> int4r* { return s_rec + ((half * kWin + s) * NQ + q) * 64 + lane; };
@@ -217,19 +218,23 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
       const int g0 = s0 + u0;                   // ... in the row
       const bool frag_ok = g0 < U;              // the fragment starts inside the row
       const uint32_t frag_off = frag_ok ? (uint32_t)(2 * g0) : 0u;  // lanes past the row re-read its first bytes
-      short2r hlp[SPH];                         // low bytes of -h~
+      short2r hlp[SPH];                         // what a record adds to the rounding bytes: the low byte of
+      short2r hfp[SPH];                         // -h~, or the whole of it where every -h~ / 256 is small
       uint32_t xmask = 0;                       // bytes of the fragment that are coordinates < d
 #pragma unroll
       for (int i = 0; i < SPH; ++i) {
-        int hl[2];
+        int hl[2], hf[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
           const int j = 2 * (g0 + i) + e;
           const bool ok = j < d;
-          hl[e] = ok ? (-(int)hg[ok ? j : 0]) & 0xFF : 0;
+          const int hneg = ok ? -(int)hg[ok ? j : 0] : 0;
+          hl[e] = hneg & 0xFF;
+          hf[e] = hneg;
           if (ok) xmask |= 0xFFu << (16 * i + 8 * e);
         }
         hlp[i] = short2r{(short)hl[0], (short)hl[1]};
+        hfp[i] = short2r{(short)hf[0], (short)hf[1]};
       }
       // The rows of a window: its eight sample indices in two LDS reads (every entry of the
       // index ring is a valid row at any time, so windows past the end of the epoch fetch
@@ -273,6 +278,10 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
         }
       };
       __syncthreads();  // P0: the first two batches are in place
+      if (s_fold) {
+#pragma unroll
+        for (int i = 0; i < SPH; ++i) hlp[i] = hfp[i];
+      }
       request(f0, 0);
       request(f1, 1);
       request(f2, 2);
@@ -333,6 +342,17 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
     zp[u] = short2r{(short)zv[0], (short)zv[1]};
     hhp[u] = short2r{(short)hh[0], (short)hh[1]};
   }
+  // With -h~ = 256 hh + hl the update adds hh behind the shift.  Where every hh lies in
+  // [-64, 62], -gamma x + r - h~ itself fits 16 bits (|gamma x| <= 2^14, 0 <= r < 256): the
+  // records then carry r - h~ whole and the chain wave saves the addition of hh, one
+  // instruction per strip and step.
+  bool hh_small = true;
+#pragma unroll
+  for (int u = 0; u < UPL; ++u)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) hh_small = hh_small && (int)hhp[u][e] >= -64 && (int)hhp[u][e] <= 62;
+  const bool fold = __ballot(!hh_small) == 0;  // uniform
+  if (lane == 0) s_fold = fold ? 1 : 0;
   unsigned int n_zclamp = 0, n_reg = 0;  // uniform over the wave
   unsigned int n_gclamp_v = 0;          // per lane, the same in every lane
   __syncthreads();  // P0
@@ -368,9 +388,10 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
   };
   load_draws(0);
 
-  auto window = [&](int64_t t0, auto full_tag, auto reg_tag) {
+  auto window = [&](int64_t t0, auto full_tag, auto reg_tag, auto fold_tag) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr bool REGW = decltype(reg_tag)::value;  // some step of the window may have c_lambda != 0
+    constexpr bool FOLD = decltype(fold_tag)::value;  // the records carry the whole of -h~
     const int base = (int)(t0 & kMask);
     const int half = (int)((t0 >> 3) & 1);
     double rho[kWin];
@@ -449,7 +470,8 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
 #pragma unroll
           for (int u = 0; u < UPL; ++u) {
             short2r v = xp[u] * ngp + crp[u];
-            v = (v >> (short2r)(8)) + (hhp[u] + zp[u]);  // the sum in brackets does not wait for gamma
+            if (FOLD) v = (v >> (short2r)(8)) + zp[u];
+            else v = (v >> (short2r)(8)) + (hhp[u] + zp[u]);  // the sum in brackets does not wait for gamma
             vq[u / 4][u % 4] = __builtin_bit_cast(int, v);
             zp[u] = __builtin_elementwise_min(__builtin_elementwise_max(v, (short2r)(QMIN)), (short2r)(QMAX));
           }
@@ -466,7 +488,7 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
               const int zk = (int)zp[u][e], xk = (int)xp[u][e];
-              const int hr = ((int)hhp[u][e] << 8) + (int)crp[u][e];
+              const int hr = FOLD ? (int)crp[u][e] : ((int)hhp[u][e] << 8) + (int)crp[u][e];
               const int v = mad24(-cl, zk, mad24(ng, xk, hr));
               const int zuk = zk + (v >> 8);
               const int zc = min(max(zuk, QMIN), QMAX);
@@ -489,16 +511,20 @@ __global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InAr
     return __builtin_amdgcn_readfirstlane(any) != 0;
   };
   int64_t t0 = 0;
-  for (; t0 + kWin <= T; t0 += kWin) {
-    if (any_creg(t0)) window(t0, std::true_type{}, std::true_type{});
-    else window(t0, std::true_type{}, std::false_type{});
-    __syncthreads();  // window t0 / 8 is consumed, the records of the next one are in place
-  }
-  if (t0 < T) {
-    if (use_reg) window(t0, std::false_type{}, std::true_type{});
-    else window(t0, std::false_type{}, std::false_type{});
-    __syncthreads();
-  }
+  auto run = [&](auto fold_tag) __attribute__((always_inline)) {
+    for (; t0 + kWin <= T; t0 += kWin) {
+      if (any_creg(t0)) window(t0, std::true_type{}, std::true_type{}, fold_tag);
+      else window(t0, std::true_type{}, std::false_type{}, fold_tag);
+      __syncthreads();  // window t0 / 8 is consumed, the records of the next one are in place
+    }
+    if (t0 < T) {
+      if (use_reg) window(t0, std::false_type{}, std::true_type{}, fold_tag);
+      else window(t0, std::false_type{}, std::false_type{}, fold_tag);
+      __syncthreads();
+    }
+  };
+  if (fold) run(std::true_type{});
+  else run(std::false_type{});
 
   // ---- w~ <- w~ + delta_m z (option I); hand z out
 #pragma unroll
