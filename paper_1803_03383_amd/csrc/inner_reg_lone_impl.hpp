@@ -15,11 +15,16 @@
 // handed over through LDS as one record per lane and step: per strip the sign-extended
 // pair of row values and the pair of rounding bytes with hl added.  A helper serves one or
 // two of the strips of every lane: it draws their Philox blocks, requests the row fragments
-// three windows ahead and writes its dwords of the records.  A service wave
-// refills the 256-step batches of step-indexed draws (sample indices, rounding draws of
-// gamma and of the L2 term, margins and labels of the sampled rows).  One barrier per
-// window orders every hand-over: in period w the chain wave consumes window w from one half
-// of the record ring while the helpers fill the other half with window w + 1.
+// three windows ahead and writes its dwords of the records.  Where -h~ / 256 is small in
+// every coordinate the records carry r - h~ whole (it fits 16 bits beside -gamma x) and the
+// chain wave adds no hh.  A service wave refills the 256-step batches of step-indexed draws
+// (sample indices, rounding draws of gamma and of the L2 term, margins and labels of the
+// sampled rows) and counts the clamped coordinates: the chain wave stores the unclamped strips
+// of a step in LDS instead of comparing them with the clamped ones, and the service wave
+// counts the halves outside [-128, 127] a window later.  One barrier per window orders every
+// hand-over: in period w the chain wave consumes window w from one half of the record ring
+// and fills one half of the log, while the helpers fill the other half of the ring with
+// window w + 1 and the service wave reads the other half of the log (window w - 1).
 //
 // The chain wave is wave 0; the helpers and the service wave are placed on the other three
 // SIMDs (waves w and w + 4 of a workgroup share a SIMD: wave 4 only keeps the barriers).
