@@ -9,7 +9,7 @@ int launch_inner_reg_b8(const InArgs& a, int nw, int upl, int R, bool packed, hi
 int launch_inner_reg_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
 int launch_inner_reg_helped_b8(const InArgs& a, int nw, int upl, int R, hipStream_t s);
 int launch_inner_reg_helped_b16(const InArgs& a, int nw, int upl, int R, hipStream_t s);
-int launch_inner_reg_lone_b8(const InArgs& a, int upl, int R, hipStream_t s);
+int launch_inner_reg_lone_b8(const InArgs& a, int upl, int R, bool pair, hipStream_t s);
 
 namespace {
 
@@ -117,7 +117,7 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const int lone_upl = lone_strips(h);
   if (lone_upl > 0 && (h.inner_helpers == 3 || (h.inner_helpers == 0 && h.inner_waves == 0 && lone_pays(h, lone_upl) &&
                                                  (int64_t)p.R <= (int64_t)kLoneChainsPerCu * h.num_cus)))
-    return launch_inner_reg_lone_b8(a, lone_upl, p.R, s);
+    return launch_inner_reg_lone_b8(a, lone_upl, p.R, (int64_t)p.R > (int64_t)h.num_cus, s);  // more chains than CUs: the build that fits twice
   if (h.inner_helpers == 3) return HALP_ERR_UNSUPPORTED;
   Shape sh = pick_shape(p, auto_waves(h));
   const int ct = 16 / p.b;

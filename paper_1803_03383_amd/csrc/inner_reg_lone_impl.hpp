@@ -50,8 +50,11 @@ typedef int int4r __attribute__((ext_vector_type(4)));
 // waves of a workgroup: chain, helpers, the service wave, and wave 4 kept idle when there is one
 constexpr int waves_of(int upl) { return upl == 2 ? 4 : (upl == 4 ? 7 : 8); }
 
-template <int LOSS, int UPL>
-__global__ __launch_bounds__(64 * waves_of(UPL)) void inner_reg_lone_kernel(InArgs a) {
+// PAIR: built for two workgroups per CU (more chains than CUs): their 14 waves need four wave
+// slots on two of the SIMDs, i.e. at most 128 registers per lane, which costs the single
+// workgroup of a CU a few spills (2.59 against 2.50 ms per 16384 steps at 4 strips per lane).
+template <int LOSS, int UPL, bool PAIR>
+__global__ __launch_bounds__(64 * waves_of(UPL), PAIR ? 4 : 2) void inner_reg_lone_kernel(InArgs a) {
   static_assert(UPL == 2 || UPL == 4 || UPL == 8, "two, four or eight strips per lane");
   constexpr int BITS = 8;
   constexpr int NQ = UPL / 2;           // 16-byte quads of a record: UPL value pairs, then UPL rounding pairs
@@ -559,13 +562,13 @@ constexpr size_t ring_bytes(int upl) {
   return (size_t)2 * kWin * (upl / 2) * 64 * 16 + (size_t)2 * kWin * (upl >= 4 ? upl / 4 : 1) * 64 * 16;
 }
 
-template <int UPL>
+template <int UPL, bool PAIR>
 int launch_one(const InArgs& a, int R, hipStream_t s) {
   const dim3 grid(R), block(64 * waves_of(UPL));
   const size_t smem = ring_bytes(UPL);
 #define HALP_LONE(LOSS_)                                                                          \
   do {                                                                                            \
-    auto kern = inner_reg_lone_kernel<LOSS_, UPL>;                                                \
+    auto kern = inner_reg_lone_kernel<LOSS_, UPL, PAIR>;                                          \
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) \
       return HALP_ERR_HIP;                                                                        \

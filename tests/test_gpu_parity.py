@@ -449,6 +449,42 @@ def test_inner_loop_packed_form_bit_exact(loss, N, d, b, lam, R, T, mu):
         assert e.value.code == hp.ERR_INVALID
 
 
+@pytest.mark.parametrize("d", [200, 500])
+def test_more_chains_than_cus_on_the_one_chain_wave_form(d):
+    """Between one and two chains per CU the library still takes the form with one chain wave, in a
+    build that fits a CU twice (at most 128 registers): 400 chains over shared data, forced, agree
+    with the form that has a helper beside every chain wave, and sampled chains match the oracle."""
+    N, b, T, R, seed = 128, 8, 83, 400, 91
+    X, y, _ = inp.linreg(N, d, seed=6, x_var="inv_d")
+    dd = inp.default_delta_d(X, b)
+    Xq = ref.quantize_data(X, dd, b)
+    rng = np.random.default_rng(3)
+    w1 = (0.05 * rng.standard_normal((1, d))).astype(np.float32)
+    probs = [ref.make_problem(N, d, b=b, alpha=0.02, mu=0.05, delta_d=dd, seed=seed + r) for r in range(R)]
+    phi, g, _ = ref.full_gradient(probs[0], X, y, w1)
+    phi, g = phi.astype(np.float32), g.astype(np.float32)
+    rec = [ref.recenter(pr, g, 1) for pr in probs]
+    res = []
+    for helpers in (3, 1):
+        P = GpuProblem(X, Xq, y, R=R, b=b, T=T, alpha=0.02, mu=0.05, delta_d=dd, seed=seed, share_data=True,
+                       w0=np.repeat(w1[None], R, axis=0))
+        P.put("phi", np.repeat(phi.reshape(1, -1), R, axis=0))
+        P.put("h", np.stack([h for _, h, _ in rec]))
+        P.put("scales", np.stack([s for s, _, _ in rec]))
+        P.st["z"].zero_()
+        P.h.set_option(hp.OPT_INNER_HELPERS, helpers)
+        P.h.inner_loop(1)
+        res.append({k: P.get(k).copy() for k in ("z", "w", "counters")})
+    a, c = res
+    assert np.array_equal(a["z"], c["z"]) and np.array_equal(a["w"], c["w"])
+    assert np.array_equal(a["counters"], c["counters"])
+    for r in (0, 255, 256, 399):
+        s_ref, h_ref, _ = rec[r]
+        out = ref.inner_loop(probs[r], Xq, phi, y, h_ref, s_ref, 1, T)
+        assert np.array_equal(a["z"][r].astype(np.int32), out["z"]), f"chain {r}"
+        assert np.array_equal(a["counters"][r].astype(np.uint64), out["counters"])
+
+
 def test_many_chains_take_the_packed_form_by_themselves():
     """2048 chains over shared data (every SIMD holds two): the default launch and the one with
     the packed form switched off agree bit for bit, and sampled chains match the oracle."""
