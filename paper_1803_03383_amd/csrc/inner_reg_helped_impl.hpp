@@ -82,6 +82,8 @@ __global__ __launch_bounds__(128 * NWT) void inner_reg_helped_kernel(InArgs a) {
   __shared__ __attribute__((aligned(16))) int s_creg[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_phi[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_y[2 * kBatch];
+  // logistic loss: l'(phi_i) of the sampled rows, evaluated four per lane when a batch is drawn
+  __shared__ __attribute__((aligned(16))) double s_dl0[LOSS == HALP_LOSS_LOGISTIC ? 2 * kBatch : 2];
   __shared__ __attribute__((aligned(16))) AccT s_part[2][16];
   __shared__ unsigned long long s_cnt[3];
   __shared__ AccT s_dump[64 * NWT];  // where lanes 0..62 of a chain wave put their partial folds
@@ -120,6 +122,11 @@ __global__ __launch_bounds__(128 * NWT) void inner_reg_helped_kernel(InArgs a) {
       float4 yv;
       yv.x = y[iv.x]; yv.y = y[iv.y]; yv.z = y[iv.z]; yv.w = y[iv.w];
       *reinterpret_cast<float4*>(&s_y[half + 4 * lane]) = yv;
+      const float4 pw = *reinterpret_cast<const float4*>(&s_phi[half + 4 * lane]);
+      s_dl0[half + 4 * lane + 0] = logistic_dl((double)pw.x, (double)yv.x);
+      s_dl0[half + 4 * lane + 1] = logistic_dl((double)pw.y, (double)yv.y);
+      s_dl0[half + 4 * lane + 2] = logistic_dl((double)pw.z, (double)yv.z);
+      s_dl0[half + 4 * lane + 3] = logistic_dl((double)pw.w, (double)yv.w);
     }
     s_rho[half + 4 * lane + 0] = __dmul_rn((double)rg.x, 0x1p-32);
     s_rho[half + 4 * lane + 1] = __dmul_rn((double)rg.y, 0x1p-32);
@@ -313,9 +320,11 @@ __global__ __launch_bounds__(128 * NWT) void inner_reg_helped_kernel(InArgs a) {
     const int base = (int)(t0 & kMask);
     double rho[kWin];
     float phi8[kWin], y8[kWin];
+    double dl08[kWin];
     int creg[kWin];
 #pragma unroll
     for (int s = 0; s < kWin; ++s) {
+      dl08[s] = 0.0;
       phi8[s] = y8[s] = 0.f;
       creg[s] = 0;
     }
@@ -330,6 +339,12 @@ __global__ __launch_bounds__(128 * NWT) void inner_reg_helped_kernel(InArgs a) {
       const float4 y1 = *reinterpret_cast<const float4*>(&s_y[base + 4]);
       y8[0] = y0.x; y8[1] = y0.y; y8[2] = y0.z; y8[3] = y0.w;
       y8[4] = y1.x; y8[5] = y1.y; y8[6] = y1.z; y8[7] = y1.w;
+#pragma unroll
+      for (int s = 0; s < kWin; s += 2) {
+        const double2 d2 = *reinterpret_cast<const double2*>(&s_dl0[base + s]);
+        dl08[s] = d2.x;
+        dl08[s + 1] = d2.y;
+      }
     }
     if (REGW) {
       const int4 c0 = *reinterpret_cast<const int4*>(&s_creg[base]);
@@ -401,7 +416,7 @@ __global__ __launch_bounds__(128 * NWT) void inner_reg_helped_kernel(InArgs a) {
         if (logistic) {
           const double a0 = (double)phi8[s], yi = (double)y8[s];
           const double a1 = lp ? delta : __dadd_rn(a0, delta);
-          diff = __dadd_rn(logistic_dl(a1, yi), -logistic_dl(a0, yi));
+          diff = __dadd_rn(logistic_dl(a1, yi), -dl08[s]);  // l'(phi_i) comes with the batch
         } else if (need_phi) {
           diff = __dadd_rn(delta, -(double)phi8[s]);
         }

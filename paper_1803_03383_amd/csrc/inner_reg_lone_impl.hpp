@@ -47,6 +47,9 @@ using innerreg::short2r;
 
 typedef int int4r __attribute__((ext_vector_type(4)));
 
+template <int LOSS>
+constexpr bool logistic_c = LOSS == HALP_LOSS_LOGISTIC;
+
 // waves of a workgroup: chain, helpers, the service wave, and wave 4 kept idle when there is one
 constexpr int waves_of(int upl) { return upl == 2 ? 4 : (upl == 4 ? 7 : 8); }
 
@@ -111,6 +114,8 @@ __global__ __launch_bounds__(64 * waves_of(UPL), PAIR ? 4 : 2) void inner_reg_lo
   __shared__ __attribute__((aligned(16))) int s_creg[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_phi[2 * kBatch];
   __shared__ __attribute__((aligned(16))) float s_y[2 * kBatch];
+  // logistic loss: l'(phi_i) of the sampled rows, which no step has to evaluate itself
+  __shared__ __attribute__((aligned(16))) double s_dl0[logistic_c<LOSS> ? 2 * kBatch : 2];
   __shared__ unsigned long long s_cnt[4];
   __shared__ int s_fold;  // 1: the whole of -h~ rides in the records (set by the chain wave before the first barrier)
   // records: [half of the ring][step of the window][quad][lane], 16 bytes each
@@ -156,6 +161,11 @@ __global__ __launch_bounds__(64 * waves_of(UPL), PAIR ? 4 : 2) void inner_reg_lo
         float4 yv;
         yv.x = y[iv.x]; yv.y = y[iv.y]; yv.z = y[iv.z]; yv.w = y[iv.w];
         *reinterpret_cast<float4*>(&s_y[half + 4 * lane]) = yv;
+        const float4 pv = *reinterpret_cast<const float4*>(&s_phi[half + 4 * lane]);
+        s_dl0[half + 4 * lane + 0] = logistic_dl((double)pv.x, (double)yv.x);
+        s_dl0[half + 4 * lane + 1] = logistic_dl((double)pv.y, (double)yv.y);
+        s_dl0[half + 4 * lane + 2] = logistic_dl((double)pv.z, (double)yv.z);
+        s_dl0[half + 4 * lane + 3] = logistic_dl((double)pv.w, (double)yv.w);
       }
       s_rho[half + 4 * lane + 0] = __dmul_rn((double)rg.x, 0x1p-32);
       s_rho[half + 4 * lane + 1] = __dmul_rn((double)rg.y, 0x1p-32);
@@ -369,10 +379,13 @@ __global__ __launch_bounds__(64 * waves_of(UPL), PAIR ? 4 : 2) void inner_reg_lo
 
   // step-indexed draws of a window (rounding draws of gamma, margins and labels of its rows),
   // read from the batch ring one window before they are used
-  double rho_n[kWin];
+  double rho_n[kWin], dl0_n[kWin];
   float phi_n[kWin], y_n[kWin];
 #pragma unroll
-  for (int s = 0; s < kWin; ++s) phi_n[s] = y_n[s] = 0.f;
+  for (int s = 0; s < kWin; ++s) {
+    phi_n[s] = y_n[s] = 0.f;
+    dl0_n[s] = 0.0;
+  }
   auto load_draws = [&](int64_t tt) {
     const int base = (int)(tt & kMask);
     if (need_phi) {
@@ -386,6 +399,12 @@ __global__ __launch_bounds__(64 * waves_of(UPL), PAIR ? 4 : 2) void inner_reg_lo
       const float4 y1 = *reinterpret_cast<const float4*>(&s_y[base + 4]);
       y_n[0] = y0.x; y_n[1] = y0.y; y_n[2] = y0.z; y_n[3] = y0.w;
       y_n[4] = y1.x; y_n[5] = y1.y; y_n[6] = y1.z; y_n[7] = y1.w;
+#pragma unroll
+      for (int s = 0; s < kWin; s += 2) {
+        const double2 d2 = *reinterpret_cast<const double2*>(&s_dl0[base + s]);
+        dl0_n[s] = d2.x;
+        dl0_n[s + 1] = d2.y;
+      }
     }
 #pragma unroll
     for (int s = 0; s < kWin; s += 2) {
@@ -402,11 +421,12 @@ __global__ __launch_bounds__(64 * waves_of(UPL), PAIR ? 4 : 2) void inner_reg_lo
     constexpr bool FOLD = decltype(fold_tag)::value;  // the records carry the whole of -h~
     const int base = (int)(t0 & kMask);
     const int half = (int)((t0 >> 3) & 1);
-    double rho[kWin];
+    double rho[kWin], dl08[kWin];
     float phi8[kWin], y8[kWin];
     int creg[kWin];
 #pragma unroll
     for (int s = 0; s < kWin; ++s) {
+      dl08[s] = dl0_n[s];
       rho[s] = rho_n[s];
       phi8[s] = phi_n[s];
       y8[s] = y_n[s];
@@ -451,7 +471,7 @@ __global__ __launch_bounds__(64 * waves_of(UPL), PAIR ? 4 : 2) void inner_reg_lo
         if (logistic) {
           const double a0 = (double)phi8[s], yi = (double)y8[s];
           const double a1 = lp ? delta : __dadd_rn(a0, delta);
-          diff = __dadd_rn(logistic_dl(a1, yi), -logistic_dl(a0, yi));
+          diff = __dadd_rn(logistic_dl(a1, yi), -dl08[s]);  // l'(phi_i) comes with the draws
         } else if (need_phi) {
           diff = __dadd_rn(delta, -(double)phi8[s]);
         }
