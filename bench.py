@@ -539,11 +539,11 @@ def main():
     laneops = 3.0 if args.algorithm == "svrg" else LANEOPS_PER_UPDATE_B8
     # at the headline shape (few chains, four waves each) the register kernel with helper waves runs
     # the library's launch rule at 8 bits, restated: one chain wave + helpers on the other SIMDs for
-    # rows of 129 .. 512 coordinates up to two chains per CU; chain waves with a helper beside each
+    # rows of 129 .. 512 coordinates up to two chains per CU (.. 1024 up to one); chain waves with a helper beside each
     # up to five chains per CU; one wave per chain beyond
     lone = (args.algorithm != "svrg" and d <= 1024 and
-            (args.inner_helpers == 3 or (args.inner_helpers == 0 and args.inner_waves == 0
-                                         and 128 < d <= 512 and R <= 2 * 256)))
+            (args.inner_helpers == 3 or (args.inner_helpers == 0 and args.inner_waves == 0 and 128 < d
+                                         and R <= (2 if d <= 512 else 1) * 256)))
     helped = (not lone and args.algorithm != "svrg" and args.inner_helpers in (0, 1)
               and args.inner_waves in (0, 2, 4) and d <= 1024 and (R <= 5 * 256 or args.inner_helpers == 1))
     inner_kernel = "inner_svrg_kernel" if args.algorithm == "svrg" else (

@@ -188,7 +188,8 @@ typedef struct {
                                     helper waves on the other SIMDs of the CU, for rows up to
                                     1024 coordinates (HALP_ERR_UNSUPPORTED elsewhere); 0 takes
                                     it for rows of 129 .. 512 coordinates at up to two chains
-                                    per CU.  Results do not depend on it                       */
+                                    per CU and for wider rows at up to one.  Results do not
+                                    depend on it                                              */
 
 #define HALP_OPT_EXCHANGE_POLL_DELAY 11 /* split minibatch loop: sleeps of 256 cycles between a
                                     workgroup publishing its sums of a step and its first poll

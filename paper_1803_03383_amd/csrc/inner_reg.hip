@@ -68,14 +68,20 @@ int lone_strips(const halp_handle& h) {
   return upl;
 }
 
-// Where the library takes that form by itself: up to two chains per CU, rows of 129 .. 512
-// coordinates (two or four strips per lane).  Measured per epoch of 16384 steps at d = 512 (ms):
+// Where the library takes that form by itself: rows of 129 .. 512 coordinates (two or four strips
+// per lane) up to two chains per CU, wider rows up to one.  Measured per epoch of 16384 steps at d = 512 (ms):
 // 128 chains 2.57 against 2.91 for four chain waves with helpers, 256: 2.66 / 3.00, 384: 3.19 /
 // 3.67, 512: 3.26 / 3.69; 768: 5.95 against 4.27 for the library's choice there, 1024: 6.43 / 5.15.
 // d = 256 at 256 chains: 2.10 against 2.91.  d = 1024: 3.97 against 3.79 (the single wave issues
 // ~9 instructions per strip and step); up to 128 coordinates one wave without helpers is faster.
-constexpr int kLoneChainsPerCu = 2;
-bool lone_pays(const halp_handle& h, int upl) { return upl <= 4 && h.p.d > 128; }
+// Rows of 513 .. 1024 coordinates (eight strips per lane) gain little -- 3.76 against 3.80 ms at 256
+// chains, 22.4 against 22.8 ms for the single chain of 100000 steps, logistic 5.56 against 5.80 -- and only
+// with a CU per chain.
+bool lone_pays(const halp_handle& h, int upl) {
+  if (h.p.d <= 128) return false;
+  const int64_t per_cu = upl <= 4 ? 2 : 1;
+  return (int64_t)h.p.R <= per_cu * h.num_cus;
+}
 
 // waves per chain: use the chip's SIMDs when chains are few, one wave per chain
 // when they are many
@@ -115,8 +121,7 @@ int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
   const InArgs a = make_inner_args(h, epoch);
   // 8 bits, at most one chain per CU: one chain wave with all of z, helpers on the other SIMDs
   const int lone_upl = lone_strips(h);
-  if (lone_upl > 0 && (h.inner_helpers == 3 || (h.inner_helpers == 0 && h.inner_waves == 0 && lone_pays(h, lone_upl) &&
-                                                 (int64_t)p.R <= (int64_t)kLoneChainsPerCu * h.num_cus)))
+  if (lone_upl > 0 && (h.inner_helpers == 3 || (h.inner_helpers == 0 && h.inner_waves == 0 && lone_pays(h, lone_upl))))
     return launch_inner_reg_lone_b8(a, lone_upl, p.R, (int64_t)p.R > (int64_t)h.num_cus, s);  // more chains than CUs: the build that fits twice
   if (h.inner_helpers == 3) return HALP_ERR_UNSUPPORTED;
   Shape sh = pick_shape(p, auto_waves(h));
