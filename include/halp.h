@@ -198,6 +198,12 @@ typedef struct {
                                     more were measured to lengthen the step, so the default
                                     only skips the polls that cannot succeed for free.
                                     Results do not depend on it                                 */
+#define HALP_OPT_GRADIENT_FP32 12 /* softmax gradient pass on rows of up to 800 coordinates, a
+                                    multiple of 4: 0 (default): both matrix products take every
+                                    fp32 operand as the sum of two halves (22 of its 24 bits)
+                                    and accumulate in fp32, on the 16-bit path of the matrix
+                                    cores; 1: fp32 products.  Both stay within the pass's
+                                    1e-5; the first is the faster one                          */
 
 /* Validates p (HALP_ERR_INVALID / HALP_ERR_UNSUPPORTED) and allocates the
  * library's own device workspace on the current device.                               */
@@ -206,7 +212,9 @@ int halp_destroy(halp_handle* h);
 
 /* Records the caller's buffers (the struct is copied).  Checks alignment and
  * strides.  Any pointer may be NULL if no later call needs it; calls that do
- * return HALP_ERR_NOT_BOUND.                                                          */
+ * return HALP_ERR_NOT_BOUND.  The training set X is taken to stay as it is while bound:
+ * bind again after changing it (the softmax gradient pass takes the largest |X| once per
+ * bind, on its first call, and later calls reuse it).                                  */
 int halp_bind(halp_handle* h, const halp_buffers* buf);
 
 int halp_set_option(halp_handle* h, int32_t option, int64_t value);
@@ -236,7 +244,9 @@ int halp_quantize_data(halp_handle* h, void* stream);
 
 /* Algorithm 4, outer lines: phi_i = x_i^T w~ for every example and
  * g~ = (1/N) sum_i l_i'(phi_i) x_i + lambda w~, in fp32 with X read once;
- * also f(w~) into scales[6].  Needs X, y, w, phi, g, scales.                          */
+ * also f(w~) into scales[6].  Needs X, y, w, phi, g, scales.  Softmax on rows of up to 800
+ * coordinates: see HALP_OPT_GRADIENT_FP32; the first call after a halp_bind also makes one
+ * more pass over X on the stream, for its largest magnitude.                            */
 int halp_full_gradient(halp_handle* h, void* stream);
 
 /* halp_full_gradient for callers that cannot allocate device memory: code under HIP graph

@@ -16,6 +16,7 @@ ALG_HALP, ALG_LPSVRG, ALG_SVRG = 0, 1, 2
 OPT_INNER_VARIANT, OPT_TIMING, OPT_FULLGRAD_BLOCKS, OPT_INNER_WAVES, OPT_OPTION_II = 1, 2, 4, 5, 6
 OPT_INNER_PARTS, OPT_EXCHANGE_SPIN_LIMIT, OPT_INNER_PACKED, OPT_INNER_HELPERS = 7, 8, 9, 10
 OPT_EXCHANGE_POLL_DELAY = 11
+OPT_GRADIENT_FP32 = 12
 ERR_NULL, ERR_INVALID, ERR_UNSUPPORTED, ERR_NOT_BOUND, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6
 ERR_TOO_LARGE = -7
 ERR_EXCHANGE_TIMEOUT = -8

@@ -479,6 +479,7 @@ struct FgPlan {
   int parts;
   int loss_parts;  // entries per chain of partial_loss in use (its rows are max(parts, loss_parts) long)
   float* resid;    // [R][N][16] for the two-pass softmax form, else unused
+  const uint32_t* xabsmax = nullptr;  // softmax: bits of the largest |X|, or null (fp32 products)
 };
 
 static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
@@ -493,7 +494,7 @@ static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
   a.x_chain_stride = p.share_data ? 0 : p.N * buf.ldx;
   a.y_chain_stride = p.share_data ? 0 : p.N;
   a.d = p.d; a.K = p.K; a.parts = f.parts; a.fscale = f.fscale;
-  a.loss_parts = f.loss_parts; a.resid = f.resid;
+  a.loss_parts = f.loss_parts; a.resid = f.resid; a.xabsmax = f.xabsmax;
   const dim3 grid(f.parts, p.R);
   const int nv = nv_for(p.d);
   if (p.loss == HALP_LOSS_SOFTMAX) {
@@ -528,8 +529,19 @@ static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
 }
 
 int launch_full_gradient(const halp_handle& h, hipStream_t s) {
-  const FgPlan f{&h.p, &h.buf, h.fscale, h.partial_g, h.partial_loss, h.parts, h.loss_parts, h.resid};
+  const bool halves = h.xabsmax && h.xabsmax_fresh && !h.gradient_fp32;
+  const FgPlan f{&h.p, &h.buf, h.fscale, h.partial_g, h.partial_loss, h.parts, h.loss_parts, h.resid,
+                 halves ? h.xabsmax : nullptr};
   return launch_full_gradient_plan(f, s);
+}
+
+int prepare_full_gradient(halp_handle& h, hipStream_t s) {
+  if (!h.xabsmax || h.xabsmax_fresh || h.gradient_fp32 || !h.buf.X) return HALP_OK;
+  // chains with data of their own lie one after the other: N rows each
+  const int64_t rows = h.p.share_data ? h.p.N : h.p.N * (int64_t)h.p.R;
+  const int rc = launch_absmax(h.buf.X, rows, h.p.d, h.buf.ldx, h.xabsmax, s);
+  if (rc == HALP_OK) h.xabsmax_fresh = true;
+  return rc;
 }
 
 // ---- allocation-free form -------------------------------------------------------

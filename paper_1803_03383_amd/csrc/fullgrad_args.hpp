@@ -20,6 +20,9 @@ struct FgArgs {
   int64_t x_chain_stride, y_chain_stride;  // 0 when chains share the data
   int d, K, parts;
   int loss_parts;       // workgroups that write a partial loss (parts, except where noted)
+  // softmax: bits of the largest |X| over the data (one word, device), or null if not known:
+  // with it both products of the pass take their operands as pairs of halves
+  const uint32_t* xabsmax = nullptr;
 };
 
 // softmax: margins and gradient as two matrix products on the matrix cores
@@ -27,6 +30,8 @@ int fullgrad_softmax_supported(const halp_params& p);
 int launch_fullgrad_softmax(const FgArgs& a, int R, hipStream_t s);
 // true where the pipelined form runs: one workgroup per CU instead of two
 bool fullgrad_softmax_pipelined(int d);
+// *out = bits of the largest |X[r][c]| over rows < rows, columns < d (rows ldx apart); one word, device
+int launch_absmax(const float* X, int64_t rows, int d, int64_t ldx, uint32_t* out, hipStream_t s);
 // true where the softmax pass keeps a tile of rows on chip (d <= 1024); wider rows take two passes
 bool fullgrad_softmax_one_pass(int d);
 

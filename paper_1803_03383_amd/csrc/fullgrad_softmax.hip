@@ -17,6 +17,7 @@
 // by 256 threads (one per row and class; a row of 16 classes is a DPP row), and the
 // residuals go back through LDS, transposed, as the A operand of the second product.
 // Per-workgroup partial gradients and losses are summed by the common second-stage kernel.
+#include <algorithm>
 #include <type_traits>
 
 #include "fullgrad_args.hpp"
@@ -26,6 +27,40 @@ namespace halp {
 namespace {
 
 typedef float F4 __attribute__((ext_vector_type(4)));
+typedef float F16 __attribute__((ext_vector_type(16)));
+typedef _Float16 H8 __attribute__((ext_vector_type(8)));
+typedef uint32_t U4v __attribute__((ext_vector_type(4)));
+
+// Eight fp32 numbers as two vectors of halves with v = hi + lo up to 2^-22 |v|: hi is v rounded
+// to a half, v - hi is exact in fp32, lo is that difference rounded to a half.  Two numbers so
+// split multiply as hi hi' + hi lo' + lo hi' (+ lo lo') on the matrix cores' 16-bit path, which
+// takes eight times the contraction depth of the fp32 one per instruction, to fp32 accuracy.
+// The caller keeps |v| below 2^15; halves below the normal range lose nothing the fp32 sum
+// would keep as long as the largest |v| is 2^-3 or more (the matrix cores take subnormal halves
+// as they are).
+__device__ __forceinline__ void split8(const float (&v)[8], H8& hi, H8& lo) {
+  typedef float F2 __attribute__((ext_vector_type(2)));
+  typedef _Float16 H2 __attribute__((ext_vector_type(2)));
+  uint32_t hu[4], lu[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    hu[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(F2{v[2 * p], v[2 * p + 1]}, H2));
+    float r0, r1;  // v - hi in one instruction each, the half taken from its packed place
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r0) : "v"(hu[p]), "v"(v[2 * p]));
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r1) : "v"(hu[p]), "v"(v[2 * p + 1]));
+    lu[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(F2{r0, r1}, H2));
+  }
+  hi = __builtin_bit_cast(H8, U4v{hu[0], hu[1], hu[2], hu[3]});
+  lo = __builtin_bit_cast(H8, U4v{lu[0], lu[1], lu[2], lu[3]});
+}
+
+// 2^k with max 2^k in [2^13, 2^14), from the bits of max >= 0 (1 for max = 0), and its inverse
+__device__ __forceinline__ void half_scale(uint32_t max_bits, float& s, float& inv) {
+  const int e = (int)(max_bits >> 23) & 0xff;
+  const int f = max_bits == 0 ? 127 : min(267 - e, 253);
+  s = __builtin_bit_cast(float, (uint32_t)f << 23);
+  inv = __builtin_bit_cast(float, (uint32_t)(254 - f) << 23);
+}
 
 constexpr int kRows = 16;    // rows per tile
 constexpr int kRtStride = 20;  // floats between classes in the transposed residual tile
@@ -271,7 +306,11 @@ constexpr int kPipeMaxD = 800;
 constexpr int kPipeGroups = 7;   // groups of 32 columns per matrix wave: 4 x 7 x 32 = 896 >= 800
 constexpr int kPipeSlots = 13;   // float4 slots per helper thread and tile: 16 x 200 / 256 = 12.5
 
+// SERIAL: rows of whole float4s (the launch decides); HALVES: the serial form with both products
+// on operands split into halves, which needs the largest |X| of the data (FgArgs::xabsmax)
+template <bool SERIAL, bool HALVES>
 __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) {
+  static_assert(SERIAL || !HALVES, "operands in halves exist in the serial form only");
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -290,6 +329,8 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
   extern __shared__ __attribute__((aligned(16))) float s_x[];                       // [3][kRows][LDT]
   __shared__ __attribute__((aligned(16))) float s_pphi[4 * kRows * 16];             // partial margins per matrix wave
   __shared__ __attribute__((aligned(16))) float s_rt[2 * 16 * kRtStride];           // residuals [2][class][row]
+  __shared__ __attribute__((aligned(16))) _Float16 s_rp[2 * 16 * kRows];            // residuals in halves [piece][class][row]
+  __shared__ uint32_t s_wmax;                                                       // bits of the largest |W~ / s|
   const int tile_floats = kRows * LDT;
 
   const int li = lane & 15, lq = lane >> 4;
@@ -306,6 +347,8 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
   }
   // a matrix wave that narrow rows leave without columns never writes its partial margins
   for (int k = tid; k < 4 * kRows * 16; k += 512) s_pphi[k] = 0.f;
+  if (tid == 0) s_wmax = 0u;
+  __syncthreads();
 
   // ---------------------------------------------------------------- matrix waves: set-up
   const int ngr = matrix_wave ? max(0, ((d + 31) / 32 - wave + 3) / 4) : 0;  // groups wave, wave+4, ..
@@ -313,7 +356,7 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
   F4 gacc[kPipeGroups][2];
   // Rows of whole float4s take the serial form of a period (see below): the matrix waves also
   // take the softmax, of four rows each, so `ht` names a matrix thread there
-  const bool serial = (d & 3) == 0;
+  constexpr bool serial = SERIAL;
   // ---------------------------------------------------------------- helper waves: set-up
   const int ht = (serial && matrix_wave) ? tid : tid - 256;
   const int nf4 = (d + 3) / 4;
@@ -348,6 +391,48 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
         }
 #pragma unroll
     for (int i = 0; i < kPipeGroups; ++i) gacc[i][0] = gacc[i][1] = F4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (HALVES) {
+      float m = 0.f;
+#pragma unroll
+      for (int i = 0; i < kPipeGroups; ++i)
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) m = fmaxf(m, fabsf(wreg[i][c2][e]));
+      m = row_fold(m, [](float x, float y2) { return fmaxf(x, y2); });
+      if (li == 0) atomicMax(&s_wmax, __builtin_bit_cast(uint32_t, m));
+    }
+  }
+  __syncthreads();
+  // Operands in halves are scaled by powers of two into the halves' range: W~ by sw (from its
+  // largest magnitude, found above), the residuals by 2^13, X by sx -- but only where the data's
+  // largest magnitude lies outside [2^-3, 2^15): inside, X is split as it is, and a tile costs
+  // one multiplication per element less.
+  float sx = 1.f, isx = 1.f, sw = 1.f, isw = 1.f;
+  bool x_scaled = false;
+  constexpr float kSr = 8192.f, kIsr = 1.f / 8192.f;
+  H8 wh[kPipeGroups], wl[kPipeGroups];
+  F16 gacc16[kPipeGroups];
+  if constexpr (HALVES) {
+    const uint32_t xm = *a.xabsmax;
+    const int xe = (int)(xm >> 23);
+    x_scaled = xm != 0u && (xe < 124 || xe > 141);
+    if (x_scaled) half_scale(xm, sx, isx);
+    half_scale(s_wmax, sw, isw);
+    if (matrix_wave) {
+#pragma unroll
+      for (int i = 0; i < kPipeGroups; ++i) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = wreg[i][0][e] * sw;
+          v[4 + e] = wreg[i][1][e] * sw;
+        }
+        split8(v, wh[i], wl[i]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) gacc16[i][j] = 0.f;
+      }
+    }
   }
 
   // matrix waves, first product: partial margins [16 rows] x [16 classes] of this wave's columns.
@@ -407,6 +492,68 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
         gacc[i][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(rtk[kk], xb[i][kk].y, gacc[i][1], 0, 0, 0);
       }
   };
+  // The same two products on operands in halves.  First product: a group of 32 columns is one
+  // 16x16x32 contraction per pair of pieces; lane (row j, q) holds columns 4q .. 4q+3 and
+  // 16+4q .. 16+4q+3 of the group on both sides.  lo lo' is left out: 2^-22 of the product.
+  auto margins_h = [&](auto ngr_c, auto scaled_c, int buf) {
+    constexpr int NGR = decltype(ngr_c)::value;
+    constexpr bool SCALED = decltype(scaled_c)::value;
+    const float* xr = s_x + buf * tile_floats + li * LDT + 32 * wave + 4 * lq;
+    F4 x0[NGR], x1[NGR];
+#pragma unroll
+    for (int i = 0; i < NGR; ++i) {
+      x0[i] = *reinterpret_cast<const F4*>(xr + 128 * i);
+      x1[i] = *reinterpret_cast<const F4*>(xr + 128 * i + 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // all reads are in flight before the first conversion
+    F4 pa = F4{0.f, 0.f, 0.f, 0.f}, pb = F4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NGR; ++i) {
+      float v[8] = {x0[i].x, x0[i].y, x0[i].z, x0[i].w, x1[i].x, x1[i].y, x1[i].z, x1[i].w};
+      if constexpr (SCALED) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= sx;
+      }
+      H8 ah, al;
+      split8(v, ah, al);
+      pa = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, wh[i], pa, 0, 0, 0);
+      pb = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, wh[i], pb, 0, 0, 0);
+      pb = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, wl[i], pb, 0, 0, 0);
+    }
+    // component r of lane (j, q) is row 4 q + r, class j
+    float* pp = s_pphi + wave * kRows * 16 + (4 * lq) * 16 + li;
+    pp[0] = ((pa.x + pb.x) * isx) * isw;
+    pp[16] = ((pa.y + pb.y) * isx) * isw;
+    pp[32] = ((pa.z + pb.z) * isx) * isw;
+    pp[48] = ((pa.w + pb.w) * isx) * isw;
+  };
+  // Second product, G^T[column][class] += X^T R as 32x32x16 contractions over the tile's rows:
+  // lane (m, h) holds column m of a group, rows 8h .. 8h+7, and of the residuals class m % 16,
+  // piece m / 16, the same rows: the upper and the lower piece of R are 16 columns each of one
+  // right operand, so two contractions (the pieces of X) give all four products of pieces.
+  const int gm = lane & 31, gh = lane >> 5;
+  auto gradient_h = [&](auto ngr_c, auto scaled_c, int buf) {
+    constexpr int NGR = decltype(ngr_c)::value;
+    constexpr bool SCALED = decltype(scaled_c)::value;
+    const float* xc = s_x + buf * tile_floats + (8 * gh) * LDT + 32 * wave + gm;
+    const H8 rb = *reinterpret_cast<const H8*>(s_rp + gm * kRows + 8 * gh);
+    float xv[NGR][8];
+#pragma unroll
+    for (int i = 0; i < NGR; ++i)
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) xv[i][kk] = xc[kk * LDT + 128 * i];
+    __builtin_amdgcn_sched_barrier(0);  // all reads are in flight before the first conversion
+#pragma unroll
+    for (int i = 0; i < NGR; ++i) {
+      float v[8];
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) v[kk] = SCALED ? xv[i][kk] * sx : xv[i][kk];
+      H8 ah, al;
+      split8(v, ah, al);
+      gacc16[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, rb, gacc16[i], 0, 0, 0);
+      gacc16[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, rb, gacc16[i], 0, 0, 0);
+    }
+  };
   // helper waves: thread (row ht / 16, class ht % 16).  Every instruction here competes with
   // the matrix waves for the SIMD, so the transcendental steps are single hardware instructions
   // (2^x, log2, reciprocal: 1 ulp each, far inside the pass's 1e-5) and nothing branches.
@@ -424,7 +571,14 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
     const float rc = live ? e * __builtin_amdgcn_rcpf(se) - (mine ? 1.0f : 0.f) : 0.f;
     if (live) (phi + tile * kRows * K)[phi_off] = logit;
     loss_acc += (live && mine) ? (double)(__builtin_amdgcn_logf(se) * 0.6931471805599453f + mx - logit) : 0.0;
-    s_rt[par * 16 * kRtStride + c * kRtStride + r] = rc;
+    if constexpr (HALVES) {  // pieces [piece][class][row], scaled into the halves' range
+      const float rs = rc * kSr;
+      const _Float16 rh = (_Float16)rs;
+      s_rp[c * kRows + r] = rh;
+      s_rp[16 * kRows + c * kRows + r] = (_Float16)(rs - (float)rh);
+    } else {
+      s_rt[par * 16 * kRtStride + c * kRtStride + r] = rc;
+    }
   };
 
   // Two loops, one per role, with the same barriers at the same places: the registers of the
@@ -456,7 +610,7 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
       __builtin_amdgcn_s_barrier();
       HALP_PHASE_BORDER();
     };
-    auto periods_serial = [&](auto ngr_c) {
+    auto periods_serial = [&](auto ngr_c, auto scaled_c) {
       constexpr int NGR = decltype(ngr_c)::value;
       int y_cur = 0, y_nxt = n > 0 ? y[min(tile_of(0) * kRows + (ht >> 4), N - 1)] : 0;
       int buf = 0;
@@ -464,26 +618,36 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
       for (int k = 0; k < n; ++k) {
         y_cur = y_nxt;
         if (k + 1 < n) y_nxt = y[min(tile_of(k + 1) * kRows + (ht >> 4), N - 1)];
-        if constexpr (NGR > 0) margins(ngr_c, buf);
+        if constexpr (NGR > 0) {
+          if constexpr (HALVES) margins_h(ngr_c, scaled_c, buf);
+          else margins(ngr_c, buf);
+        }
         lds_barrier();
         softmax(tile_of(k), 0, y_cur);
         lds_barrier();
-        if constexpr (NGR > 0) gradient(ngr_c, buf, 0);
+        if constexpr (NGR > 0) {
+          if constexpr (HALVES) gradient_h(ngr_c, scaled_c, buf);
+          else gradient(ngr_c, buf, 0);
+        }
         lds_barrier();  // the buffer is free, the next tile has landed
         buf = buf == 2 ? 0 : buf + 1;
       }
     };
-    if (serial) {
-      switch (ngr) {
-        case 7: periods_serial(std::integral_constant<int, 7>{}); break;
-        case 6: periods_serial(std::integral_constant<int, 6>{}); break;
-        case 5: periods_serial(std::integral_constant<int, 5>{}); break;
-        case 4: periods_serial(std::integral_constant<int, 4>{}); break;
-        case 3: periods_serial(std::integral_constant<int, 3>{}); break;
-        case 2: periods_serial(std::integral_constant<int, 2>{}); break;
-        case 1: periods_serial(std::integral_constant<int, 1>{}); break;
-        default: periods_serial(std::integral_constant<int, 0>{}); break;
-      }
+    if constexpr (serial) {
+      auto by_groups = [&](auto scaled_c) {
+        switch (ngr) {
+          case 7: periods_serial(std::integral_constant<int, 7>{}, scaled_c); break;
+          case 6: periods_serial(std::integral_constant<int, 6>{}, scaled_c); break;
+          case 5: periods_serial(std::integral_constant<int, 5>{}, scaled_c); break;
+          case 4: periods_serial(std::integral_constant<int, 4>{}, scaled_c); break;
+          case 3: periods_serial(std::integral_constant<int, 3>{}, scaled_c); break;
+          case 2: periods_serial(std::integral_constant<int, 2>{}, scaled_c); break;
+          case 1: periods_serial(std::integral_constant<int, 1>{}, scaled_c); break;
+          default: periods_serial(std::integral_constant<int, 0>{}, scaled_c); break;
+        }
+      };
+      if (HALVES && x_scaled) by_groups(std::true_type{});
+      else by_groups(std::false_type{});
     } else
     switch (ngr) {  // same barriers in every case
       case 7: periods(std::integral_constant<int, 7>{}); break;
@@ -502,6 +666,19 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
     }
     // partial gradient of this workgroup
     float* pg = a.partial_g + ((int64_t)chain * a.parts + blockIdx.x) * (int64_t)K * d;
+    if constexpr (HALVES) {
+      // component j of lane (m, h) is column 8 (j / 4) + 4 h + j % 4 of the group, class m % 16,
+      // piece m / 16 of R: the two pieces are 16 lanes apart
+#pragma unroll
+      for (int i = 0; i < kPipeGroups; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float v = gacc16[i][j];
+          const float t = ((v + __shfl_xor(v, 16)) * kIsr) * isx;
+          const int col = 32 * (wave + 4 * i) + 8 * (j >> 2) + 4 * gh + (j & 3);
+          if (gm < K && col < d) pg[(int64_t)gm * d + col] = t;
+        }
+    } else
 #pragma unroll
     for (int i = 0; i < kPipeGroups; ++i)
 #pragma unroll
@@ -625,20 +802,20 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
       // per block, with nothing else in between
       auto run = [&](auto nbw_c) {
         constexpr int NBW = decltype(nbw_c)::value;
-        auto dma = [&](int buf, int64_t tile) {
+        // blocks [LO, HI) of this wave's share of a tile
+        auto dma_part = [&](auto lo_c, auto hi_c, int buf, int64_t tile) {
+          constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
           const char* tb = reinterpret_cast<const char*>(X + tile * kRows * ldx);
           char* lb = reinterpret_cast<char*>(s_x + buf * tile_floats) + 1024 * hw;
           const int rows_in = (int)min((int64_t)kRows, N - tile * kRows);
           if (rows_in == kRows) {
 #pragma unroll
-            for (int s2 = 0; s2 + 1 < NBW; ++s2)
-              __builtin_amdgcn_global_load_lds((GPtr)(tb + gofs[s2]), (LPtr)(lb + 4096 * s2), 16, 0, 2);
-            if (NBW > 0 && lane < last_lanes)
-              __builtin_amdgcn_global_load_lds((GPtr)(tb + gofs[NBW > 0 ? NBW - 1 : 0]),
-                                               (LPtr)(lb + 4096 * (NBW > 0 ? NBW - 1 : 0)), 16, 0, 2);
+            for (int s2 = LO; s2 < HI; ++s2)
+              if (s2 + 1 < NBW || lane < last_lanes)
+                __builtin_amdgcn_global_load_lds((GPtr)(tb + gofs[s2]), (LPtr)(lb + 4096 * s2), 16, 0, 2);
           } else {  // the last tile: rows past N repeat row N - 1 (their residuals are 0)
 #pragma unroll
-            for (int s2 = 0; s2 < NBW; ++s2) {
+            for (int s2 = LO; s2 < HI; ++s2) {
               uint32_t go = gofs[s2];
               const int r = (int)(go / row_bytes);
               if (r >= rows_in) go -= (uint32_t)(r - (rows_in - 1)) * row_bytes;
@@ -647,6 +824,11 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
             }
           }
         };
+        typedef std::integral_constant<int, 0> C0;
+        typedef std::integral_constant<int, (NBW + 2) / 3> C1;
+        typedef std::integral_constant<int, (2 * NBW + 2) / 3> C2;
+        typedef std::integral_constant<int, NBW> C3;
+        auto dma = [&](int buf, int64_t tile) { dma_part(C0{}, C3{}, buf, tile); };
         // s_waitcnt for "at most NBW loads in flight" (the youngest tile), every other counter left alone
         constexpr int kLeaveOne = (NBW & 0xF) | (0x7 << 4) | (0xF << 8) | ((NBW >> 4) << 14);
         auto bare_barrier = [&]() {  // never waits for the tiles in flight
@@ -669,9 +851,13 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
         bare_barrier();
         int b2 = 2;
         for (int k = 0; k < n; ++k) {
-          if (k + 2 < n) dma(b2, tile_of(k + 2));
+          // the next tile but one is started in three parts, one beside each phase of the matrix
+          // waves: no barrier then waits for a whole tile's loads to be issued
+          if (k + 2 < n) dma_part(C0{}, C1{}, b2, tile_of(k + 2));
           bare_barrier();
+          if (k + 2 < n) dma_part(C1{}, C2{}, b2, tile_of(k + 2));
           bare_barrier();
+          if (k + 2 < n) dma_part(C2{}, C3{}, b2, tile_of(k + 2));
           landed(k + 2 < n);
           bare_barrier();
           b2 = b2 == 2 ? 0 : b2 + 1;
@@ -695,7 +881,7 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
       }
     };
     const int nslots = (kRows * nf4 + 255) / 256;
-    if ((d & 3) == 0) helper_dma();
+    if constexpr (serial) helper_dma();
     else if (nslots <= 2) helper(std::integral_constant<int, 2>{});
     else if (nslots <= 7) helper(std::integral_constant<int, 7>{});
     else helper(std::integral_constant<int, kPipeSlots>{});
@@ -717,7 +903,9 @@ int launch_pipe(const FgArgs& a, int R, hipStream_t s) {
   const int LDT = (a.d + 31) / 32 * 32 + 8;  // 8 mod 16: the 8-byte reads of the second product
                                              // (rows 4 apart per half-wave) do not collide
   const size_t smem = (size_t)3 * kRows * LDT * sizeof(float);  // 155136 bytes at most; 6.6 KB more are static
-  auto kern = fullgrad_softmax_pipe;
+  const bool serial = (a.d & 3) == 0;
+  auto kern = !serial ? fullgrad_softmax_pipe<false, false>
+                      : (a.xabsmax ? fullgrad_softmax_pipe<true, true> : fullgrad_softmax_pipe<true, false>);
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
     return HALP_ERR_HIP;
@@ -748,6 +936,39 @@ int fullgrad_softmax_supported(const halp_params& p) {
 bool fullgrad_softmax_one_pass(int d) { return d <= 1024; }
 
 bool fullgrad_softmax_pipelined(int d) { return d <= kPipeMaxD; }
+
+bool fullgrad_softmax_wants_absmax(int d) { return fullgrad_softmax_pipelined(d) && (d & 3) == 0; }
+
+namespace {
+constexpr int kAbsmaxBlocks = 2048;
+__global__ __launch_bounds__(256) void absmax_zero(uint32_t* out) { *out = 0u; }
+// largest |X[r][c]|, rows of whole float4s: bit patterns of non-negative floats order like the numbers
+__global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ X, int64_t rows, int nf4,
+                                                     int64_t ldx, uint32_t* out) {
+  float m = 0.f;
+  const int64_t total = rows * nf4;
+  for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
+    const int64_t r = k / nf4;
+    const int c4 = (int)(k - r * nf4);
+    const F4 v = *reinterpret_cast<const F4*>(X + r * ldx + 4 * c4);
+    m = fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+  }
+  uint32_t b = __builtin_bit_cast(uint32_t, m);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) b = max(b, (uint32_t)__shfl_xor((int)b, o));
+  if ((threadIdx.x & 63) == 0) atomicMax(out, b);
+}
+}  // namespace
+
+int launch_absmax(const float* X, int64_t rows, int d, int64_t ldx, uint32_t* out, hipStream_t s) {
+  if ((d & 3) != 0) return HALP_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(absmax_zero, dim3(1), dim3(1), 0, s, out);
+  const int64_t total = rows * (d / 4);
+  const int blocks = (int)std::min<int64_t>(kAbsmaxBlocks, (total + 255) / 256);
+  if (blocks > 0)
+    hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, s, X, rows, d / 4, ldx, out);
+  return hip_ok(hipGetLastError());
+}
 
 int launch_fullgrad_softmax(const FgArgs& a, int R, hipStream_t s) {
   if (!fullgrad_softmax_one_pass(a.d)) return launch_fullgrad_softmax_wide(a, R, s);

@@ -147,6 +147,11 @@ int halp_create(halp_handle** out, const halp_params* p) {
       halp_destroy(h);
       return HALP_ERR_HIP;
     }
+    if (p->loss == HALP_LOSS_SOFTMAX && fullgrad_softmax_wants_absmax(p->d) &&
+        hip_fail(hipMalloc(reinterpret_cast<void**>(&h->xabsmax), 256), "hipMalloc(xabsmax)")) {
+      halp_destroy(h);
+      return HALP_ERR_HIP;
+    }
     if (fullgrad_needs_resid(h->p) &&
         hip_fail(hipMalloc(reinterpret_cast<void**>(&h->resid), sizeof(float) * (size_t)p->R * p->N * 16),
                  "hipMalloc(resid)")) {
@@ -181,6 +186,7 @@ int halp_destroy(halp_handle* h) {
   if (h->partial_g) (void)hipFree(h->partial_g);
   if (h->partial_loss) (void)hipFree(h->partial_loss);
   if (h->resid) (void)hipFree(h->resid);
+  if (h->xabsmax) (void)hipFree(h->xabsmax);
   if (h->hyper) (void)hipFree(h->hyper);
   if (h->zh_work) (void)hipFree(h->zh_work);
   if (h->batch_xbuf) (void)hipFree(h->batch_xbuf);
@@ -241,6 +247,7 @@ int halp_bind(halp_handle* h, const halp_buffers* b) {
     return HALP_ERR_ALIGN;
   h->buf = *b;
   h->bound = true;
+  h->xabsmax_fresh = false;
   return HALP_OK;
 }
 
@@ -278,6 +285,10 @@ int halp_set_option(halp_handle* h, int32_t option, int64_t value) {
     case HALP_OPT_INNER_HELPERS:
       if (value < 0 || value > 3) return HALP_ERR_INVALID;
       h->inner_helpers = (int)value;
+      return HALP_OK;
+    case HALP_OPT_GRADIENT_FP32:
+      if (value != 0 && value != 1) return HALP_ERR_INVALID;
+      h->gradient_fp32 = value != 0;
       return HALP_OK;
     case HALP_OPT_INNER_WAVES:
       if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
@@ -328,6 +339,7 @@ int halp_full_gradient(halp_handle* h, void* stream) {
   if (!h) return HALP_ERR_NULL;
   int rc = need_full_gradient(*h);
   if (rc != HALP_OK) return rc;
+  if ((rc = prepare_full_gradient(*h, as_stream(stream))) != HALP_OK) return rc;
   return launch_full_gradient(*h, as_stream(stream));
 }
 
@@ -390,6 +402,7 @@ int halp_epoch(halp_handle* h, int64_t epoch, void* stream) {
   if (!svrg && (rc = need_recenter(*h)) != HALP_OK) return rc;
   if ((rc = need_inner(*h, variant)) != HALP_OK) return rc;
   hipStream_t s = as_stream(stream);
+  if ((rc = prepare_full_gradient(*h, s)) != HALP_OK) return rc;
   hipEvent_t* ev = h->ev[h->timed % halp_handle::kTimedEpochs];
   if (h->timing && hipEventRecord(ev[0], s) != hipSuccess) return HALP_ERR_HIP;
   if ((rc = launch_full_gradient(*h, s)) != HALP_OK) return rc;

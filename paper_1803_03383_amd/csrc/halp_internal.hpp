@@ -28,6 +28,10 @@ struct halp_handle {
   int loss_parts = 0;            // partial losses per chain (rows of partial_loss are max(parts, loss_parts) long)
   float* resid = nullptr;        // [R][N][16] residuals of the two-pass softmax gradient form, or null
   size_t partial_g_bytes = 0;
+  // softmax gradient pass with operands in halves: the largest |X| of the bound data
+  uint32_t* xabsmax = nullptr;   // one word (device), where that form exists for the shape
+  bool xabsmax_fresh = false;    // taken since the last halp_bind
+  bool gradient_fp32 = false;    // HALP_OPT_GRADIENT_FP32
   const float* fscale = nullptr; // caller's per-feature data scales [d] (device), or null
   // minibatch inner loop split over several workgroups per chain: partial dots and tags
   long long* batch_xbuf = nullptr;   // [R][2][kBatchSlots][64] tagged partial dots, margins and labels
@@ -63,7 +67,11 @@ int fullgrad_supported(const halp_params& p);
 int fullgrad_parts(const halp_handle& h);  // workgroups per chain for this shape
 int fullgrad_loss_parts(const halp_handle& h);
 bool fullgrad_needs_resid(const halp_params& p);
+// true where the softmax pass can take its operands in halves, given the largest |X| of the data
+bool fullgrad_softmax_wants_absmax(int d);
 int launch_full_gradient(const halp_handle& h, hipStream_t s);
+// what the pass needs once per bound data set (the largest |X| for the softmax form in halves)
+int prepare_full_gradient(halp_handle& h, hipStream_t s);
 // the same pass with its workspace in the library's fixed device array: no allocation
 int launch_full_gradient_static(const halp_params& p, const halp_buffers& buf, hipStream_t s);
 int launch_recenter(const halp_handle& h, uint32_t epoch, hipStream_t s);

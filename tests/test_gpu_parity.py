@@ -183,6 +183,57 @@ def test_full_gradient_matches_oracle(loss, N, d, K, R, lam):
     assert np.array_equal(P.get("g"), g) and np.array_equal(P.get("phi"), phi)
 
 
+# The softmax pass on rows of whole float4s up to 800 coordinates multiplies on the matrix cores'
+# 16-bit path, every fp32 operand as the sum of two halves.  X is scaled into the halves' range
+# where its largest magnitude lies outside [2^-3, 2^15): every branch of that choice, the fp32
+# products it replaces, and what the pair of halves costs in accuracy.
+@pytest.mark.parametrize("N,d,K,R", [(1500, 784, 10, 1), (700, 100, 3, 2), (333, 800, 16, 1)])
+@pytest.mark.parametrize("xscale", [1.0, 2.0 ** -14, 3.0e-2, 4.1e4, 7.0e8])
+def test_softmax_gradient_in_halves_over_data_ranges(N, d, K, R, xscale):
+    rng = np.random.default_rng(5)
+    Xs, ys = zip(*[_make_data(hp.LOSS_SOFTMAX, N, d, K, seed=30 + r) for r in range(R)])
+    X, y = (np.stack(Xs) * np.float32(xscale)).astype(np.float32), np.stack(ys)
+    w0 = (rng.standard_normal((R, K, d)) * 0.3 / xscale).astype(np.float32)
+    P = GpuProblem(X, None, y, K=K, R=R, loss=hp.LOSS_SOFTMAX, lam=1e-4, w0=w0)
+    err = {}
+    for fp32 in (0, 1):
+        P.h.set_option(hp.OPT_GRADIENT_FP32, fp32)
+        P.h.full_gradient()
+        phi, g, sc = P.get("phi"), P.get("g"), P.get("scales")
+        e = []
+        for r in range(R):
+            prob = ref.make_problem(N, d, K=K, loss=hp.LOSS_SOFTMAX, lam=1e-4)
+            phi_r, g_r, loss_r = ref.full_gradient(prob, X[r], y[r], w0[r])
+            e.append((rel_l2(phi[r], phi_r), rel_l2(g[r], g_r)))
+            assert e[-1][0] <= TOL and e[-1][1] <= TOL
+            assert abs(sc[r, 6] - loss_r) <= TOL * abs(loss_r)
+        err[fp32] = np.max(np.array(e), axis=0)
+    # two halves carry 22 of the 24 bits: the pass keeps the accuracy of fp32 products
+    assert np.all(err[0] <= 2.0 * err[1] + 1e-6), (err[0], err[1])
+
+
+def test_softmax_gradient_in_halves_follows_a_new_bind():
+    N, d, K = 900, 784, 10
+    X, y = _make_data(hp.LOSS_SOFTMAX, N, d, K, seed=41)
+    rng = np.random.default_rng(6)
+    w0 = (rng.standard_normal((1, K, d)) * 0.3).astype(np.float32)
+    P = GpuProblem(X, None, y, K=K, loss=hp.LOSS_SOFTMAX, w0=w0)
+    P.h.full_gradient()
+    g1 = P.get("g")
+    # all-zero data, then data 2^20 times larger: each bound anew, each with its own largest |X|
+    prob = ref.make_problem(N, d, K=K, loss=hp.LOSS_SOFTMAX)
+    for factor in (0.0, 2.0 ** 20):
+        P.X.copy_(torch.from_numpy(np.ascontiguousarray(X * np.float32(factor)))[None])
+        P.st["w"].copy_(torch.from_numpy(w0 / (factor if factor else 1.0)).reshape(P.st["w"].shape))
+        P.h.bind(X=P.X, Xq=P.Xq, y=P.y, ldx=d, ldxq=P.Xq.shape[-1], **P.st)
+        P.h.full_gradient()
+        phi_r, g_r, loss_r = ref.full_gradient(prob, (X * np.float32(factor)).astype(np.float32), y,
+                                               (w0[0] / (factor if factor else 1.0)).astype(np.float32))
+        assert np.all(np.isfinite(P.get("g")))
+        assert rel_l2(P.get("phi")[0], phi_r) <= TOL and rel_l2(P.get("g")[0], g_r) <= TOL
+    assert np.all(np.isfinite(g1))
+
+
 def test_full_gradient_shared_data_and_block_counts():
     X, y = _make_data(hp.LOSS_SQUARED, 2000, 512, 1, seed=3)
     rng = np.random.default_rng(1)
