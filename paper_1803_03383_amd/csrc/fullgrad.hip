@@ -323,46 +323,50 @@ struct RedArgs {
   double lambda;
 };
 
-// A workgroup sums 32 entries: thread (entry tid % 32, group tid / 32) adds every eighth
-// partial in index order, the eight group sums are then added in group order: a fixed order
-// with eight times as many loads in flight as one thread per entry would have.
-__global__ __launch_bounds__(256) void fullgrad_reduce(RedArgs a) {
+// A workgroup sums 32 entries: thread (entry tid % 32, group tid / 32) adds every 32nd partial
+// in index order, the 32 group sums are then added in group order: a fixed order, with a
+// thread's few loads all in flight at once (the pass is as long as its longest chain of waits).
+constexpr int kReduceGroups = 32;
+__global__ __launch_bounds__(32 * kReduceGroups) void fullgrad_reduce(RedArgs a) {
   const int chain = blockIdx.y;
   const int e = threadIdx.x & 31, grp = threadIdx.x >> 5;
   const int k = blockIdx.x * 32 + e;
   const float* pg = a.partial_g + (int64_t)chain * a.parts * a.n;
   const float* w = a.w + (int64_t)chain * a.n;
-  __shared__ double gsum[8][32];
+  __shared__ double gsum[kReduceGroups][32];
   double s = 0.0;
   if (k < a.n) {
 #pragma unroll 8
-    for (int p = grp; p < a.parts; p += 8) s += (double)pg[(int64_t)p * a.n + k];
+    for (int p = grp; p < a.parts; p += kReduceGroups) s += (double)pg[(int64_t)p * a.n + k];
   }
   gsum[grp][e] = s;
   __syncthreads();
   if (grp == 0 && k < a.n) {
     double t = gsum[0][e];
 #pragma unroll
-    for (int q = 1; q < 8; ++q) t += gsum[q][e];
+    for (int q = 1; q < kReduceGroups; ++q) t += gsum[q][e];
     double gk = t / (double)a.N + a.lambda * (double)w[k];
     if (a.fscale) gk = gk / (double)a.fscale[k % a.d];
     a.g[(int64_t)chain * a.n + k] = (float)gk;
   }
   if (blockIdx.x == 0) {  // f(w~): data term plus lambda/2 ||w~||^2
-    __shared__ double red[256];
-    double w2 = 0.0;
-    for (int j = threadIdx.x; j < a.n; j += 256) w2 += (double)w[j] * (double)w[j];
+    constexpr int NT = 32 * kReduceGroups;
+    __shared__ double red[NT], redl[NT];
+    double w2 = 0.0, l = 0.0;  // thread t takes entries t, t + NT, ..; then a tree: a fixed order
+    for (int j = threadIdx.x; j < a.n; j += NT) w2 += (double)w[j] * (double)w[j];
+    for (int p = threadIdx.x; p < a.loss_parts; p += NT) l += a.partial_loss[(int64_t)chain * a.loss_stride + p];
     red[threadIdx.x] = w2;
+    redl[threadIdx.x] = l;
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-      if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    for (int h = NT / 2; h > 0; h >>= 1) {
+      if ((int)threadIdx.x < h) {
+        red[threadIdx.x] += red[threadIdx.x + h];
+        redl[threadIdx.x] += redl[threadIdx.x + h];
+      }
       __syncthreads();
     }
-    if (threadIdx.x == 0) {
-      double l = 0.0;
-      for (int p = 0; p < a.loss_parts; ++p) l += a.partial_loss[(int64_t)chain * a.loss_stride + p];
-      a.scales[(int64_t)chain * 8 + 6] = l / (double)a.N + 0.5 * a.lambda * red[0];
-    }
+    if (threadIdx.x == 0)
+      a.scales[(int64_t)chain * 8 + 6] = redl[0] / (double)a.N + 0.5 * a.lambda * red[0];
   }
 }
 
@@ -524,7 +528,7 @@ static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
   r.scales = buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = f.parts; r.lambda = p.lambda;
   r.fscale = f.fscale; r.d = p.d;
   r.loss_parts = f.loss_parts; r.loss_stride = f.parts > f.loss_parts ? f.parts : f.loss_parts;
-  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 31) / 32, p.R), dim3(256), 0, s, r);
+  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 31) / 32, p.R), dim3(32 * kReduceGroups), 0, s, r);
   return hip_ok(hipGetLastError());
 }
 
