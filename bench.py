@@ -321,21 +321,33 @@ def softmax_gradient_pass(hp, torch, rows, reps):
                 delta_d=1.0 / 127.0, seed=0)
     h.bind(X=X, Xq=Xq, y=y, **st)
     warm, reps = 20, max(reps, 40)
-    for _ in range(warm):
-        h.full_gradient()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        h.full_gradient()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / reps
+
+    def timed():
+        for _ in range(warm):
+            h.full_gradient()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            h.full_gradient()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms = timed()
+    loss = h.get_stats(0).loss
+    g_halves = st["g"].clone()
+    # the same pass with fp32 products, for comparison: time, and how far its gradient lies
+    h.set_option(hp.OPT_GRADIENT_FP32, 1)
+    ms_fp32 = timed()
+    dg = float((st["g"].double() - g_halves.double()).norm() / st["g"].double().norm())
     nbytes = rows * (4 * d + 4 * K + 4)
     out = dict(workload=f"softmax gradient pass, N={rows}, d={d}, K={K}, fp32 data and accumulation, "
                         "products on pairs of halves", passes=reps, warmup_passes=warm, ms=ms, bytes=nbytes,
                achieved=nbytes / (ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
-               frac=nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, loss=h.get_stats(0).loss)
+               frac=nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, loss=loss,
+               fp32_products=dict(ms=ms_fp32, frac=nbytes / (ms_fp32 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                  rel_l2_of_gradients=dg))
     h.close()
     return out
 
