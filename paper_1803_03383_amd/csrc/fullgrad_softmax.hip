@@ -646,8 +646,12 @@ __global__ __launch_bounds__(512) void fullgrad_softmax_pipe(FgArgs a, int LDT) 
           default: periods_serial(std::integral_constant<int, 0>{}, scaled_c); break;
         }
       };
-      if (HALVES && x_scaled) by_groups(std::true_type{});
-      else by_groups(std::false_type{});
+      if constexpr (HALVES) {
+        if (x_scaled) by_groups(std::true_type{});
+        else by_groups(std::false_type{});
+      } else {
+        by_groups(std::false_type{});
+      }
     } else
     switch (ngr) {  // same barriers in every case
       case 7: periods(std::integral_constant<int, 7>{}); break;
