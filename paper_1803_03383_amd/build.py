@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 OUT = os.path.join(HERE, "libhalp.so")
 SOURCES = ["halp_api.hip", "fullgrad.hip", "recenter.hip", "inner_generic.hip", "inner_reg.hip",
-           "inner_reg_b8.hip", "inner_reg_b16.hip", "inner_reg_helped_b8.hip", "inner_reg_helped_b16.hip", "inner_reg_lone_b8.hip", "inner_softmax.hip", "fullgrad_softmax.hip", "fullgrad_wide.hip", "inner_svrg.hip", "inner_batch.hip", "step_latency.hip"]
+           "inner_reg_b8.hip", "inner_reg_b16.hip", "inner_reg_helped_b8.hip", "inner_reg_helped_b16.hip", "inner_reg_lone_b8.hip", "inner_softmax.hip", "inner_softmax_batch.hip", "fullgrad_softmax.hip", "fullgrad_wide.hip", "inner_svrg.hip", "inner_batch.hip", "step_latency.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -79,6 +79,8 @@ int inner_reg_supported(const halp_params& p);
 int launch_inner_reg(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_softmax_supported(const halp_handle& h);
 int launch_inner_softmax(const halp_handle& h, uint32_t epoch, hipStream_t s);
+int inner_softmax_batch_supported(const halp_handle& h);  // softmax with a minibatch
+int launch_inner_softmax_batch(const halp_handle& h, uint32_t epoch, hipStream_t s);
 int inner_generic_supported(const halp_params& p);
 bool inner_generic_needs_workspace(const halp_params& p);
 size_t inner_generic_workspace_bytes(const halp_params& p);

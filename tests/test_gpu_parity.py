@@ -630,6 +630,62 @@ def test_inner_loop_softmax_bit_exact(N, d, K, b, lam, R, T, mu, variant):
         assert cnt[0, 0] > 0
 
 
+SOFTMAX_BATCH_CASES = [
+    # N, d, K, B, b, lam, R, T, mu
+    (400, 784, 10, 8, 8, 1e-4, 2, 60, 0.05),      # the 10-class shape, 12-wave build
+    (300, 100, 3, 64, 8, 1e-2, 1, 100, 0.05),     # the widest minibatch, few lanes on the row, L2 draws
+    (300, 256, 15, 5, 16, 1e-3, 1, 50, 0.05),     # 15 classes at 16 bits: 16 waves
+    (200, 1024, 7, 4, 8, 0.0, 1, 40, 0.05),       # every lane full, 8-wave build
+    (300, 784, 10, 16, 16, 1e-4, 1, 30, 0.05),    # 16 strips per lane at 16 bits
+    (150, 1008, 2, 3, 16, 0.0, 1, 33, 500.0),     # ... saturating
+    (200, 781, 4, 6, 16, 1e-2, 2, 25, 0.05),      # ragged last lane
+    (100, 64, 2, 2, 8, 0.0, 1, 1, 0.05),          # a single step
+    (100, 64, 2, 2, 8, 0.0, 1, 0, 0.05),          # no step at all
+    (60, 7, 12, 64, 8, 1e-2, 1, 9, 0.05),         # a row inside one lane
+    (64, 64, 4, 32, 8, 0.0, 1, 200, 500.0),       # box far too small: z saturates
+    (2, 1, 2, 2, 8, 0.0, 1, 40, 0.05),            # two examples, one feature
+]
+
+
+@pytest.mark.parametrize("variant", [2, 0, 1])
+@pytest.mark.parametrize("N,d,K,B,b,lam,R,T,mu", SOFTMAX_BATCH_CASES)
+def test_inner_loop_softmax_minibatch_bit_exact(N, d, K, B, b, lam, R, T, mu, variant):
+    loss = hp.LOSS_SOFTMAX
+    seed = 90 + d + T + B
+    case = _inner_case(loss, N, d, K, B, b, lam, R, T, seed, mu=mu)
+    P = _run_inner(case, loss, K, B, b, lam, R, T, seed, variant, mu=mu)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    assert P.h.get_stats(0).inner_variant == (1 if variant == 1 else 2)
+    for r in range(R):
+        prob = case["mk"](r)
+        out = ref.inner_loop(prob, case["Xq"][r], case["phi"][r], case["y"][r], case["h"][r],
+                             case["scales"][r], 3, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        assert np.array_equal(w[r], ref.apply_offset(prob, case["scales"][r], out["z"], case["w"][r]))
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    if mu > 100:
+        assert cnt[0, 0] > 0
+
+
+def test_softmax_minibatch_shapes_outside_the_register_kernel_fall_back():
+    # 16 classes would need a seventeenth wave, and 100 rows per step do not fit the kernel's tables
+    for K, B in ((16, 4), (3, 100)):
+        loss, N, d, b, T = hp.LOSS_SOFTMAX, 150, 96, 8, 12
+        case = _inner_case(loss, N, d, K, B, b, 0.0, 1, T, 55, mu=0.05)
+        P = _run_inner(case, loss, K, B, b, 0.0, 1, T, 55, 0, mu=0.05)
+        P.h.inner_loop(3)
+        assert P.h.get_stats(0).inner_variant == 1
+        prob = case["mk"](0)
+        out = ref.inner_loop(prob, case["Xq"][0], case["phi"][0], case["y"][0], case["h"][0],
+                             case["scales"][0], 3, T)
+        assert np.array_equal(P.get("z")[0].astype(np.int32), out["z"])
+        P.h.set_option(hp.OPT_INNER_VARIANT, 2)
+        with pytest.raises(hp.HalpError) as e:
+            P.h.inner_loop(3)
+        assert e.value.code == hp.ERR_UNSUPPORTED
+
+
 def test_softmax_shapes_outside_the_register_kernel_fall_back():
     # 1600 coordinates at 16 bits need more than 16 strips per lane: the automatic choice is the
     # general kernel, and forcing the register kernel is an error, not a wrong answer
