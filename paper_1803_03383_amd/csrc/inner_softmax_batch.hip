@@ -46,7 +46,10 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
   const int64_t N = a.N, ldxq = a.ldxq;
   const int row_dw = (int)(ldxq * (BITS / 8) / 4);
   const int slot_dw = slot_bytes / 4;
-  const int copy_dw = min(row_dw, slot_dw);
+  const int copy_dw = min(row_dw, slot_dw);     // at most 512: a slot holds 1024 strips of 2 bytes
+  constexpr int kRowLoads = 8;                   // dwords per lane and row at most
+  const int nq = (copy_dw + 63) / 64;
+  const int NW = NT >> 6;
   const unsigned char* __restrict__ Xq = reinterpret_cast<const unsigned char*>(a.Xq) +
                                          (int64_t)chain * a.xq_chain_stride * (BITS / 8);
   const float* __restrict__ phi = a.phi + (int64_t)chain * N * K;
@@ -68,10 +71,12 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
   __shared__ double s_es[kMaxB * kKPad * 2];   // exponentials before / after
   __shared__ double s_rowst[kMaxB * 4];        // per row: max0, max1, sum0, sum1
   __shared__ int s_gam[kMaxB * kKPad];
+  __shared__ __attribute__((aligned(4))) int8_t s_gamb[kKPad * kMaxB];  // 8 bits: gamma as bytes [class][row]
   __shared__ unsigned long long s_cnt[3];
   __shared__ int s_clambda;
   if (tid < 3) s_cnt[tid] = 0;
   if (tid == 0) s_clambda = 0;
+  for (int e = tid; e < kKPad * kMaxB / 4; e += NT) reinterpret_cast<int*>(s_gamb)[e] = 0;  // rows past B stay 0
 
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
@@ -131,20 +136,47 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
     }
     __syncthreads();
     // the B rows into LDS: both the dot products and the update read them there
-    for (int e = tid; e < B * copy_dw; e += NT) {
-      const int m = e / copy_dw, q = e - m * copy_dw;
-      s_rows[m * slot_dw + q] = reinterpret_cast<const uint32_t*>(Xq + s_idx[m] * ldxq * (BITS / 8))[q];
+    // (a wave takes whole rows, 256 bytes per load, and has all loads of a row in flight at once)
+#pragma unroll 2
+    for (int m = wave; m < B; m += NW) {
+      const uint32_t* src = reinterpret_cast<const uint32_t*>(Xq + s_idx[m] * ldxq * (BITS / 8));
+      uint32_t v[kRowLoads];
+#pragma unroll
+      for (int i = 0; i < kRowLoads; ++i)
+        if (i < nq) v[i] = src[min(lane + 64 * i, copy_dw - 1)];
+#pragma unroll
+      for (int i = 0; i < kRowLoads; ++i)
+        if (i < nq && lane + 64 * i < copy_dw) s_rows[m * slot_dw + lane + 64 * i] = v[i];
     }
     __syncthreads();
     // integer dot products x_m^T z_c
     if (class_wave) {
-      for (int m = 0; m < B; ++m) {
+      int zpk[BITS == 8 ? CPL / 4 : 1];  // 8 bits: z as bytes, four to a register
+      if constexpr (BITS == 8) {
+#pragma unroll
+        for (int q = 0; q < CPL / 4; ++q)
+          zpk[q] = (z[4 * q] & 0xff) | ((z[4 * q + 1] & 0xff) << 8) | ((z[4 * q + 2] & 0xff) << 16) |
+                   (int)((uint32_t)z[4 * q + 3] << 24);
+      }
+#pragma unroll 4
+      for (int m = 0; m < B; ++m) {  // four rows at a time: their reads and folds overlap
         uint4 f[FQ];
 #pragma unroll
         for (int q = 0; q < FQ; ++q) f[q] = frag[m * (slot_dw / 4) + q];
         AccT acc = 0;
+        if constexpr (BITS == 8) {  // four coordinates per instruction, z as packed bytes
+          int a32 = 0;
 #pragma unroll
-        for (int k = 0; k < CPL; ++k) acc += (AccT)(x_of(f, k) * z[k]);  // |x z| < 2^30; z = 0 past the row
+          for (int q = 0; q < CPL / 4; ++q) {
+            const uint4& fq = f[q / 4];
+            const uint32_t xv = q % 4 == 0 ? fq.x : (q % 4 == 1 ? fq.y : (q % 4 == 2 ? fq.z : fq.w));
+            a32 = __builtin_amdgcn_sdot4((int)xv, zpk[q], a32, false);
+          }
+          acc = a32;
+        } else {
+#pragma unroll
+          for (int k = 0; k < CPL; ++k) acc += (AccT)(x_of(f, k) * z[k]);  // |x z| < 2^30; z = 0 past the row
+        }
         long long tot;
         if (BITS == 8) tot = (long long)wave_sum_i32((int)acc);
         else tot = wave_sum_i64((long long)acc);
@@ -204,7 +236,9 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
       const uint64_t nn = ((uint64_t)t * (uint64_t)B + (uint64_t)m) * (uint64_t)K + (uint64_t)c;
       const uint32_t r = pick(stream_block(seed, kGamma, a.epoch, nn >> 2), (uint32_t)(nn & 3));
       bool hit = false;
-      s_gam[pr] = (int)quantize_real(beta, inv_s, r, qmind, qmaxd, &hit);
+      const int gq = (int)quantize_real(beta, inv_s, r, qmind, qmaxd, &hit);
+      s_gam[pr] = gq;
+      if constexpr (BITS == 8) s_gamb[c * kMaxB + m] = (int8_t)gq;
       if (hit) my_gclamp += 1;
     }
     __syncthreads();
@@ -214,13 +248,39 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
       AccT gsum[CPL];
 #pragma unroll
       for (int k = 0; k < CPL; ++k) gsum[k] = 0;
-      for (int m = 0; m < B; ++m) {
-        uint4 f[FQ];
+      if constexpr (BITS == 8) {
+        // four rows at a time: their bytes of a coordinate are brought into one register (a 4 x 4
+        // byte transpose per dword of the fragments) and meet the rows' four gammas in one
+        // 4-way dot product
+        for (int m = 0; m < B; m += 4) {
+          uint4 f[4];
 #pragma unroll
-        for (int q = 0; q < FQ; ++q) f[q] = frag[m * (slot_dw / 4) + q];
-        const int g = s_gam[m * K + cls];
+          for (int i = 0; i < 4; ++i) f[i] = frag[min(m + i, B - 1) * (slot_dw / 4)];  // gamma is 0 past B
+          const int g4 = reinterpret_cast<const int*>(s_gamb)[(cls * kMaxB + m) >> 2];
 #pragma unroll
-        for (int k = 0; k < CPL; ++k) gsum[k] += (AccT)g * (AccT)x_of(f, k);
+          for (int q = 0; q < 4; ++q) {
+            auto dw = [&](const uint4& v) { return q == 0 ? v.x : (q == 1 ? v.y : (q == 2 ? v.z : v.w)); };
+            const uint32_t ra = dw(f[0]), rb = dw(f[1]), rc = dw(f[2]), rd = dw(f[3]);
+            const uint32_t ab_lo = __builtin_amdgcn_perm(rb, ra, 0x05010400u), ab_hi = __builtin_amdgcn_perm(rb, ra, 0x07030602u);
+            const uint32_t cd_lo = __builtin_amdgcn_perm(rd, rc, 0x05010400u), cd_hi = __builtin_amdgcn_perm(rd, rc, 0x07030602u);
+            const uint32_t t0 = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x05040100u), t1 = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x07060302u);
+            const uint32_t t2 = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x05040100u), t3 = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
+            gsum[4 * q + 0] = __builtin_amdgcn_sdot4((int)t0, g4, (int)gsum[4 * q + 0], false);
+            gsum[4 * q + 1] = __builtin_amdgcn_sdot4((int)t1, g4, (int)gsum[4 * q + 1], false);
+            gsum[4 * q + 2] = __builtin_amdgcn_sdot4((int)t2, g4, (int)gsum[4 * q + 2], false);
+            gsum[4 * q + 3] = __builtin_amdgcn_sdot4((int)t3, g4, (int)gsum[4 * q + 3], false);
+          }
+        }
+      } else {
+#pragma unroll 4
+        for (int m = 0; m < B; ++m) {
+          uint4 f[FQ];
+#pragma unroll
+          for (int q = 0; q < FQ; ++q) f[q] = frag[m * (slot_dw / 4) + q];
+          const int g = s_gam[m * K + cls];
+#pragma unroll
+          for (int k = 0; k < CPL; ++k) gsum[k] += (AccT)g * (AccT)x_of(f, k);
+        }
       }
       if ((t & 7) == 0) {
 #pragma unroll

@@ -84,6 +84,8 @@ LP_CASES = [
     (hp.LOSS_SOFTMAX, 200, 784, 10, 1, 8, 2, 203, (2, 1)),  # the 10-class shape, ragged epoch
     (hp.LOSS_SOFTMAX, 150, 256, 15, 1, 16, 1, 150, (2, 1)),  # 15 classes at 16 bits
     (hp.LOSS_SOFTMAX, 150, 300, 16, 1, 8, 1, 150, (2, 1)),   # 16 classes: two rows of z per class wave
+    (hp.LOSS_SOFTMAX, 200, 200, 5, 6, 8, 1, 60, (2, 1)),     # softmax with a minibatch
+    (hp.LOSS_SOFTMAX, 120, 600, 3, 16, 16, 1, 40, (2, 1)),   # ... 16 strips per lane at 16 bits
 ]
 
 
