@@ -17,18 +17,22 @@
 //   class waves       sum_m gamma_{m,c} x_m from the rows in LDS, integer update of row c | barrier
 // The arithmetic of every stage is that of the general kernel (inner_generic.hip): the same
 // streams, the same order of the floating-point operations.
+#include <algorithm>
+
 #include "halp_device.hpp"
 #include "inner_args.hpp"
 
 namespace halp {
 namespace {
 
-constexpr int kMaxB = 64;     // rows per step
+constexpr int kMaxB = 64;     // rows of a step in LDS at a time (a step has up to 512)
 constexpr int kMaxK = 15;     // classes: one wave each, and one wave more
 constexpr int kKPad = 16;     // classes are padded to 16 in the pairwise sums
 
 // WAVES: the most waves a launch of this instance has (K + 1 <= WAVES): fewer waves, more registers each
-template <int BITS, int UPL, int WAVES>
+// MANY: more rows per step than LDS holds at a time (the loop over chunks then has one pass, and the
+// sums of the update live only inside it)
+template <int BITS, int UPL, int WAVES, bool MANY>
 __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs a, int slot_bytes) {
   using XT = typename std::conditional<BITS == 8, int8_t, int16_t>::type;
   using HT = typename std::conditional<BITS == 8, int16_t, int32_t>::type;
@@ -40,7 +44,7 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
   const int tid = threadIdx.x, NT = blockDim.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int d = a.d, K = a.K, B = a.B;
+  const int d = a.d, K = a.K, Bt = a.B;  // Bt rows per step, taken kMaxB at a time
   const int n = K * d;
   const int U = (d + CT - 1) / CT;
   const int64_t N = a.N, ldxq = a.ldxq;
@@ -81,7 +85,7 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
   const double delta_m = sc[0], inv_s = sc[5];
   const double dscale = __dmul_rn(a.delta_d, delta_m);
   const double alpha = a.hyper[2 * chain];
-  const double aB = __ddiv_rn(alpha, (double)B);
+  const double aB = __ddiv_rn(alpha, (double)Bt);
   const bool lp = a.lp != 0;
   // the margin after the move: Algorithm 4 adds x^T z to phi, in Algorithm 2 x^T w is all of it
   auto after_margin = [&](double a0, long long D) {
@@ -121,18 +125,25 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
 
   const int64_t T = epoch_steps(seed, a.epoch, a.T, a.option2);
   for (int64_t t = 0; t < T; ++t) {
+    // sum_m gamma_{m,c} x_m over the whole minibatch, and c_lambda: class waves, across the chunks
+    AccT gsum[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) gsum[k] = 0;
+    int cl = 0;
+    for (int mb = 0; mb < (MANY ? Bt : 1); mb += kMaxB) {
+    const int B = min(kMaxB, Bt - mb);  // rows of this chunk: mb .. mb + B - 1 of the step
     // sample i uniformly (with replacement)
     if (tid < B) {
-      const uint64_t nn = (uint64_t)t * (uint64_t)B + (uint64_t)tid;
+      const uint64_t nn = (uint64_t)t * (uint64_t)Bt + (uint64_t)(mb + tid);
       const uint32_t r = pick(stream_block(seed, kIdx, a.epoch, nn >> 2), (uint32_t)(nn & 3));
       s_idx[tid] = (long long)(((uint64_t)r * (uint64_t)N) >> 32);
     }
-    if (tid == 0 && a.lambda > 0) {  // c_lambda = Q_(2^-b, b)(alpha lambda)
+    if (mb == 0 && tid == 0 && a.lambda > 0) {  // c_lambda = Q_(2^-b, b)(alpha lambda)
       const uint32_t r = pick(stream_block(seed, kReg, a.epoch, (uint64_t)t >> 2), (uint32_t)(t & 3));
-      const int cl = (int)quantize_real(__dmul_rn(alpha, a.lambda), (double)(1 << BITS), r, 0.0,
-                                        qmaxd, nullptr);
-      s_clambda = cl;
-      if (cl != 0) s_cnt[2] += 1;
+      const int clq = (int)quantize_real(__dmul_rn(alpha, a.lambda), (double)(1 << BITS), r, 0.0,
+                                         qmaxd, nullptr);
+      s_clambda = clq;
+      if (clq != 0) s_cnt[2] += 1;
     }
     __syncthreads();
     // the B rows into LDS: both the dot products and the update read them there
@@ -233,7 +244,7 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
       const double p0 = __ddiv_rn(s_es[2 * pr + 0], s_rowst[4 * m + 2]);
       const double p1 = __ddiv_rn(s_es[2 * pr + 1], s_rowst[4 * m + 3]);
       const double beta = __dmul_rn(aB, __dadd_rn(p1, -p0));
-      const uint64_t nn = ((uint64_t)t * (uint64_t)B + (uint64_t)m) * (uint64_t)K + (uint64_t)c;
+      const uint64_t nn = ((uint64_t)t * (uint64_t)Bt + (uint64_t)(mb + m)) * (uint64_t)K + (uint64_t)c;
       const uint32_t r = pick(stream_block(seed, kGamma, a.epoch, nn >> 2), (uint32_t)(nn & 3));
       bool hit = false;
       const int gq = (int)quantize_real(beta, inv_s, r, qmind, qmaxd, &hit);
@@ -241,13 +252,16 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
       if constexpr (BITS == 8) s_gamb[c * kMaxB + m] = (int8_t)gq;
       if (hit) my_gclamp += 1;
     }
+    if constexpr (BITS == 8) {  // the update takes rows in fours: no gamma for the rows past the chunk
+      if (tid < 4 * K) {
+        const int m = B + (tid & 3);
+        if (m < ((B + 3) & ~3)) s_gamb[(tid >> 2) * kMaxB + m] = 0;
+      }
+    }
     __syncthreads();
     // u = z - sum_m gamma_m x_m - h~ (- c_lambda z) in (delta_i, 2b); z = Q_(delta_m, b)(u)
     if (class_wave) {
-      const int cl = s_clambda;
-      AccT gsum[CPL];
-#pragma unroll
-      for (int k = 0; k < CPL; ++k) gsum[k] = 0;
+      cl = s_clambda;
       if constexpr (BITS == 8) {
         // four rows at a time: their bytes of a coordinate are brought into one register (a 4 x 4
         // byte transpose per dword of the fragments) and meet the rows' four gammas in one
@@ -282,6 +296,10 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
           for (int k = 0; k < CPL; ++k) gsum[k] += (AccT)g * (AccT)x_of(f, k);
         }
       }
+    }
+    __syncthreads();  // the rows, indices and gammas of this chunk are done with
+    }
+    if (class_wave) {
       if ((t & 7) == 0) {
 #pragma unroll
         for (int u = 0; u < UPL; ++u)
@@ -305,7 +323,6 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
         }
       }
     }
-    __syncthreads();  // the rows, indices and gammas of this step are done with
   }
 
   // w~ <- w~ + delta_m z (option I), and hand z out
@@ -343,8 +360,9 @@ int slot_bytes_of(const halp_params& p, int upl) {
 
 template <int BITS, int UPL, int WAVES>
 int launch_waves(const InArgs& a, int R, int slot_bytes, hipStream_t s) {
-  const size_t smem = (size_t)a.B * slot_bytes;
-  auto kern = inner_softmax_batch_kernel<BITS, UPL, WAVES>;
+  const size_t smem = (size_t)std::min(a.B, kMaxB) * slot_bytes;
+  auto kern = a.B > kMaxB ? inner_softmax_batch_kernel<BITS, UPL, WAVES, true>
+                          : inner_softmax_batch_kernel<BITS, UPL, WAVES, false>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)smem) != hipSuccess)
     return HALP_ERR_HIP;
@@ -363,13 +381,13 @@ int launch_one(const InArgs& a, int R, int slot_bytes, hipStream_t s) {
 
 int inner_softmax_batch_supported(const halp_handle& h) {
   const halp_params& p = h.p;
-  if (p.loss != HALP_LOSS_SOFTMAX || p.B < 2 || p.B > kMaxB || p.K < 2 || p.K > kMaxK)
+  if (p.loss != HALP_LOSS_SOFTMAX || p.B < 2 || p.B > 512 || p.K < 2 || p.K > kMaxK)
     return HALP_ERR_UNSUPPORTED;
   const int upl = strips_per_lane(p);
   if (upl == 0) return HALP_ERR_UNSUPPORTED;
   if (!h.bound || !h.buf.Xq) return HALP_ERR_NOT_BOUND;
   // 128 KB of rows beside the 31 KB of per-step scalars
-  if ((size_t)p.B * slot_bytes_of(p, upl) > 128 * 1024) return HALP_ERR_UNSUPPORTED;
+  if ((size_t)std::min(p.B, kMaxB) * slot_bytes_of(p, upl) > 128 * 1024) return HALP_ERR_UNSUPPORTED;
   return HALP_OK;
 }
 

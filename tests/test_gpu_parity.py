@@ -644,6 +644,10 @@ SOFTMAX_BATCH_CASES = [
     (60, 7, 12, 64, 8, 1e-2, 1, 9, 0.05),         # a row inside one lane
     (64, 64, 4, 32, 8, 0.0, 1, 200, 500.0),       # box far too small: z saturates
     (2, 1, 2, 2, 8, 0.0, 1, 40, 0.05),            # two examples, one feature
+    (300, 100, 3, 65, 8, 1e-2, 1, 30, 0.05),      # more rows than LDS holds at a time: 64 + 1
+    (200, 784, 10, 130, 8, 1e-4, 1, 12, 0.05),    # ... three chunks, the last of two rows
+    (150, 256, 5, 512, 16, 1e-3, 1, 6, 0.05),     # ... the widest minibatch, 16 bits
+    (120, 64, 4, 200, 8, 0.0, 1, 20, 500.0),      # ... saturating
 ]
 
 
@@ -669,8 +673,8 @@ def test_inner_loop_softmax_minibatch_bit_exact(N, d, K, B, b, lam, R, T, mu, va
 
 
 def test_softmax_minibatch_shapes_outside_the_register_kernel_fall_back():
-    # 16 classes would need a seventeenth wave, and 100 rows per step do not fit the kernel's tables
-    for K, B in ((16, 4), (3, 100)):
+    # 16 classes would need a seventeenth wave
+    for K, B in ((16, 4), (16, 100)):
         loss, N, d, b, T = hp.LOSS_SOFTMAX, 150, 96, 8, 12
         case = _inner_case(loss, N, d, K, B, b, 0.0, 1, T, 55, mu=0.05)
         P = _run_inner(case, loss, K, B, b, 0.0, 1, T, 55, 0, mu=0.05)
