@@ -140,7 +140,7 @@ typedef struct {
                                     strips per lane of one wave at 8 bits, 16 at 16 bits -- 8
                                     at either width for 16 classes, which share waves in
                                     pairs -- and the staged rows within the LDS of a CU), and
-                                    for softmax with 2 <= B <= 512 (up to 15 classes, a class's
+                                    for softmax with 2 <= B <= 512 (a class's
                                     row of z within 8 strips per lane at 8 bits, 16 at 16
                                     bits, 64 rows of a step within 128 KB of LDS); auto takes
                                     them when the shape fits, 2 fails with HALP_ERR_UNSUPPORTED

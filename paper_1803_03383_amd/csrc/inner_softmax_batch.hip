@@ -1,8 +1,8 @@
 // Inner loop of Algorithm 4 (LM-HALP) for softmax regression with a minibatch: K classes,
 // B sampled rows per step, register-resident form.
 //
-// One workgroup per chain: K class waves and one more wave that only takes part in the
-// work that is dealt by thread.  Class wave c owns row c of z ([K][d]): lane l holds the UPL
+// One workgroup per chain: K class waves and (up to 15 classes) one more wave that only takes
+// part in the work that is dealt by thread.  Class wave c owns row c of z ([K][d]): lane l holds the UPL
 // consecutive strips (16 rounding bits each: two coordinates at 8 bits, one at 16) starting at
 // l * UPL, with h~ and the strips' Philox blocks of the current window of 8 steps, in
 // registers for the whole epoch.
@@ -26,7 +26,7 @@ namespace halp {
 namespace {
 
 constexpr int kMaxB = 64;     // rows of a step in LDS at a time (a step has up to 512)
-constexpr int kMaxK = 15;     // classes: one wave each, and one wave more
+constexpr int kMaxK = 16;     // classes: one wave each, and one wave more where 16 waves allow it
 constexpr int kKPad = 16;     // classes are padded to 16 in the pairwise sums
 
 // WAVES: the most waves a launch of this instance has (K + 1 <= WAVES): fewer waves, more registers each
@@ -366,7 +366,7 @@ int launch_waves(const InArgs& a, int R, int slot_bytes, hipStream_t s) {
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)smem) != hipSuccess)
     return HALP_ERR_HIP;
-  hipLaunchKernelGGL(kern, dim3(R), dim3(64 * (a.K + 1)), smem, s, a, slot_bytes);
+  hipLaunchKernelGGL(kern, dim3(R), dim3(64 * std::min(a.K + 1, 16)), smem, s, a, slot_bytes);
   return hip_ok(hipGetLastError());
 }
 

@@ -648,6 +648,9 @@ SOFTMAX_BATCH_CASES = [
     (200, 784, 10, 130, 8, 1e-4, 1, 12, 0.05),    # ... three chunks, the last of two rows
     (150, 256, 5, 512, 16, 1e-3, 1, 6, 0.05),     # ... the widest minibatch, 16 bits
     (120, 64, 4, 200, 8, 0.0, 1, 20, 500.0),      # ... saturating
+    (200, 300, 16, 7, 8, 1e-3, 1, 40, 0.05),      # 16 classes: sixteen class waves and no other
+    (150, 512, 16, 64, 16, 0.0, 1, 10, 0.05),     # ... at 16 bits, 1024 (row, class) pairs per step
+    (100, 96, 16, 70, 8, 1e-2, 1, 15, 0.05),      # ... in two chunks
 ]
 
 
@@ -673,9 +676,9 @@ def test_inner_loop_softmax_minibatch_bit_exact(N, d, K, B, b, lam, R, T, mu, va
 
 
 def test_softmax_minibatch_shapes_outside_the_register_kernel_fall_back():
-    # 16 classes would need a seventeenth wave
-    for K, B in ((16, 4), (16, 100)):
-        loss, N, d, b, T = hp.LOSS_SOFTMAX, 150, 96, 8, 12
+    # rows of more than 512 strips (8 bits) do not fit a class wave at 8 strips per lane
+    for K, B in ((3, 4), (16, 100)):
+        loss, N, d, b, T = hp.LOSS_SOFTMAX, 150, 1100, 8, 12
         case = _inner_case(loss, N, d, K, B, b, 0.0, 1, T, 55, mu=0.05)
         P = _run_inner(case, loss, K, B, b, 0.0, 1, T, 55, 0, mu=0.05)
         P.h.inner_loop(3)
