@@ -142,7 +142,8 @@ typedef struct {
                                     pairs -- and the staged rows within the LDS of a CU), and
                                     for softmax with 2 <= B <= 512 (a class's
                                     row of z within 8 strips per lane at 8 bits, 16 at 16
-                                    bits, 64 rows of a step within 128 KB of LDS); auto takes
+                                    bits, 64 rows of a step within 128 KB of LDS; the same kernel
+                                    takes K = 1 with 64 < B <= 512 on such rows); auto takes
                                     them when the shape fits, 2 fails with HALP_ERR_UNSUPPORTED
                                     when it does not.  HALP_ALG_SVRG has one fp32 kernel and
                                     ignores this option                                      */

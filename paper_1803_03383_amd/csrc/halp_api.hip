@@ -61,12 +61,14 @@ int launch_inner(const halp_handle& h, int variant, uint32_t epoch, hipStream_t 
 
 // the register-resident family: one kernel for scalar margins, one for softmax
 int reg_supported(const halp_handle& h) {
+  if (h.p.loss != HALP_LOSS_SOFTMAX && h.p.B > 64) return inner_softmax_batch_supported(h);
   if (h.p.loss != HALP_LOSS_SOFTMAX && h.p.B > 1) return inner_batch_supported(h);
   if (h.p.loss == HALP_LOSS_SOFTMAX && h.p.B > 1) return inner_softmax_batch_supported(h);
   return h.p.loss == HALP_LOSS_SOFTMAX ? inner_softmax_supported(h) : inner_reg_supported(h.p);
 }
 
 int launch_reg(const halp_handle& h, uint32_t epoch, hipStream_t s) {
+  if (h.p.loss != HALP_LOSS_SOFTMAX && h.p.B > 64) return launch_inner_softmax_batch(h, epoch, s);
   if (h.p.loss != HALP_LOSS_SOFTMAX && h.p.B > 1) return launch_inner_batch(h, epoch, s);
   if (h.p.loss == HALP_LOSS_SOFTMAX && h.p.B > 1) return launch_inner_softmax_batch(h, epoch, s);
   return h.p.loss == HALP_LOSS_SOFTMAX ? launch_inner_softmax(h, epoch, s)

@@ -1,5 +1,6 @@
 // Inner loop of Algorithm 4 (LM-HALP) for softmax regression with a minibatch: K classes,
-// B sampled rows per step, register-resident form.
+// B sampled rows per step, register-resident form.  Also takes the scalar margins (K = 1,
+// squared or logistic loss) of minibatches wider than the kernel for that case holds.
 //
 // One workgroup per chain: K class waves and (up to 15 classes) one more wave that only takes
 // part in the work that is dealt by thread.  Class wave c owns row c of z ([K][d]): lane l holds the UPL
@@ -29,6 +30,11 @@ constexpr int kMaxB = 64;     // rows of a step in LDS at a time (a step has up 
 constexpr int kMaxK = 16;     // classes: one wave each, and one wave more where 16 waves allow it
 constexpr int kKPad = 16;     // classes are padded to 16 in the pairwise sums
 
+__device__ __forceinline__ double logistic_dl(double a, double y) {
+  // l'(a) for l(a) = log(1 + exp(-y a))
+  return __ddiv_rn(-y, __dadd_rn(1.0, halp_exp(__dmul_rn(y, a))));
+}
+
 // WAVES: the most waves a launch of this instance has (K + 1 <= WAVES): fewer waves, more registers each
 // MANY: more rows per step than LDS holds at a time (the loop over chunks then has one pass, and the
 // sums of the update live only inside it)
@@ -57,6 +63,8 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
   const unsigned char* __restrict__ Xq = reinterpret_cast<const unsigned char*>(a.Xq) +
                                          (int64_t)chain * a.xq_chain_stride * (BITS / 8);
   const float* __restrict__ phi = a.phi + (int64_t)chain * N * K;
+  const float* __restrict__ y = reinterpret_cast<const float*>(a.y) + (int64_t)chain * a.y_chain_stride;
+  const bool softmax = a.loss == HALP_LOSS_SOFTMAX;  // else K = 1: squared or logistic loss
   const HT* __restrict__ hg = reinterpret_cast<const HT*>(a.h) + (int64_t)chain * n;
   XT* __restrict__ zg = reinterpret_cast<XT*>(a.z) + (int64_t)chain * n;
   float* __restrict__ wg = a.w + (int64_t)chain * n;
@@ -197,6 +205,7 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
     __syncthreads();
     // beta = (alpha/B)(p_c(phi_i + x_i^T z) - p_c(phi_i)); gamma = Q_(delta_s, b)(beta).
     // The normalisers are formed per row, the exponentials summed pairwise over adjacent classes.
+    if (softmax) {
     if (tid < B) {
       const long long i = s_idx[tid];
       double mx0 = (double)phi[i * K];
@@ -239,11 +248,26 @@ __global__ __launch_bounds__(64 * WAVES) void inner_softmax_batch_kernel(InArgs 
       }
     }
     __syncthreads();
+    }
     for (int pr = tid; pr < B * K; pr += NT) {
       const int m = pr / K, c = pr - m * K;
-      const double p0 = __ddiv_rn(s_es[2 * pr + 0], s_rowst[4 * m + 2]);
-      const double p1 = __ddiv_rn(s_es[2 * pr + 1], s_rowst[4 * m + 3]);
-      const double beta = __dmul_rn(aB, __dadd_rn(p1, -p0));
+      double diff;
+      if (softmax) {
+        const double p0 = __ddiv_rn(s_es[2 * pr + 0], s_rowst[4 * m + 2]);
+        const double p1 = __ddiv_rn(s_es[2 * pr + 1], s_rowst[4 * m + 3]);
+        diff = __dadd_rn(p1, -p0);
+      } else {
+        const long long i = s_idx[m];
+        const double delta = __dmul_rn(dscale, (double)s_D[pr]);
+        if (a.loss == HALP_LOSS_SQUARED) {
+          // Algorithm 4: (phi + Delta - y) - (phi - y) = Delta; Algorithm 2: (x^T w - y) - (phi - y)
+          diff = lp ? __dadd_rn(delta, -(double)phi[i]) : delta;
+        } else {
+          const double a0 = (double)phi[i], yi = (double)y[i];
+          diff = __dadd_rn(logistic_dl(after_margin(a0, s_D[pr]), yi), -logistic_dl(a0, yi));
+        }
+      }
+      const double beta = __dmul_rn(aB, diff);
       const uint64_t nn = ((uint64_t)t * (uint64_t)Bt + (uint64_t)(mb + m)) * (uint64_t)K + (uint64_t)c;
       const uint32_t r = pick(stream_block(seed, kGamma, a.epoch, nn >> 2), (uint32_t)(nn & 3));
       bool hit = false;
@@ -381,8 +405,9 @@ int launch_one(const InArgs& a, int R, int slot_bytes, hipStream_t s) {
 
 int inner_softmax_batch_supported(const halp_handle& h) {
   const halp_params& p = h.p;
-  if (p.loss != HALP_LOSS_SOFTMAX || p.B < 2 || p.B > 512 || p.K < 2 || p.K > kMaxK)
-    return HALP_ERR_UNSUPPORTED;
+  if (p.B < 2 || p.B > 512 || p.K > kMaxK) return HALP_ERR_UNSUPPORTED;
+  // softmax; or a scalar margin with more rows per step than the kernel for that case takes
+  if (p.loss == HALP_LOSS_SOFTMAX ? p.K < 2 : (p.K != 1 || p.B <= 64)) return HALP_ERR_UNSUPPORTED;
   const int upl = strips_per_lane(p);
   if (upl == 0) return HALP_ERR_UNSUPPORTED;
   if (!h.bound || !h.buf.Xq) return HALP_ERR_NOT_BOUND;

@@ -751,6 +751,44 @@ def test_inner_loop_minibatch_bit_exact(loss, N, d, B, b, lam, R, T, variant, pa
         assert cnt[0, 0] > 0
 
 
+WIDE_BATCH_CASES = [
+    # loss, N, d, B, b, lam, R, T, mu: more than 64 rows per step with a scalar margin
+    (hp.LOSS_SQUARED, 400, 64, 65, 8, 0.0, 2, 40, 0.05),
+    (hp.LOSS_SQUARED, 300, 1000, 100, 8, 1e-2, 1, 25, 0.05),   # ragged row, L2 draws
+    (hp.LOSS_LOGISTIC, 500, 256, 512, 16, 1e-5, 1, 8, 0.05),   # the widest minibatch
+    (hp.LOSS_LOGISTIC, 200, 1024, 130, 16, 0.0, 1, 12, 0.05),  # 16 strips per lane
+    (hp.LOSS_SQUARED, 64, 64, 200, 8, 0.0, 1, 60, 500.0),      # box far too small: z saturates
+]
+
+
+@pytest.mark.parametrize("variant", [2, 0, 1])
+@pytest.mark.parametrize("loss,N,d,B,b,lam,R,T,mu", WIDE_BATCH_CASES)
+def test_inner_loop_wide_minibatch_bit_exact(loss, N, d, B, b, lam, R, T, mu, variant):
+    seed = 40 + d + B
+    case = _inner_case(loss, N, d, 1, B, b, lam, R, T, seed, mu=mu)
+    P = _run_inner(case, loss, 1, B, b, lam, R, T, seed, variant, mu=mu)
+    P.h.inner_loop(3)
+    z, w, cnt = P.get("z"), P.get("w"), P.get("counters")
+    assert P.h.get_stats(0).inner_variant == (1 if variant == 1 else 2)
+    for r in range(R):
+        out = _oracle_inner(case, r, T)
+        assert np.array_equal(z[r].astype(np.int32), out["z"]), f"chain {r}"
+        w_r = ref.apply_offset(case["mk"](r), case["scales"][r], out["z"], case["w"][r])
+        assert np.array_equal(w[r], w_r)
+        assert np.array_equal(cnt[r].astype(np.uint64), out["counters"])
+    if mu > 100:
+        assert cnt[0, 0] > 0
+
+
+def test_wide_minibatch_on_rows_too_wide_for_a_class_wave_falls_back():
+    loss, N, d, B, b, T = hp.LOSS_LOGISTIC, 150, 4096, 96, 16, 6
+    case = _inner_case(loss, N, d, 1, B, b, 0.0, 1, T, 21, mu=0.05)
+    P = _run_inner(case, loss, 1, B, b, 0.0, 1, T, 21, 0, mu=0.05)
+    P.h.inner_loop(3)
+    assert P.h.get_stats(0).inner_variant == 1
+    assert np.array_equal(P.get("z")[0].astype(np.int32), _oracle_inner(case, 0, T)["z"])
+
+
 GENERIC_CASES = [
     # loss, N, d, K, B, b, lam, R, T
     (hp.LOSS_SOFTMAX, 400, 784, 10, 1, 8, 1e-4, 1, 300),
