@@ -86,6 +86,8 @@ LP_CASES = [
     (hp.LOSS_SOFTMAX, 150, 300, 16, 1, 8, 1, 150, (2, 1)),   # 16 classes: two rows of z per class wave
     (hp.LOSS_SOFTMAX, 200, 200, 5, 6, 8, 1, 60, (2, 1)),     # softmax with a minibatch
     (hp.LOSS_SOFTMAX, 120, 600, 3, 16, 16, 1, 40, (2, 1)),   # ... 16 strips per lane at 16 bits
+    (hp.LOSS_SQUARED, 300, 64, 1, 100, 8, 1, 30, (2, 1)),    # a scalar margin, more than 64 rows per step
+    (hp.LOSS_LOGISTIC, 200, 300, 1, 70, 16, 1, 25, (2, 1)),
 ]
 
 
