@@ -4,9 +4,11 @@
 //   R   = softmax(Phi) - onehot(y)    [N x K]   residuals l'
 //   G   = R^T X                       [K x d]   gradient sum (the 1/N and lambda W~ come later)
 // Both products are dense contractions with one small dimension (K <= 16): they run on the
-// matrix cores as v_mfma_f32_16x16x4_f32 with the classes padded to 16.
+// matrix cores with the classes padded to 16 -- as fp32 products (v_mfma_f32_16x16x4_f32), or,
+// in the pipelined form further down on rows of whole float4s, with every fp32 operand split
+// into two halves on the 16-bit path (fp32 accumulation, the accuracy of fp32 products).
 //
-// A workgroup (4 waves) takes tiles of 16 rows.  The tile is fetched from HBM once, with
+// First form (rows of 801 .. 1024 coordinates): a workgroup (4 waves) takes tiles of 16 rows.  The tile is fetched from HBM once, with
 // row-contiguous 16-byte loads, into LDS, from where both products read it: as the A
 // operand (rows x columns) of the first and as the B operand (rows x columns, rows being the
 // contraction index) of the second.  The next tile's loads are in flight (into registers) while
@@ -278,26 +280,33 @@ __global__ __launch_bounds__(256, 2) void fullgrad_softmax_mfma(FgArgs a) {
 }
 
 // ---- pipelined form (d <= 800): specialised waves, three tiles in LDS ---------------------
-// One workgroup of eight waves per CU.  Waves 0-3 do nothing but the two products (one per
-// SIMD, so the matrix pipe of every SIMD has one instruction stream); waves 4-7 move data and
-// take the softmax.  The work on a tile is spread over three periods, a period being two halves
-// closed by a barrier each:
+// One workgroup of eight waves per CU; waves 0-3 (one per SIMD) do the two products, three tile
+// buffers of 16 rows in LDS.
+//
+// Serial form (rows of whole float4s, the 10-class shape): the matrix waves take a tile through
+// margins -> softmax (wave w the rows 4w .. 4w+3) -> gradient sum, three barriers that wait for
+// LDS traffic only; waves 4-7 do nothing but start tiles on their way from memory straight into
+// LDS (global_load_lds, 1 KB per instruction, no registers and no LDS stores) and wait for them:
+// tile k+2 is started during period k, a third of its loads beside each phase, into the buffer
+// tile k-1 left, and has to be there when period k+1 ends.  With HALVES both products take their
+// fp32 operands as pairs of halves (split8 above) on the 16-bit path of the matrix cores:
+// 16x16x32 contractions for the margins, 32x32x16 over the tile's rows for the gradient sum,
+// fp32 accumulators; without it they are fp32 products (16x16x4).
+//
+// Overlapped form (other rows, fp32 products): the work on a tile is spread over three periods, a
+// period being two halves closed by a barrier each:
 //                      half A                               half B
 //   matrix waves       margins of tile k (first product)    gradient sum of tile k-1 (second product)
-//   helper waves       start tile k+1 on its way to LDS     softmax of tile k -> residuals of tile k
-// so the matrix waves never wait for a softmax or for memory, and the three tiles in flight
-// (k-1, k, k+1) take three buffers of 16 rows in LDS.  Rows that are whole float4s travel from
-// memory straight into LDS (global_load_lds, 1 KB per instruction, no registers and no LDS
-// stores from the helper waves; the tile has a whole period to land); other rows go through
-// registers, two tiles ahead, and are masked on their way into LDS.
+//   helper waves       stage tile k+1 through registers     softmax of tile k -> residuals of tile k
+// (requested two tiles ahead, masked on the way into LDS).
+//
 // Columns are dealt to the matrix waves in groups of 32 (group g to wave g % 4): d = 784 = 24.5
 // groups costs the half group only, not a padding of every wave's share.  The group count of a
 // wave is a compile-time constant of its loop, so that all operand reads of a tile are issued
-// before its first product and the products follow back to back.
-// What bounds it: a helper wave that shares a SIMD with a wave issuing fp32 matrix products gets
+// before its first product.
+// What bounded the fp32 products: a helper wave that shares a SIMD with a wave issuing them gets
 // about one instruction through per product (~30 cycles each, whatever the instruction), and a
-// tile's loads are accepted by the memory pipeline over ~1.4 us; both are longer than the 0.85 us
-// the products of a half take, so the period is set by the helper waves.
+// tile's loads are accepted by the memory pipeline over ~1.4 us.
 // The compiler may not move instructions across the borders of a phase: left to itself it
 // spreads a phase's LDS traffic and address arithmetic into its neighbours, where they queue
 // behind the other role's work (measured: 0.80 ms against 0.71 ms at N = 960000).
