@@ -266,12 +266,16 @@ def side_inner_loop(hp, inp, torch, which, T, poll_delay=-1):
     b=8/16; logistic with a minibatch of 64 at b=16), at a reduced step count; `inner_variant`
     says which kernel ran (1 general, 2 register-resident)."""
     out = {}
-    if which == "c3":
+    if which in ("c3", "c3batch"):
         N, d, K = 60000, 784, 10
         X, y, _ = inp.softmax_sparse(N, d, K, seed=0)
         Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
         cases = [dict(b=8, B=1, loss=hp.LOSS_SOFTMAX, lam=1e-4, alpha=1e-2, mu=2.5),
                  dict(b=16, B=1, loss=hp.LOSS_SOFTMAX, lam=1e-4, alpha=1e-2, mu=2.5)]
+        if which == "c3batch":  # the same data with 64 rows per step: class-wave kernel, general kernel
+            cases = [dict(b=8, B=64, loss=hp.LOSS_SOFTMAX, lam=1e-4, alpha=1e-2, mu=2.5, variant=0),
+                     dict(b=16, B=64, loss=hp.LOSS_SOFTMAX, lam=1e-4, alpha=1e-2, mu=2.5, variant=0),
+                     dict(b=8, B=64, loss=hp.LOSS_SOFTMAX, lam=1e-4, alpha=1e-2, mu=2.5, variant=1)]
     else:
         N, d, K = 1_000_000, 4096, 1
         Xd, yd, _ = inp.logistic_device(N, d, seed=0)
@@ -288,11 +292,13 @@ def side_inner_loop(hp, inp, torch, which, T, poll_delay=-1):
         h.quantize_data()
         if poll_delay >= 0:
             h.set_option(hp.OPT_EXCHANGE_POLL_DELAY, poll_delay)
+        if c.get("variant"):
+            h.set_option(hp.OPT_INNER_VARIANT, c["variant"])
         h.set_option(hp.OPT_TIMING, 1)
         for k in range(3):
             h.epoch(k)
         s = h.get_stats(0)
-        out[f"{which}_b{b}_B{c['B']}"] = dict(
+        out[f"{which}_b{b}_B{c['B']}" + ("_general" if c.get("variant") == 1 else "")] = dict(
             N=N, d=d, K=K, b=b, B=c["B"], T=T, inner_variant=s.inner_variant,
             ms_inner_loop=s.ms_inner_loop, ms_full_gradient=s.ms_full_gradient,
             steps_per_s=T / (s.ms_inner_loop * 1e-3),
@@ -454,7 +460,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c5", "c3grad", "cond", "clip"],
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS) + ["c3", "c3batch", "c5", "c3grad", "cond", "clip"],
                     help="c4 (default), c2, c1: the headline line; c3, c5: inner-loop step rate "
                          "of the softmax and minibatch configurations; c3grad: the softmax "
                          "gradient pass; cond: the conditioning sweep (5 x --steps epochs); clip: the "
@@ -509,7 +515,7 @@ def main():
         print(json.dumps({"workload": "cond", "conditioning_sweep":
                           conditioning_sweep(hp, inp, torch, max(args.steps, 1) * 5, 1000)}))
         return
-    if args.workload in ("c3", "c5"):
+    if args.workload in ("c3", "c3batch", "c5"):
         print(json.dumps({"workload": args.workload, "side_inner_loop":
                           side_inner_loop(hp, inp, torch, args.workload, args.inner_steps, args.poll_delay)}))
         return
