@@ -323,10 +323,12 @@ struct RedArgs {
   double lambda;
 };
 
-// A workgroup sums 32 entries: thread (entry tid % 32, group tid / 32) adds every 32nd partial
-// in index order, the 32 group sums are then added in group order: a fixed order, with a
+// A workgroup sums 32 entries: thread (entry tid % 32, group tid / 32) adds every GROUPS-th
+// partial in index order, the group sums are then added in group order: a fixed order, with a
 // thread's few loads all in flight at once (the pass is as long as its longest chain of waits).
-constexpr int kReduceGroups = 32;
+// GROUPS = 32 where a chain has many partials, 8 where it has few (a chain of the headline
+// workload has two).
+template <int kReduceGroups>
 __global__ __launch_bounds__(32 * kReduceGroups) void fullgrad_reduce(RedArgs a) {
   const int chain = blockIdx.y;
   const int e = threadIdx.x & 31, grp = threadIdx.x >> 5;
@@ -528,7 +530,10 @@ static int launch_full_gradient_plan(const FgPlan& f, hipStream_t s) {
   r.scales = buf.scales; r.N = p.N; r.n = p.K * p.d; r.parts = f.parts; r.lambda = p.lambda;
   r.fscale = f.fscale; r.d = p.d;
   r.loss_parts = f.loss_parts; r.loss_stride = f.parts > f.loss_parts ? f.parts : f.loss_parts;
-  hipLaunchKernelGGL(fullgrad_reduce, dim3((r.n + 31) / 32, p.R), dim3(32 * kReduceGroups), 0, s, r);
+  if (f.parts > 64)
+    hipLaunchKernelGGL(fullgrad_reduce<32>, dim3((r.n + 31) / 32, p.R), dim3(32 * 32), 0, s, r);
+  else
+    hipLaunchKernelGGL(fullgrad_reduce<8>, dim3((r.n + 31) / 32, p.R), dim3(32 * 8), 0, s, r);
   return hip_ok(hipGetLastError());
 }
 
