@@ -137,6 +137,10 @@ FG_CASES = [
     (hp.LOSS_SOFTMAX, 5000, 800, 16, 1, 1e-4),
     (hp.LOSS_SOFTMAX, 4100, 33, 4, 3, 0.0),
     (hp.LOSS_SOFTMAX, 17, 96, 2, 1, 0.0),
+    (hp.LOSS_SOFTMAX, 1, 4, 2, 1, 0.0),           # one row, one float4: a single tile, one column group
+    (hp.LOSS_SOFTMAX, 16, 12, 3, 2, 0.0),         # exactly one tile
+    (hp.LOSS_SOFTMAX, 33, 800, 10, 2, 1e-4),      # the widest rows of the pipelined form, three tiles
+    (hp.LOSS_SOFTMAX, 4099, 36, 16, 1, 1e-3),     # more workgroups than tiles per workgroup, 16 classes
     # rows wider than a wave holds (K = 1: the row cut across the waves of a workgroup)
     (hp.LOSS_SQUARED, 403, 4097, 1, 1, 0.0),
     (hp.LOSS_LOGISTIC, 301, 5000, 1, 2, 1e-5),
