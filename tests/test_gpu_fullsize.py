@@ -311,3 +311,32 @@ def test_ten_class_ten_thousand_feature_epoch():
     assert np.array_equal(st["z"][0].cpu().numpy().astype(np.int32), out["z"])
     assert np.array_equal(st["counters"][0].cpu().numpy().astype(np.uint64), out["counters"])
     assert np.any(out["z"] != 0)
+
+
+@pytest.mark.timeout(600)
+def test_softmax_gradient_pass_at_the_bench_row_count():
+    """The softmax gradient pass at the row count `bench.py --workload c3grad` times (960000 rows of the
+    configuration-3 recipe, 3 GB: past the last-level cache), in the launch shape of that run, against the
+    oracle on every output: both forms of the products (pairs of halves, fp32)."""
+    N, d, K, lam = 960000, 784, 10, 1e-4
+    X, y, _ = inp.softmax_sparse(N, d, K, seed=6)
+    rng = np.random.default_rng(3)
+    W0 = (0.01 * rng.standard_normal((1, K, d))).astype(np.float32)
+    prob = ref.make_problem(N, d, K=K, loss=ref.SOFTMAX, lam=lam)
+    phi_ref, g_ref, loss_ref = ref.full_gradient(prob, X, y, W0[0])
+    st = hp.alloc_state(N, d, K=K, b=8)
+    st["w"].copy_(torch.from_numpy(W0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    h = hp.Halp(N, d, K=K, loss=hp.LOSS_SOFTMAX, b=8, T=8, alpha=1e-2, mu=2.5, lam=lam, delta_d=1.0 / 127.0,
+                seed=0)
+    h.bind(X=Xd, y=yd, **st)
+    for fp32 in (0, 1):
+        h.set_option(hp.OPT_GRADIENT_FP32, fp32)
+        st["phi"].zero_(); st["g"].zero_()
+        h.full_gradient()
+        torch.cuda.synchronize()
+        assert rel_l2(st["phi"][0].cpu().numpy(), phi_ref) <= TOL, fp32
+        assert rel_l2(st["g"][0].cpu().numpy(), g_ref) <= TOL, fp32
+        assert abs(st["scales"][0, 6].item() - loss_ref) <= TOL * abs(loss_ref), fp32
+    h.close()
+
