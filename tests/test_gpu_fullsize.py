@@ -135,6 +135,40 @@ def test_config3_softmax_full_size(b):
     assert np.array_equal(st["counters"][0].cpu().numpy().astype(np.uint64), out["counters"])
 
 
+@pytest.mark.parametrize("b", [8, 16])
+def test_config3_softmax_minibatch_full_size(b):
+    """The data of configuration 3 with 64 rows per step (what `bench.py --workload c3batch` runs): 43
+    steps of the class-wave kernel against the oracle, counters included."""
+    N, d, K, B, T = 60000, 784, 10, 64, 43
+    alpha, mu, lam, seed = 1e-2, 2.5, 1e-4, 4
+    X, y, _ = inp.softmax_sparse(N, d, K, seed=seed)
+    delta_d = inp.default_delta_d(X, b)
+    Xq_ref = ref.quantize_data(X, delta_d, b)
+    rng = np.random.default_rng(2)
+    W0 = (0.01 * rng.standard_normal((1, K, d))).astype(np.float32)
+    prob = ref.make_problem(N, d, K=K, loss=ref.SOFTMAX, b=b, B=B, alpha=alpha, mu=mu, lam=lam,
+                            delta_d=delta_d, seed=seed)
+    phi_ref, g_ref, _ = ref.full_gradient(prob, X, y, W0[0])
+    st = hp.alloc_state(N, d, K=K, b=b)
+    st["w"].copy_(torch.from_numpy(W0))
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    Xq = torch.from_numpy(Xq_ref.astype(np.int8 if b == 8 else np.int16))[None].cuda()
+    h = hp.Halp(N, d, K=K, loss=hp.LOSS_SOFTMAX, b=b, B=B, T=T, alpha=alpha, mu=mu, lam=lam,
+                delta_d=delta_d, seed=seed)
+    h.bind(X=Xd, Xq=Xq, y=yd, **st)
+    st["g"][0].copy_(torch.from_numpy(g_ref.astype(np.float32)))
+    st["phi"][0].copy_(torch.from_numpy(phi_ref.astype(np.float32)))
+    h.recenter(1)
+    h.inner_loop(1)
+    torch.cuda.synchronize()
+    assert h.get_stats(0).inner_variant == 2  # not the general kernel
+    sc, hh, _ = ref.recenter(prob, g_ref.astype(np.float32), 1)
+    out = ref.inner_loop(prob, Xq_ref, phi_ref.astype(np.float32), y, hh, sc, 1, T)
+    assert np.array_equal(st["z"][0].cpu().numpy().astype(np.int32), out["z"])
+    assert np.array_equal(st["counters"][0].cpu().numpy().astype(np.uint64), out["counters"])
+    h.close()
+
+
 def test_config5_logistic_full_size():
     """N=1e6, d=4096 fp32 (16.4 GB), lambda=1e-5, b=16, B=64.  Gradient pass: every margin, the
     gradient and the loss against the oracle run once over the whole matrix on the host (the
